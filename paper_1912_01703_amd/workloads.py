@@ -1,0 +1,133 @@
+"""Seeded synthetic convolution layers shaped like the paper's CNN benchmarks.
+
+The paper's throughput table (Section 6.3, Table 1) trains AlexNet, VGG-19,
+ResNet-50 and MobileNet in 32-bit floats but names no dataset, batch size or
+layer list, so the layers below are synthetic stand-ins of those networks'
+well-known convolution shapes.  This module only draws random inputs and packs
+them as fp32 or bf16; it contains none of the convolution arithmetic and is
+the one module the HIP path's callers and the CPU oracle's callers share.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, Tuple
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Layer:
+    name: str
+    N: int
+    C: int
+    H: int
+    W: int
+    K: int
+    R: int
+    S: int
+    stride: int
+    pad: int
+    groups: int
+    seed: int
+    x_dist: str = "normal"   # "normal" -> N(0,1); "uniform" -> U[-1,1]
+    note: str = ""
+
+    @property
+    def P(self) -> int:
+        return (self.H + 2 * self.pad - self.R) // self.stride + 1
+
+    @property
+    def Q(self) -> int:
+        return (self.W + 2 * self.pad - self.S) // self.stride + 1
+
+    @property
+    def x_shape(self) -> Tuple[int, int, int, int]:
+        return (self.N, self.C, self.H, self.W)
+
+    @property
+    def w_shape(self) -> Tuple[int, int, int, int]:
+        return (self.K, self.C // self.groups, self.R, self.S)
+
+    @property
+    def y_shape(self) -> Tuple[int, int, int, int]:
+        return (self.N, self.K, self.P, self.Q)
+
+    @property
+    def flops(self) -> int:
+        """Nominal FLOPs of one pass (the same count is used for all three)."""
+        return 2 * self.N * self.K * self.P * self.Q * (self.C // self.groups) * self.R * self.S
+
+    def conv_args(self):
+        """(N,C,H,W,K,R,S,stride_h,stride_w,pad_h,pad_w,groups)"""
+        return (self.N, self.C, self.H, self.W, self.K, self.R, self.S,
+                self.stride, self.stride, self.pad, self.pad, self.groups)
+
+
+# seed = 16 * (index of the configuration group) + (index of the layer in it)
+LAYERS: Dict[str, Layer] = {l.name: l for l in [
+    Layer("1", 2, 3, 16, 16, 8, 3, 3, 1, 1, 1, seed=0, note="tiny 3x3"),
+    Layer("2a", 64, 256, 14, 14, 256, 3, 3, 1, 1, 1, seed=16, note="ResNet-50 bottleneck 3x3"),
+    Layer("2b", 64, 1024, 14, 14, 256, 1, 1, 1, 0, 1, seed=17, note="ResNet-50 bottleneck 1x1"),
+    Layer("2c", 64, 128, 28, 28, 128, 3, 3, 2, 1, 1, seed=18, note="ResNet-50 3x3 stride 2"),
+    Layer("3", 128, 3, 224, 224, 64, 11, 11, 4, 2, 1, seed=32, x_dist="uniform",
+          note="AlexNet first layer"),
+    Layer("4a", 64, 64, 224, 224, 64, 3, 3, 1, 1, 1, seed=48, note="VGG 3x3 at 224x224"),
+    Layer("4b", 64, 512, 28, 28, 512, 3, 3, 1, 1, 1, seed=49, note="VGG 3x3 at 28x28"),
+    Layer("5a", 128, 512, 14, 14, 512, 3, 3, 1, 1, 512, seed=64, note="MobileNet depthwise 3x3"),
+    Layer("5b", 128, 512, 14, 14, 512, 1, 1, 1, 0, 1, seed=65, note="MobileNet pointwise 1x1"),
+]}
+
+
+def custom_layer(name, N, C, H, W, K, R, S, stride=1, pad=0, groups=1, seed=1234, x_dist="normal"):
+    return Layer(name, N, C, H, W, K, R, S, stride, pad, groups, seed, x_dist)
+
+
+def make_inputs(layer: Layer):
+    """Draw (x, w, dy) as float32, in that order, from PCG64(layer.seed).
+
+    x ~ N(0,1) (or U[-1,1]); w ~ N(0, 2/fan_in) with fan_in = (C/groups)*R*S
+    (Kaiming-normal, no truncation); dy ~ N(0,1).
+    """
+    rng = np.random.Generator(np.random.PCG64(layer.seed))
+    if layer.x_dist == "uniform":
+        x = rng.uniform(-1.0, 1.0, size=layer.x_shape).astype(np.float32)
+    else:
+        x = rng.standard_normal(size=layer.x_shape, dtype=np.float32)
+    fan_in = (layer.C // layer.groups) * layer.R * layer.S
+    w = rng.standard_normal(size=layer.w_shape, dtype=np.float32)
+    w *= np.float32(np.sqrt(2.0 / fan_in))
+    dy = rng.standard_normal(size=layer.y_shape, dtype=np.float32)
+    return x, w, dy
+
+
+def to_bf16_bits(a: np.ndarray) -> np.ndarray:
+    """Round float32 to bfloat16 (nearest, ties to even); returns uint16 bit patterns.
+    NaN inputs are not expected in the synthetic data and are not special-cased."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    rounded = u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))
+    return (rounded >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    """Exact widening of bf16 bit patterns to float32."""
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def sample_indices(shape, count, seed):
+    """A seeded sample of flat indices into a 4-d tensor that always includes
+    the four spatial corners, points on each edge and interior points of the
+    first and last (dim0, dim1) planes, followed by uniform random picks."""
+    d0, d1, d2, d3 = shape
+    total = d0 * d1 * d2 * d3
+    rng = np.random.Generator(np.random.PCG64(seed))
+    forced = []
+    for a in sorted({0, d0 - 1}):
+        for b in sorted({0, d1 - 1}):
+            for i in sorted({0, d2 // 2, d2 - 1}):
+                for j in sorted({0, d3 // 2, d3 - 1}):
+                    forced.append(((a * d1 + b) * d2 + i) * d3 + j)
+    forced = np.asarray(forced, dtype=np.int64)
+    if count >= total:
+        return np.arange(total, dtype=np.int64)
+    extra = rng.integers(0, total, size=max(0, count - forced.size), dtype=np.int64)
+    return np.unique(np.concatenate([forced, extra]))
