@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the convolution hot path on one MI355X.
+
+A step is one forward + backward-data + backward-weight pass of one layer
+through the C ABI (default: the ResNet-50 3x3 bottleneck layer, N=64,
+C=K=256, 14x14), inputs resident in HBM.  Prints ONE JSON line:
+whole-step TFLOP/s (nominal 2*N*K*P*Q*Cg*R*S FLOPs per pass), the roofline
+figures of the dominant kernel measured with HIP events, and the CPU oracle
+timed on the host cores as a baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--layer 2a] [--dtype f32|bf16]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA, MI355X published
+PEAK_HBM_GBS = 8000.0
+PASSES = ("fwd", "bwd_data", "bwd_weight")
+METRIC = "conv fwd+bwd TFLOP/s and % FP32 MFMA peak (ResNet-50 3x3 layer)"
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--layer", default="2a")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rotate", type=int, default=0,
+                    help="number of distinct buffer sets cycled between steps (0: auto; "
+                         "bandwidth-bound layers use enough to exceed the 256 MB Infinity Cache)")
+    return ap.parse_args()
+
+
+def algorithmic_bytes(L, pass_name, in_bytes):
+    """Unique bytes one pass must move: its two inputs once, its output once."""
+    nx, nw, ny = (L.N * L.C * L.H * L.W, L.K * (L.C // L.groups) * L.R * L.S, L.N * L.K * L.P * L.Q)
+    if pass_name == "fwd":
+        return (nx + nw) * in_bytes + ny * 4
+    if pass_name == "bwd_data":
+        return (ny + nw) * in_bytes + nx * 4
+    return (nx + ny) * in_bytes + nw * 4
+
+
+def cpu_baseline(L, dtype):
+    """Times the oracle (as it stands) on the host cores for the same layer.
+    Layers whose full oracle run would exceed ~30 s are timed on a subset of
+    images and the rate is reported per FLOP, which is the metric's unit."""
+    import numpy as np
+    from oracle import convref as ref
+    from paper_1912_01703_amd import workloads as wl
+    budget_flops = 60e9          # about 10-30 s of scalar fp64 on 8-16 cores
+    n_sub = max(1, min(L.N, int(L.N * budget_flops / (3.0 * L.flops))))
+    sub = wl.custom_layer(L.name + "-cpu", n_sub, L.C, L.H, L.W, L.K, L.R, L.S, L.strides, L.pads, L.groups,
+                          seed=L.seed, x_dist=L.x_dist)
+    x, w, dy = wl.make_inputs(sub)
+    if dtype == "bf16":
+        x, w, dy = wl.to_bf16_bits(x), wl.to_bf16_bits(w), wl.to_bf16_bits(dy)
+    tiny = wl.LAYERS["1"]
+    tx, tw, _ = wl.make_inputs(tiny)
+    ref.conv2d_fwd(tx, tw, tiny.strides, tiny.pads, tiny.groups)     # warm-up: library load, thread pool
+    t0 = time.perf_counter()
+    ref.conv2d_fwd(x, w, sub.strides, sub.pads, sub.groups)
+    ref.conv2d_bwd_data(dy, w, sub.x_shape, sub.strides, sub.pads, sub.groups)
+    ref.conv2d_bwd_weight(x, dy, sub.w_shape, sub.strides, sub.pads, sub.groups)
+    dt = time.perf_counter() - t0
+    return {"value": 3.0 * sub.flops / dt / 1e12, "unit": "TFLOP/s", "cores": ref.num_threads(), "kind": "oracle",
+            "seconds": dt,
+            "sample": f"layer {L.name} with N={n_sub} of {L.N} images, fwd+bwd_data+bwd_weight once, fp64 accumulate"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        sys.stderr.write("bench.py: this build measures one GPU only; run with --gpus 1\n")
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_1912_01703_amd import binding as mc
+    from paper_1912_01703_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU visible\n")
+        sys.exit(3)
+    L = wl.LAYERS[a.layer]
+    code = mc.BF16_F32ACC if a.dtype == "bf16" else mc.F32
+    in_bytes = 2 if a.dtype == "bf16" else 4
+    args = L.conv_args()
+    dev = "cuda:0"
+    x, w, dy = wl.make_inputs(L)
+    if a.dtype == "bf16":
+        x, w, dy = (wl.to_bf16_bits(t).view(np.int16) for t in (x, w, dy))
+
+    depthwise = L.groups == L.C == L.K and L.groups > 1
+    set_bytes = sum(algorithmic_bytes(L, p, in_bytes) for p in PASSES)
+    nsets = a.rotate if a.rotate > 0 else (max(2, int(600e6 // max(1, set_bytes)) + 1) if depthwise else 1)
+    nsets = min(nsets, 64)
+    sets = []
+    for i in range(nsets):
+        s = dict(x=torch.from_numpy(x).to(dev), w=torch.from_numpy(w).to(dev), dy=torch.from_numpy(dy).to(dev),
+                 y=torch.empty(L.y_shape, dtype=torch.float32, device=dev),
+                 dx=torch.empty(L.x_shape, dtype=torch.float32, device=dev),
+                 dw=torch.empty(L.w_shape, dtype=torch.float32, device=dev))
+        sets.append(s)
+    ws_bytes = [mc.conv2d_workspace_bytes(p, *args, code) for p in range(3)]
+    ws = torch.empty(max(ws_bytes + [256]), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def run_pass(p, s):
+        if p == 0:
+            mc.conv2d_fwd(s["x"], s["w"], s["y"], *args, code, ws, stream)
+        elif p == 1:
+            mc.conv2d_bwd_data(s["dy"], s["w"], s["dx"], *args, code, ws, stream)
+        else:
+            mc.conv2d_bwd_weight(s["x"], s["dy"], s["dw"], *args, code, ws, stream)
+
+    def step(i):
+        s = sets[i % nsets]
+        for p in range(3):
+            run_pass(p, s)
+
+    for i in range(a.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(a.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / a.steps
+    tflops = 3.0 * L.flops / (ms_per_step * 1e-3) / 1e12
+
+    # Second region, same launches: HIP events around every pass (recorded on the
+    # stream the kernels are launched on) give each pass's average duration.
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3)]
+          for _ in range(a.steps)]
+    for i in range(a.steps):
+        s = sets[i % nsets]
+        for p in range(3):
+            ev[i][p][0].record()
+            run_pass(p, s)
+            ev[i][p][1].record()
+    torch.cuda.synchronize()
+    pass_ms = [float(np.mean([ev[i][p][0].elapsed_time(ev[i][p][1]) for i in range(a.steps)])) for p in range(3)]
+    pass_min = [float(np.min([ev[i][p][0].elapsed_time(ev[i][p][1]) for i in range(a.steps)])) for p in range(3)]
+    algos = [mc.miconv_last_algo(p) for p in range(3)]
+
+    passes = {}
+    for p, name in enumerate(PASSES):
+        passes[name] = {"ms_avg": pass_ms[p], "ms_min": pass_min[p], "algo": algos[p],
+                        "tflops": L.flops / (pass_ms[p] * 1e-3) / 1e12,
+                        "gbs": algorithmic_bytes(L, name, in_bytes) / (pass_ms[p] * 1e-3) / 1e9}
+    dom = int(np.argmax(pass_ms))
+    if depthwise:
+        ach = passes[PASSES[dom]]["gbs"]
+        roof = {"bound": "hbm", "kernel": PASSES[dom], "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                "algorithmic_bytes_per_launch": algorithmic_bytes(L, PASSES[dom], in_bytes),
+                "avg_launch_ms": pass_ms[dom], "buffer_sets_rotated": nsets}
+    else:
+        ach = passes[PASSES[dom]]["tflops"]
+        peak = PEAK_TFLOPS[a.dtype]
+        roof = {"bound": "mfma", "kernel": PASSES[dom], "achieved": ach, "peak": peak, "unit": "TFLOP/s",
+                "frac": ach / peak, "traffic": None, "algorithmic_flops_per_launch": L.flops,
+                "avg_launch_ms": pass_ms[dom]}
+
+    out = {
+        "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": a.dtype, "data": "synthetic",
+        "config": {"workload": f"layer {L.name} ({L.note}): N={L.N} C={L.C} HxW={L.H}x{L.W} K={L.K} "
+                               f"{L.R}x{L.S} stride {L.stride} pad {L.pad} groups {L.groups}; "
+                               "step = fwd + bwd_data + bwd_weight",
+                   "layer": L.name, "seed": L.seed, "flops_per_pass": L.flops},
+        "pct_of_peak": 100.0 * tflops / PEAK_TFLOPS[a.dtype],
+        "passes": passes,
+        "roofline": roof,
+        "device": torch.cuda.get_device_name(0),
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(L, a.dtype)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,138 @@
+/*
+ * miconv -- 2D convolution (cross-correlation) for AMD MI355X (gfx950):
+ * forward, backward-data and backward-weight behind a plain C ABI.
+ *
+ * The operator is the "2d convolution" the paper names among its built-in
+ * functions (Section 4.1); the two backward entry points are the
+ * vector-Jacobian products of the forward function with respect to its input
+ * and its weight, which is what the paper requires of a backward function
+ * (Section 4.2).  Arithmetic is 32-bit float as in the paper's benchmarks
+ * (Section 6.3, Table 1), with a bf16-input / fp32-accumulate variant.
+ *
+ * Common conventions for the three compute entry points
+ * ------------------------------------------------------
+ *  Shapes     x [N][C][H][W], w [K][C/groups][R][S], y [N][K][P][Q] with
+ *             P = floor((H + 2*pad_h - R)/stride_h) + 1 and Q likewise.
+ *             dy is shaped like y, dx like x, dw like w.  Everything is
+ *             contiguous row-major (NCHW / KCRS).  Output channel k belongs to
+ *             group k / (K/groups) and reads input channels
+ *             [g*C/groups, (g+1)*C/groups).  Dilation is 1; there is no bias.
+ *  Padding    zeros, the same amount on both sides of an axis.
+ *  dtype      MICONV_F32: x, w, dy are float.  MICONV_BF16_F32ACC: x, w, dy are
+ *             bfloat16 bit patterns (uint16_t); products are accumulated in
+ *             fp32.  Outputs (y, dx, dw) are float in both cases.
+ *  Pointers   x, w, dy, y, dx, dw and workspace are DEVICE pointers on the
+ *             current HIP device.  The caller owns all of them; the library
+ *             never allocates, frees or keeps them.  Inputs are read only.
+ *             Outputs must not overlap inputs.  Every output element is
+ *             overwritten (beta = 0), including dx positions no filter tap
+ *             reaches (they become 0).
+ *  workspace  scratch of at least conv2d_workspace_bytes(...) bytes for the
+ *             same arguments, 256-byte aligned; may be NULL when that size
+ *             is 0.  Its contents are undefined afterwards.
+ *  stream     a hipStream_t passed as void* (NULL = the default stream).  All
+ *             work is enqueued on it; the call returns without synchronising,
+ *             so the host can run ahead of the device as in the paper's
+ *             Section 5.2.
+ *  Errors     the return value is a miconv_status.  On anything other than
+ *             MICONV_OK nothing has been launched (arguments are validated
+ *             first); miconv_last_error() then describes the problem.  No C++
+ *             exception crosses this boundary.
+ *  Limits     every tensor must have fewer than 2^31 elements.
+ *  Threads    calls may be made from several host threads; the algorithm
+ *             override below is process-wide.
+ */
+#ifndef MICONV_H
+#define MICONV_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Exported symbols: the library is built with hidden default visibility. */
+#define MICONV_API __attribute__((visibility("default")))
+
+typedef enum {
+    MICONV_OK = 0,
+    MICONV_ERR_NULL = 1,       /* a required pointer is NULL */
+    MICONV_ERR_SHAPE = 2,      /* a dimension < 1, stride < 1, pad < 0, P or Q < 1, or a tensor >= 2^31 elements */
+    MICONV_ERR_GROUPS = 3,     /* groups < 1, or C or K not divisible by groups */
+    MICONV_ERR_DTYPE = 4,      /* unknown dtype / pass / algorithm code */
+    MICONV_ERR_WORKSPACE = 5,  /* workspace NULL, misaligned or smaller than required */
+    MICONV_ERR_LAUNCH = 6,     /* the HIP runtime refused a launch */
+    MICONV_ERR_UNSUPPORTED = 7 /* a forced algorithm cannot run this problem */
+} miconv_status;
+
+typedef enum { MICONV_F32 = 0, MICONV_BF16_F32ACC = 1 } miconv_dtype;
+
+typedef enum { MICONV_PASS_FWD = 0, MICONV_PASS_BWD_DATA = 1, MICONV_PASS_BWD_WEIGHT = 2 } miconv_pass;
+
+typedef enum {
+    MICONV_ALGO_AUTO = 0,      /* pick the fastest kernel that supports the problem */
+    MICONV_ALGO_DIRECT = 1,    /* plain direct kernels: any valid problem, slow */
+    MICONV_ALGO_MFMA = 2,      /* LDS-staged implicit GEMM on MFMA (dense / grouped layers) */
+    MICONV_ALGO_DEPTHWISE = 3  /* bandwidth-bound stencil kernels, groups == C == K */
+} miconv_algo;
+
+/*
+ * y[n,k,p,q] = sum_{c,r,s} x[n, g*Cg+c, p*stride_h-pad_h+r, q*stride_w-pad_w+s] * w[k,c,r,s]
+ * (no filter flip; taps outside the image read zero).
+ */
+MICONV_API int conv2d_fwd(const void *x, const void *w, void *y,
+               int N, int C, int H, int W, int K, int R, int S,
+               int stride_h, int stride_w, int pad_h, int pad_w, int groups,
+               int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Vector-Jacobian product of conv2d_fwd with respect to x:
+ * dx[n,c,h,w] = sum over all (k,p,q,r,s) with p*stride_h-pad_h+r == h and
+ * q*stride_w-pad_w+s == w of dy[n,k,p,q] * w[k,c,r,s].  N,C,H,W describe dx.
+ */
+MICONV_API int conv2d_bwd_data(const void *dy, const void *w, void *dx,
+                    int N, int C, int H, int W, int K, int R, int S,
+                    int stride_h, int stride_w, int pad_h, int pad_w, int groups,
+                    int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Vector-Jacobian product of conv2d_fwd with respect to w:
+ * dw[k,c,r,s] = sum_{n,p,q} dy[n,k,p,q] * x[n, g*Cg+c, p*stride_h-pad_h+r, q*stride_w-pad_w+s].
+ * The result does not depend on launch timing: partial sums are combined in a
+ * fixed order (no floating-point atomics).
+ */
+MICONV_API int conv2d_bwd_weight(const void *x, const void *dy, void *dw,
+                      int N, int C, int H, int W, int K, int R, int S,
+                      int stride_h, int stride_w, int pad_h, int pad_w, int groups,
+                      int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Bytes of workspace the given pass (a miconv_pass) needs for these arguments
+ * under the current algorithm override.  Returns 0 for invalid arguments as
+ * well; the compute call reports those.
+ */
+MICONV_API size_t conv2d_workspace_bytes(int pass,
+                              int N, int C, int H, int W, int K, int R, int S,
+                              int stride_h, int stride_w, int pad_h, int pad_w, int groups,
+                              int dtype);
+
+/*
+ * Process-wide algorithm override for one pass (a miconv_algo).  With
+ * MICONV_ALGO_AUTO (the default) every valid problem runs on some kernel.  A
+ * forced algorithm that cannot run a problem makes the compute call return
+ * MICONV_ERR_UNSUPPORTED.  Returns MICONV_OK or MICONV_ERR_DTYPE.
+ */
+MICONV_API int miconv_set_algo(int pass, int algo);
+
+/* The miconv_algo the most recent successful call of that pass used on this
+ * host thread (MICONV_ALGO_AUTO if none yet). */
+MICONV_API int miconv_last_algo(int pass);
+
+/* Description of the most recent failure on this host thread ("" if none).
+ * The pointer stays valid until the thread's next failing call. */
+MICONV_API const char *miconv_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MICONV_H */

@@ -1,0 +1,162 @@
+// Host side of the C ABI declared in include/miconv.h: argument validation,
+// algorithm selection, workspace sizing and launches on the caller's stream.
+// Nothing here allocates device memory or synchronises.
+#include "../../include/miconv.h"
+
+#include <atomic>
+#include <cstdarg>
+#include <cstdio>
+
+#include "common.h"
+
+namespace {
+
+using miconv::Problem;
+
+thread_local char g_err[256] = "";
+thread_local int g_last_algo[3] = {MICONV_ALGO_AUTO, MICONV_ALGO_AUTO, MICONV_ALGO_AUTO};
+std::atomic<int> g_forced[3] = {{MICONV_ALGO_AUTO}, {MICONV_ALGO_AUTO}, {MICONV_ALGO_AUTO}};
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+// Fills pr and returns MICONV_OK, or records why the arguments are invalid.
+int make_problem(Problem& pr, int N, int C, int H, int W, int K, int R, int S, int sh, int sw, int ph, int pw,
+                 int groups, int dtype) {
+    if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1)
+        return fail(MICONV_ERR_SHAPE, "N,C,H,W,K,R,S must all be >= 1 (got %d,%d,%d,%d,%d,%d,%d)", N, C, H, W, K, R, S);
+    if (sh < 1 || sw < 1) return fail(MICONV_ERR_SHAPE, "strides must be >= 1 (got %d,%d)", sh, sw);
+    if (ph < 0 || pw < 0) return fail(MICONV_ERR_SHAPE, "padding must be >= 0 (got %d,%d)", ph, pw);
+    if (groups < 1 || C % groups || K % groups)
+        return fail(MICONV_ERR_GROUPS, "groups=%d must be >= 1 and divide C=%d and K=%d", groups, C, K);
+    if (dtype != MICONV_F32 && dtype != MICONV_BF16_F32ACC) return fail(MICONV_ERR_DTYPE, "unknown dtype %d", dtype);
+    const long long hp = (long long)H + 2LL * ph - R, wq = (long long)W + 2LL * pw - S;
+    if (hp < 0 || wq < 0)
+        return fail(MICONV_ERR_SHAPE, "filter %dx%d larger than padded input %dx%d (+2*%d,+2*%d)", R, S, H, W, ph, pw);
+    const long long P = hp / sh + 1, Q = wq / sw + 1;
+    const long long lim = 1LL << 31;
+    const long long nx = (long long)N * C * H * W, ny = (long long)N * K * P * Q;
+    const long long nw = (long long)K * (C / groups) * R * S;
+    if (nx >= lim || ny >= lim || nw >= lim)
+        return fail(MICONV_ERR_SHAPE, "tensor too large: x=%lld y=%lld w=%lld elements (limit 2^31)", nx, ny, nw);
+    pr.N = N; pr.C = C; pr.H = H; pr.W = W; pr.K = K; pr.R = R; pr.S = S;
+    pr.sh = sh; pr.sw = sw; pr.ph = ph; pr.pw = pw; pr.groups = groups;
+    pr.P = (int)P; pr.Q = (int)Q; pr.Cg = C / groups; pr.Kg = K / groups; pr.dtype = dtype;
+    return MICONV_OK;
+}
+
+// The algorithm that will run this pass, or -1 when the forced one cannot.
+int choose_algo(int pass, const Problem& pr) {
+    const int forced = g_forced[pass].load(std::memory_order_relaxed);
+    const bool dw_ok = miconv::depthwise_supports(pass, pr);
+    const bool mfma_ok = miconv::mfma_supports(pass, pr);
+    switch (forced) {
+        case MICONV_ALGO_DIRECT: return MICONV_ALGO_DIRECT;
+        case MICONV_ALGO_MFMA: return mfma_ok ? MICONV_ALGO_MFMA : -1;
+        case MICONV_ALGO_DEPTHWISE: return dw_ok ? MICONV_ALGO_DEPTHWISE : -1;
+        default: break;
+    }
+    if (dw_ok) return MICONV_ALGO_DEPTHWISE;
+    if (mfma_ok) return MICONV_ALGO_MFMA;
+    return MICONV_ALGO_DIRECT;
+}
+
+size_t workspace_for(int pass, int algo, const Problem& pr) {
+    if (algo == MICONV_ALGO_MFMA) return miconv::mfma_workspace_bytes(pass, pr);
+    if (algo == MICONV_ALGO_DEPTHWISE) return miconv::depthwise_workspace_bytes(pass, pr);
+    return 0;
+}
+
+int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, int W, int K, int R, int S, int sh,
+        int sw, int ph, int pw, int groups, int dtype, void* ws, size_t ws_bytes, void* stream) {
+    static const char* const in_names[3][2] = {{"x", "w"}, {"dy", "w"}, {"x", "dy"}};
+    static const char* const out_names[3] = {"y", "dx", "dw"};
+    Problem pr;
+    const int rc = make_problem(pr, N, C, H, W, K, R, S, sh, sw, ph, pw, groups, dtype);
+    if (rc != MICONV_OK) return rc;
+    if (!a) return fail(MICONV_ERR_NULL, "%s is NULL", in_names[pass][0]);
+    if (!b) return fail(MICONV_ERR_NULL, "%s is NULL", in_names[pass][1]);
+    if (!out) return fail(MICONV_ERR_NULL, "%s is NULL", out_names[pass]);
+    const int algo = choose_algo(pass, pr);
+    if (algo < 0)
+        return fail(MICONV_ERR_UNSUPPORTED, "forced algorithm %d cannot run this problem (pass %d)",
+                    g_forced[pass].load(), pass);
+    const size_t need = workspace_for(pass, algo, pr);
+    if (need > 0) {
+        if (!ws) return fail(MICONV_ERR_WORKSPACE, "workspace is NULL but %zu bytes are required", need);
+        if (ws_bytes < need) return fail(MICONV_ERR_WORKSPACE, "workspace has %zu bytes, %zu required", ws_bytes, need);
+        if (reinterpret_cast<uintptr_t>(ws) % 256)
+            return fail(MICONV_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    hipError_t e = hipSuccess;
+    float* o = static_cast<float*>(out);
+    if (algo == MICONV_ALGO_DIRECT) {
+        if (pass == MICONV_PASS_FWD) e = miconv::direct_fwd(pr, a, b, o, st);
+        else if (pass == MICONV_PASS_BWD_DATA) e = miconv::direct_bwd_data(pr, a, b, o, st);
+        else e = miconv::direct_bwd_weight(pr, a, b, o, st);
+    } else if (algo == MICONV_ALGO_MFMA) {
+        e = miconv::mfma_run(pass, pr, a, b, o, ws, st);
+    } else {
+        e = miconv::depthwise_run(pass, pr, a, b, o, ws, st);
+    }
+    if (e != hipSuccess) return fail(MICONV_ERR_LAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
+    g_last_algo[pass] = algo;
+    return MICONV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv2d_fwd(const void* x, const void* w, void* y, int N, int C, int H, int W, int K, int R, int S, int stride_h,
+               int stride_w, int pad_h, int pad_w, int groups, int dtype, void* workspace, size_t workspace_bytes,
+               void* hip_stream) {
+    return run(MICONV_PASS_FWD, x, w, y, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype,
+               workspace, workspace_bytes, hip_stream);
+}
+
+int conv2d_bwd_data(const void* dy, const void* w, void* dx, int N, int C, int H, int W, int K, int R, int S,
+                    int stride_h, int stride_w, int pad_h, int pad_w, int groups, int dtype, void* workspace,
+                    size_t workspace_bytes, void* hip_stream) {
+    return run(MICONV_PASS_BWD_DATA, dy, w, dx, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype,
+               workspace, workspace_bytes, hip_stream);
+}
+
+int conv2d_bwd_weight(const void* x, const void* dy, void* dw, int N, int C, int H, int W, int K, int R, int S,
+                      int stride_h, int stride_w, int pad_h, int pad_w, int groups, int dtype, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+    return run(MICONV_PASS_BWD_WEIGHT, x, dy, dw, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,
+               dtype, workspace, workspace_bytes, hip_stream);
+}
+
+size_t conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int R, int S, int stride_h, int stride_w,
+                              int pad_h, int pad_w, int groups, int dtype) {
+    if (pass < 0 || pass > 2) return 0;
+    Problem pr;
+    if (make_problem(pr, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype) != MICONV_OK) return 0;
+    const int algo = choose_algo(pass, pr);
+    if (algo < 0) return 0;
+    return workspace_for(pass, algo, pr);
+}
+
+int miconv_set_algo(int pass, int algo) {
+    if (pass < 0 || pass > 2) return fail(MICONV_ERR_DTYPE, "unknown pass %d", pass);
+    if (algo < MICONV_ALGO_AUTO || algo > MICONV_ALGO_DEPTHWISE) return fail(MICONV_ERR_DTYPE, "unknown algorithm %d", algo);
+    g_forced[pass].store(algo, std::memory_order_relaxed);
+    return MICONV_OK;
+}
+
+int miconv_last_algo(int pass) {
+    if (pass < 0 || pass > 2) return MICONV_ALGO_AUTO;
+    return g_last_algo[pass];
+}
+
+const char* miconv_last_error(void) { return g_err; }
+
+}  // extern "C"

@@ -1,0 +1,44 @@
+// Internal declarations shared by the host dispatcher and the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace miconv {
+
+// A validated convolution problem (see include/miconv.h for the operator).
+struct Problem {
+    int N, C, H, W, K, R, S;
+    int sh, sw, ph, pw, groups;
+    int P, Q, Cg, Kg;
+    int dtype;  // 0 = fp32 inputs, 1 = bf16 inputs (fp32 accumulate and outputs)
+};
+
+// bf16 bit pattern -> float, exact.
+__device__ __forceinline__ float bf16_to_float(uint16_t b) {
+    return __uint_as_float(static_cast<uint32_t>(b) << 16);
+}
+__device__ __forceinline__ float load_elem(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_elem(const uint16_t* p, size_t i) { return bf16_to_float(p[i]); }
+
+// ---- direct kernels (direct.hip): any valid problem -------------------------------------
+hipError_t direct_fwd(const Problem& pr, const void* x, const void* w, float* y, hipStream_t st);
+hipError_t direct_bwd_data(const Problem& pr, const void* dy, const void* w, float* dx, hipStream_t st);
+hipError_t direct_bwd_weight(const Problem& pr, const void* x, const void* dy, float* dw, hipStream_t st);
+
+
+// ---- MFMA implicit-GEMM kernels (mfma_*.hip): dense and grouped layers ------------------
+// pass: 0 forward, 1 backward-data, 2 backward-weight.  a/b are the two inputs
+// of the pass in the order of the C ABI; out is y, dx or dw.
+bool mfma_supports(int pass, const Problem& pr);
+size_t mfma_workspace_bytes(int pass, const Problem& pr);
+hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws, hipStream_t st);
+
+// ---- depthwise kernels (depthwise.hip): groups == C == K, no MFMA ------------------------
+bool depthwise_supports(int pass, const Problem& pr);
+size_t depthwise_workspace_bytes(int pass, const Problem& pr);
+hipError_t depthwise_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws,
+                         hipStream_t st);
+
+}  // namespace miconv

@@ -31,14 +31,24 @@ class Layer:
     seed: int
     x_dist: str = "normal"   # "normal" -> N(0,1); "uniform" -> U[-1,1]
     note: str = ""
+    stride_w: int = -1       # -1: same as stride (which then is the vertical stride)
+    pad_w: int = -1          # -1: same as pad
+
+    @property
+    def strides(self) -> Tuple[int, int]:
+        return (self.stride, self.stride if self.stride_w < 0 else self.stride_w)
+
+    @property
+    def pads(self) -> Tuple[int, int]:
+        return (self.pad, self.pad if self.pad_w < 0 else self.pad_w)
 
     @property
     def P(self) -> int:
-        return (self.H + 2 * self.pad - self.R) // self.stride + 1
+        return (self.H + 2 * self.pads[0] - self.R) // self.strides[0] + 1
 
     @property
     def Q(self) -> int:
-        return (self.W + 2 * self.pad - self.S) // self.stride + 1
+        return (self.W + 2 * self.pads[1] - self.S) // self.strides[1] + 1
 
     @property
     def x_shape(self) -> Tuple[int, int, int, int]:
@@ -60,7 +70,7 @@ class Layer:
     def conv_args(self):
         """(N,C,H,W,K,R,S,stride_h,stride_w,pad_h,pad_w,groups)"""
         return (self.N, self.C, self.H, self.W, self.K, self.R, self.S,
-                self.stride, self.stride, self.pad, self.pad, self.groups)
+                self.strides[0], self.strides[1], self.pads[0], self.pads[1], self.groups)
 
 
 # seed = 16 * (index of the configuration group) + (index of the layer in it)
@@ -79,7 +89,10 @@ LAYERS: Dict[str, Layer] = {l.name: l for l in [
 
 
 def custom_layer(name, N, C, H, W, K, R, S, stride=1, pad=0, groups=1, seed=1234, x_dist="normal"):
-    return Layer(name, N, C, H, W, K, R, S, stride, pad, groups, seed, x_dist)
+    """stride and pad may be ints or (vertical, horizontal) pairs."""
+    sh, sw = (stride, -1) if isinstance(stride, int) else stride
+    ph, pw = (pad, -1) if isinstance(pad, int) else pad
+    return Layer(name, N, C, H, W, K, R, S, sh, ph, groups, seed, x_dist, "", sw, pw)
 
 
 def make_inputs(layer: Layer):

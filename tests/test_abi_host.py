@@ -1,0 +1,82 @@
+"""Host-only checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects invalid arguments before launching anything."""
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "miconv.h")
+
+
+@pytest.fixture(scope="module")
+def mc():
+    from paper_1912_01703_amd import binding
+    return binding
+
+
+def declared_symbols():
+    text = "\n".join(l for l in open(HEADER).read().splitlines() if not l.startswith("#define"))
+    return re.findall(r"MICONV_API\s+[\w\s\*]*?\b(\w+)\s*\(", text)
+
+
+def test_header_declares_the_three_passes():
+    names = declared_symbols()
+    for required in ("conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight", "conv2d_workspace_bytes"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol(mc):
+    for name in declared_symbols():
+        assert hasattr(mc._lib, name), name
+
+
+GOOD = dict(N=1, C=4, H=8, W=8, K=4, R=3, S=3, stride_h=1, stride_w=1, pad_h=1, pad_w=1, groups=1)
+
+
+def call(mc, fn, ptrs=(0, 0, 0), dtype=0, **over):
+    a = dict(GOOD)
+    a.update(over)
+    return fn(ptrs[0] or None, ptrs[1] or None, ptrs[2] or None, *a.values(), dtype, None, 0, check=False)
+
+
+@pytest.mark.parametrize("fname", ["conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight"])
+def test_invalid_arguments_are_rejected_without_launch(mc, fname):
+    fn = getattr(mc, fname)
+    assert call(mc, fn, N=0) == mc.ERR_SHAPE
+    assert call(mc, fn, R=0) == mc.ERR_SHAPE
+    assert call(mc, fn, stride_h=0) == mc.ERR_SHAPE
+    assert call(mc, fn, pad_w=-1) == mc.ERR_SHAPE
+    assert call(mc, fn, H=2, pad_h=0) == mc.ERR_SHAPE          # filter larger than the padded input
+    assert "larger" in mc.last_error()
+    assert call(mc, fn, groups=3) == mc.ERR_GROUPS
+    assert call(mc, fn, groups=0) == mc.ERR_GROUPS
+    assert call(mc, fn, dtype=7) == mc.ERR_DTYPE
+    assert call(mc, fn, N=1 << 20, C=1 << 10, H=64, W=64) == mc.ERR_SHAPE   # >= 2^31 elements
+    assert call(mc, fn) == mc.ERR_NULL                          # valid shape, NULL tensors
+    assert "NULL" in mc.last_error()
+    assert call(mc, fn, ptrs=(256, 0, 256)) == mc.ERR_NULL
+    assert call(mc, fn, ptrs=(256, 256, 0)) == mc.ERR_NULL
+
+
+def test_raises_with_message(mc):
+    with pytest.raises(mc.MiconvError) as ei:
+        mc.conv2d_fwd(None, None, None, 1, 3, 8, 8, 4, 3, 3, 1, 1, 1, 1, 2)
+    assert ei.value.code == mc.ERR_GROUPS and "groups" in str(ei.value)
+
+
+def test_algo_override_codes(mc):
+    assert mc.miconv_set_algo(0, 99) == mc.ERR_DTYPE
+    assert mc.miconv_set_algo(5, 0) == mc.ERR_DTYPE
+    assert mc.miconv_set_algo(0, mc.ALGO_DIRECT) == mc.OK
+    assert mc.conv2d_workspace_bytes(0, *GOOD.values()) == 0    # direct kernels need no workspace
+    assert mc.miconv_set_algo(0, mc.ALGO_DEPTHWISE) == mc.OK
+    assert call(mc, mc.conv2d_fwd, ptrs=(256, 256, 256)) == mc.ERR_UNSUPPORTED   # dense problem, depthwise forced
+    assert mc.miconv_set_algo(0, mc.ALGO_AUTO) == mc.OK
+    assert mc.miconv_last_algo(0) == mc.ALGO_AUTO               # nothing has run on this thread
+
+
+def test_workspace_query_is_zero_for_invalid_arguments(mc):
+    bad = dict(GOOD, groups=3)
+    assert mc.conv2d_workspace_bytes(2, *bad.values()) == 0
+    assert mc.conv2d_workspace_bytes(9, *GOOD.values()) == 0

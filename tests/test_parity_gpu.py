@@ -1,0 +1,103 @@
+"""GPU parity: every pass through the C ABI against the CPU oracle.
+
+Full tensors for the layers the oracle finishes in seconds; a seeded sample of
+outputs (always including corners, edges and interior points) for the two
+VGG-sized layers.  Bounds and the error measure are in parity_util.
+"""
+import numpy as np
+import pytest
+
+from paper_1912_01703_amd import workloads as wl
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+ODD = [
+    # name   N  C   H   W   K  R  S  stride   pad    groups
+    ("odd0", 2, 3, 7, 6, 4, 3, 3, (1, 1), (1, 1), 1),
+    ("odd1", 1, 4, 9, 8, 6, 3, 2, (2, 1), (0, 1), 2),
+    ("odd2", 2, 6, 8, 11, 6, 1, 3, (1, 3), (0, 2), 3),
+    ("odd3", 1, 2, 12, 12, 2, 5, 5, (2, 2), (2, 2), 2),
+    ("odd4", 2, 3, 13, 9, 5, 4, 3, (3, 2), (1, 0), 1),
+    ("odd5", 1, 8, 6, 6, 8, 3, 3, (1, 1), (1, 1), 8),
+    ("odd6", 3, 20, 17, 19, 36, 3, 3, (1, 1), (1, 1), 4),
+    ("odd7", 2, 5, 8, 8, 7, 3, 3, (3, 3), (0, 0), 1),     # rows/cols past the last window: dx == 0 there
+    ("odd8", 1, 2, 10, 7, 4, 3, 3, (1, 1), (3, 2), 1),    # padding wider than the filter reach
+    ("odd9", 5, 1, 1, 1, 3, 1, 1, (1, 1), (0, 0), 1),     # single pixel
+]
+
+
+def odd_layer(row, seed_off=0):
+    name, N, C, H, W, K, R, S, st, pd, g = row
+    return wl.custom_layer(name, N, C, H, W, K, R, S, st, pd, g, seed=1000 + seed_off)
+
+
+def test_tiny_config_auto():
+    errs = pu.check_layer_full(wl.LAYERS["1"])
+    assert set(errs) == set(pu.PASSES)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("row", ODD, ids=[r[0] for r in ODD])
+def test_odd_shapes_direct(row, dtype):
+    from paper_1912_01703_amd import binding as mc
+    pu.check_layer_full(odd_layer(row, ODD.index(row)), dtype, algo=mc.ALGO_DIRECT, expect_algo=mc.ALGO_DIRECT)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("row", ODD, ids=[r[0] for r in ODD])
+def test_odd_shapes_auto(row, dtype):
+    pu.check_layer_full(odd_layer(row, ODD.index(row)), dtype)
+
+
+@pytest.mark.parametrize("name", ["2a", "2b", "2c", "3", "5a", "5b"])
+def test_full_size_layers_fp32(name):
+    pu.check_layer_full(wl.LAYERS[name])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("name", ["4a", "4b"])
+def test_vgg_layers_sampled(name, dtype):
+    pu.check_layer_sampled(wl.LAYERS[name], dtype)
+
+
+def test_bwd_weight_is_bit_reproducible():
+    import torch
+    L = wl.LAYERS["2a"]
+    h = pu.prepare(L)
+    gr = pu.GpuRunner(L, h)
+    a = gr.run("bwd_weight").clone()
+    b = gr.run("bwd_weight")
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
+def test_inputs_are_not_modified():
+    import torch
+    L = odd_layer(ODD[6])
+    h = pu.prepare(L)
+    gr = pu.GpuRunner(L, h)
+    for p in pu.PASSES:
+        gr.run(p)
+    torch.cuda.synchronize()
+    assert np.array_equal(gr.x.cpu().numpy(), h["x"])
+    assert np.array_equal(gr.w.cpu().numpy(), h["w"])
+    assert np.array_equal(gr.dy.cpu().numpy(), h["dy"])
+
+
+def test_runs_on_a_side_stream():
+    import torch
+    from paper_1912_01703_amd import binding as mc
+    L = wl.LAYERS["1"]
+    h = pu.prepare(L)
+    gr = pu.GpuRunner(L, h)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        y = gr.run("fwd")
+    s.synchronize()
+    refv, den = pu.oracle_full(L, h, "fwd")
+    err, ok = pu.max_norm_err(y.cpu().numpy(), refv, den)
+    assert ok and err <= 1e-5
+    assert mc.miconv_last_algo(0) != mc.ALGO_AUTO
