@@ -35,6 +35,10 @@ bool mfma_supports(int pass, const Problem& pr);
 size_t mfma_workspace_bytes(int pass, const Problem& pr);
 hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws, hipStream_t st);
 
+// Tiled forward / stride-1 backward-data kernels (mfma_tile.hip).
+bool tile_supports(int pass, const Problem& pr);
+hipError_t tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, hipStream_t st);
+
 // ---- depthwise kernels (depthwise.hip): groups == C == K, no MFMA ------------------------
 bool depthwise_supports(int pass, const Problem& pr);
 size_t depthwise_workspace_bytes(int pass, const Problem& pr);

@@ -1,0 +1,294 @@
+// Forward and stride-1 backward-data convolution as an implicit GEMM on the
+// fp32 matrix cores (v_mfma_f32_16x16x4_f32), written for gfx950.
+//
+// Both passes are the same computation on different operands:
+//   dst[n, g*Fg+f, oh, ow] = sum_{c<Rg, r, s} src[n, g*Rg+c, oh*ST-pad_h+r, ow*ST-pad_w+s] * Wt(f,c,r,s)
+//   forward        src = x,  dst = y,  Wt(f,c,r,s) = w[g*Fg+f][c][r][s]
+//   backward-data  src = dy, dst = dx, Wt(f,c,r,s) = w[g*Rg+c][f][R-1-r][S-1-s], pad' = R-1-pad (stride 1)
+//
+// Decomposition.  A workgroup owns one image, one TH x TW rectangle of output
+// pixels and 16*WF filters, and walks the reduction channels in chunks of CK.
+//   * The source patch a chunk needs ((TH-1)*ST+R rows, (TW-1)*ST+S columns, CK
+//     channels, zero-filled outside the image) is gathered once into LDS with
+//     coalesced row reads; the R*S-fold reuse of every input value (the im2col
+//     expansion) only ever happens as LDS reads at a per-tap address offset.
+//   * Filter values go straight from global memory into registers in the MFMA
+//     A-operand layout (each wave owns 16 filters, so there is nothing to share).
+//   * MFMA roles: M = 16 filters, N = 16 output pixels, K = 4 reduction channels.
+//     Lane l holds A[f = l%16][k = l/16], B[k = l/16][pixel = l%16] and
+//     D[f = 4*(l/16)+v][pixel = l%16] in accumulator register v.
+//   * Global loads for chunk i+1 are issued before the MFMA work of chunk i and
+//     land in the other LDS buffer afterwards: one barrier per chunk.
+#include "common.h"
+
+namespace miconv {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct TileArgs {
+    const void* src;
+    const void* wgt;
+    float* dst;
+    int N, Csrc, IH, IW;   // source tensor [N][Csrc][IH][IW]
+    int Cdst, OH, OW;      // destination tensor [N][Cdst][OH][OW]
+    int Fg, Rg, groups;    // destination / reduction channels per group
+    int pad_h, pad_w;      // source row = oh*ST - pad_h + r
+    int tiles_h, tiles_w;  // spatial tiles per image
+    int fblocks;           // filter blocks per group
+    int units;             // N * groups * tiles_h * tiles_w
+};
+
+__device__ __forceinline__ float ldf(const float* p, int i) { return p[i]; }
+__device__ __forceinline__ float ldf(const uint16_t* p, int i) { return bf16_to_float(p[i]); }
+
+constexpr int pad_to_16_mod_32(int v) {
+    int r = v % 32;
+    return r <= 16 ? v + (16 - r) : v + (48 - r);
+}
+
+// T: element type of src and wgt (float, or uint16_t holding bf16).
+// R,S: filter size.  ST: stride.  TH,TW: output tile.  CK: channels per chunk (multiple of 4).
+// WF: waves along filters (16 filters each).  WP: waves along pixel blocks.  BWD: backward-data operand mapping.
+template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD>
+__global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
+    constexpr int NT = 64 * WF * WP;
+    constexpr int RS = R * S;
+    constexpr int PH = (TH - 1) * ST + R, PW = (TW - 1) * ST + S;
+    constexpr int PSZ = PH * PW;
+    constexpr int CS = pad_to_16_mod_32(PSZ);  // channel stride in LDS: lanes k and k+1 hit disjoint bank halves
+    constexpr int XE = CK * PSZ;
+    constexpr int XPT = (XE + NT - 1) / NT;
+    constexpr int NPX = TH * TW;
+    constexpr int NB = (NPX + 15) / 16;     // 16-pixel blocks in the tile
+    constexpr int NBW = (NB + WP - 1) / WP;  // blocks per wave
+    constexpr int KQ = CK / 4;              // channels per lane-quarter: lane group kk owns channels [kk*KQ, kk*KQ+KQ)
+    static_assert(CK % 4 == 0, "CK must be a multiple of the MFMA K dimension");
+
+    __shared__ float xs[2][CK * CS];
+
+    // ---- which unit of work -------------------------------------------------------------
+    // Consecutive workgroup ids land on different XCDs (8 of them, one L2 each).  All filter
+    // blocks of one (image, tile) are given ids that differ by multiples of 8 so that they share an L2.
+    const int b = blockIdx.x;
+    const int xcd = b & 7;
+    const int rest = b >> 3;
+    const int fblk = rest % a.fblocks;
+    const int unit = (rest / a.fblocks) * 8 + xcd;
+    if (unit >= a.units) return;
+    int u = unit;
+    const int tj = u % a.tiles_w; u /= a.tiles_w;
+    const int ti = u % a.tiles_h; u /= a.tiles_h;
+    const int g = u % a.groups;
+    const int n = u / a.groups;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wf = wave % WF, wp = wave / WF;
+    const int li = lane & 15, kk = lane >> 4;
+
+    const int oh0 = ti * TH, ow0 = tj * TW;
+    const int ih0 = oh0 * ST - a.pad_h, iw0 = ow0 * ST - a.pad_w;
+    const int plane = a.IH * a.IW;
+
+    const T* src = static_cast<const T*>(a.src) + (size_t)(n * a.Csrc + g * a.Rg) * plane;
+    const T* wgt = static_cast<const T*>(a.wgt);
+
+    // ---- per-thread gather plan for the source patch (same for every chunk) ---------------
+    int goff[XPT];   // offset inside the chunk's channels, or -1 where the patch lies outside the image
+    int loff[XPT];
+    int cch[XPT];    // channel within the chunk (the last chunk may be partial)
+#pragma unroll
+    for (int m = 0; m < XPT; ++m) {
+        const int e = tid + NT * m;
+        const int c = e / PSZ, rem = e - c * PSZ;
+        const int ph = rem / PW, pw = rem - ph * PW;
+        const int ih = ih0 + ph, iw = iw0 + pw;
+        const bool ok = (e < XE) && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
+        goff[m] = ok ? c * plane + ih * a.IW + iw : -1;
+        loff[m] = (e < XE) ? c * CS + rem : -1;
+        cch[m] = c;
+    }
+
+    // ---- per-lane filter addressing ---------------------------------------------------------
+    // This wave's 16 filters; lane li owns filter f, lane group kk owns KQ consecutive channels.
+    const int f = fblk * (16 * WF) + wf * 16 + li;
+    const bool f_ok = f < a.Fg;
+    // forward:  w[(g*Fg+f)][c][tap]       -> contiguous over (c, tap) for a fixed filter
+    // backward: w[(g*Rg+c)][f][RS-1-tap]  -> one run of RS values per reduction channel
+    const size_t wbase = BWD ? ((size_t)(g * a.Rg + kk * KQ) * a.Fg + (f_ok ? f : 0)) * RS
+                             : ((size_t)(g * a.Fg + (f_ok ? f : 0)) * a.Rg + kk * KQ) * RS;
+    const int wstep_k = BWD ? a.Fg * RS : RS;        // next reduction channel
+    const size_t wstep_chunk = (size_t)CK * wstep_k;  // next chunk
+
+    // ---- per-lane pixel offsets into the LDS patch -----------------------------------------
+    int pixoff[NBW];
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) {
+        int j = 16 * (wp + WP * i) + li;
+        if (j >= NPX) j = 0;  // padding lanes read a valid address; their results are never stored
+        const int th = j / TW, tw = j - th * TW;
+        pixoff[i] = kk * KQ * CS + th * ST * PW + tw * ST;
+    }
+
+    v4f acc[NBW];
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    float areg[RS][KQ];   // A operands of the chunk being computed
+    float anext[RS][KQ];  // ... of the chunk in flight
+    float xreg[XPT];
+
+    auto load_chunk = [&](int ch) {
+        const T* s = src + (size_t)ch * CK * plane;
+        const int left = a.Rg - ch * CK;  // reduction channels still to go (< CK only in the last chunk)
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) xreg[m] = (goff[m] >= 0 && cch[m] < left) ? ldf(s, goff[m]) : 0.f;
+        const T* wp_ = wgt + wbase + ch * wstep_chunk;
+#pragma unroll
+        for (int k4 = 0; k4 < KQ; ++k4)
+#pragma unroll
+            for (int t = 0; t < RS; ++t) {
+                const int gi = BWD ? k4 * wstep_k + (RS - 1 - t) : k4 * RS + t;
+                anext[t][k4] = (f_ok && kk * KQ + k4 < left) ? ldf(wp_, gi) : 0.f;
+            }
+    };
+    auto store_patch = [&](int buf) {
+#pragma unroll
+        for (int m = 0; m < XPT; ++m)
+            if (loff[m] >= 0) xs[buf][loff[m]] = xreg[m];
+    };
+    auto take_filters = [&]() {
+#pragma unroll
+        for (int t = 0; t < RS; ++t)
+#pragma unroll
+            for (int k4 = 0; k4 < KQ; ++k4) areg[t][k4] = anext[t][k4];
+    };
+
+    const int nchunks = (a.Rg + CK - 1) / CK;
+    load_chunk(0);
+    store_patch(0);
+    take_filters();
+    __syncthreads();
+
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const int cur = ch & 1;
+        const bool more = ch + 1 < nchunks;
+        if (more) load_chunk(ch + 1);
+
+        const float* xb = xs[cur];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int s = 0; s < S; ++s)
+#pragma unroll
+                for (int k4 = 0; k4 < KQ; ++k4) {
+                    const float av = areg[r * S + s][k4];
+#pragma unroll
+                    for (int i = 0; i < NBW; ++i) {
+                        if (NB % WP != 0 && i == NBW - 1 && wp + WP * i >= NB) continue;  // wave-uniform
+                        const float bv = xb[pixoff[i] + k4 * CS + r * PW + s];
+                        acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[i], 0, 0, 0);
+                    }
+                }
+
+        if (more) {
+            store_patch(cur ^ 1);
+            take_filters();
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: D[f = 4*kk+v][pixel = li] ---------------------------------------------------
+    const int fq = fblk * (16 * WF) + wf * 16 + 4 * kk;
+    float* dst = a.dst + (size_t)(n * a.Cdst + g * a.Fg) * a.OH * a.OW;
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) {
+        const int j = 16 * (wp + WP * i) + li;
+        if (j >= NPX) continue;
+        const int th = j / TW, tw = j - th * TW;
+        const int oh = oh0 + th, ow = ow0 + tw;
+        if (oh >= a.OH || ow >= a.OW) continue;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (fq + v < a.Fg) dst[(size_t)(fq + v) * a.OH * a.OW + oh * a.OW + ow] = acc[i][v];
+    }
+}
+
+template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD>
+hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
+    TileArgs a = base;
+    a.tiles_h = (a.OH + TH - 1) / TH;
+    a.tiles_w = (a.OW + TW - 1) / TW;
+    a.fblocks = (a.Fg + 16 * WF - 1) / (16 * WF);
+    a.units = a.N * a.groups * a.tiles_h * a.tiles_w;
+    const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
+    conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD><<<grid, 64 * WF * WP, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+// Picks the instantiation for a filter size / stride.  Returns false when none fits.
+template <typename T, bool BWD>
+bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, bool dry, hipError_t* err) {
+    *err = hipSuccess;
+    if (R == 3 && S == 3 && stride == 1) {
+        if (!dry) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 1, BWD>(a, st);
+        return true;
+    }
+    if (R == 1 && S == 1 && stride == 1) {
+        if (!dry) *err = launch_tile<T, 1, 1, 1, 14, 14, 16, 4, 1, BWD>(a, st);
+        return true;
+    }
+    if (!BWD && R == 3 && S == 3 && stride == 2) {
+        if (!dry) *err = launch_tile<T, 3, 3, 2, 14, 14, 8, 4, 1, false>(a, st);
+        return true;
+    }
+    return false;
+}
+
+// Builds the operand view of a pass; false when the tiled kernel cannot run it.
+bool make_args(int pass, const Problem& pr, const void* in0, const void* in1, float* out, TileArgs& a, int& stride) {
+    if (pr.sh != pr.sw) return false;
+    if (pass == 0) {
+        a = TileArgs{in0, in1, out, pr.N, pr.C, pr.H, pr.W, pr.K, pr.P, pr.Q, pr.Kg, pr.Cg, pr.groups,
+                     pr.ph, pr.pw, 0, 0, 0, 0};
+        stride = pr.sh;
+        return true;
+    }
+    if (pass == 1) {
+        if (pr.sh != 1) return false;
+        a = TileArgs{in0, in1, out, pr.N, pr.K, pr.P, pr.Q, pr.C, pr.H, pr.W, pr.Cg, pr.Kg, pr.groups,
+                     pr.R - 1 - pr.ph, pr.S - 1 - pr.pw, 0, 0, 0, 0};
+        stride = 1;
+        return true;
+    }
+    return false;
+}
+
+}  // namespace
+
+bool tile_supports(int pass, const Problem& pr) {
+    TileArgs a;
+    int stride;
+    hipError_t e;
+    if (!make_args(pass, pr, nullptr, nullptr, nullptr, a, stride)) return false;
+    return pass == 0 ? dispatch_tile<float, false>(pr.R, pr.S, stride, a, nullptr, true, &e)
+                     : dispatch_tile<float, true>(pr.R, pr.S, stride, a, nullptr, true, &e);
+}
+
+hipError_t tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, hipStream_t st) {
+    TileArgs a;
+    int stride;
+    hipError_t e = hipErrorNotSupported;
+    if (!make_args(pass, pr, in0, in1, out, a, stride)) return e;
+    bool ok;
+    if (pr.dtype == 0)
+        ok = pass == 0 ? dispatch_tile<float, false>(pr.R, pr.S, stride, a, st, false, &e)
+                       : dispatch_tile<float, true>(pr.R, pr.S, stride, a, st, false, &e);
+    else
+        ok = pass == 0 ? dispatch_tile<uint16_t, false>(pr.R, pr.S, stride, a, st, false, &e)
+                       : dispatch_tile<uint16_t, true>(pr.R, pr.S, stride, a, st, false, &e);
+    return ok ? e : hipErrorNotSupported;
+}
+
+}  // namespace miconv

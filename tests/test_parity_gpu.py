@@ -51,6 +51,32 @@ def test_odd_shapes_auto(row, dtype):
     pu.check_layer_full(odd_layer(row, ODD.index(row)), dtype)
 
 
+MFMA = [
+    # name     N   C   H   W   K  R  S  stride  pad   groups
+    ("m3x3a", 2, 32, 14, 14, 64, 3, 3, 1, 1, 1),
+    ("m3x3b", 3, 16, 17, 19, 40, 3, 3, 1, 1, 1),      # ragged tiles, K not a multiple of 16
+    ("m3x3c", 2, 32, 9, 30, 24, 3, 3, 1, 0, 1),       # no padding
+    ("m3x3d", 1, 48, 15, 15, 16, 3, 3, 1, 2, 1),      # padding 2: backward-data sees pad' = 0
+    ("m3x3g", 2, 64, 14, 14, 96, 3, 3, 1, 1, 2),      # two groups
+    ("m1x1a", 2, 48, 14, 14, 80, 1, 1, 1, 0, 1),
+    ("m1x1b", 1, 128, 7, 29, 33, 1, 1, 1, 0, 1),
+    ("m3x3t", 2, 3, 20, 20, 10, 3, 3, 1, 1, 1),       # reduction channels not a multiple of the chunk
+    ("m3x3u", 2, 21, 14, 14, 35, 3, 3, 1, 1, 1),
+    ("m3x3s2", 2, 32, 28, 28, 32, 3, 3, 2, 1, 1),     # forward only on the tiled kernel
+    ("m3x3s2b", 1, 16, 31, 27, 20, 3, 3, 2, 1, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("row", MFMA, ids=[r[0] for r in MFMA])
+def test_mfma_shapes(row, dtype):
+    from paper_1912_01703_amd import binding as mc
+    name, N, C, H, W, K, R, S, st, pd, g = row
+    L = wl.custom_layer(name, N, C, H, W, K, R, S, st, pd, g, seed=2000 + MFMA.index(row))
+    passes = ("fwd",) if st != 1 else ("fwd", "bwd_data")
+    pu.check_layer_full(L, dtype, passes=passes, algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+
+
 @pytest.mark.parametrize("name", ["2a", "2b", "2c", "3", "5a", "5b"])
 def test_full_size_layers_fp32(name):
     pu.check_layer_full(wl.LAYERS[name])
