@@ -39,6 +39,10 @@ hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, f
 bool tile_supports(int pass, const Problem& pr);
 hipError_t tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, hipStream_t st);
 
+// Backward-weight kernels (mfma_wgrad.hip).  ws_bytes receives the partial-sum buffer size.
+bool wgrad_supports(const Problem& pr, size_t* ws_bytes);
+hipError_t wgrad_run(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st);
+
 // ---- depthwise kernels (depthwise.hip): groups == C == K, no MFMA ------------------------
 bool depthwise_supports(int pass, const Problem& pr);
 size_t depthwise_workspace_bytes(int pass, const Problem& pr);

@@ -2,17 +2,24 @@
 #include "common.h"
 namespace miconv {
 
+static bool is_depthwise(const Problem& pr) { return pr.groups == pr.C && pr.groups == pr.K && pr.groups > 1; }
+
 bool mfma_supports(int pass, const Problem& pr) {
-    if (pr.groups == pr.C && pr.groups == pr.K && pr.groups > 1) return false;  // depthwise: no contraction to speak of
+    if (is_depthwise(pr)) return false;  // one input channel per filter: nothing to contract
     if (pass == 0 || pass == 1) return tile_supports(pass, pr);
-    return false;
+    size_t ws;
+    return wgrad_supports(pr, &ws);
 }
 
-size_t mfma_workspace_bytes(int, const Problem&) { return 0; }
+size_t mfma_workspace_bytes(int pass, const Problem& pr) {
+    size_t ws = 0;
+    if (pass == 2 && !is_depthwise(pr)) wgrad_supports(pr, &ws);
+    return ws;
+}
 
-hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void*, hipStream_t st) {
+hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws, hipStream_t st) {
     if (pass == 0 || pass == 1) return tile_run(pass, pr, a, b, out, st);
-    return hipErrorNotSupported;
+    return wgrad_run(pr, a, b, out, ws, st);
 }
 
 }  // namespace miconv

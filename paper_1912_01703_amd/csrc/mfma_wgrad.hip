@@ -1,0 +1,318 @@
+// Backward-weight convolution on the fp32 matrix cores (v_mfma_f32_16x16x4_f32), gfx950.
+//
+//   dw[k,c,r,s] = sum_{n,p,q} dy[n,k,p,q] * x[n, g*Cg+c, p*ST-pad_h+r, q*ST-pad_w+s]
+//
+// As a GEMM the output is Kg x (Cg*R*S) and the reduction runs over all N*P*Q
+// output pixels.  MFMA roles: M = 16 output channels k (A from dy), N = 16 input
+// channels c (B from x), K = 4 output pixels; one accumulator block per filter tap.
+//
+// Decomposition.  A workgroup owns 16*KB output channels x 16*CB input channels
+// (all R*S taps) of one group and a contiguous share ("split") of the stages; a
+// stage is one image and one TH x TW rectangle of output pixels.  Per stage the
+// dy tile and the x patch under it (zero-filled outside the image) are gathered
+// into LDS with coalesced row reads; the tap shift is an LDS address offset, so
+// every x value is read from global memory once per stage and reused R*S times.
+// Waves are arranged WK x WC x WS: WK and WC divide the accumulator blocks, WS
+// divides the pixel steps of a stage.  Stage i+1 is fetched into registers while
+// stage i is multiplied and is written to the other LDS buffer afterwards.
+// At the end the WS partial accumulators are summed through LDS in a fixed order
+// and written with coalesced stores, either to dw (one split) or to a partial
+// buffer that reduce_splits_kernel sums in split order: no floating-point
+// atomics anywhere, so dw is bit-reproducible.
+#include "common.h"
+
+namespace miconv {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+struct WgradArgs {
+    const void* x;
+    const void* dy;
+    float* out;        // dw, or the partial buffer [nsplit][K*Cg*R*S]
+    int N, C, H, W, K, P, Q;
+    int Cg, Kg, groups;
+    int pad_h, pad_w;
+    int tiles_h, tiles_w;
+    int kblocks, cblocks;  // per group
+    int nsplit, stages;    // stages = tiles_h*tiles_w*N, ordered tile-major
+    int total_wgs;
+};
+
+__device__ __forceinline__ float ldg(const float* p, int i) { return p[i]; }
+__device__ __forceinline__ float ldg(const uint16_t* p, int i) { return bf16_to_float(p[i]); }
+
+constexpr int next_2_mod_4(int v) { return v + ((6 - v % 4) % 4); }   // smallest >= v that is 2 mod 4
+constexpr int next_odd(int v) { return v | 1; }
+constexpr int cmax(int a, int b) { return a > b ? a : b; }
+
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS>
+__global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
+    constexpr int NT = 64 * WK * WC * WS;
+    constexpr int RS = R * S;
+    constexpr int PH = (TH - 1) * ST + R, PW = (TW - 1) * ST + S, PSZ = PH * PW;
+    constexpr int NPX = TH * TW;
+    static_assert(NPX % 4 == 0, "tile pixels must fill whole MFMA steps");
+    static_assert(KB % WK == 0 && CB % WC == 0, "wave grid must divide the block grid");
+    constexpr int NSTEPS = NPX / 4;
+    constexpr int KBW = KB / WK, CBW = CB / WC;
+    // LDS row strides: 16 lanes x 2 adjacent pixels must fall in 32 distinct banks.
+    constexpr int DS = next_2_mod_4(NPX);
+    constexpr int XS = ST == 1 ? next_2_mod_4(PSZ) : next_odd(PSZ);
+    constexpr int YE = 16 * KB * NPX, XE = 16 * CB * PSZ;
+    constexpr int YPT = (YE + NT - 1) / NT, XPT = (XE + NT - 1) / NT;
+    constexpr int STAGE = 16 * KB * DS + 16 * CB * XS;   // floats per LDS buffer
+    constexpr int OUTSZ = 16 * KB * 16 * CB * RS;        // accumulator elements of the workgroup
+    constexpr int LDSF = cmax(2 * STAGE, WS * OUTSZ);
+    static_assert(LDSF * 4 <= 160 * 1024, "LDS budget");
+
+    __shared__ float lds[LDSF];
+
+    // ---- which output block / split ----------------------------------------------------------
+    // Workgroup ids are dealt round-robin to the 8 XCDs; giving each XCD a contiguous run of
+    // block ids makes the blocks that share dy tiles and x patches share an L2.
+    const int per_xcd = (a.total_wgs + 7) / 8;
+    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (L >= a.total_wgs) return;
+    int u = L;
+    const int cbi = u % a.cblocks; u /= a.cblocks;
+    const int kbi = u % a.kblocks; u /= a.kblocks;
+    const int g = u % a.groups;
+    const int sp = u / a.groups;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15, kk = lane >> 4;
+    const int wk = wave % WK, wc = (wave / WK) % WC, ws = wave / (WK * WC);
+
+    const int k0 = kbi * 16 * KB, c0 = cbi * 16 * CB;   // within the group
+    const int s_begin = (int)((long long)a.stages * sp / a.nsplit);
+    const int s_end = (int)((long long)a.stages * (sp + 1) / a.nsplit);
+
+    const T* xg = static_cast<const T*>(a.x);
+    const T* dyg = static_cast<const T*>(a.dy);
+    const int xplane = a.H * a.W, yplane = a.P * a.Q;
+
+    // ---- gather plans (depend on the tile position only) -----------------------------------------
+    int ygo[YPT], xgo[XPT];   // global offsets relative to the stage's image, -1 = store zero
+    auto plan = [&](int tile) {
+        const int ti = tile / a.tiles_w, tj = tile - ti * a.tiles_w;
+        const int p0 = ti * TH, q0 = tj * TW;
+        const int h0 = p0 * ST - a.pad_h, v0 = q0 * ST - a.pad_w;
+#pragma unroll
+        for (int m = 0; m < YPT; ++m) {
+            const int e = tid + NT * m;
+            const int kl = e / NPX, px = e - kl * NPX;
+            const int th = px / TW, tw = px - th * TW;
+            const int p = p0 + th, q = q0 + tw;
+            const bool ok = e < YE && k0 + kl < a.Kg && p < a.P && q < a.Q;
+            ygo[m] = ok ? (g * a.Kg + k0 + kl) * yplane + p * a.Q + q : -1;
+        }
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) {
+            const int e = tid + NT * m;
+            const int cl = e / PSZ, rem = e - cl * PSZ;
+            const int ph = rem / PW, pw = rem - ph * PW;
+            const int h = h0 + ph, v = v0 + pw;
+            const bool ok = e < XE && c0 + cl < a.Cg && h >= 0 && h < a.H && v >= 0 && v < a.W;
+            xgo[m] = ok ? (g * a.Cg + c0 + cl) * xplane + h * a.W + v : -1;
+        }
+    };
+
+    float yreg[YPT], xreg[XPT];
+    auto fetch = [&](int stage) {
+        const int n = stage % a.N;
+        const T* yb = dyg + (size_t)n * a.K * yplane;
+        const T* xb = xg + (size_t)n * a.C * xplane;
+#pragma unroll
+        for (int m = 0; m < YPT; ++m) yreg[m] = ygo[m] >= 0 ? ldg(yb, ygo[m]) : 0.f;
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) xreg[m] = xgo[m] >= 0 ? ldg(xb, xgo[m]) : 0.f;
+    };
+    auto stash = [&](int buf) {
+        float* ys = lds + buf * STAGE;
+        float* xs = ys + 16 * KB * DS;
+#pragma unroll
+        for (int m = 0; m < YPT; ++m) {
+            const int e = tid + NT * m;
+            const int kl = e / NPX, px = e - kl * NPX;
+            if (e < YE) ys[kl * DS + px] = yreg[m];
+        }
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) {
+            const int e = tid + NT * m;
+            const int cl = e / PSZ, rem = e - cl * PSZ;
+            if (e < XE) xs[cl * XS + rem] = xreg[m];
+        }
+    };
+
+    v4f acc[KBW][CBW][RS];
+#pragma unroll
+    for (int i = 0; i < KBW; ++i)
+#pragma unroll
+        for (int j = 0; j < CBW; ++j)
+#pragma unroll
+            for (int t = 0; t < RS; ++t) acc[i][j][t] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    if (s_begin < s_end) {
+        int tile = s_begin / a.N;
+        plan(tile);
+        fetch(s_begin);
+        stash(0);
+        __syncthreads();
+        int buf = 0;
+        for (int stage = s_begin; stage < s_end; ++stage) {
+            const bool more = stage + 1 < s_end;
+            if (more) {
+                const int nt = (stage + 1) / a.N;
+                if (nt != tile) { tile = nt; plan(tile); }
+                fetch(stage + 1);
+            }
+            const float* ys = lds + buf * STAGE + (16 * (wk * KBW) + li) * DS;
+            const float* xs = lds + buf * STAGE + 16 * KB * DS + (16 * (wc * CBW) + li) * XS;
+#pragma unroll 2
+            for (int t = ws; t < NSTEPS; t += WS) {
+                const int px = 4 * t + kk;
+                const int th = px / TW, tw = px - th * TW;
+                const int xo = th * ST * PW + tw * ST;
+                float av[KBW];
+#pragma unroll
+                for (int i = 0; i < KBW; ++i) av[i] = ys[i * 16 * DS + px];
+#pragma unroll
+                for (int j = 0; j < CBW; ++j)
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int s = 0; s < S; ++s) {
+                            const float bv = xs[j * 16 * XS + xo + r * PW + s];
+#pragma unroll
+                            for (int i = 0; i < KBW; ++i)
+                                acc[i][j][r * S + s] =
+                                    __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv, acc[i][j][r * S + s], 0, 0, 0);
+                        }
+            }
+            if (more) stash(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+
+    // ---- combine the WS pixel-step shares and write out ---------------------------------------------
+    // LDS layout of one share: [k local][c local][tap], i.e. the order of dw within the block.
+    __syncthreads();
+    constexpr int ROW = 16 * CB * RS;
+#pragma unroll
+    for (int i = 0; i < KBW; ++i)
+#pragma unroll
+        for (int j = 0; j < CBW; ++j)
+#pragma unroll
+            for (int t = 0; t < RS; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int kl = 16 * (wk * KBW + i) + 4 * kk + v;
+                    const int cl = 16 * (wc * CBW + j) + li;
+                    lds[ws * OUTSZ + kl * ROW + cl * RS + t] = acc[i][j][t][v];
+                }
+    __syncthreads();
+    const size_t wsize = (size_t)a.K * a.Cg * RS;
+    float* out = a.out + (a.nsplit > 1 ? (size_t)sp * wsize : 0);
+    for (int o = tid; o < OUTSZ; o += NT) {
+        const int kl = o / ROW, rem = o - kl * ROW;
+        const int cl = rem / RS;
+        if (k0 + kl >= a.Kg || c0 + cl >= a.Cg) continue;
+        float sum = lds[o];
+#pragma unroll
+        for (int w = 1; w < WS; ++w) sum += lds[w * OUTSZ + o];
+        out[((size_t)(g * a.Kg + k0 + kl) * a.Cg + c0) * RS + rem] = sum;
+    }
+}
+
+__global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                            int nsplit, size_t count) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    float sum = part[i];
+    for (int s = 1; s < nsplit; ++s) sum += part[(size_t)s * count + i];
+    dw[i] = sum;
+}
+
+struct Plan {
+    int nsplit;
+    size_t ws_bytes;
+};
+
+template <int TH, int TW, int KB, int CB>
+Plan make_plan(const Problem& pr, WgradArgs& a) {
+    a.tiles_h = (pr.P + TH - 1) / TH;
+    a.tiles_w = (pr.Q + TW - 1) / TW;
+    a.kblocks = (pr.Kg + 16 * KB - 1) / (16 * KB);
+    a.cblocks = (pr.Cg + 16 * CB - 1) / (16 * CB);
+    a.stages = a.tiles_h * a.tiles_w * pr.N;
+    const int blocks = a.kblocks * a.cblocks * pr.groups;
+    // Enough workgroups to cover the 256 CUs, but never more partial buffers than stages.
+    int nsplit = (256 + blocks - 1) / blocks;
+    if (nsplit > a.stages) nsplit = a.stages;
+    if (nsplit < 1) nsplit = 1;
+    a.nsplit = nsplit;
+    a.total_wgs = blocks * nsplit;
+    const size_t wbytes = (size_t)pr.K * pr.Cg * pr.R * pr.S * sizeof(float);
+    return Plan{nsplit, nsplit > 1 ? nsplit * wbytes : 0};
+}
+
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS>
+hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st,
+                        bool dry, size_t* ws_bytes) {
+    WgradArgs a{};
+    a.x = x; a.dy = dy;
+    a.N = pr.N; a.C = pr.C; a.H = pr.H; a.W = pr.W; a.K = pr.K; a.P = pr.P; a.Q = pr.Q;
+    a.Cg = pr.Cg; a.Kg = pr.Kg; a.groups = pr.groups; a.pad_h = pr.ph; a.pad_w = pr.pw;
+    const Plan pl = make_plan<TH, TW, KB, CB>(pr, a);
+    *ws_bytes = pl.ws_bytes;
+    if (dry) return hipSuccess;
+    a.out = pl.nsplit > 1 ? static_cast<float*>(ws) : dw;
+    const int grid = ((a.total_wgs + 7) / 8) * 8;
+    wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || pl.nsplit == 1) return e;
+    const size_t count = (size_t)pr.K * pr.Cg * pr.R * pr.S;
+    reduce_splits_kernel<<<(unsigned)((count + 255) / 256), 256, 0, st>>>(static_cast<const float*>(ws), dw,
+                                                                          pl.nsplit, count);
+    return hipGetLastError();
+}
+
+template <typename T>
+bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st, bool dry,
+                    size_t* ws_bytes, hipError_t* err) {
+    *err = hipSuccess;
+    *ws_bytes = 0;
+    if (pr.sh != pr.sw) return false;
+    if (pr.R == 3 && pr.S == 3 && pr.sh == 1) {
+        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 4>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        return true;
+    }
+    if (pr.R == 3 && pr.S == 3 && pr.sh == 2) {
+        *err = launch_wgrad<T, 3, 3, 2, 14, 14, 1, 1, 1, 1, 4>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        return true;
+    }
+    if (pr.R == 1 && pr.S == 1 && pr.sh == 1) {
+        *err = launch_wgrad<T, 1, 1, 1, 2, 14, 8, 8, 2, 2, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        return true;
+    }
+    return false;
+}
+
+}  // namespace
+
+bool wgrad_supports(const Problem& pr, size_t* ws_bytes) {
+    hipError_t e;
+    return dispatch_wgrad<float>(pr, nullptr, nullptr, nullptr, nullptr, nullptr, true, ws_bytes, &e);
+}
+
+hipError_t wgrad_run(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st) {
+    hipError_t e = hipErrorNotSupported;
+    size_t bytes;
+    const bool ok = pr.dtype == 0 ? dispatch_wgrad<float>(pr, x, dy, dw, ws, st, false, &bytes, &e)
+                                  : dispatch_wgrad<uint16_t>(pr, x, dy, dw, ws, st, false, &bytes, &e);
+    return ok ? e : hipErrorNotSupported;
+}
+
+}  // namespace miconv

@@ -62,7 +62,9 @@ MFMA = [
     ("m1x1b", 1, 128, 7, 29, 33, 1, 1, 1, 0, 1),
     ("m3x3t", 2, 3, 20, 20, 10, 3, 3, 1, 1, 1),       # reduction channels not a multiple of the chunk
     ("m3x3u", 2, 21, 14, 14, 35, 3, 3, 1, 1, 1),
-    ("m3x3s2", 2, 32, 28, 28, 32, 3, 3, 2, 1, 1),     # forward only on the tiled kernel
+    ("m1x1c", 3, 200, 14, 14, 136, 1, 1, 1, 0, 1),    # several 128-wide blocks with ragged edges
+    ("m3x3n", 9, 16, 14, 14, 16, 3, 3, 1, 1, 1),      # more images than one split holds
+    ("m3x3s2", 2, 32, 28, 28, 32, 3, 3, 2, 1, 1),     # stride 2: backward-data is not on this path
     ("m3x3s2b", 1, 16, 31, 27, 20, 3, 3, 2, 1, 1),
 ]
 
@@ -73,7 +75,7 @@ def test_mfma_shapes(row, dtype):
     from paper_1912_01703_amd import binding as mc
     name, N, C, H, W, K, R, S, st, pd, g = row
     L = wl.custom_layer(name, N, C, H, W, K, R, S, st, pd, g, seed=2000 + MFMA.index(row))
-    passes = ("fwd",) if st != 1 else ("fwd", "bwd_data")
+    passes = ("fwd", "bwd_weight") if st != 1 else pu.PASSES
     pu.check_layer_full(L, dtype, passes=passes, algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
 
 
