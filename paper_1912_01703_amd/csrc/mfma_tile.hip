@@ -37,18 +37,35 @@ struct TileArgs {
     int tiles_h, tiles_w;  // spatial tiles per image
     int fblocks;           // filter blocks per group
     int units;             // N * groups * tiles_h * tiles_w
+    int wvec;              // forward filters may be read four at a time (Rg is a multiple of 4)
+    unsigned wgt_bytes;    // size of the filter tensor
 };
 
-__device__ __forceinline__ float ldf(const float* p, int i) { return p[i]; }
-__device__ __forceinline__ float ldf(const uint16_t* p, int i) { return bf16_to_float(p[i]); }
+// Buffer loads: the hardware compares the byte offset with the descriptor's size and returns 0
+// beyond it, so an element that must read as zero (outside the image, past the last channel, an
+// absent filter) is given the offset kOob and costs neither a branch nor a select on the result.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+constexpr unsigned kOob = 0x80000000u;  // tensors handled here are smaller than 2 GiB
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const float*) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0));
+}
+__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const uint16_t*) {
+    return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_raw_buffer_load_b16(r, byte_off, 0, 0)) << 16);
+}
 
-constexpr int pad_to_16_mod_32(int v) {
-    int r = v % 32;
-    return r <= 16 ? v + (16 - r) : v + (48 - r);
+// Smallest channel stride >= v such that kq consecutive channels span 16 banks (mod 32): the two
+// lane groups of a half-wave, which are kq channels apart, then read disjoint halves of the 32 LDS banks.
+constexpr int lds_channel_stride(int v, int kq) {
+    while ((v * kq) % 32 != 16) ++v;
+    return v;
 }
 
 // T: element type of src and wgt (float, or uint16_t holding bf16).
-// R,S: filter size.  ST: stride.  TH,TW: output tile.  CK: channels per chunk (multiple of 4).
+// R,S: filter size.  ST: stride.  TH,TW: output tile.  CK: channels per chunk (4, 8, 16 or 32).
 // WF: waves along filters (16 filters each).  WP: waves along pixel blocks.  BWD: backward-data operand mapping.
 template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD>
 __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
@@ -56,14 +73,14 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int RS = R * S;
     constexpr int PH = (TH - 1) * ST + R, PW = (TW - 1) * ST + S;
     constexpr int PSZ = PH * PW;
-    constexpr int CS = pad_to_16_mod_32(PSZ);  // channel stride in LDS: lanes k and k+1 hit disjoint bank halves
+    constexpr int KQ = CK / 4;  // channels per lane group: lane group kk owns channels [kk*KQ, kk*KQ+KQ) of a chunk
+    static_assert(CK == 4 || CK == 8 || CK == 16 || CK == 32, "CK must be 4, 8, 16 or 32");
+    constexpr int CS = lds_channel_stride(PSZ, KQ);
     constexpr int XE = CK * PSZ;
     constexpr int XPT = (XE + NT - 1) / NT;
     constexpr int NPX = TH * TW;
-    constexpr int NB = (NPX + 15) / 16;     // 16-pixel blocks in the tile
+    constexpr int NB = (NPX + 15) / 16;      // 16-pixel blocks in the tile
     constexpr int NBW = (NB + WP - 1) / WP;  // blocks per wave
-    constexpr int KQ = CK / 4;              // channels per lane-quarter: lane group kk owns channels [kk*KQ, kk*KQ+KQ)
-    static_assert(CK % 4 == 0, "CK must be a multiple of the MFMA K dimension");
 
     __shared__ float xs[2][CK * CS];
 
@@ -92,12 +109,12 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     const int plane = a.IH * a.IW;
 
     const T* src = static_cast<const T*>(a.src) + (size_t)(n * a.Csrc + g * a.Rg) * plane;
-    const T* wgt = static_cast<const T*>(a.wgt);
+    const T* const tnull = nullptr;
+    const rsrc_t wrs = make_rsrc(a.wgt, a.wgt_bytes);
 
     // ---- per-thread gather plan for the source patch (same for every chunk) ---------------
-    int goff[XPT];   // offset inside the chunk's channels, or -1 where the patch lies outside the image
+    unsigned goff[XPT];  // byte offset inside the chunk's channels, kOob where the patch lies outside the image
     int loff[XPT];
-    int cch[XPT];    // channel within the chunk (the last chunk may be partial)
 #pragma unroll
     for (int m = 0; m < XPT; ++m) {
         const int e = tid + NT * m;
@@ -105,9 +122,8 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         const int ph = rem / PW, pw = rem - ph * PW;
         const int ih = ih0 + ph, iw = iw0 + pw;
         const bool ok = (e < XE) && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
-        goff[m] = ok ? c * plane + ih * a.IW + iw : -1;
+        goff[m] = ok ? (unsigned)(c * plane + ih * a.IW + iw) * (unsigned)sizeof(T) : kOob;
         loff[m] = (e < XE) ? c * CS + rem : -1;
-        cch[m] = c;
     }
 
     // ---- per-lane filter addressing ---------------------------------------------------------
@@ -116,10 +132,10 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     const bool f_ok = f < a.Fg;
     // forward:  w[(g*Fg+f)][c][tap]       -> contiguous over (c, tap) for a fixed filter
     // backward: w[(g*Rg+c)][f][RS-1-tap]  -> one run of RS values per reduction channel
-    const size_t wbase = BWD ? ((size_t)(g * a.Rg + kk * KQ) * a.Fg + (f_ok ? f : 0)) * RS
-                             : ((size_t)(g * a.Fg + (f_ok ? f : 0)) * a.Rg + kk * KQ) * RS;
-    const int wstep_k = BWD ? a.Fg * RS : RS;        // next reduction channel
-    const size_t wstep_chunk = (size_t)CK * wstep_k;  // next chunk
+    const int wbase = BWD ? ((g * a.Rg + kk * KQ) * a.Fg + (f_ok ? f : 0)) * RS
+                          : ((g * a.Fg + (f_ok ? f : 0)) * a.Rg + kk * KQ) * RS;
+    const int wstep_k = BWD ? a.Fg * RS : RS;  // next reduction channel
+    const int wstep_chunk = CK * wstep_k;      // next chunk
 
     // ---- per-lane pixel offsets into the LDS patch -----------------------------------------
     int pixoff[NBW];
@@ -135,67 +151,93 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 #pragma unroll
     for (int i = 0; i < NBW; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    float areg[RS][KQ];   // A operands of the chunk being computed
-    float anext[RS][KQ];  // ... of the chunk in flight
     float xreg[XPT];
 
-    auto load_chunk = [&](int ch) {
-        const T* s = src + (size_t)ch * CK * plane;
+    // The chunk's descriptor covers exactly the channels it still has, so a partial last chunk
+    // reads zeros for the channels past the end without any per-element test.
+    auto load_chunk = [&](int ch, float (&an)[RS * KQ]) {
         const int left = a.Rg - ch * CK;  // reduction channels still to go (< CK only in the last chunk)
+        const rsrc_t xrs = make_rsrc(src + (size_t)ch * CK * plane,
+                                     (unsigned)((left < CK ? left : CK) * plane) * (unsigned)sizeof(T));
 #pragma unroll
-        for (int m = 0; m < XPT; ++m) xreg[m] = (goff[m] >= 0 && cch[m] < left) ? ldf(s, goff[m]) : 0.f;
-        const T* wp_ = wgt + wbase + ch * wstep_chunk;
+        for (int m = 0; m < XPT; ++m) xreg[m] = buf_load(xrs, goff[m], tnull);
+        const int wb = wbase + ch * wstep_chunk;
+        if constexpr (!BWD && sizeof(T) == 4 && (RS * KQ) % 4 == 0) {
+            if (a.wvec) {
+                // The lane's KQ channels x RS taps are RS*KQ consecutive floats (Rg is a multiple of KQ,
+                // so they are all present or all absent).
+                const unsigned vo = (f_ok && kk * KQ < left) ? (unsigned)wb * 4u : kOob;
 #pragma unroll
-        for (int k4 = 0; k4 < KQ; ++k4)
-#pragma unroll
-            for (int t = 0; t < RS; ++t) {
-                const int gi = BWD ? k4 * wstep_k + (RS - 1 - t) : k4 * RS + t;
-                anext[t][k4] = (f_ok && kk * KQ + k4 < left) ? ldf(wp_, gi) : 0.f;
+                for (int j = 0; j < RS * KQ / 4; ++j) {
+                    const v4u v = __builtin_amdgcn_raw_buffer_load_b128(wrs, vo + 16u * j, 0, 0);
+                    an[4 * j + 0] = __uint_as_float(v.x);
+                    an[4 * j + 1] = __uint_as_float(v.y);
+                    an[4 * j + 2] = __uint_as_float(v.z);
+                    an[4 * j + 3] = __uint_as_float(v.w);
+                }
+                return;
             }
+        }
+#pragma unroll
+        for (int k4 = 0; k4 < KQ; ++k4) {
+            const unsigned vo = (f_ok && kk * KQ + k4 < left) ? (unsigned)(wb + k4 * wstep_k) * (unsigned)sizeof(T) : kOob;
+#pragma unroll
+            for (int t = 0; t < RS; ++t)
+                an[k4 * RS + t] = buf_load(wrs, vo + (unsigned)((BWD ? RS - 1 - t : t) * sizeof(T)), tnull);
+        }
     };
-    auto store_patch = [&](int buf) {
+    auto store_patch = [&](float* buf) {
+        // Everything fetched for the next chunk (patch and filters) was issued a whole chunk of MFMA
+        // work ago; retiring all of it here keeps waits on these loads out of the next MFMA loop.
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 #pragma unroll
         for (int m = 0; m < XPT; ++m)
-            if (loff[m] >= 0) xs[buf][loff[m]] = xreg[m];
+            if (loff[m] >= 0) buf[loff[m]] = xreg[m];
     };
-    auto take_filters = [&]() {
+    // One "group" = one (tap, reduction channel) pair = NBW MFMAs sharing an A operand.  The B operands
+    // of group g+1 are read from LDS while the MFMAs of group g issue; a scheduling fence after every
+    // group keeps the compiler from undoing that distance or from hoisting more than one group ahead.
+    auto compute = [&](const float* xb, const float (&ac)[RS * KQ]) {
+        constexpr int G = RS * KQ;
+        float bq[2][NBW];
 #pragma unroll
-        for (int t = 0; t < RS; ++t)
+        for (int i = 0; i < NBW; ++i) bq[0][i] = xb[pixoff[i]];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int k4 = 0; k4 < KQ; ++k4) areg[t][k4] = anext[t][k4];
-    };
-
-    const int nchunks = (a.Rg + CK - 1) / CK;
-    load_chunk(0);
-    store_patch(0);
-    take_filters();
-    __syncthreads();
-
-    for (int ch = 0; ch < nchunks; ++ch) {
-        const int cur = ch & 1;
-        const bool more = ch + 1 < nchunks;
-        if (more) load_chunk(ch + 1);
-
-        const float* xb = xs[cur];
+        for (int g = 0; g < G; ++g) {
+            if (g + 1 < G) {
+                const int k4 = (g + 1) % KQ, t = (g + 1) / KQ;
+                const int off = k4 * CS + (t / S) * PW + (t % S);
 #pragma unroll
-        for (int r = 0; r < R; ++r)
+                for (int i = 0; i < NBW; ++i) bq[(g + 1) & 1][i] = xb[pixoff[i] + off];
+            }
+            __builtin_amdgcn_sched_barrier(0);  // reads of the next group are issued before this group's MFMAs
+            const float av = ac[(g % KQ) * RS + g / KQ];
 #pragma unroll
-            for (int s = 0; s < S; ++s)
-#pragma unroll
-                for (int k4 = 0; k4 < KQ; ++k4) {
-                    const float av = areg[r * S + s][k4];
-#pragma unroll
-                    for (int i = 0; i < NBW; ++i) {
-                        if (NB % WP != 0 && i == NBW - 1 && wp + WP * i >= NB) continue;  // wave-uniform
-                        const float bv = xb[pixoff[i] + k4 * CS + r * PW + s];
-                        acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bv, acc[i], 0, 0, 0);
-                    }
-                }
-
-        if (more) {
-            store_patch(cur ^ 1);
-            take_filters();
+            for (int i = 0; i < NBW; ++i)
+                acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[g & 1][i], acc[i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);  // nothing moves across groups
         }
+    };
+
+    // Two register sets for the filters and two LDS buffers for the patch alternate, so the loop
+    // is written out for an even and an odd chunk: no register copies, LDS addresses are immediates.
+    float A0[RS * KQ], A1[RS * KQ];
+    const int nchunks = (a.Rg + CK - 1) / CK;
+    load_chunk(0, A0);
+    store_patch(xs[0]);
+    __syncthreads();
+    for (int ch = 0; ch < nchunks; ch += 2) {
+        const bool more1 = ch + 1 < nchunks;
+        if (more1) load_chunk(ch + 1, A1);
+        compute(xs[0], A0);
+        if (more1) store_patch(xs[1]);
+        __syncthreads();
+        if (!more1) break;
+        const bool more2 = ch + 2 < nchunks;
+        if (more2) load_chunk(ch + 2, A0);
+        compute(xs[1], A1);
+        if (more2) store_patch(xs[0]);
         __syncthreads();
     }
 
@@ -222,6 +264,7 @@ hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
     a.tiles_w = (a.OW + TW - 1) / TW;
     a.fblocks = (a.Fg + 16 * WF - 1) / (16 * WF);
     a.units = a.N * a.groups * a.tiles_h * a.tiles_w;
+    a.wvec = (a.Rg % 4 == 0);
     const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
     conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD><<<grid, 64 * WF * WP, 0, st>>>(a);
     return hipGetLastError();
@@ -249,16 +292,21 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
 // Builds the operand view of a pass; false when the tiled kernel cannot run it.
 bool make_args(int pass, const Problem& pr, const void* in0, const void* in1, float* out, TileArgs& a, int& stride) {
     if (pr.sh != pr.sw) return false;
+    // Buffer descriptors address at most 2 GiB here.
+    const size_t esz = pr.dtype == 0 ? 4 : 2;
+    const size_t lim = (size_t)1 << 31;
+    if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
+    const unsigned wbytes = (unsigned)((size_t)pr.K * pr.Cg * pr.R * pr.S * esz);
     if (pass == 0) {
         a = TileArgs{in0, in1, out, pr.N, pr.C, pr.H, pr.W, pr.K, pr.P, pr.Q, pr.Kg, pr.Cg, pr.groups,
-                     pr.ph, pr.pw, 0, 0, 0, 0};
+                     pr.ph, pr.pw, 0, 0, 0, 0, 0, wbytes};
         stride = pr.sh;
         return true;
     }
     if (pass == 1) {
         if (pr.sh != 1) return false;
         a = TileArgs{in0, in1, out, pr.N, pr.K, pr.P, pr.Q, pr.C, pr.H, pr.W, pr.Cg, pr.Kg, pr.groups,
-                     pr.R - 1 - pr.ph, pr.S - 1 - pr.pw, 0, 0, 0, 0};
+                     pr.R - 1 - pr.ph, pr.S - 1 - pr.pw, 0, 0, 0, 0, 0, wbytes};
         stride = 1;
         return true;
     }
