@@ -39,8 +39,19 @@ struct WgradArgs {
     int total_wgs;
 };
 
-__device__ __forceinline__ float ldg(const float* p, int i) { return p[i]; }
-__device__ __forceinline__ float ldg(const uint16_t* p, int i) { return bf16_to_float(p[i]); }
+// Buffer loads return 0 for a byte offset at or beyond the descriptor's size: elements that must
+// read as zero (outside the image or the tile, absent channels) are given the offset kOob.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr unsigned kOob = 0x80000000u;  // one image's channels are far smaller than 2 GiB
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const float*) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0));
+}
+__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const uint16_t*) {
+    return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_raw_buffer_load_b16(r, byte_off, 0, 0)) << 16);
+}
 
 constexpr int next_2_mod_4(int v) { return v + ((6 - v % 4) % 4); }   // smallest >= v that is 2 mod 4
 constexpr int next_odd(int v) { return v | 1; }
@@ -93,7 +104,7 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     const int xplane = a.H * a.W, yplane = a.P * a.Q;
 
     // ---- gather plans (depend on the tile position only) -----------------------------------------
-    int ygo[YPT], xgo[XPT];   // global offsets relative to the stage's image, -1 = store zero
+    unsigned ygo[YPT], xgo[XPT];   // byte offsets inside the stage's image, kOob = reads as zero
     auto plan = [&](int tile) {
         const int ti = tile / a.tiles_w, tj = tile - ti * a.tiles_w;
         const int p0 = ti * TH, q0 = tj * TW;
@@ -105,7 +116,7 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
             const int th = px / TW, tw = px - th * TW;
             const int p = p0 + th, q = q0 + tw;
             const bool ok = e < YE && k0 + kl < a.Kg && p < a.P && q < a.Q;
-            ygo[m] = ok ? (g * a.Kg + k0 + kl) * yplane + p * a.Q + q : -1;
+            ygo[m] = ok ? (unsigned)((g * a.Kg + k0 + kl) * yplane + p * a.Q + q) * (unsigned)sizeof(T) : kOob;
         }
 #pragma unroll
         for (int m = 0; m < XPT; ++m) {
@@ -114,21 +125,27 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
             const int ph = rem / PW, pw = rem - ph * PW;
             const int h = h0 + ph, v = v0 + pw;
             const bool ok = e < XE && c0 + cl < a.Cg && h >= 0 && h < a.H && v >= 0 && v < a.W;
-            xgo[m] = ok ? (g * a.Cg + c0 + cl) * xplane + h * a.W + v : -1;
+            xgo[m] = ok ? (unsigned)((g * a.Cg + c0 + cl) * xplane + h * a.W + v) * (unsigned)sizeof(T) : kOob;
         }
     };
 
     float yreg[YPT], xreg[XPT];
+    const T* const tnull = nullptr;
+    const unsigned ybytes = (unsigned)(a.K * yplane) * (unsigned)sizeof(T);
+    const unsigned xbytes = (unsigned)(a.C * xplane) * (unsigned)sizeof(T);
     auto fetch = [&](int stage) {
         const int n = stage % a.N;
-        const T* yb = dyg + (size_t)n * a.K * yplane;
-        const T* xb = xg + (size_t)n * a.C * xplane;
+        const rsrc_t yrs = make_rsrc(dyg + (size_t)n * a.K * yplane, ybytes);
+        const rsrc_t xrs = make_rsrc(xg + (size_t)n * a.C * xplane, xbytes);
 #pragma unroll
-        for (int m = 0; m < YPT; ++m) yreg[m] = ygo[m] >= 0 ? ldg(yb, ygo[m]) : 0.f;
+        for (int m = 0; m < YPT; ++m) yreg[m] = buf_load(yrs, ygo[m], tnull);
 #pragma unroll
-        for (int m = 0; m < XPT; ++m) xreg[m] = xgo[m] >= 0 ? ldg(xb, xgo[m]) : 0.f;
+        for (int m = 0; m < XPT; ++m) xreg[m] = buf_load(xrs, xgo[m], tnull);
     };
     auto stash = [&](int buf) {
+        // The stage in flight was requested a whole stage of MFMA work ago: retire all of it here so
+        // that no wait on these loads ends up inside the MFMA loop.
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         float* ys = lds + buf * STAGE;
         float* xs = ys + 16 * KB * DS;
 #pragma unroll
@@ -153,6 +170,52 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
 #pragma unroll
             for (int t = 0; t < RS; ++t) acc[i][j][t] = v4f{0.f, 0.f, 0.f, 0.f};
 
+    // ---- this wave's pixel steps: t = ws, ws+WS, ...; the LDS offsets of its lanes never change ----
+    constexpr int IT_FULL = NSTEPS / WS, IT_REM = NSTEPS % WS, ITER = IT_FULL + (IT_REM ? 1 : 0);
+    int yoff[ITER], xoff[ITER];
+#pragma unroll
+    for (int i = 0; i < ITER; ++i) {
+        int px = 4 * (ws + WS * i) + kk;
+        if (px >= NPX) px = NPX - 1;  // only in the step that waves with ws >= IT_REM skip; keeps the read in range
+        const int th = px / TW, tw = px - th * TW;
+        yoff[i] = (16 * (wk * KBW) + li) * DS + px;
+        xoff[i] = 16 * KB * DS + (16 * (wc * CBW) + li) * XS + th * ST * PW + tw * ST;
+    }
+
+    // One step = KBW*CBW*RS MFMAs on KBW + CBW*RS operands.  The operands of step i+1 are read from
+    // LDS before the MFMAs of step i issue; scheduling fences keep the compiler from undoing that.
+    auto multiply = [&](const float* sb) {
+        float av[2][KBW], bv[2][CBW * RS];
+        auto read_step = [&](int i, float (&ao)[KBW], float (&bo)[CBW * RS]) {
+#pragma unroll
+            for (int ib = 0; ib < KBW; ++ib) ao[ib] = sb[yoff[i] + ib * 16 * DS];
+#pragma unroll
+            for (int j = 0; j < CBW; ++j)
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int s2 = 0; s2 < S; ++s2) bo[j * RS + r * S + s2] = sb[xoff[i] + j * 16 * XS + r * PW + s2];
+        };
+        read_step(0, av[0], bv[0]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < ITER; ++i) {
+            if (i + 1 < ITER) read_step(i + 1, av[(i + 1) & 1], bv[(i + 1) & 1]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (i < IT_FULL || ws < IT_REM) {  // wave-uniform
+#pragma unroll
+                for (int j = 0; j < CBW; ++j)
+#pragma unroll
+                    for (int t = 0; t < RS; ++t)
+#pragma unroll
+                        for (int ib = 0; ib < KBW; ++ib)
+                            acc[ib][j][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i & 1][ib], bv[i & 1][j * RS + t],
+                                                                                 acc[ib][j][t], 0, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
     if (s_begin < s_end) {
         int tile = s_begin / a.N;
         plan(tile);
@@ -167,29 +230,7 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
                 if (nt != tile) { tile = nt; plan(tile); }
                 fetch(stage + 1);
             }
-            const float* ys = lds + buf * STAGE + (16 * (wk * KBW) + li) * DS;
-            const float* xs = lds + buf * STAGE + 16 * KB * DS + (16 * (wc * CBW) + li) * XS;
-#pragma unroll 2
-            for (int t = ws; t < NSTEPS; t += WS) {
-                const int px = 4 * t + kk;
-                const int th = px / TW, tw = px - th * TW;
-                const int xo = th * ST * PW + tw * ST;
-                float av[KBW];
-#pragma unroll
-                for (int i = 0; i < KBW; ++i) av[i] = ys[i * 16 * DS + px];
-#pragma unroll
-                for (int j = 0; j < CBW; ++j)
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int s = 0; s < S; ++s) {
-                            const float bv = xs[j * 16 * XS + xo + r * PW + s];
-#pragma unroll
-                            for (int i = 0; i < KBW; ++i)
-                                acc[i][j][r * S + s] =
-                                    __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv, acc[i][j][r * S + s], 0, 0, 0);
-                        }
-            }
+            multiply(lds + buf * STAGE);
             if (more) stash(buf ^ 1);
             __syncthreads();
             buf ^= 1;
