@@ -239,6 +239,206 @@ __global__ __launch_bounds__(256) void dw_reduce_splits_kernel(const float* __re
     dw[i] = sum;
 }
 
+// ====================================================================================================
+// Wave-private variants for small planes (the usual depthwise shapes: 7x7 ... 28x28).
+// A wave owns whole planes: it fetches PB planes at once (PB*NPI loads in flight per lane), copies
+// them into its own zero-bordered LDS region and computes them, so there is no workgroup barrier at
+// all and every quantity that depends only on the lane (gather offsets, LDS offsets of the four
+// outputs a lane produces) is computed once per kernel instead of once per element.
+// ====================================================================================================
+struct DwWaveArgs {
+    const void* src;
+    const void* w;
+    float* dst;
+    int planes, C;
+    int IH, IW, OH, OW, pad_h, pad_w;
+    int PPH, PPW;
+    int NO, LS;        // a lane produces outputs lane + LS*o, o < NO (LS <= 64, NO*LS >= OH*OW)
+    float inv_ppw, inv_ow;
+    int flip, nbatches;
+    unsigned src_bytes;
+};
+
+// NPI: 64-lane passes over the padded plane (NPI*64 >= PPH*PPW).  NOM: most outputs per lane.
+// PB: planes fetched together.  Consecutive lanes produce consecutive outputs, so LDS reads are
+// conflict-free and every store instruction writes one contiguous run.
+template <typename T, int ST, int NPI, int NOM, int PB>
+__global__ __launch_bounds__(kThreads) void dw_wave_stencil_kernel(DwWaveArgs a) {
+    extern __shared__ float lds[];
+    constexpr unsigned ESZ = sizeof(T);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
+    const int PPS = a.PPH * a.PPW;
+    const int iplane = a.IH * a.IW, oplane = a.OH * a.OW;
+    const T* const tnull = nullptr;
+    const T* __restrict__ wg = static_cast<const T*>(a.w);
+    float* my = lds + wave * PB * PPS;
+
+    unsigned goff[NPI];
+#pragma unroll
+    for (int i = 0; i < NPI; ++i) {
+        const int e = lane + 64 * i;
+        const int ph = fdiv(e, a.inv_ppw), pw = e - ph * a.PPW;
+        const int ih = ph - a.pad_h, iw = pw - a.pad_w;
+        const bool ok = e < PPS && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
+        goff[i] = ok ? (unsigned)(ih * a.IW + iw) * ESZ : kOob;
+    }
+    int xo[NOM];      // LDS offset of the window of output o
+    int jo[NOM];      // its index in the output plane, -1 if this lane has no such output
+#pragma unroll
+    for (int o = 0; o < NOM; ++o) {
+        const int j = lane + a.LS * o;
+        const bool ok = o < a.NO && lane < a.LS && j < oplane;
+        const int jc = ok ? j : 0;
+        const int p = fdiv(jc, a.inv_ow), q = jc - p * a.OW;
+        xo[o] = p * ST * a.PPW + q * ST;
+        jo[o] = ok ? j : -1;
+    }
+
+    const rsrc_t srs = make_rsrc(a.src, a.src_bytes);
+    const int nw = gridDim.x * (kThreads / 64);
+    for (int b = blockIdx.x * (kThreads / 64) + wave; b < a.nbatches; b += nw) {
+        const int p0 = b * PB;
+        float v[PB][NPI];
+        // Planes past the end lie beyond the descriptor (and kOob pushes any offset beyond it): zeros.
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+            for (int i = 0; i < NPI; ++i)
+                v[pb][i] = buf_load(srs, (unsigned)((p0 + pb) * iplane) * ESZ + goff[i], tnull);
+        // The filters of the batch: wave-uniform addresses (scalar loads where the type allows).
+        float wv[PB][9];
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            const int pc = p0 + pb < a.planes ? p0 + pb : a.planes - 1;
+            const int c = pc % a.C;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) wv[pb][t] = load_elem(wg, (size_t)(c * 9 + (a.flip ? 8 - t : t)));
+        }
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb)
+#pragma unroll
+            for (int i = 0; i < NPI; ++i)
+                if (lane + 64 * i < PPS) my[pb * PPS + lane + 64 * i] = v[pb][i];
+#pragma unroll
+        for (int pb = 0; pb < PB; ++pb) {
+            const int plane = p0 + pb;
+            if (plane >= a.planes) break;
+            const float* xp = my + pb * PPS;
+            float* d = a.dst + (size_t)plane * oplane;
+#pragma unroll
+            for (int o = 0; o < NOM; ++o) {
+                if (o >= a.NO) break;
+                const float* xq = xp + xo[o];
+                float acc = 0.f;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int s = 0; s < 3; ++s) acc = fmaf(xq[r * a.PPW + s], wv[pb][r * 3 + s], acc);
+                if (jo[o] >= 0) d[jo[o]] = acc;
+            }
+        }
+    }
+}
+
+struct DwWaveWArgs {
+    const void* x;
+    const void* dy;
+    float* out;      // [nsplit][C*9] (or dw itself when nsplit == 1)
+    int N, C, H, W, P, Q, pad_h, pad_w;
+    int PPH, PPW;
+    int NO, LS;
+    float inv_ppw, inv_q;
+    int nsplit;
+    unsigned x_bytes, y_bytes;
+};
+
+// One wave = one channel and a contiguous range of images.  The nine partial sums of every lane stay
+// in registers over the image loop, the next image is fetched while the current one is multiplied,
+// and the lanes are combined at the end by a fixed butterfly: bit-reproducible, no atomics.
+template <typename T, int ST, int NPI, int NOM>
+__global__ __launch_bounds__(kThreads) void dw_wave_wgrad_kernel(DwWaveWArgs a) {
+    extern __shared__ float lds[];
+    constexpr unsigned ESZ = sizeof(T);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int PPS = a.PPH * a.PPW;
+    const int xplane = a.H * a.W, yplane = a.P * a.Q;
+    const T* const tnull = nullptr;
+    float* my = lds + wave * PPS;
+    const int unit = blockIdx.x * (kThreads / 64) + wave;   // = sp * C + c
+    if (unit >= a.C * a.nsplit) return;
+    const int c = unit % a.C, sp = unit / a.C;
+    const int n0 = (int)((long long)a.N * sp / a.nsplit), n1 = (int)((long long)a.N * (sp + 1) / a.nsplit);
+
+    unsigned goff[NPI];
+#pragma unroll
+    for (int i = 0; i < NPI; ++i) {
+        const int e = lane + 64 * i;
+        const int ph = fdiv(e, a.inv_ppw), pw = e - ph * a.PPW;
+        const int ih = ph - a.pad_h, iw = pw - a.pad_w;
+        const bool ok = e < PPS && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+        goff[i] = ok ? (unsigned)(ih * a.W + iw) * ESZ : kOob;
+    }
+    int xo[NOM];
+    unsigned yoff[NOM];
+#pragma unroll
+    for (int o = 0; o < NOM; ++o) {
+        const int j = lane + a.LS * o;
+        const bool ok = o < a.NO && lane < a.LS && j < yplane;
+        const int jc = ok ? j : 0;
+        const int p = fdiv(jc, a.inv_q), q = jc - p * a.Q;
+        xo[o] = p * ST * a.PPW + q * ST;
+        yoff[o] = ok ? (unsigned)j * ESZ : kOob;   // absent pixels multiply by zero
+    }
+
+    const rsrc_t xrs = make_rsrc(a.x, a.x_bytes);
+    const rsrc_t yrs = make_rsrc(a.dy, a.y_bytes);
+    float acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) acc[t] = 0.f;
+
+    float xv[NPI], yv[NOM];
+    auto fetch = [&](int n) {
+        const unsigned xb = (unsigned)((n * a.C + c) * xplane) * ESZ, yb = (unsigned)((n * a.C + c) * yplane) * ESZ;
+#pragma unroll
+        for (int i = 0; i < NPI; ++i) xv[i] = buf_load(xrs, xb + goff[i], tnull);
+#pragma unroll
+        for (int o = 0; o < NOM; ++o) yv[o] = buf_load(yrs, yb + yoff[o], tnull);
+    };
+    if (n0 < n1) fetch(n0);
+    for (int n = n0; n < n1; ++n) {
+        float yc[NOM];
+#pragma unroll
+        for (int i = 0; i < NPI; ++i)
+            if (lane + 64 * i < PPS) my[lane + 64 * i] = xv[i];
+#pragma unroll
+        for (int o = 0; o < NOM; ++o) yc[o] = yv[o];
+        if (n + 1 < n1) fetch(n + 1);
+#pragma unroll
+        for (int o = 0; o < NOM; ++o) {
+            if (o >= a.NO) break;
+            const float* xq = my + xo[o];
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int s = 0; s < 3; ++s) acc[r * 3 + s] = fmaf(yc[o], xq[r * a.PPW + s], acc[r * 3 + s]);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        float v = acc[t];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+        acc[t] = v;
+    }
+    if (lane == 0) {
+        float* out = a.out + (size_t)sp * a.C * 9 + (size_t)c * 9;
+#pragma unroll
+        for (int t = 0; t < 9; ++t) out[t] = acc[t];
+    }
+}
+
 bool is_depthwise(const Problem& pr) { return pr.groups == pr.C && pr.groups == pr.K && pr.groups > 1; }
 
 // Planes per workgroup: fills the 256 threads' rounds of 4-output items as evenly as possible
@@ -319,12 +519,82 @@ bool wgrad_args(const Problem& pr, const void* x, const void* dy, DwWArgs& a) {
     return true;
 }
 
+// ---- wave-private variants: host side ----------------------------------------------------------------
+bool wave_shape_ok(const Problem& pr, int pps, int outs) {
+    const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
+    if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
+    return pps <= 1024 && outs <= 1024;
+}
+// Outputs per lane and lane stride: NO = ceil(outs/64), LS = ceil(outs/NO).
+void lane_split(int outs, int& no, int& ls) {
+    no = (outs + 63) / 64;
+    ls = (outs + no - 1) / no;
+}
+
+bool wave_stencil_args(int pass, const Problem& pr, const void* in0, const void* in1, float* out, DwWaveArgs& a,
+                       int& stride) {
+    DwArgs b{};
+    if (!stencil_args(pass, pr, in0, in1, out, b, stride)) return false;
+    const int pps = b.PPH * b.PPW;
+    if (!wave_shape_ok(pr, pps, b.OH * b.OW)) return false;
+    const unsigned esz = pr.dtype == 0 ? 4 : 2;
+    a.src = b.src; a.w = b.w; a.dst = b.dst; a.planes = b.planes; a.C = b.C;
+    a.IH = b.IH; a.IW = b.IW; a.OH = b.OH; a.OW = b.OW; a.pad_h = b.pad_h; a.pad_w = b.pad_w;
+    a.PPH = b.PPH; a.PPW = b.PPW; a.inv_ppw = b.inv_ppw; a.inv_ow = b.inv_ow;
+    lane_split(b.OH * b.OW, a.NO, a.LS);
+    a.flip = b.flip;
+    a.src_bytes = (unsigned)((size_t)a.planes * a.IH * a.IW * esz);
+    return true;
+}
+
+template <typename T, int ST>
+hipError_t launch_wave_stencil(DwWaveArgs a, hipStream_t st) {
+    const int pps = a.PPH * a.PPW;
+    const bool small = pps <= 256 && a.NO <= 4;
+    const int pb = small ? 4 : 1;
+    a.nbatches = (a.planes + pb - 1) / pb;
+    int grid = (a.nbatches + 3) / 4;
+    if (grid > 4096) grid = 4096;
+    const size_t smem = (size_t)4 * pb * pps * sizeof(float);
+    if (small) dw_wave_stencil_kernel<T, ST, 4, 4, 4><<<grid, kThreads, smem, st>>>(a);
+    else dw_wave_stencil_kernel<T, ST, 16, 16, 1><<<grid, kThreads, smem, st>>>(a);
+    return hipGetLastError();
+}
+
+bool wave_wgrad_args(const Problem& pr, const void* x, const void* dy, DwWaveWArgs& a) {
+    if (!is_depthwise(pr) || pr.R != 3 || pr.S != 3 || pr.sh != pr.sw || pr.sh > 2) return false;
+    a.PPH = (pr.P - 1) * pr.sh + 3; a.PPW = (pr.Q - 1) * pr.sh + 3;
+    if (!wave_shape_ok(pr, a.PPH * a.PPW, pr.P * pr.Q)) return false;
+    lane_split(pr.P * pr.Q, a.NO, a.LS);
+    const unsigned esz = pr.dtype == 0 ? 4 : 2;
+    a.x = x; a.dy = dy;
+    a.N = pr.N; a.C = pr.C; a.H = pr.H; a.W = pr.W; a.P = pr.P; a.Q = pr.Q; a.pad_h = pr.ph; a.pad_w = pr.pw;
+    a.inv_ppw = 1.0f / a.PPW; a.inv_q = 1.0f / pr.Q;
+    int nsplit = (8192 + pr.C - 1) / pr.C;   // about 8192 waves in flight cover the HBM latency
+    if (nsplit > pr.N) nsplit = pr.N;
+    a.nsplit = nsplit;
+    a.x_bytes = (unsigned)((size_t)pr.N * pr.C * pr.H * pr.W * esz);
+    a.y_bytes = (unsigned)((size_t)pr.N * pr.C * pr.P * pr.Q * esz);
+    return true;
+}
+
+template <typename T, int ST>
+hipError_t launch_wave_wgrad(const DwWaveWArgs& a, hipStream_t st) {
+    const int pps = a.PPH * a.PPW;
+    const int grid = (a.C * a.nsplit + 3) / 4;
+    const size_t smem = (size_t)4 * pps * sizeof(float);
+    if (pps <= 256 && a.NO <= 4) dw_wave_wgrad_kernel<T, ST, 4, 4><<<grid, kThreads, smem, st>>>(a);
+    else dw_wave_wgrad_kernel<T, ST, 16, 16><<<grid, kThreads, smem, st>>>(a);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 bool depthwise_supports(int pass, const Problem& pr) {
     if (pass == 2) {
         DwWArgs a{};
-        return wgrad_args(pr, nullptr, nullptr, a);
+        DwWaveWArgs b{};
+        return wave_wgrad_args(pr, nullptr, nullptr, b) || wgrad_args(pr, nullptr, nullptr, a);
     }
     DwArgs a{};
     int stride;
@@ -333,6 +603,8 @@ bool depthwise_supports(int pass, const Problem& pr) {
 
 size_t depthwise_workspace_bytes(int pass, const Problem& pr) {
     if (pass != 2) return 0;
+    DwWaveWArgs b{};
+    if (wave_wgrad_args(pr, nullptr, nullptr, b)) return b.nsplit > 1 ? (size_t)b.nsplit * pr.C * 9 * sizeof(float) : 0;
     DwWArgs a{};
     if (!wgrad_args(pr, nullptr, nullptr, a)) return 0;
     return a.nsplit > 1 ? (size_t)a.nsplit * pr.C * 9 * sizeof(float) : 0;
@@ -340,7 +612,18 @@ size_t depthwise_workspace_bytes(int pass, const Problem& pr) {
 
 hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
                          hipStream_t st) {
+    const int count = pr.C * 9;
     if (pass == 2) {
+        DwWaveWArgs b{};
+        if (wave_wgrad_args(pr, in0, in1, b)) {
+            b.out = b.nsplit > 1 ? static_cast<float*>(ws) : out;
+            hipError_t e;
+            if (pr.dtype == 0) e = pr.sh == 1 ? launch_wave_wgrad<float, 1>(b, st) : launch_wave_wgrad<float, 2>(b, st);
+            else e = pr.sh == 1 ? launch_wave_wgrad<uint16_t, 1>(b, st) : launch_wave_wgrad<uint16_t, 2>(b, st);
+            if (e != hipSuccess || b.nsplit == 1) return e;
+            dw_reduce_splits_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, b.nsplit, count);
+            return hipGetLastError();
+        }
         DwWArgs a{};
         if (!wgrad_args(pr, in0, in1, a)) return hipErrorNotSupported;
         a.out = a.nsplit > 1 ? static_cast<float*>(ws) : out;
@@ -357,12 +640,16 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess || a.nsplit == 1) return e;
-        const int count = pr.C * 9;
         dw_reduce_splits_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, a.nsplit, count);
         return hipGetLastError();
     }
-    DwArgs a{};
+    DwWaveArgs wv{};
     int stride;
+    if (wave_stencil_args(pass, pr, in0, in1, out, wv, stride)) {
+        if (pr.dtype == 0) return stride == 1 ? launch_wave_stencil<float, 1>(wv, st) : launch_wave_stencil<float, 2>(wv, st);
+        return stride == 1 ? launch_wave_stencil<uint16_t, 1>(wv, st) : launch_wave_stencil<uint16_t, 2>(wv, st);
+    }
+    DwArgs a{};
     if (!stencil_args(pass, pr, in0, in1, out, a, stride)) return hipErrorNotSupported;
     return pr.dtype == 0 ? launch_stencil<float>(a, stride, st) : launch_stencil<uint16_t>(a, stride, st);
 }
