@@ -22,6 +22,7 @@ namespace {
 constexpr int kThreads = 256;
 
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 constexpr unsigned kOob = 0x80000000u;
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
@@ -230,134 +231,217 @@ __global__ __launch_bounds__(kThreads) void dw_wgrad_kernel(DwWArgs a) {
     }
 }
 
+// Sums the split partials in a fixed order.  All loads of an element are issued before the first add.
 __global__ __launch_bounds__(256) void dw_reduce_splits_kernel(const float* __restrict__ part, float* __restrict__ dw,
                                                                int nsplit, int count) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
-    float sum = part[i];
-    for (int s = 1; s < nsplit; ++s) sum += part[(size_t)s * count + i];
+    float sum = 0.f;
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = s0 + k < nsplit ? part[(size_t)(s0 + k) * count + i] : 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sum += v[k];
+    }
     dw[i] = sum;
 }
 
 // ====================================================================================================
-// Wave-private variants for small planes (the usual depthwise shapes: 7x7 ... 28x28).
-// A wave owns whole planes: it fetches PB planes at once (PB*NPI loads in flight per lane), copies
-// them into its own zero-bordered LDS region and computes them, so there is no workgroup barrier at
-// all and every quantity that depends only on the lane (gather offsets, LDS offsets of the four
-// outputs a lane produces) is computed once per kernel instead of once per element.
+// Wave-private "strip" kernels for the usual depthwise plane sizes (output width <= 64, padded plane
+// <= 1024 floats: 7x7 ... 28x28, stride 1 or 2).
+//
+// A wave owns whole planes, so there is no workgroup barrier.  It fetches a batch of PB planes with
+// coalesced row reads into its own zero-bordered LDS region while it computes the previous batch.
+// In the compute step a lane owns one output column q of one 7-row segment of one plane and slides
+// down it: a 9x3 window of inputs (27 LDS reads) yields 7 outputs (63 FMAs), instead of 9 reads per
+// output.  Lanes of a segment read consecutive LDS words and write consecutive outputs.  Everything
+// that depends only on the lane (gather offsets, window and output offsets) is computed once.
 // ====================================================================================================
-struct DwWaveArgs {
+constexpr int kSeg = 7;   // output rows per lane
+
+struct DwStripArgs {
     const void* src;
     const void* w;
     float* dst;
     int planes, C;
     int IH, IW, OH, OW, pad_h, pad_w;
     int PPH, PPW;
-    int NO, LS;        // a lane produces outputs lane + LS*o, o < NO (LS <= 64, NO*LS >= OH*OW)
-    float inv_ppw, inv_ow;
+    int PB;            // planes per batch
+    int NSEG;          // 7-row segments per plane
+    int UPP;           // (plane, segment) units per 64-lane pass = 64 / OW
+    int passes;        // ceil(PB*NSEG / UPP)
+    int lds_per_wave;  // floats: [PB planes][slack rows][9*PB filter taps][PB output planes (wide path)]
+    int w_off, o_off;  // where the filter taps and the output staging start inside a wave's region
+    float inv_ppw, inv_pps, inv_ow, inv_nseg, inv_c, inv_iplane, inv_iw;
     int flip, nbatches;
-    unsigned src_bytes;
+    unsigned src_bytes, w_bytes;
 };
 
-// NPI: 64-lane passes over the padded plane (NPI*64 >= PPH*PPW).  NOM: most outputs per lane.
-// PB: planes fetched together.  Consecutive lanes produce consecutive outputs, so LDS reads are
-// conflict-free and every store instruction writes one contiguous run.
-template <typename T, int ST, int NPI, int NOM, int PB>
-__global__ __launch_bounds__(kThreads) void dw_wave_stencil_kernel(DwWaveArgs a) {
+// NPIB: 64-lane passes over the batch's padded planes (NPIB*64 >= PB*PPH*PPW).  NPS: most compute passes.
+// WIDE: global memory is touched only with 16-byte accesses per lane (the texture-address unit moves a
+// quarter of its peak with 4-byte ones, which is what bounds this kernel): the batch is read as
+// consecutive float4 and scattered into the padded planes, results are gathered from an LDS staging
+// area as float4.  Needs fp32 planes whose sizes are multiples of 4 and 16-byte aligned tensors.
+template <typename T, int ST, int NPIB, int NPS, bool WIDE>
+__global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs a) {
+    constexpr int NLV = 4;   // float4 passes over a batch's input / output (PB*plane/4 <= 256)
     extern __shared__ float lds[];
     constexpr unsigned ESZ = sizeof(T);
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in a scalar register
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int PPS = a.PPH * a.PPW;
     const int iplane = a.IH * a.IW, oplane = a.OH * a.OW;
     const T* const tnull = nullptr;
-    const T* __restrict__ wg = static_cast<const T*>(a.w);
-    float* my = lds + wave * PB * PPS;
+    float* my = lds + wave * a.lds_per_wave;
+    float* wl = my + a.w_off;   // behind the planes and the slack rows masked strips read
+    float* ol = my + a.o_off;
 
-    unsigned goff[NPI];
+    // wide path: lane's float4 f = lane + 64*i of the batch and where its four values land in LDS
+    unsigned vgo[NLV];
+    int lo[NLV][4];
+    if constexpr (WIDE) {
 #pragma unroll
-    for (int i = 0; i < NPI; ++i) {
-        const int e = lane + 64 * i;
-        const int ph = fdiv(e, a.inv_ppw), pw = e - ph * a.PPW;
-        const int ih = ph - a.pad_h, iw = pw - a.pad_w;
-        const bool ok = e < PPS && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
-        goff[i] = ok ? (unsigned)(ih * a.IW + iw) * ESZ : kOob;
+        for (int i = 0; i < NLV; ++i) {
+            const int f = lane + 64 * i;
+            vgo[i] = 4 * f < a.PB * iplane ? (unsigned)f * 16u : kOob;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int idx = 4 * f + k;
+                const int pl = fdiv(idx, a.inv_iplane), rem = idx - pl * iplane;
+                const int ih = fdiv(rem, a.inv_iw), iw = rem - ih * a.IW;
+                const int ph = ih + a.pad_h, pw = iw + a.pad_w;
+                const bool ok = idx < a.PB * iplane && ph >= 0 && ph < a.PPH && pw >= 0 && pw < a.PPW;
+                lo[i][k] = ok ? pl * PPS + ph * a.PPW + pw : -1;
+            }
+        }
+        // borders (and the slack) are written once; the scatter only ever touches interior words
+        for (int e = lane; e < a.w_off; e += 64) my[e] = 0.f;
     }
-    int xo[NOM];      // LDS offset of the window of output o
-    int jo[NOM];      // its index in the output plane, -1 if this lane has no such output
+
+    unsigned goff[NPIB];   // byte offset inside the batch, kOob = zero
 #pragma unroll
-    for (int o = 0; o < NOM; ++o) {
-        const int j = lane + a.LS * o;
-        const bool ok = o < a.NO && lane < a.LS && j < oplane;
-        const int jc = ok ? j : 0;
-        const int p = fdiv(jc, a.inv_ow), q = jc - p * a.OW;
-        xo[o] = p * ST * a.PPW + q * ST;
-        jo[o] = ok ? j : -1;
+    for (int i = 0; i < NPIB; ++i) {
+        const int e = lane + 64 * i;
+        const int pl = fdiv(e, a.inv_pps), rem = e - pl * PPS;
+        const int ph = fdiv(rem, a.inv_ppw), pw = rem - ph * a.PPW;
+        const int ih = ph - a.pad_h, iw = pw - a.pad_w;
+        const bool ok = e < a.PB * PPS && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
+        goff[i] = ok ? (unsigned)(pl * iplane + ih * a.IW + iw) * ESZ : kOob;
+    }
+    int win[NPS], oo[NPS], rows[NPS], wof[NPS];
+    {
+        const int ul = fdiv(lane, a.inv_ow), q = lane - ul * a.OW;
+#pragma unroll
+        for (int ps = 0; ps < NPS; ++ps) {
+            const int u = ps * a.UPP + ul;
+            const bool ok = ps < a.passes && ul < a.UPP && u < a.PB * a.NSEG;
+            const int uc = ok ? u : 0;
+            const int pl = fdiv(uc, a.inv_nseg), seg = uc - pl * a.NSEG;
+            const int p0 = seg * kSeg;
+            win[ps] = pl * PPS + p0 * ST * a.PPW + q * ST;
+            oo[ps] = pl * oplane + p0 * a.OW + q;
+            rows[ps] = ok ? min(kSeg, a.OH - p0) : 0;
+            wof[ps] = pl * 9;
+        }
     }
 
     const rsrc_t srs = make_rsrc(a.src, a.src_bytes);
+    const rsrc_t wrs = make_rsrc(a.w, a.w_bytes);
     const int nw = gridDim.x * (kThreads / 64);
-    for (int b = blockIdx.x * (kThreads / 64) + wave; b < a.nbatches; b += nw) {
-        const int p0 = b * PB;
-        float v[PB][NPI];
-        // Planes past the end lie beyond the descriptor (and kOob pushes any offset beyond it): zeros.
+    float v[WIDE ? 1 : NPIB];
+    v4u v4[WIDE ? NLV : 1];
+    float wreg;
+    // Planes past the end of the tensor lie beyond the descriptor: zeros.
+    auto fetch = [&](int b) {
+        const unsigned base = (unsigned)(b * a.PB * iplane) * ESZ;
+        if constexpr (WIDE) {
 #pragma unroll
-        for (int pb = 0; pb < PB; ++pb)
+            for (int i = 0; i < NLV; ++i) v4[i] = __builtin_amdgcn_raw_buffer_load_b128(srs, base + vgo[i], 0, 0);
+        } else {
 #pragma unroll
-            for (int i = 0; i < NPI; ++i)
-                v[pb][i] = buf_load(srs, (unsigned)((p0 + pb) * iplane) * ESZ + goff[i], tnull);
-        // The filters of the batch: wave-uniform addresses (scalar loads where the type allows).
-        float wv[PB][9];
-#pragma unroll
-        for (int pb = 0; pb < PB; ++pb) {
-            const int pc = p0 + pb < a.planes ? p0 + pb : a.planes - 1;
-            const int c = pc % a.C;
-#pragma unroll
-            for (int t = 0; t < 9; ++t) wv[pb][t] = load_elem(wg, (size_t)(c * 9 + (a.flip ? 8 - t : t)));
+            for (int i = 0; i < NPIB; ++i) v[i] = buf_load(srs, base + goff[i], tnull);
         }
+        // lane l < 9*PB fetches tap l%9 of the batch's plane l/9
+        const int pl = lane / 9, t = lane - pl * 9;
+        const int plane = b * a.PB + pl;
+        const int c = plane - fdiv(plane, a.inv_c) * a.C;
+        wreg = buf_load(wrs, (pl < a.PB && plane < a.planes) ? (unsigned)(c * 9 + (a.flip ? 8 - t : t)) * ESZ : kOob, tnull);
+    };
+    int b = blockIdx.x * (kThreads / 64) + wave;
+    if (b < a.nbatches) fetch(b);
+    for (; b < a.nbatches; b += nw) {
+        if constexpr (WIDE) {
 #pragma unroll
-        for (int pb = 0; pb < PB; ++pb)
+            for (int i = 0; i < NLV; ++i)
 #pragma unroll
-            for (int i = 0; i < NPI; ++i)
-                if (lane + 64 * i < PPS) my[pb * PPS + lane + 64 * i] = v[pb][i];
+                for (int k = 0; k < 4; ++k)
+                    if (lo[i][k] >= 0) my[lo[i][k]] = __uint_as_float(v4[i][k]);
+        } else {
 #pragma unroll
-        for (int pb = 0; pb < PB; ++pb) {
-            const int plane = p0 + pb;
-            if (plane >= a.planes) break;
-            const float* xp = my + pb * PPS;
-            float* d = a.dst + (size_t)plane * oplane;
+            for (int i = 0; i < NPIB; ++i)
+                if (lane + 64 * i < a.PB * PPS) my[lane + 64 * i] = v[i];
+        }
+        if (lane < 9 * a.PB) wl[lane] = wreg;
+        if (b + nw < a.nbatches) fetch(b + nw);   // the next batch travels while this one is computed
+        float* d = a.dst + (size_t)b * a.PB * oplane;
+        const int live = min(a.PB, a.planes - b * a.PB) * oplane;   // outputs that exist in this batch
 #pragma unroll
-            for (int o = 0; o < NOM; ++o) {
-                if (o >= a.NO) break;
-                const float* xq = xp + xo[o];
+        for (int ps = 0; ps < NPS; ++ps) {
+            if (ps >= a.passes) break;
+            const float* xq = my + win[ps];
+            float wv[9];
+#pragma unroll
+            for (int t = 0; t < 9; ++t) wv[t] = wl[wof[ps] + t];
+            float xw[(kSeg - 1) * ST + 3][3];
+#pragma unroll
+            for (int r = 0; r < (kSeg - 1) * ST + 3; ++r)
+#pragma unroll
+                for (int s = 0; s < 3; ++s) xw[r][s] = xq[r * a.PPW + s];
+#pragma unroll
+            for (int i = 0; i < kSeg; ++i) {
                 float acc = 0.f;
 #pragma unroll
                 for (int r = 0; r < 3; ++r)
 #pragma unroll
-                    for (int s = 0; s < 3; ++s) acc = fmaf(xq[r * a.PPW + s], wv[pb][r * 3 + s], acc);
-                if (jo[o] >= 0) d[jo[o]] = acc;
+                    for (int s = 0; s < 3; ++s) acc = fmaf(xw[i * ST + r][s], wv[r * 3 + s], acc);
+                const int o = oo[ps] + i * a.OW;
+                if constexpr (WIDE) {
+                    if (i < rows[ps]) ol[o] = acc;
+                } else {
+                    if (i < rows[ps] && o < live) d[o] = acc;
+                }
+            }
+        }
+        if constexpr (WIDE) {
+#pragma unroll
+            for (int i = 0; i < NLV; ++i) {
+                const int f = lane + 64 * i;
+                if (4 * f < live) *reinterpret_cast<float4*>(d + 4 * f) = *reinterpret_cast<const float4*>(ol + 4 * f);
             }
         }
     }
 }
 
-struct DwWaveWArgs {
+struct DwStripWArgs {
     const void* x;
     const void* dy;
-    float* out;      // [nsplit][C*9] (or dw itself when nsplit == 1)
+    float* out;        // [nsplit][C*9] (or dw itself when nsplit == 1)
     int N, C, H, W, P, Q, pad_h, pad_w;
     int PPH, PPW;
-    int NO, LS;
-    float inv_ppw, inv_q;
+    int PB, NSEG, UPP, passes, lds_per_wave, w_off, o_off;
+    float inv_ppw, inv_pps, inv_q, inv_nseg, inv_xplane, inv_w, inv_yplane;
     int nsplit;
     unsigned x_bytes, y_bytes;
 };
 
-// One wave = one channel and a contiguous range of images.  The nine partial sums of every lane stay
-// in registers over the image loop, the next image is fetched while the current one is multiplied,
-// and the lanes are combined at the end by a fixed butterfly: bit-reproducible, no atomics.
-template <typename T, int ST, int NPI, int NOM>
-__global__ __launch_bounds__(kThreads) void dw_wave_wgrad_kernel(DwWaveWArgs a) {
+// One wave = one channel and a contiguous range of images, taken PB images at a time.  The nine
+// partial sums of every lane stay in registers over the whole range, the next images are fetched
+// while the current ones are multiplied, and the lanes are combined at the end by a fixed
+// butterfly: bit-reproducible, no atomics.
+template <typename T, int ST, int NPIB, int NPS, bool WIDE>
+__global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a) {
+    constexpr int NLV = 4;   // float4 passes over a batch of x / dy planes
     extern __shared__ float lds[];
     constexpr unsigned ESZ = sizeof(T);
     const int lane = threadIdx.x & 63;
@@ -365,31 +449,75 @@ __global__ __launch_bounds__(kThreads) void dw_wave_wgrad_kernel(DwWaveWArgs a) 
     const int PPS = a.PPH * a.PPW;
     const int xplane = a.H * a.W, yplane = a.P * a.Q;
     const T* const tnull = nullptr;
-    float* my = lds + wave * PPS;
+    float* my = lds + wave * a.lds_per_wave;
     const int unit = blockIdx.x * (kThreads / 64) + wave;   // = sp * C + c
     if (unit >= a.C * a.nsplit) return;
     const int c = unit % a.C, sp = unit / a.C;
     const int n0 = (int)((long long)a.N * sp / a.nsplit), n1 = (int)((long long)a.N * (sp + 1) / a.nsplit);
 
-    unsigned goff[NPI];
+    float* yl = my + a.o_off;   // wide path: the batch's dy planes, unpadded
+
+    // wide path: float4 f = lane + 64*i of the batch's x planes (and dy planes) and where the values land
+    unsigned vgx[NLV], vgy[NLV];
+    int vpx[NLV], vpy[NLV];
+    int lo[NLV][4];
+    if constexpr (WIDE) {
 #pragma unroll
-    for (int i = 0; i < NPI; ++i) {
-        const int e = lane + 64 * i;
-        const int ph = fdiv(e, a.inv_ppw), pw = e - ph * a.PPW;
-        const int ih = ph - a.pad_h, iw = pw - a.pad_w;
-        const bool ok = e < PPS && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-        goff[i] = ok ? (unsigned)(ih * a.W + iw) * ESZ : kOob;
+        for (int i = 0; i < NLV; ++i) {
+            const int f = lane + 64 * i;
+            {
+                const int pl = fdiv(4 * f, a.inv_xplane), rem = 4 * f - pl * xplane;
+                vgx[i] = 4 * f < a.PB * xplane ? (unsigned)(pl * a.C * xplane + rem) * 4u : kOob;
+                vpx[i] = pl;
+            }
+            {
+                const int pl = fdiv(4 * f, a.inv_yplane), rem = 4 * f - pl * yplane;
+                vgy[i] = 4 * f < a.PB * yplane ? (unsigned)(pl * a.C * yplane + rem) * 4u : kOob;
+                vpy[i] = pl;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int idx = 4 * f + k;
+                const int pl = fdiv(idx, a.inv_xplane), rem = idx - pl * xplane;
+                const int ih = fdiv(rem, a.inv_w), iw = rem - ih * a.W;
+                const int ph = ih + a.pad_h, pw = iw + a.pad_w;
+                const bool ok = idx < a.PB * xplane && ph >= 0 && ph < a.PPH && pw >= 0 && pw < a.PPW;
+                lo[i][k] = ok ? pl * PPS + ph * a.PPW + pw : -1;
+            }
+        }
+        for (int e = lane; e < a.w_off; e += 64) my[e] = 0.f;   // borders and slack, written once
     }
-    int xo[NOM];
-    unsigned yoff[NOM];
+
+    // image i of a batch is the plane (n+i)*C + c: offsets are relative to image n, channel c
+    unsigned goff[NPIB];
+    int gpl[NPIB];
 #pragma unroll
-    for (int o = 0; o < NOM; ++o) {
-        const int j = lane + a.LS * o;
-        const bool ok = o < a.NO && lane < a.LS && j < yplane;
-        const int jc = ok ? j : 0;
-        const int p = fdiv(jc, a.inv_q), q = jc - p * a.Q;
-        xo[o] = p * ST * a.PPW + q * ST;
-        yoff[o] = ok ? (unsigned)j * ESZ : kOob;   // absent pixels multiply by zero
+    for (int i = 0; i < NPIB; ++i) {
+        const int e = lane + 64 * i;
+        const int pl = fdiv(e, a.inv_pps), rem = e - pl * PPS;
+        const int ph = fdiv(rem, a.inv_ppw), pw = rem - ph * a.PPW;
+        const int ih = ph - a.pad_h, iw = pw - a.pad_w;
+        const bool ok = e < a.PB * PPS && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+        goff[i] = ok ? (unsigned)(pl * a.C * xplane + ih * a.W + iw) * ESZ : kOob;
+        gpl[i] = pl;
+    }
+    int win[NPS], rows[NPS], ypl[NPS], yli[NPS];
+    unsigned yo[NPS];
+    {
+        const int ul = fdiv(lane, a.inv_q), q = lane - ul * a.Q;
+#pragma unroll
+        for (int ps = 0; ps < NPS; ++ps) {
+            const int u = ps * a.UPP + ul;
+            const bool ok = ps < a.passes && ul < a.UPP && u < a.PB * a.NSEG;
+            const int uc = ok ? u : 0;
+            const int pl = fdiv(uc, a.inv_nseg), seg = uc - pl * a.NSEG;
+            const int p0 = seg * kSeg;
+            win[ps] = pl * PPS + p0 * ST * a.PPW + q * ST;
+            yo[ps] = (unsigned)(pl * a.C * yplane + p0 * a.Q + q) * ESZ;
+            yli[ps] = pl * yplane + p0 * a.Q + q;
+            rows[ps] = ok ? min(kSeg, a.P - p0) : 0;
+            ypl[ps] = pl;
+        }
     }
 
     const rsrc_t xrs = make_rsrc(a.x, a.x_bytes);
@@ -398,31 +526,74 @@ __global__ __launch_bounds__(kThreads) void dw_wave_wgrad_kernel(DwWaveWArgs a) 
 #pragma unroll
     for (int t = 0; t < 9; ++t) acc[t] = 0.f;
 
-    float xv[NPI], yv[NOM];
+    float xv[WIDE ? 1 : NPIB], yv[WIDE ? 1 : NPS][kSeg];
+    v4u x4[WIDE ? NLV : 1], y4[WIDE ? NLV : 1];
     auto fetch = [&](int n) {
+        const int left = n1 - n;   // images of the range still to come: later ones read as zero
         const unsigned xb = (unsigned)((n * a.C + c) * xplane) * ESZ, yb = (unsigned)((n * a.C + c) * yplane) * ESZ;
+        if constexpr (WIDE) {
 #pragma unroll
-        for (int i = 0; i < NPI; ++i) xv[i] = buf_load(xrs, xb + goff[i], tnull);
+            for (int i = 0; i < NLV; ++i) {
+                x4[i] = __builtin_amdgcn_raw_buffer_load_b128(xrs, vpx[i] < left ? xb + vgx[i] : kOob, 0, 0);
+                y4[i] = __builtin_amdgcn_raw_buffer_load_b128(yrs, vpy[i] < left ? yb + vgy[i] : kOob, 0, 0);
+            }
+        } else {
 #pragma unroll
-        for (int o = 0; o < NOM; ++o) yv[o] = buf_load(yrs, yb + yoff[o], tnull);
+            for (int i = 0; i < NPIB; ++i) xv[i] = buf_load(xrs, gpl[i] < left ? xb + goff[i] : kOob, tnull);
+#pragma unroll
+            for (int ps = 0; ps < NPS; ++ps)
+#pragma unroll
+                for (int i = 0; i < kSeg; ++i)
+                    yv[ps][i] = buf_load(yrs, (i < rows[ps] && ypl[ps] < left) ? yb + yo[ps] + (unsigned)(i * a.Q) * ESZ : kOob, tnull);
+        }
     };
     if (n0 < n1) fetch(n0);
-    for (int n = n0; n < n1; ++n) {
-        float yc[NOM];
+    for (int n = n0; n < n1; n += a.PB) {
+        float yc[NPS][kSeg];
+        if constexpr (WIDE) {
 #pragma unroll
-        for (int i = 0; i < NPI; ++i)
-            if (lane + 64 * i < PPS) my[lane + 64 * i] = xv[i];
+            for (int i = 0; i < NLV; ++i) {
 #pragma unroll
-        for (int o = 0; o < NOM; ++o) yc[o] = yv[o];
-        if (n + 1 < n1) fetch(n + 1);
+                for (int k = 0; k < 4; ++k)
+                    if (lo[i][k] >= 0) my[lo[i][k]] = __uint_as_float(x4[i][k]);
+                const int f = lane + 64 * i;
+                if (4 * f < a.PB * yplane)
+                    *reinterpret_cast<float4*>(yl + 4 * f) = make_float4(__uint_as_float(y4[i].x), __uint_as_float(y4[i].y),
+                                                                         __uint_as_float(y4[i].z), __uint_as_float(y4[i].w));
+            }
+            if (n + a.PB < n1) fetch(n + a.PB);
 #pragma unroll
-        for (int o = 0; o < NOM; ++o) {
-            if (o >= a.NO) break;
-            const float* xq = my + xo[o];
+            for (int ps = 0; ps < NPS; ++ps)
 #pragma unroll
-            for (int r = 0; r < 3; ++r)
+                for (int i = 0; i < kSeg; ++i) yc[ps][i] = i < rows[ps] ? yl[yli[ps] + i * a.Q] : 0.f;
+        } else {
 #pragma unroll
-                for (int s = 0; s < 3; ++s) acc[r * 3 + s] = fmaf(yc[o], xq[r * a.PPW + s], acc[r * 3 + s]);
+            for (int i = 0; i < NPIB; ++i)
+                if (lane + 64 * i < a.PB * PPS) my[lane + 64 * i] = xv[i];
+#pragma unroll
+            for (int ps = 0; ps < NPS; ++ps)
+#pragma unroll
+                for (int i = 0; i < kSeg; ++i) yc[ps][i] = yv[ps][i];
+            if (n + a.PB < n1) fetch(n + a.PB);
+        }
+#pragma unroll
+        for (int ps = 0; ps < NPS; ++ps) {
+            if (ps >= a.passes) break;
+            const float* xq = my + win[ps];
+            float xw[(kSeg - 1) * ST + 3][3];
+#pragma unroll
+            for (int r = 0; r < (kSeg - 1) * ST + 3; ++r)
+#pragma unroll
+                for (int s = 0; s < 3; ++s) xw[r][s] = xq[r * a.PPW + s];
+            // rows this lane does not own are skipped outright (their window may be another plane's data)
+#pragma unroll
+            for (int i = 0; i < kSeg; ++i) {
+                if (i >= rows[ps]) continue;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int s = 0; s < 3; ++s) acc[r * 3 + s] = fmaf(yc[ps][i], xw[i * ST + r][s], acc[r * 3 + s]);
+            }
         }
     }
 #pragma unroll
@@ -519,59 +690,85 @@ bool wgrad_args(const Problem& pr, const void* x, const void* dy, DwWArgs& a) {
     return true;
 }
 
-// ---- wave-private variants: host side ----------------------------------------------------------------
-bool wave_shape_ok(const Problem& pr, int pps, int outs) {
+// ---- strip kernels: host side ----------------------------------------------------------------------------
+struct StripPlan {
+    int PB, NSEG, UPP, passes, lds_per_wave, w_off, o_off;
+};
+
+// false when the plane shape does not fit the strip kernels (then the workgroup-level kernels run).
+bool strip_plan(const Problem& pr, int oh, int ow, int pph, int ppw, int stride, int iplane, StripPlan& sp) {
     const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
     if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
-    return pps <= 1024 && outs <= 1024;
-}
-// Outputs per lane and lane stride: NO = ceil(outs/64), LS = ceil(outs/NO).
-void lane_split(int outs, int& no, int& ls) {
-    no = (outs + 63) / 64;
-    ls = (outs + no - 1) / no;
+    const int pps = pph * ppw;
+    if (ow > 64 || pps > 1024) return false;
+    sp.NSEG = (oh + kSeg - 1) / kSeg;
+    sp.UPP = 64 / ow;
+    int pb = 0;
+    for (int cand = 1; cand <= 28 && cand * pps <= 1024 && cand * 9 <= 64 && cand * iplane <= 1024 &&
+                       cand * oh * ow <= 1024; ++cand)
+        if ((cand * sp.NSEG + sp.UPP - 1) / sp.UPP <= 2) pb = cand;
+    if (pb == 0) return false;
+    sp.PB = pb;
+    sp.passes = (pb * sp.NSEG + sp.UPP - 1) / sp.UPP;
+    sp.w_off = (pb * pps + (kSeg * stride + 3) * ppw + 3) & ~3;
+    sp.o_off = (sp.w_off + 9 * pb + 3) & ~3;
+    sp.lds_per_wave = (sp.o_off + pb * oh * ow + 3) & ~3;
+    return true;
 }
 
-bool wave_stencil_args(int pass, const Problem& pr, const void* in0, const void* in1, float* out, DwWaveArgs& a,
-                       int& stride) {
+bool strip_stencil_args(int pass, const Problem& pr, const void* in0, const void* in1, float* out, DwStripArgs& a,
+                        int& stride) {
     DwArgs b{};
     if (!stencil_args(pass, pr, in0, in1, out, b, stride)) return false;
-    const int pps = b.PPH * b.PPW;
-    if (!wave_shape_ok(pr, pps, b.OH * b.OW)) return false;
+    StripPlan sp;
+    if (!strip_plan(pr, b.OH, b.OW, b.PPH, b.PPW, stride, b.IH * b.IW, sp)) return false;
     const unsigned esz = pr.dtype == 0 ? 4 : 2;
     a.src = b.src; a.w = b.w; a.dst = b.dst; a.planes = b.planes; a.C = b.C;
     a.IH = b.IH; a.IW = b.IW; a.OH = b.OH; a.OW = b.OW; a.pad_h = b.pad_h; a.pad_w = b.pad_w;
-    a.PPH = b.PPH; a.PPW = b.PPW; a.inv_ppw = b.inv_ppw; a.inv_ow = b.inv_ow;
-    lane_split(b.OH * b.OW, a.NO, a.LS);
+    a.PPH = b.PPH; a.PPW = b.PPW;
+    a.PB = sp.PB; a.NSEG = sp.NSEG; a.UPP = sp.UPP; a.passes = sp.passes; a.lds_per_wave = sp.lds_per_wave;
+    a.w_off = sp.w_off; a.o_off = sp.o_off;
+    a.inv_ppw = b.inv_ppw; a.inv_pps = b.inv_pps; a.inv_ow = b.inv_ow;
+    a.inv_nseg = 1.0f / sp.NSEG; a.inv_c = 1.0f / pr.C; a.inv_iplane = 1.0f / (b.IH * b.IW); a.inv_iw = 1.0f / b.IW;
     a.flip = b.flip;
+    a.nbatches = (a.planes + sp.PB - 1) / sp.PB;
     a.src_bytes = (unsigned)((size_t)a.planes * a.IH * a.IW * esz);
+    a.w_bytes = (unsigned)((size_t)pr.C * 9 * esz);
     return true;
 }
 
 template <typename T, int ST>
-hipError_t launch_wave_stencil(DwWaveArgs a, hipStream_t st) {
-    const int pps = a.PPH * a.PPW;
-    const bool small = pps <= 256 && a.NO <= 4;
-    const int pb = small ? 4 : 1;
-    a.nbatches = (a.planes + pb - 1) / pb;
+hipError_t launch_strip_stencil(const DwStripArgs& a, hipStream_t st) {
+    // Persistent waves: each keeps one batch in flight while it computes the previous one.
+    // The grid is what is resident at once (256 CUs x the occupancy the register budget allows).
     int grid = (a.nbatches + 3) / 4;
-    if (grid > 4096) grid = 4096;
-    const size_t smem = (size_t)4 * pb * pps * sizeof(float);
-    if (small) dw_wave_stencil_kernel<T, ST, 4, 4, 4><<<grid, kThreads, smem, st>>>(a);
-    else dw_wave_stencil_kernel<T, ST, 16, 16, 1><<<grid, kThreads, smem, st>>>(a);
+    const int resident = 256 * 3;
+    if (grid > resident) grid = resident;
+    const size_t smem = (size_t)4 * a.lds_per_wave * sizeof(float);
+    const bool wide = sizeof(T) == 4 && (a.IH * a.IW) % 4 == 0 && (a.OH * a.OW) % 4 == 0 &&
+                      reinterpret_cast<uintptr_t>(a.src) % 16 == 0 && reinterpret_cast<uintptr_t>(a.dst) % 16 == 0;
+    if (wide) dw_strip_stencil_kernel<T, ST, 16, 2, true><<<grid, kThreads, smem, st>>>(a);
+    else dw_strip_stencil_kernel<T, ST, 16, 2, false><<<grid, kThreads, smem, st>>>(a);
     return hipGetLastError();
 }
 
-bool wave_wgrad_args(const Problem& pr, const void* x, const void* dy, DwWaveWArgs& a) {
+bool strip_wgrad_args(const Problem& pr, const void* x, const void* dy, DwStripWArgs& a) {
     if (!is_depthwise(pr) || pr.R != 3 || pr.S != 3 || pr.sh != pr.sw || pr.sh > 2) return false;
     a.PPH = (pr.P - 1) * pr.sh + 3; a.PPW = (pr.Q - 1) * pr.sh + 3;
-    if (!wave_shape_ok(pr, a.PPH * a.PPW, pr.P * pr.Q)) return false;
-    lane_split(pr.P * pr.Q, a.NO, a.LS);
+    StripPlan sp;
+    if (!strip_plan(pr, pr.P, pr.Q, a.PPH, a.PPW, pr.sh, pr.H * pr.W, sp)) return false;
     const unsigned esz = pr.dtype == 0 ? 4 : 2;
     a.x = x; a.dy = dy;
     a.N = pr.N; a.C = pr.C; a.H = pr.H; a.W = pr.W; a.P = pr.P; a.Q = pr.Q; a.pad_h = pr.ph; a.pad_w = pr.pw;
-    a.inv_ppw = 1.0f / a.PPW; a.inv_q = 1.0f / pr.Q;
-    int nsplit = (8192 + pr.C - 1) / pr.C;   // about 8192 waves in flight cover the HBM latency
+    a.PB = sp.PB; a.NSEG = sp.NSEG; a.UPP = sp.UPP; a.passes = sp.passes; a.lds_per_wave = sp.lds_per_wave;
+    a.w_off = sp.w_off; a.o_off = sp.o_off;
+    a.inv_ppw = 1.0f / a.PPW; a.inv_pps = 1.0f / (a.PPH * a.PPW); a.inv_q = 1.0f / pr.Q; a.inv_nseg = 1.0f / sp.NSEG;
+    a.inv_xplane = 1.0f / (pr.H * pr.W); a.inv_w = 1.0f / pr.W; a.inv_yplane = 1.0f / (pr.P * pr.Q);
+    // One wave per (channel, split): two waves per SIMD (256 CUs x 4 SIMDs x 2) measured best, each
+    // running a long, prefetched image loop.
+    int nsplit = (2048 + pr.C - 1) / pr.C;
     if (nsplit > pr.N) nsplit = pr.N;
+    if (nsplit < 1) nsplit = 1;
     a.nsplit = nsplit;
     a.x_bytes = (unsigned)((size_t)pr.N * pr.C * pr.H * pr.W * esz);
     a.y_bytes = (unsigned)((size_t)pr.N * pr.C * pr.P * pr.Q * esz);
@@ -579,12 +776,13 @@ bool wave_wgrad_args(const Problem& pr, const void* x, const void* dy, DwWaveWAr
 }
 
 template <typename T, int ST>
-hipError_t launch_wave_wgrad(const DwWaveWArgs& a, hipStream_t st) {
-    const int pps = a.PPH * a.PPW;
+hipError_t launch_strip_wgrad(const DwStripWArgs& a, hipStream_t st) {
     const int grid = (a.C * a.nsplit + 3) / 4;
-    const size_t smem = (size_t)4 * pps * sizeof(float);
-    if (pps <= 256 && a.NO <= 4) dw_wave_wgrad_kernel<T, ST, 4, 4><<<grid, kThreads, smem, st>>>(a);
-    else dw_wave_wgrad_kernel<T, ST, 16, 16><<<grid, kThreads, smem, st>>>(a);
+    const size_t smem = (size_t)4 * a.lds_per_wave * sizeof(float);
+    const bool wide = sizeof(T) == 4 && (a.H * a.W) % 4 == 0 && (a.P * a.Q) % 4 == 0 &&
+                      reinterpret_cast<uintptr_t>(a.x) % 16 == 0 && reinterpret_cast<uintptr_t>(a.dy) % 16 == 0;
+    if (wide) dw_strip_wgrad_kernel<T, ST, 16, 2, true><<<grid, kThreads, smem, st>>>(a);
+    else dw_strip_wgrad_kernel<T, ST, 16, 2, false><<<grid, kThreads, smem, st>>>(a);
     return hipGetLastError();
 }
 
@@ -593,8 +791,8 @@ hipError_t launch_wave_wgrad(const DwWaveWArgs& a, hipStream_t st) {
 bool depthwise_supports(int pass, const Problem& pr) {
     if (pass == 2) {
         DwWArgs a{};
-        DwWaveWArgs b{};
-        return wave_wgrad_args(pr, nullptr, nullptr, b) || wgrad_args(pr, nullptr, nullptr, a);
+        DwStripWArgs b{};
+        return strip_wgrad_args(pr, nullptr, nullptr, b) || wgrad_args(pr, nullptr, nullptr, a);
     }
     DwArgs a{};
     int stride;
@@ -603,8 +801,8 @@ bool depthwise_supports(int pass, const Problem& pr) {
 
 size_t depthwise_workspace_bytes(int pass, const Problem& pr) {
     if (pass != 2) return 0;
-    DwWaveWArgs b{};
-    if (wave_wgrad_args(pr, nullptr, nullptr, b)) return b.nsplit > 1 ? (size_t)b.nsplit * pr.C * 9 * sizeof(float) : 0;
+    DwStripWArgs b{};
+    if (strip_wgrad_args(pr, nullptr, nullptr, b)) return b.nsplit > 1 ? (size_t)b.nsplit * pr.C * 9 * sizeof(float) : 0;
     DwWArgs a{};
     if (!wgrad_args(pr, nullptr, nullptr, a)) return 0;
     return a.nsplit > 1 ? (size_t)a.nsplit * pr.C * 9 * sizeof(float) : 0;
@@ -614,12 +812,12 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
                          hipStream_t st) {
     const int count = pr.C * 9;
     if (pass == 2) {
-        DwWaveWArgs b{};
-        if (wave_wgrad_args(pr, in0, in1, b)) {
+        DwStripWArgs b{};
+        if (strip_wgrad_args(pr, in0, in1, b)) {
             b.out = b.nsplit > 1 ? static_cast<float*>(ws) : out;
             hipError_t e;
-            if (pr.dtype == 0) e = pr.sh == 1 ? launch_wave_wgrad<float, 1>(b, st) : launch_wave_wgrad<float, 2>(b, st);
-            else e = pr.sh == 1 ? launch_wave_wgrad<uint16_t, 1>(b, st) : launch_wave_wgrad<uint16_t, 2>(b, st);
+            if (pr.dtype == 0) e = pr.sh == 1 ? launch_strip_wgrad<float, 1>(b, st) : launch_strip_wgrad<float, 2>(b, st);
+            else e = pr.sh == 1 ? launch_strip_wgrad<uint16_t, 1>(b, st) : launch_strip_wgrad<uint16_t, 2>(b, st);
             if (e != hipSuccess || b.nsplit == 1) return e;
             dw_reduce_splits_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, b.nsplit, count);
             return hipGetLastError();
@@ -643,11 +841,11 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
         dw_reduce_splits_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, a.nsplit, count);
         return hipGetLastError();
     }
-    DwWaveArgs wv{};
+    DwStripArgs sa{};
     int stride;
-    if (wave_stencil_args(pass, pr, in0, in1, out, wv, stride)) {
-        if (pr.dtype == 0) return stride == 1 ? launch_wave_stencil<float, 1>(wv, st) : launch_wave_stencil<float, 2>(wv, st);
-        return stride == 1 ? launch_wave_stencil<uint16_t, 1>(wv, st) : launch_wave_stencil<uint16_t, 2>(wv, st);
+    if (strip_stencil_args(pass, pr, in0, in1, out, sa, stride)) {
+        if (pr.dtype == 0) return stride == 1 ? launch_strip_stencil<float, 1>(sa, st) : launch_strip_stencil<float, 2>(sa, st);
+        return stride == 1 ? launch_strip_stencil<uint16_t, 1>(sa, st) : launch_strip_stencil<uint16_t, 2>(sa, st);
     }
     DwArgs a{};
     if (!stencil_args(pass, pr, in0, in1, out, a, stride)) return hipErrorNotSupported;
