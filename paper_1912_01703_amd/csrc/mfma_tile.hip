@@ -20,6 +20,7 @@
 //   * Global loads for chunk i+1 are issued before the MFMA work of chunk i and
 //     land in the other LDS buffer afterwards: one barrier per chunk.
 #include "common.h"
+#include <cstdlib>
 
 namespace miconv {
 namespace {
@@ -37,7 +38,6 @@ struct TileArgs {
     int tiles_h, tiles_w;  // spatial tiles per image
     int fblocks;           // filter blocks per group
     int units;             // N * groups * tiles_h * tiles_w
-    int wvec;              // forward filters may be read four at a time (Rg is a multiple of 4)
     unsigned wgt_bytes;    // size of the filter tensor
 };
 
@@ -46,6 +46,7 @@ struct TileArgs {
 // absent filter) is given the offset kOob and costs neither a branch nor a select on the result.
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v3u __attribute__((ext_vector_type(3)));
 constexpr unsigned kOob = 0x80000000u;  // tensors handled here are smaller than 2 GiB
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
@@ -67,7 +68,8 @@ constexpr int lds_channel_stride(int v, int kq) {
 // T: element type of src and wgt (float, or uint16_t holding bf16).
 // R,S: filter size.  ST: stride.  TH,TW: output tile.  CK: channels per chunk (4, 8, 16 or 32).
 // WF: waves along filters (16 filters each).  WP: waves along pixel blocks.  BWD: backward-data operand mapping.
-template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD>
+// WV: the reduction channels per group are a multiple of 4 (forward filters can be read four values at a time).
+template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, bool WV>
 __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int NT = 64 * WF * WP;
     constexpr int RS = R * S;
@@ -153,51 +155,63 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 
     float xreg[XPT];
 
-    // The chunk's descriptor covers exactly the channels it still has, so a partial last chunk
-    // reads zeros for the channels past the end without any per-element test.
-    auto load_chunk = [&](int ch, float (&an)[RS * KQ]) {
-        const int left = a.Rg - ch * CK;  // reduction channels still to go (< CK only in the last chunk)
-        const rsrc_t xrs = make_rsrc(src + (size_t)ch * CK * plane,
-                                     (unsigned)((left < CK ? left : CK) * plane) * (unsigned)sizeof(T));
-#pragma unroll
-        for (int m = 0; m < XPT; ++m) xreg[m] = buf_load(xrs, goff[m], tnull);
+    // ---- fetching a chunk -------------------------------------------------------------------------
+    // The patch descriptor covers exactly the channels the chunk still has, so a partial last chunk
+    // (or a chunk past the end: zero channels) reads zeros without any per-element test.  The fetch
+    // is cut into single load instructions ("pieces") so that the MFMA loop can issue them a few at
+    // a time: issued in one burst they back up in the address unit and stall every wave.
+    constexpr bool W4 = WV && !BWD && sizeof(T) == 4 && (RS * KQ) % 4 == 0;   // 4 filter values per load
+    constexpr bool W3 = !W4 && sizeof(T) == 4 && RS % 3 == 0;                 // 3 filter values per load
+    constexpr int WPIECES = W4 ? RS * KQ / 4 : (W3 ? RS * KQ / 3 : RS * KQ);
+    constexpr int NPIECES = XPT + WPIECES;
+    auto prepare = [&](int ch, rsrc_t& xrs, unsigned (&wvo)[KQ]) {
+        const int left = a.Rg - ch * CK;  // reduction channels from this chunk on (<= 0: no such chunk)
+        const int have = left <= 0 ? 0 : (left < CK ? left : CK);
+        xrs = make_rsrc(src + (size_t)ch * CK * plane, (unsigned)(have * plane) * (unsigned)sizeof(T));
         const int wb = wbase + ch * wstep_chunk;
-        if constexpr (!BWD && sizeof(T) == 4 && (RS * KQ) % 4 == 0) {
-            if (a.wvec) {
-                // The lane's KQ channels x RS taps are RS*KQ consecutive floats (Rg is a multiple of KQ,
-                // so they are all present or all absent).
-                const unsigned vo = (f_ok && kk * KQ < left) ? (unsigned)wb * 4u : kOob;
 #pragma unroll
-                for (int j = 0; j < RS * KQ / 4; ++j) {
-                    const v4u v = __builtin_amdgcn_raw_buffer_load_b128(wrs, vo + 16u * j, 0, 0);
-                    an[4 * j + 0] = __uint_as_float(v.x);
-                    an[4 * j + 1] = __uint_as_float(v.y);
-                    an[4 * j + 2] = __uint_as_float(v.z);
-                    an[4 * j + 3] = __uint_as_float(v.w);
-                }
-                return;
-            }
+        for (int k4 = 0; k4 < KQ; ++k4)
+            wvo[k4] = (f_ok && kk * KQ + k4 < left) ? (unsigned)(wb + k4 * wstep_k) * (unsigned)sizeof(T) : kOob;
+    };
+    auto issue = [&](int piece, const rsrc_t& xrs, const unsigned (&wvo)[KQ], float (&an)[RS * KQ]) {
+        if (piece < XPT) {
+            xreg[piece] = buf_load(xrs, goff[piece], tnull);
+            return;
         }
+        const int q = piece - XPT;
+        if constexpr (W4) {
+            // forward: the lane's KQ channels x RS taps are RS*KQ consecutive floats (Rg is a multiple
+            // of KQ, so they are all present or all absent)
+            const v4u v = __builtin_amdgcn_raw_buffer_load_b128(wrs, wvo[0] + 16u * q, 0, 0);
+            an[4 * q + 0] = __uint_as_float(v.x);
+            an[4 * q + 1] = __uint_as_float(v.y);
+            an[4 * q + 2] = __uint_as_float(v.z);
+            an[4 * q + 3] = __uint_as_float(v.w);
+        } else if constexpr (W3) {
+            const int k4 = q / (RS / 3), j = q % (RS / 3);
+            const v3u v = __builtin_amdgcn_raw_buffer_load_b96(wrs, wvo[k4] + 12u * j, 0, 0);
 #pragma unroll
-        for (int k4 = 0; k4 < KQ; ++k4) {
-            const unsigned vo = (f_ok && kk * KQ + k4 < left) ? (unsigned)(wb + k4 * wstep_k) * (unsigned)sizeof(T) : kOob;
-#pragma unroll
-            for (int t = 0; t < RS; ++t)
-                an[k4 * RS + t] = buf_load(wrs, vo + (unsigned)((BWD ? RS - 1 - t : t) * sizeof(T)), tnull);
+            for (int e = 0; e < 3; ++e) {
+                const int t = 3 * j + e;   // tap as stored; backward-data uses it rotated by 180 degrees
+                an[k4 * RS + (BWD ? RS - 1 - t : t)] = __uint_as_float(v[e]);
+            }
+        } else {
+            const int k4 = q / RS, t = q % RS;
+            an[k4 * RS + (BWD ? RS - 1 - t : t)] = buf_load(wrs, wvo[k4] + (unsigned)(t * sizeof(T)), tnull);
         }
     };
     auto store_patch = [&](float* buf) {
-        // Everything fetched for the next chunk (patch and filters) was issued a whole chunk of MFMA
-        // work ago; retiring all of it here keeps waits on these loads out of the next MFMA loop.
+        // Everything fetched for the next chunk (patch and filters) was issued during the MFMA loop;
+        // retiring all of it here keeps waits on these loads out of the next MFMA loop.
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 #pragma unroll
         for (int m = 0; m < XPT; ++m)
             if (loff[m] >= 0) buf[loff[m]] = xreg[m];
     };
-    // One "group" = one (tap, reduction channel) pair = NBW MFMAs sharing an A operand.  The B operands
-    // of group g+1 are read from LDS while the MFMAs of group g issue; a scheduling fence after every
-    // group keeps the compiler from undoing that distance or from hoisting more than one group ahead.
-    auto compute = [&](const float* xb, const float (&ac)[RS * KQ]) {
+    // One "group" = one (tap, reduction channel) pair = NBW MFMAs sharing an A operand.  While chunk i
+    // is multiplied out of xb/ac, the pieces of chunk i+1 are issued into xreg/an.
+    auto compute = [&](const float* xb, const float (&ac)[RS * KQ], const rsrc_t& xrs, const unsigned (&wvo)[KQ],
+                       float (&an)[RS * KQ]) {
         constexpr int G = RS * KQ;
         float bq[2][NBW];
 #pragma unroll
@@ -205,18 +219,21 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            if (g + 1 < G) {
-                const int k4 = (g + 1) % KQ, t = (g + 1) / KQ;
-                const int off = k4 * CS + (t / S) * PW + (t % S);
 #pragma unroll
-                for (int i = 0; i < NBW; ++i) bq[(g + 1) & 1][i] = xb[pixoff[i] + off];
-            }
-            __builtin_amdgcn_sched_barrier(0);  // reads of the next group are issued before this group's MFMAs
+            for (int piece = 0; piece < NPIECES; ++piece)
+                if (piece * G / NPIECES == g) issue(piece, xrs, wvo, an);
+            __builtin_amdgcn_sched_barrier(0);
+            const int k4n = (g + 1) % KQ, tn = (g + 1) / KQ;
+            const int off = k4n * CS + (tn / S) * PW + (tn % S);
             const float av = ac[(g % KQ) * RS + g / KQ];
+            // MFMA i of this group, then the LDS read of operand i of the next group: the read issues
+            // while the matrix pipe is busy, and every operand is requested a full group before its use.
 #pragma unroll
-            for (int i = 0; i < NBW; ++i)
+            for (int i = 0; i < NBW; ++i) {
                 acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[g & 1][i], acc[i], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);  // nothing moves across groups
+                if (g + 1 < G) bq[(g + 1) & 1][i] = xb[pixoff[i] + off];
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
 
@@ -224,20 +241,22 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     // is written out for an even and an odd chunk: no register copies, LDS addresses are immediates.
     float A0[RS * KQ], A1[RS * KQ];
     const int nchunks = (a.Rg + CK - 1) / CK;
-    load_chunk(0, A0);
+    rsrc_t xrs;
+    unsigned wvo[KQ];
+    prepare(0, xrs, wvo);
+#pragma unroll
+    for (int piece = 0; piece < NPIECES; ++piece) issue(piece, xrs, wvo, A0);
     store_patch(xs[0]);
     __syncthreads();
     for (int ch = 0; ch < nchunks; ch += 2) {
-        const bool more1 = ch + 1 < nchunks;
-        if (more1) load_chunk(ch + 1, A1);
-        compute(xs[0], A0);
-        if (more1) store_patch(xs[1]);
+        prepare(ch + 1, xrs, wvo);
+        compute(xs[0], A0, xrs, wvo, A1);
+        if (ch + 1 >= nchunks) break;
+        store_patch(xs[1]);
         __syncthreads();
-        if (!more1) break;
-        const bool more2 = ch + 2 < nchunks;
-        if (more2) load_chunk(ch + 2, A0);
-        compute(xs[1], A1);
-        if (more2) store_patch(xs[0]);
+        prepare(ch + 2, xrs, wvo);
+        compute(xs[1], A1, xrs, wvo, A0);
+        if (ch + 2 < nchunks) store_patch(xs[0]);
         __syncthreads();
     }
 
@@ -259,14 +278,17 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 
 template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD>
 hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
+    static_assert(CK == 16 || CK == 8, "the four-at-a-time filter read assumes whole lane groups of channels");
     TileArgs a = base;
     a.tiles_h = (a.OH + TH - 1) / TH;
     a.tiles_w = (a.OW + TW - 1) / TW;
     a.fblocks = (a.Fg + 16 * WF - 1) / (16 * WF);
     a.units = a.N * a.groups * a.tiles_h * a.tiles_w;
-    a.wvec = (a.Rg % 4 == 0);
     const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
-    conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD><<<grid, 64 * WF * WP, 0, st>>>(a);
+    if (a.Rg % (CK / 4) == 0 && a.Rg % 4 == 0)
+        conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true><<<grid, 64 * WF * WP, 0, st>>>(a);
+    else
+        conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, false><<<grid, 64 * WF * WP, 0, st>>>(a);
     return hipGetLastError();
 }
 
@@ -275,7 +297,9 @@ template <typename T, bool BWD>
 bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, bool dry, hipError_t* err) {
     *err = hipSuccess;
     if (R == 3 && S == 3 && stride == 1) {
-        if (!dry) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 1, BWD>(a, st);
+        static const int wp = getenv("MICONV_TILE_WP") ? atoi(getenv("MICONV_TILE_WP")) : 1;
+        if (!dry) *err = wp == 2 ? launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD>(a, st)
+                                 : launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 1, BWD>(a, st);
         return true;
     }
     if (R == 1 && S == 1 && stride == 1) {
@@ -299,14 +323,14 @@ bool make_args(int pass, const Problem& pr, const void* in0, const void* in1, fl
     const unsigned wbytes = (unsigned)((size_t)pr.K * pr.Cg * pr.R * pr.S * esz);
     if (pass == 0) {
         a = TileArgs{in0, in1, out, pr.N, pr.C, pr.H, pr.W, pr.K, pr.P, pr.Q, pr.Kg, pr.Cg, pr.groups,
-                     pr.ph, pr.pw, 0, 0, 0, 0, 0, wbytes};
+                     pr.ph, pr.pw, 0, 0, 0, 0, wbytes};
         stride = pr.sh;
         return true;
     }
     if (pass == 1) {
         if (pr.sh != 1) return false;
         a = TileArgs{in0, in1, out, pr.N, pr.K, pr.P, pr.Q, pr.C, pr.H, pr.W, pr.Cg, pr.Kg, pr.groups,
-                     pr.R - 1 - pr.ph, pr.S - 1 - pr.pw, 0, 0, 0, 0, 0, wbytes};
+                     pr.R - 1 - pr.ph, pr.S - 1 - pr.pw, 0, 0, 0, 0, wbytes};
         stride = 1;
         return true;
     }
