@@ -35,7 +35,8 @@ struct WgradArgs {
     int pad_h, pad_w;
     int tiles_h, tiles_w;
     int kblocks, cblocks;  // per group
-    int nsplit, stages;    // stages = tiles_h*tiles_w*N, ordered tile-major
+    int nsplit, stages;    // stages = tiles_h*tiles_w*img_stages, ordered tile-major
+    int img_stages;        // ceil(N / images per stage)
     int total_wgs;
 };
 
@@ -57,7 +58,9 @@ constexpr int next_2_mod_4(int v) { return v + ((6 - v % 4) % 4); }   // smalles
 constexpr int next_odd(int v) { return v | 1; }
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS>
+// IMG: images per stage.  With 4 waves sharing the pixel steps of a stage, two 14x14 images (98 steps)
+// divide almost evenly (25/25/24/24) where one (49 steps) leaves three waves idle for a step in 13.
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG>
 __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     constexpr int NT = 64 * WK * WC * WS;
     constexpr int RS = R * S;
@@ -65,15 +68,17 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     constexpr int NPX = TH * TW;
     static_assert(NPX % 4 == 0, "tile pixels must fill whole MFMA steps");
     static_assert(KB % WK == 0 && CB % WC == 0, "wave grid must divide the block grid");
-    constexpr int NSTEPS = NPX / 4;
+    constexpr int SPI = NPX / 4;           // steps per image
+    constexpr int NSTEPS = IMG * SPI;
     constexpr int KBW = KB / WK, CBW = CB / WC;
     // LDS row strides: 16 lanes x 2 adjacent pixels must fall in 32 distinct banks.
     constexpr int DS = next_2_mod_4(NPX);
     constexpr int XS = ST == 1 ? next_2_mod_4(PSZ) : next_odd(PSZ);
-    constexpr int YE = 16 * KB * NPX, XE = 16 * CB * PSZ;
-    constexpr int YPT = (YE + NT - 1) / NT, XPT = (XE + NT - 1) / NT;
-    constexpr int STAGE = 16 * KB * DS + 16 * CB * XS;   // floats per LDS buffer
-    constexpr int OUTSZ = 16 * KB * 16 * CB * RS;        // accumulator elements of the workgroup
+    constexpr int YE = 16 * KB * NPX, XE = 16 * CB * PSZ;               // per image
+    constexpr int YPT = (IMG * YE + NT - 1) / NT, XPT = (IMG * XE + NT - 1) / NT;
+    constexpr int YIMG = 16 * KB * DS, XIMG = 16 * CB * XS;             // floats per image in LDS
+    constexpr int STAGE = IMG * (YIMG + XIMG);                          // floats per LDS buffer
+    constexpr int OUTSZ = 16 * KB * 16 * CB * RS;                       // accumulator elements of the workgroup
     constexpr int LDSF = cmax(2 * STAGE, WS * OUTSZ);
     static_assert(LDSF * 4 <= 160 * 1024, "LDS budget");
 
@@ -96,15 +101,19 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     const int wk = wave % WK, wc = (wave / WK) % WC, ws = wave / (WK * WC);
 
     const int k0 = kbi * 16 * KB, c0 = cbi * 16 * CB;   // within the group
+    // a stage = IMG consecutive images of one tile; stages are ordered tile-major
     const int s_begin = (int)((long long)a.stages * sp / a.nsplit);
     const int s_end = (int)((long long)a.stages * (sp + 1) / a.nsplit);
 
     const T* xg = static_cast<const T*>(a.x);
     const T* dyg = static_cast<const T*>(a.dy);
     const int xplane = a.H * a.W, yplane = a.P * a.Q;
+    const T* const tnull = nullptr;
 
     // ---- gather plans (depend on the tile position only) -----------------------------------------
-    unsigned ygo[YPT], xgo[XPT];   // byte offsets inside the stage's image, kOob = reads as zero
+    // Offsets are relative to the first image of the stage; image i of the stage adds i whole images.
+    // Images past the end of the batch fall outside the descriptor and read as zero.
+    unsigned ygo[YPT], xgo[XPT];   // byte offsets, kOob = reads as zero
     auto plan = [&](int tile) {
         const int ti = tile / a.tiles_w, tj = tile - ti * a.tiles_w;
         const int p0 = ti * TH, q0 = tj * TW;
@@ -112,53 +121,58 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
 #pragma unroll
         for (int m = 0; m < YPT; ++m) {
             const int e = tid + NT * m;
-            const int kl = e / NPX, px = e - kl * NPX;
+            const int im = e / YE, ei = e - im * YE;
+            const int kl = ei / NPX, px = ei - kl * NPX;
             const int th = px / TW, tw = px - th * TW;
             const int p = p0 + th, q = q0 + tw;
-            const bool ok = e < YE && k0 + kl < a.Kg && p < a.P && q < a.Q;
-            ygo[m] = ok ? (unsigned)((g * a.Kg + k0 + kl) * yplane + p * a.Q + q) * (unsigned)sizeof(T) : kOob;
+            const bool ok = e < IMG * YE && k0 + kl < a.Kg && p < a.P && q < a.Q;
+            ygo[m] = ok ? (unsigned)((im * a.K + g * a.Kg + k0 + kl) * yplane + p * a.Q + q) * (unsigned)sizeof(T) : kOob;
         }
 #pragma unroll
         for (int m = 0; m < XPT; ++m) {
             const int e = tid + NT * m;
-            const int cl = e / PSZ, rem = e - cl * PSZ;
+            const int im = e / XE, ei = e - im * XE;
+            const int cl = ei / PSZ, rem = ei - cl * PSZ;
             const int ph = rem / PW, pw = rem - ph * PW;
             const int h = h0 + ph, v = v0 + pw;
-            const bool ok = e < XE && c0 + cl < a.Cg && h >= 0 && h < a.H && v >= 0 && v < a.W;
-            xgo[m] = ok ? (unsigned)((g * a.Cg + c0 + cl) * xplane + h * a.W + v) * (unsigned)sizeof(T) : kOob;
+            const bool ok = e < IMG * XE && c0 + cl < a.Cg && h >= 0 && h < a.H && v >= 0 && v < a.W;
+            xgo[m] = ok ? (unsigned)((im * a.C + g * a.Cg + c0 + cl) * xplane + h * a.W + v) * (unsigned)sizeof(T) : kOob;
         }
     };
 
+    // The fetch of a stage is cut into single load instructions ("pieces") that the MFMA loop issues
+    // a few at a time; issued in one burst they back up in the address unit and stall every wave.
     float yreg[YPT], xreg[XPT];
-    const T* const tnull = nullptr;
-    const unsigned ybytes = (unsigned)(a.K * yplane) * (unsigned)sizeof(T);
-    const unsigned xbytes = (unsigned)(a.C * xplane) * (unsigned)sizeof(T);
-    auto fetch = [&](int stage) {
-        const int n = stage % a.N;
-        const rsrc_t yrs = make_rsrc(dyg + (size_t)n * a.K * yplane, ybytes);
-        const rsrc_t xrs = make_rsrc(xg + (size_t)n * a.C * xplane, xbytes);
-#pragma unroll
-        for (int m = 0; m < YPT; ++m) yreg[m] = buf_load(yrs, ygo[m], tnull);
-#pragma unroll
-        for (int m = 0; m < XPT; ++m) xreg[m] = buf_load(xrs, xgo[m], tnull);
+    constexpr int NPIECES = YPT + XPT;
+    auto descriptors = [&](int stage, rsrc_t& yrs, rsrc_t& xrs) {
+        const int n = (stage % a.img_stages) * IMG;          // first image of the stage
+        const int left = stage < s_end ? a.N - n : 0;        // images from here to the end of the batch
+        const int have = left < IMG ? left : IMG;
+        yrs = make_rsrc(dyg + (size_t)n * a.K * yplane, (unsigned)(have * a.K * yplane) * (unsigned)sizeof(T));
+        xrs = make_rsrc(xg + (size_t)n * a.C * xplane, (unsigned)(have * a.C * xplane) * (unsigned)sizeof(T));
+    };
+    auto issue = [&](int piece, const rsrc_t& yrs, const rsrc_t& xrs) {
+        if (piece < YPT) yreg[piece] = buf_load(yrs, ygo[piece], tnull);
+        else xreg[piece - YPT] = buf_load(xrs, xgo[piece - YPT], tnull);
     };
     auto stash = [&](int buf) {
-        // The stage in flight was requested a whole stage of MFMA work ago: retire all of it here so
-        // that no wait on these loads ends up inside the MFMA loop.
+        // Everything fetched for the next stage was issued during the MFMA loop; retiring all of it
+        // here keeps waits on these loads out of the next MFMA loop.
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-        float* ys = lds + buf * STAGE;
-        float* xs = ys + 16 * KB * DS;
+        float* sb = lds + buf * STAGE;
 #pragma unroll
         for (int m = 0; m < YPT; ++m) {
             const int e = tid + NT * m;
-            const int kl = e / NPX, px = e - kl * NPX;
-            if (e < YE) ys[kl * DS + px] = yreg[m];
+            const int im = e / YE, ei = e - im * YE;
+            const int kl = ei / NPX, px = ei - kl * NPX;
+            if (e < IMG * YE) sb[im * YIMG + kl * DS + px] = yreg[m];
         }
 #pragma unroll
         for (int m = 0; m < XPT; ++m) {
             const int e = tid + NT * m;
-            const int cl = e / PSZ, rem = e - cl * PSZ;
-            if (e < XE) xs[cl * XS + rem] = xreg[m];
+            const int im = e / XE, ei = e - im * XE;
+            const int cl = ei / PSZ, rem = ei - cl * PSZ;
+            if (e < IMG * XE) sb[IMG * YIMG + im * XIMG + cl * XS + rem] = xreg[m];
         }
     };
 
@@ -175,62 +189,69 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     int yoff[ITER], xoff[ITER];
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-        int px = 4 * (ws + WS * i) + kk;
-        if (px >= NPX) px = NPX - 1;  // only in the step that waves with ws >= IT_REM skip; keeps the read in range
+        int t = ws + WS * i;
+        if (t >= NSTEPS) t = NSTEPS - 1;   // only in the step that waves with ws >= IT_REM skip; keeps the read in range
+        const int im = t / SPI;
+        const int px = 4 * (t - im * SPI) + kk;
         const int th = px / TW, tw = px - th * TW;
-        yoff[i] = (16 * (wk * KBW) + li) * DS + px;
-        xoff[i] = 16 * KB * DS + (16 * (wc * CBW) + li) * XS + th * ST * PW + tw * ST;
+        yoff[i] = im * YIMG + (16 * (wk * KBW) + li) * DS + px;
+        xoff[i] = IMG * YIMG + im * XIMG + (16 * (wc * CBW) + li) * XS + th * ST * PW + tw * ST;
     }
 
-    // One step = KBW*CBW*RS MFMAs on KBW + CBW*RS operands.  The operands of step i+1 are read from
-    // LDS before the MFMAs of step i issue; scheduling fences keep the compiler from undoing that.
-    auto multiply = [&](const float* sb) {
-        float av[2][KBW], bv[2][CBW * RS];
-        auto read_step = [&](int i, float (&ao)[KBW], float (&bo)[CBW * RS]) {
-#pragma unroll
-            for (int ib = 0; ib < KBW; ++ib) ao[ib] = sb[yoff[i] + ib * 16 * DS];
-#pragma unroll
-            for (int j = 0; j < CBW; ++j)
-#pragma unroll
-                for (int r = 0; r < R; ++r)
-#pragma unroll
-                    for (int s2 = 0; s2 < S; ++s2) bo[j * RS + r * S + s2] = sb[xoff[i] + j * 16 * XS + r * PW + s2];
+    // One step = NM = KBW*CBW*RS MFMAs on NR = KBW + CBW*RS operands.  Operand r of step i+1 is read
+    // from LDS right behind MFMA r of step i, so reads issue while the matrix pipe is busy and every
+    // operand is requested a full step before its use; scheduling fences pin that order.
+    constexpr int NM = KBW * CBW * RS, NR = KBW + CBW * RS;
+    auto multiply = [&](const float* sb, const rsrc_t& yrs, const rsrc_t& xrs) {
+        float ops[2][NR];   // [0..KBW): dy operands, then CBW*RS x operands
+        auto read_op = [&](int i, int r) -> float {
+            if (r < KBW) return sb[yoff[i] + r * 16 * DS];
+            const int q = r - KBW, j = q / RS, t = q % RS;
+            return sb[xoff[i] + j * 16 * XS + (t / S) * PW + (t % S)];
         };
-        read_step(0, av[0], bv[0]);
+#pragma unroll
+        for (int r = 0; r < NR; ++r) ops[0][r] = read_op(0, r);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < ITER; ++i) {
-            if (i + 1 < ITER) read_step(i + 1, av[(i + 1) & 1], bv[(i + 1) & 1]);
+#pragma unroll
+            for (int piece = 0; piece < NPIECES; ++piece)
+                if (piece * ITER / NPIECES == i) issue(piece, yrs, xrs);
             __builtin_amdgcn_sched_barrier(0);
-            if (i < IT_FULL || ws < IT_REM) {  // wave-uniform
+            const bool next = i + 1 < ITER;
+            if (i < IT_FULL || ws < IT_REM) {  // wave-uniform; false only in the last step
 #pragma unroll
-                for (int j = 0; j < CBW; ++j)
-#pragma unroll
-                    for (int t = 0; t < RS; ++t)
-#pragma unroll
-                        for (int ib = 0; ib < KBW; ++ib)
-                            acc[ib][j][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i & 1][ib], bv[i & 1][j * RS + t],
-                                                                                 acc[ib][j][t], 0, 0, 0);
+                for (int m = 0; m < (NM > NR ? NM : NR); ++m) {
+                    if (m < NM) {
+                        const int j = m / (RS * KBW), t = (m / KBW) % RS, ib = m % KBW;
+                        acc[ib][j][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ops[i & 1][ib], ops[i & 1][KBW + j * RS + t],
+                                                                             acc[ib][j][t], 0, 0, 0);
+                    }
+                    if (next && m < NR) ops[(i + 1) & 1][m] = read_op(i + 1, m);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
     if (s_begin < s_end) {
-        int tile = s_begin / a.N;
+        int tile = s_begin / a.img_stages;
         plan(tile);
-        fetch(s_begin);
+        rsrc_t yrs, xrs;
+        descriptors(s_begin, yrs, xrs);
+#pragma unroll
+        for (int piece = 0; piece < NPIECES; ++piece) issue(piece, yrs, xrs);
         stash(0);
         __syncthreads();
         int buf = 0;
         for (int stage = s_begin; stage < s_end; ++stage) {
             const bool more = stage + 1 < s_end;
             if (more) {
-                const int nt = (stage + 1) / a.N;
+                const int nt = (stage + 1) / a.img_stages;
                 if (nt != tile) { tile = nt; plan(tile); }
-                fetch(stage + 1);
             }
-            multiply(lds + buf * STAGE);
+            descriptors(stage + 1, yrs, xrs);   // past the split's end: empty descriptors, every load reads zero
+            multiply(lds + buf * STAGE, yrs, xrs);
             if (more) stash(buf ^ 1);
             __syncthreads();
             buf ^= 1;
@@ -281,13 +302,14 @@ struct Plan {
     size_t ws_bytes;
 };
 
-template <int TH, int TW, int KB, int CB>
+template <int TH, int TW, int KB, int CB, int IMG>
 Plan make_plan(const Problem& pr, WgradArgs& a) {
     a.tiles_h = (pr.P + TH - 1) / TH;
     a.tiles_w = (pr.Q + TW - 1) / TW;
     a.kblocks = (pr.Kg + 16 * KB - 1) / (16 * KB);
     a.cblocks = (pr.Cg + 16 * CB - 1) / (16 * CB);
-    a.stages = a.tiles_h * a.tiles_w * pr.N;
+    a.img_stages = (pr.N + IMG - 1) / IMG;
+    a.stages = a.tiles_h * a.tiles_w * a.img_stages;
     const int blocks = a.kblocks * a.cblocks * pr.groups;
     // Enough workgroups to cover the 256 CUs, but never more partial buffers than stages.
     int nsplit = (256 + blocks - 1) / blocks;
@@ -299,19 +321,19 @@ Plan make_plan(const Problem& pr, WgradArgs& a) {
     return Plan{nsplit, nsplit > 1 ? nsplit * wbytes : 0};
 }
 
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS>
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG>
 hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st,
                         bool dry, size_t* ws_bytes) {
     WgradArgs a{};
     a.x = x; a.dy = dy;
     a.N = pr.N; a.C = pr.C; a.H = pr.H; a.W = pr.W; a.K = pr.K; a.P = pr.P; a.Q = pr.Q;
     a.Cg = pr.Cg; a.Kg = pr.Kg; a.groups = pr.groups; a.pad_h = pr.ph; a.pad_w = pr.pw;
-    const Plan pl = make_plan<TH, TW, KB, CB>(pr, a);
+    const Plan pl = make_plan<TH, TW, KB, CB, IMG>(pr, a);
     *ws_bytes = pl.ws_bytes;
     if (dry) return hipSuccess;
     a.out = pl.nsplit > 1 ? static_cast<float*>(ws) : dw;
     const int grid = ((a.total_wgs + 7) / 8) * 8;
-    wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
+    wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.nsplit == 1) return e;
     const size_t count = (size_t)pr.K * pr.Cg * pr.R * pr.S;
@@ -327,15 +349,15 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
     *ws_bytes = 0;
     if (pr.sh != pr.sw) return false;
     if (pr.R == 3 && pr.S == 3 && pr.sh == 1) {
-        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 4>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 4, 2>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 3 && pr.S == 3 && pr.sh == 2) {
-        *err = launch_wgrad<T, 3, 3, 2, 14, 14, 1, 1, 1, 1, 4>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 3, 3, 2, 14, 14, 1, 1, 1, 1, 4, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1) {
-        *err = launch_wgrad<T, 1, 1, 1, 2, 14, 8, 8, 2, 2, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 1, 1, 1, 2, 14, 8, 8, 2, 2, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     return false;
