@@ -213,6 +213,9 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     auto compute = [&](const float* xb, const float (&ac)[RS * KQ], const rsrc_t& xrs, const unsigned (&wvo)[KQ],
                        float (&an)[RS * KQ]) {
         constexpr int G = RS * KQ;
+        // The next chunk's pieces all go out in the first half of the groups, so that the remaining MFMA
+        // work covers their latency before store_patch() waits for them.
+        constexpr int ISSUE_GROUPS = G >= 2 ? G / 2 : 1;
         float bq[2][NBW];
 #pragma unroll
         for (int i = 0; i < NBW; ++i) bq[0][i] = xb[pixoff[i]];
@@ -221,17 +224,18 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         for (int g = 0; g < G; ++g) {
 #pragma unroll
             for (int piece = 0; piece < NPIECES; ++piece)
-                if (piece * G / NPIECES == g) issue(piece, xrs, wvo, an);
+                if (piece * ISSUE_GROUPS / NPIECES == g) issue(piece, xrs, wvo, an);
             __builtin_amdgcn_sched_barrier(0);
             const int k4n = (g + 1) % KQ, tn = (g + 1) / KQ;
             const int off = k4n * CS + (tn / S) * PW + (tn % S);
             const float av = ac[(g % KQ) * RS + g / KQ];
-            // MFMA i of this group, then the LDS read of operand i of the next group: the read issues
-            // while the matrix pipe is busy, and every operand is requested a full group before its use.
+            // The LDS read of operand i of the next group, then MFMA i of this group: the read issues while
+            // the matrix pipe is busy with MFMA i-1, every operand is requested a full group before its
+            // use, and (being issued first) the read cannot be given a register the MFMA still reads.
 #pragma unroll
             for (int i = 0; i < NBW; ++i) {
-                acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[g & 1][i], acc[i], 0, 0, 0);
                 if (g + 1 < G) bq[(g + 1) & 1][i] = xb[pixoff[i] + off];
+                acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[g & 1][i], acc[i], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }

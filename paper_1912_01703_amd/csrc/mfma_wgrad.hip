@@ -20,11 +20,13 @@
 // buffer that reduce_splits_kernel sums in split order: no floating-point
 // atomics anywhere, so dw is bit-reproducible.
 #include "common.h"
+#include <cstdlib>
 
 namespace miconv {
 namespace {
 
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 struct WgradArgs {
     const void* x;
@@ -38,6 +40,7 @@ struct WgradArgs {
     int nsplit, stages;    // stages = tiles_h*tiles_w*img_stages, ordered tile-major
     int img_stages;        // ceil(N / images per stage)
     int total_wgs;
+    int dbg;
 };
 
 // Buffer loads return 0 for a byte offset at or beyond the descriptor's size: elements that must
@@ -60,7 +63,10 @@ constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
 // IMG: images per stage.  With 4 waves sharing the pixel steps of a stage, two 14x14 images (98 steps)
 // divide almost evenly (25/25/24/24) where one (49 steps) leaves three waves idle for a step in 13.
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG>
+// WIDE: the tile is the whole output plane and the planes are multiples of 4 floats: dy rows and x
+// planes are then read as 16-byte pieces (a quarter of the address-unit work of 4-byte reads) and the
+// x values scattered into the zero-bordered patch, whose border words are written once.
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG, bool WIDE>
 __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     constexpr int NT = 64 * WK * WC * WS;
     constexpr int RS = R * S;
@@ -75,7 +81,8 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     constexpr int DS = next_2_mod_4(NPX);
     constexpr int XS = ST == 1 ? next_2_mod_4(PSZ) : next_odd(PSZ);
     constexpr int YE = 16 * KB * NPX, XE = 16 * CB * PSZ;               // per image
-    constexpr int YPT = (IMG * YE + NT - 1) / NT, XPT = (IMG * XE + NT - 1) / NT;
+    constexpr int YPT = WIDE ? (IMG * YE / 4 + NT - 1) / NT : (IMG * YE + NT - 1) / NT;   // load pieces per thread
+    constexpr int XPT = WIDE ? (IMG * 16 * CB * (NPX * ST * ST) / 4 + NT - 1) / NT : (IMG * XE + NT - 1) / NT;
     constexpr int YIMG = 16 * KB * DS, XIMG = 16 * CB * XS;             // floats per image in LDS
     constexpr int STAGE = IMG * (YIMG + XIMG);                          // floats per LDS buffer
     constexpr int OUTSZ = 16 * KB * 16 * CB * RS;                       // accumulator elements of the workgroup
@@ -114,7 +121,37 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     // Offsets are relative to the first image of the stage; image i of the stage adds i whole images.
     // Images past the end of the batch fall outside the descriptor and read as zero.
     unsigned ygo[YPT], xgo[XPT];   // byte offsets, kOob = reads as zero
+    int ylo[WIDE ? YPT : 1], xlo[WIDE ? XPT : 1][4];   // wide path: where the pieces land in a stage's LDS buffer
     auto plan = [&](int tile) {
+        if constexpr (WIDE) {
+            // whole planes: H*W == NPX*ST*ST is not required, only that an x plane is xplane floats
+            const int xq = xplane / 4;   // float4 per x plane
+#pragma unroll
+            for (int m = 0; m < YPT; ++m) {
+                const int f = tid + NT * m;
+                const int im = f / (YE / 4), ei = 4 * f - im * YE;
+                const int kl = ei / NPX, px = ei - kl * NPX;
+                const bool ok = f < IMG * YE / 4 && k0 + kl < a.Kg;
+                ygo[m] = ok ? (unsigned)((im * a.K + g * a.Kg + k0 + kl) * yplane + px) * 4u : kOob;
+                ylo[m] = f < IMG * YE / 4 ? im * YIMG + kl * DS + px : -1;
+            }
+#pragma unroll
+            for (int m = 0; m < XPT; ++m) {
+                const int f = tid + NT * m;
+                const int pc = f / xq, rem = 4 * (f - pc * xq);      // plane (image-major, then channel), element
+                const int im = pc / (16 * CB), cl = pc - im * 16 * CB;
+                const bool ok = pc < IMG * 16 * CB && c0 + cl < a.Cg;
+                xgo[m] = ok ? (unsigned)((im * a.C + g * a.Cg + c0 + cl) * xplane + rem) * 4u : kOob;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int ih = (rem + e) / a.W, iw = (rem + e) - ih * a.W;
+                    const int ph = ih + a.pad_h, pw = iw + a.pad_w;
+                    const bool in = pc < IMG * 16 * CB && ph >= 0 && ph < PH && pw >= 0 && pw < PW;
+                    xlo[m][e] = in ? IMG * YIMG + im * XIMG + cl * XS + ph * PW + pw : -1;
+                }
+            }
+            return;
+        }
         const int ti = tile / a.tiles_w, tj = tile - ti * a.tiles_w;
         const int p0 = ti * TH, q0 = tj * TW;
         const int h0 = p0 * ST - a.pad_h, v0 = q0 * ST - a.pad_w;
@@ -142,7 +179,8 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
 
     // The fetch of a stage is cut into single load instructions ("pieces") that the MFMA loop issues
     // a few at a time; issued in one burst they back up in the address unit and stall every wave.
-    float yreg[YPT], xreg[XPT];
+    float yreg[WIDE ? 1 : YPT], xreg[WIDE ? 1 : XPT];
+    v4u yreg4[WIDE ? YPT : 1], xreg4[WIDE ? XPT : 1];
     constexpr int NPIECES = YPT + XPT;
     auto descriptors = [&](int stage, rsrc_t& yrs, rsrc_t& xrs) {
         const int n = (stage % a.img_stages) * IMG;          // first image of the stage
@@ -152,14 +190,33 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
         xrs = make_rsrc(xg + (size_t)n * a.C * xplane, (unsigned)(have * a.C * xplane) * (unsigned)sizeof(T));
     };
     auto issue = [&](int piece, const rsrc_t& yrs, const rsrc_t& xrs) {
-        if (piece < YPT) yreg[piece] = buf_load(yrs, ygo[piece], tnull);
-        else xreg[piece - YPT] = buf_load(xrs, xgo[piece - YPT], tnull);
+        if constexpr (WIDE) {
+            if (piece < YPT) yreg4[piece] = __builtin_amdgcn_raw_buffer_load_b128(yrs, ygo[piece], 0, 0);
+            else xreg4[piece - YPT] = __builtin_amdgcn_raw_buffer_load_b128(xrs, xgo[piece - YPT], 0, 0);
+        } else {
+            if (piece < YPT) yreg[piece] = buf_load(yrs, ygo[piece], tnull);
+            else xreg[piece - YPT] = buf_load(xrs, xgo[piece - YPT], tnull);
+        }
     };
     auto stash = [&](int buf) {
         // Everything fetched for the next stage was issued during the MFMA loop; retiring all of it
         // here keeps waits on these loads out of the next MFMA loop.
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
         float* sb = lds + buf * STAGE;
+        if constexpr (WIDE) {
+#pragma unroll
+            for (int m = 0; m < YPT; ++m)
+                if (ylo[m] >= 0) {   // rows are 8-byte aligned in LDS (DS is even, px a multiple of 4)
+                    *reinterpret_cast<float2*>(sb + ylo[m]) = make_float2(__uint_as_float(yreg4[m].x), __uint_as_float(yreg4[m].y));
+                    *reinterpret_cast<float2*>(sb + ylo[m] + 2) = make_float2(__uint_as_float(yreg4[m].z), __uint_as_float(yreg4[m].w));
+                }
+#pragma unroll
+            for (int m = 0; m < XPT; ++m)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (xlo[m][e] >= 0) sb[xlo[m][e]] = __uint_as_float(xreg4[m][e]);
+            return;
+        }
 #pragma unroll
         for (int m = 0; m < YPT; ++m) {
             const int e = tid + NT * m;
@@ -199,9 +256,12 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     }
 
     // One step = NM = KBW*CBW*RS MFMAs on NR = KBW + CBW*RS operands.  Operand r of step i+1 is read
-    // from LDS right behind MFMA r of step i, so reads issue while the matrix pipe is busy and every
+    // from LDS right before MFMA r of step i, so reads issue while the matrix pipe is busy and every
     // operand is requested a full step before its use; scheduling fences pin that order.
     constexpr int NM = KBW * CBW * RS, NR = KBW + CBW * RS;
+    // The next stage's pieces all go out in the first third of the steps, so that the rest of the
+    // stage's MFMA work covers their latency before stash() waits for them.
+    constexpr int ISSUE_STEPS = ITER >= 3 ? ITER / 3 : 1;
     auto multiply = [&](const float* sb, const rsrc_t& yrs, const rsrc_t& xrs) {
         float ops[2][NR];   // [0..KBW): dy operands, then CBW*RS x operands
         auto read_op = [&](int i, int r) -> float {
@@ -216,24 +276,32 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
         for (int i = 0; i < ITER; ++i) {
 #pragma unroll
             for (int piece = 0; piece < NPIECES; ++piece)
-                if (piece * ITER / NPIECES == i) issue(piece, yrs, xrs);
+                if (piece * ISSUE_STEPS / NPIECES == i) issue(piece, yrs, xrs);
             __builtin_amdgcn_sched_barrier(0);
             const bool next = i + 1 < ITER;
             if (i < IT_FULL || ws < IT_REM) {  // wave-uniform; false only in the last step
 #pragma unroll
                 for (int m = 0; m < (NM > NR ? NM : NR); ++m) {
+                    // The read goes first: the register it fills must differ from the ones the MFMA
+                    // behind it still reads (a read that overwrote an operand of the MFMA just issued
+                    // would have to wait for that MFMA to fetch it).
+                    if (next && m < NR) ops[(i + 1) & 1][m] = read_op(i + 1, m);
                     if (m < NM) {
                         const int j = m / (RS * KBW), t = (m / KBW) % RS, ib = m % KBW;
                         acc[ib][j][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ops[i & 1][ib], ops[i & 1][KBW + j * RS + t],
                                                                              acc[ib][j][t], 0, 0, 0);
                     }
-                    if (next && m < NR) ops[(i + 1) & 1][m] = read_op(i + 1, m);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
     };
 
+    if constexpr (WIDE) {
+        // patch borders (and everything else) start as zero; the scatter only writes interior words
+        for (int e = tid; e < 2 * STAGE; e += NT) lds[e] = 0.f;
+        __syncthreads();
+    }
     if (s_begin < s_end) {
         int tile = s_begin / a.img_stages;
         plan(tile);
@@ -251,10 +319,11 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
                 if (nt != tile) { tile = nt; plan(tile); }
             }
             descriptors(stage + 1, yrs, xrs);   // past the split's end: empty descriptors, every load reads zero
+            if (a.dbg & 1) { yrs = make_rsrc(dyg, 0); xrs = make_rsrc(xg, 0); }
             multiply(lds + buf * STAGE, yrs, xrs);
-            if (more) stash(buf ^ 1);
-            __syncthreads();
-            buf ^= 1;
+            if (more && !(a.dbg & 2)) stash(buf ^ 1);
+            if (!(a.dbg & 4)) __syncthreads();
+            if (!(a.dbg & 8)) buf ^= 1;
         }
     }
 
@@ -332,8 +401,12 @@ hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float*
     *ws_bytes = pl.ws_bytes;
     if (dry) return hipSuccess;
     a.out = pl.nsplit > 1 ? static_cast<float*>(ws) : dw;
+    a.dbg = getenv("MICONV_DBG") ? atoi(getenv("MICONV_DBG")) : 0;
     const int grid = ((a.total_wgs + 7) / 8) * 8;
-    wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
+    const bool wide = sizeof(T) == 4 && pr.P == TH && pr.Q == TW && (pr.H * pr.W) % 4 == 0 &&
+                      pr.H * pr.W == TH * TW * ST * ST;
+    if (wide) wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, true><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
+    else wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, false><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.nsplit == 1) return e;
     const size_t count = (size_t)pr.K * pr.Cg * pr.R * pr.S;
