@@ -20,7 +20,6 @@
 // buffer that reduce_splits_kernel sums in split order: no floating-point
 // atomics anywhere, so dw is bit-reproducible.
 #include "common.h"
-#include <cstdlib>
 
 namespace miconv {
 namespace {
@@ -40,7 +39,6 @@ struct WgradArgs {
     int nsplit, stages;    // stages = tiles_h*tiles_w*img_stages, ordered tile-major
     int img_stages;        // ceil(N / images per stage)
     int total_wgs;
-    int dbg;
 };
 
 // Buffer loads return 0 for a byte offset at or beyond the descriptor's size: elements that must
@@ -319,11 +317,10 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
                 if (nt != tile) { tile = nt; plan(tile); }
             }
             descriptors(stage + 1, yrs, xrs);   // past the split's end: empty descriptors, every load reads zero
-            if (a.dbg & 1) { yrs = make_rsrc(dyg, 0); xrs = make_rsrc(xg, 0); }
             multiply(lds + buf * STAGE, yrs, xrs);
-            if (more && !(a.dbg & 2)) stash(buf ^ 1);
-            if (!(a.dbg & 4)) __syncthreads();
-            if (!(a.dbg & 8)) buf ^= 1;
+            if (more) stash(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
         }
     }
 
@@ -390,7 +387,9 @@ Plan make_plan(const Problem& pr, WgradArgs& a) {
     return Plan{nsplit, nsplit > 1 ? nsplit * wbytes : 0};
 }
 
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG>
+// WS: pixel-step shares (waves) on the 16-byte fetch path; WSN: on the 4-byte path, which needs more
+// registers per thread and therefore runs one wave per SIMD.
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int WSN, int IMG>
 hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st,
                         bool dry, size_t* ws_bytes) {
     WgradArgs a{};
@@ -401,12 +400,11 @@ hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float*
     *ws_bytes = pl.ws_bytes;
     if (dry) return hipSuccess;
     a.out = pl.nsplit > 1 ? static_cast<float*>(ws) : dw;
-    a.dbg = getenv("MICONV_DBG") ? atoi(getenv("MICONV_DBG")) : 0;
     const int grid = ((a.total_wgs + 7) / 8) * 8;
     const bool wide = sizeof(T) == 4 && pr.P == TH && pr.Q == TW && (pr.H * pr.W) % 4 == 0 &&
                       pr.H * pr.W == TH * TW * ST * ST;
     if (wide) wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, true><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
-    else wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, false><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
+    else wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WSN, IMG, false><<<grid, 64 * WK * WC * WSN, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.nsplit == 1) return e;
     const size_t count = (size_t)pr.K * pr.Cg * pr.R * pr.S;
@@ -422,15 +420,15 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
     *ws_bytes = 0;
     if (pr.sh != pr.sw) return false;
     if (pr.R == 3 && pr.S == 3 && pr.sh == 1) {
-        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 4, 2>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 8, 4, 2>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 3 && pr.S == 3 && pr.sh == 2) {
-        *err = launch_wgrad<T, 3, 3, 2, 14, 14, 1, 1, 1, 1, 4, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 3, 3, 2, 14, 14, 1, 1, 1, 1, 4, 4, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1) {
-        *err = launch_wgrad<T, 1, 1, 1, 2, 14, 8, 8, 2, 2, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 1, 1, 1, 2, 14, 8, 8, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     return false;
