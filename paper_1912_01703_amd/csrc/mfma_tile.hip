@@ -20,7 +20,6 @@
 //   * Global loads for chunk i+1 are issued before the MFMA work of chunk i and
 //     land in the other LDS buffer afterwards: one barrier per chunk.
 #include "common.h"
-#include <cstdlib>
 
 namespace miconv {
 namespace {
@@ -149,6 +148,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         pixoff[i] = kk * KQ * CS + th * ST * PW + tw * ST;
     }
 
+    const bool last_ok = wp + WP * (NBW - 1) < NB;   // does this wave own a block in its last slot?
     v4f acc[NBW];
 #pragma unroll
     for (int i = 0; i < NBW; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
@@ -234,6 +234,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
             // use, and (being issued first) the read cannot be given a register the MFMA still reads.
 #pragma unroll
             for (int i = 0; i < NBW; ++i) {
+                if (NB % WP != 0 && i == NBW - 1 && !last_ok) continue;   // wave-uniform: this wave has one block fewer
                 if (g + 1 < G) bq[(g + 1) & 1][i] = xb[pixoff[i] + off];
                 acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[g & 1][i], acc[i], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
@@ -301,9 +302,8 @@ template <typename T, bool BWD>
 bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, bool dry, hipError_t* err) {
     *err = hipSuccess;
     if (R == 3 && S == 3 && stride == 1) {
-        static const int wp = getenv("MICONV_TILE_WP") ? atoi(getenv("MICONV_TILE_WP")) : 1;
-        if (!dry) *err = wp == 2 ? launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD>(a, st)
-                                 : launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 1, BWD>(a, st);
+        // eight waves: two per SIMD, so one wave's LDS and barrier waits are covered by the other's MFMAs
+        if (!dry) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD>(a, st);
         return true;
     }
     if (R == 1 && S == 1 && stride == 1) {
