@@ -39,6 +39,10 @@ hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, f
 bool tile_supports(int pass, const Problem& pr);
 hipError_t tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, hipStream_t st);
 
+// Strided backward-data on the tiled kernel, one launch per output phase (mfma_tile_phase.hip).
+bool tile_phase_supports(const Problem& pr);
+hipError_t tile_phase_run(const Problem& pr, const void* dy, const void* w, float* dx, hipStream_t st);
+
 // Backward-weight kernels (mfma_wgrad.hip).  ws_bytes receives the partial-sum buffer size.
 bool wgrad_supports(const Problem& pr, size_t* ws_bytes);
 hipError_t wgrad_run(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st);

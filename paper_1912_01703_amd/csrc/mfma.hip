@@ -6,7 +6,8 @@ static bool is_depthwise(const Problem& pr) { return pr.groups == pr.C && pr.gro
 
 bool mfma_supports(int pass, const Problem& pr) {
     if (is_depthwise(pr)) return false;  // one input channel per filter: nothing to contract
-    if (pass == 0 || pass == 1) return tile_supports(pass, pr);
+    if (pass == 0) return tile_supports(pass, pr);
+    if (pass == 1) return tile_supports(pass, pr) || tile_phase_supports(pr);
     size_t ws;
     return wgrad_supports(pr, &ws);
 }
@@ -18,7 +19,8 @@ size_t mfma_workspace_bytes(int pass, const Problem& pr) {
 }
 
 hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws, hipStream_t st) {
-    if (pass == 0 || pass == 1) return tile_run(pass, pr, a, b, out, st);
+    if (pass == 0) return tile_run(pass, pr, a, b, out, st);
+    if (pass == 1) return tile_supports(pass, pr) ? tile_run(pass, pr, a, b, out, st) : tile_phase_run(pr, a, b, out, st);
     return wgrad_run(pr, a, b, out, ws, st);
 }
 

@@ -64,8 +64,10 @@ MFMA = [
     ("m3x3u", 2, 21, 14, 14, 35, 3, 3, 1, 1, 1),
     ("m1x1c", 3, 200, 14, 14, 136, 1, 1, 1, 0, 1),    # several 128-wide blocks with ragged edges
     ("m3x3n", 9, 16, 14, 14, 16, 3, 3, 1, 1, 1),      # more images than one split holds
-    ("m3x3s2", 2, 32, 28, 28, 32, 3, 3, 2, 1, 1),     # stride 2: backward-data is not on this path
-    ("m3x3s2b", 1, 16, 31, 27, 20, 3, 3, 2, 1, 1),
+    ("m3x3s2", 2, 32, 28, 28, 32, 3, 3, 2, 1, 1),     # stride 2: backward-data runs once per output phase
+    ("m3x3s2b", 1, 16, 31, 27, 20, 3, 3, 2, 1, 1),    # odd sizes: phases of different extent
+    ("m3x3s2c", 2, 16, 16, 16, 24, 3, 3, 2, 0, 1),    # no padding: the last input row/column feeds nothing
+    ("m3x3s2g", 1, 32, 14, 14, 32, 3, 3, 2, 1, 2),
 ]
 
 
@@ -75,8 +77,25 @@ def test_mfma_shapes(row, dtype):
     from paper_1912_01703_amd import binding as mc
     name, N, C, H, W, K, R, S, st, pd, g = row
     L = wl.custom_layer(name, N, C, H, W, K, R, S, st, pd, g, seed=2000 + MFMA.index(row))
-    passes = ("fwd", "bwd_weight") if st != 1 else pu.PASSES
-    pu.check_layer_full(L, dtype, passes=passes, algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+    pu.check_layer_full(L, dtype, algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+
+
+PHASED = [
+    # name      N   C   H   W   K   R   S  stride pad groups      backward-data only (per-phase MFMA launches)
+    ("p5x5s2", 2, 16, 20, 20, 16, 5, 5, 2, 2, 1),
+    ("p11s4", 2, 3, 63, 63, 16, 11, 11, 4, 2, 1),     # AlexNet-like: 16 phases of 3x3 / 3x2 / 2x3 / 2x2 taps
+    ("p3x3s3", 1, 8, 17, 15, 8, 3, 3, 3, 1, 1),       # stride == filter size: every phase has one tap
+    ("p4x2s2", 2, 8, 12, 13, 12, 4, 2, (2, 1), (1, 0), 1),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("row", PHASED, ids=[r[0] for r in PHASED])
+def test_strided_bwd_data_phases(row, dtype):
+    from paper_1912_01703_amd import binding as mc
+    name, N, C, H, W, K, R, S, st, pd, g = row
+    L = wl.custom_layer(name, N, C, H, W, K, R, S, st, pd, g, seed=4000 + PHASED.index(row))
+    pu.check_layer_full(L, dtype, passes=("bwd_data",), algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
 
 
 DW = [
