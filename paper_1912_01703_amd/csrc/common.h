@@ -43,6 +43,12 @@ hipError_t tile_run(int pass, const Problem& pr, const void* in0, const void* in
 bool tile_phase_supports(const Problem& pr);
 hipError_t tile_phase_run(const Problem& pr, const void* dy, const void* w, float* dx, hipStream_t st);
 
+// Few-input-channel, large strided filter layers (mfma_smallc.hip): forward and backward-weight.
+bool smallc_supports(int pass, const Problem& pr);
+size_t smallc_workspace_bytes(int pass, const Problem& pr);
+hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
+                      hipStream_t st);
+
 // Backward-weight kernels (mfma_wgrad.hip).  ws_bytes receives the partial-sum buffer size.
 bool wgrad_supports(const Problem& pr, size_t* ws_bytes);
 hipError_t wgrad_run(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st);

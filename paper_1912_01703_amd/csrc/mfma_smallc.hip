@@ -1,0 +1,371 @@
+// Convolutions with very few input channels and a large, strided filter (the first layer of an
+// AlexNet-style network: C = 3, 11x11, stride 4) on the fp32 matrix cores.
+//
+// With C = 3 there is no channel dimension worth contracting over, so the MFMA K dimension runs
+// along the filter row instead: one step multiplies 4 consecutive taps s = 4u .. 4u+3 of one (c, r)
+// filter row.  The whole input patch of a tile (all C channels) sits in LDS; lane group kk reads the
+// patch at "+kk", so the per-step part of every LDS address is a compile-time immediate.  A filter
+// row of S taps takes ceil(S/4) steps, the taps past S carrying zero weights.
+//
+//   forward          M = 16 filters (A: weights, held in registers for the whole kernel),
+//                    N = 16 output pixels (B: patch), K = 4 taps.
+//   backward-weight  M = 16 filters (A: dy), N = 16 taps of one (c, r) filter row (B: patch, 11 of
+//                    the 16 columns are real taps), K = 4 output pixels of one output row.
+//                    Stages (image x pixel tile) are shared out over the workgroups; the partial
+//                    filters are summed afterwards in a fixed order.
+#include "common.h"
+
+namespace miconv {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr unsigned kOob = 0x80000000u;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const float*) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0));
+}
+__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const uint16_t*) {
+    return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_raw_buffer_load_b16(r, byte_off, 0, 0)) << 16);
+}
+
+struct SmallArgs {
+    const void* x;
+    const void* w;     // forward: filters; backward-weight: dy
+    float* out;        // forward: y; backward-weight: dw or partial buffer [nsplit][K*C*R*S]
+    int N, H, W, K, P, Q;
+    int pad_h, pad_w;
+    int tiles_h, tiles_w;
+    int kblocks;       // blocks of 64 filters
+    int nsplit, stages;
+    unsigned x_bytes, w_bytes;
+};
+
+// ---------------------------------------------------------------------------------------- forward
+template <typename T, int C, int R, int S, int ST, int TH, int TW>
+__global__ __launch_bounds__(256) void smallc_fwd_kernel(SmallArgs a) {
+    constexpr int NT = 256;
+    constexpr int SU = (S + 3) / 4;                 // steps per filter row
+    constexpr int NSTEP = C * R * SU;
+    constexpr int PH = (TH - 1) * ST + R;
+    constexpr int PWR = (TW - 1) * ST + S;          // columns that hold data
+    constexpr int PW = (TW - 1) * ST + 4 * SU;      // ... plus the columns the zero-weight taps read
+    constexpr int CS = PH * PW;
+    constexpr int XE = C * CS;
+    constexpr int XPT = (XE + NT - 1) / NT;
+    constexpr int NPX = TH * TW;
+    constexpr int NB = (NPX + 15) / 16;
+
+    __shared__ float patch[XE];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15, kk = lane >> 4;
+    int u = blockIdx.x;
+    const int kb = u % a.kblocks; u /= a.kblocks;
+    const int tj = u % a.tiles_w; u /= a.tiles_w;
+    const int ti = u % a.tiles_h;
+    const int n = u / a.tiles_h;
+    const int p0 = ti * TH, q0 = tj * TW;
+    const int h0 = p0 * ST - a.pad_h, v0 = q0 * ST - a.pad_w;
+    const T* const tnull = nullptr;
+
+    // ---- the tile's input patch, all channels: global -> registers -> LDS ---------------------------
+    const rsrc_t xrs = make_rsrc(static_cast<const T*>(a.x) + (size_t)n * C * a.H * a.W,
+                                 (unsigned)(C * a.H * a.W) * (unsigned)sizeof(T));
+    float xv[XPT];
+#pragma unroll
+    for (int m = 0; m < XPT; ++m) {
+        const int e = tid + NT * m;
+        const int c = e / CS, rem = e - c * CS;
+        const int ph = rem / PW, pw = rem - ph * PW;
+        const int h = h0 + ph, v = v0 + pw;
+        const bool ok = e < XE && pw < PWR && h >= 0 && h < a.H && v >= 0 && v < a.W;
+        xv[m] = buf_load(xrs, ok ? (unsigned)((c * a.H + h) * a.W + v) * (unsigned)sizeof(T) : kOob, tnull);
+    }
+
+    // ---- this lane's filter values: w[f][c][r][4u+kk], zero past the end of a filter row -----------
+    const int f = kb * 64 + wave * 16 + li;
+    const rsrc_t wrs = make_rsrc(a.w, a.w_bytes);
+    float wa[NSTEP];
+#pragma unroll
+    for (int st = 0; st < NSTEP; ++st) {
+        const int cr = st / SU, uu = st - cr * SU;
+        const int s = 4 * uu + kk;
+        const bool ok = f < a.K && s < S;
+        wa[st] = buf_load(wrs, ok ? (unsigned)((f * C * R + cr) * S + s) * (unsigned)sizeof(T) : kOob, tnull);
+    }
+#pragma unroll
+    for (int m = 0; m < XPT; ++m)
+        if (tid + NT * m < XE) patch[tid + NT * m] = xv[m];
+    __syncthreads();
+
+    int pixoff[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        int j = 16 * i + li;
+        if (j >= NPX) j = 0;
+        const int th = j / TW, tw = j - th * TW;
+        pixoff[i] = th * ST * PW + tw * ST + kk;
+    }
+    v4f acc[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    // Operand i of the next step is read from LDS right before MFMA i of this step.
+    float bq[2][NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) bq[0][i] = patch[pixoff[i]];
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int st = 0; st < NSTEP; ++st) {
+        const int sn = st + 1;
+        const int crn = sn / SU, un = sn - crn * SU;
+        const int off = (crn / R) * CS + (crn % R) * PW + 4 * un;
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            if (sn < NSTEP) bq[sn & 1][i] = patch[pixoff[i] + off];
+            acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[st], bq[st & 1][i], acc[i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // ---- D[f = 4*kk+v][pixel = li] ---------------------------------------------------------------------
+    const int fq = kb * 64 + wave * 16 + 4 * kk;
+    float* y = a.out + (size_t)n * a.K * a.P * a.Q;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        const int j = 16 * i + li;
+        if (j >= NPX) continue;
+        const int th = j / TW, tw = j - th * TW;
+        const int p = p0 + th, q = q0 + tw;
+        if (p >= a.P || q >= a.Q) continue;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            if (fq + v < a.K) y[((size_t)(fq + v) * a.P + p) * a.Q + q] = acc[i][v];
+    }
+}
+
+// -------------------------------------------------------------------------------- backward-weight
+// Workgroup = 64 filters (one 16-filter block per wave) x all C*R filter rows, for a contiguous run
+// of stages; stage = one image x TH output rows x TQ4*4 output columns.
+template <typename T, int C, int R, int S, int ST, int TH, int TQ4>
+__global__ __launch_bounds__(256) void smallc_wgrad_kernel(SmallArgs a) {
+    constexpr int NT = 256;
+    static_assert(S <= 16, "one MFMA column block per filter row");
+    constexpr int TW = 4 * TQ4;                     // output columns of a tile
+    constexpr int PH = (TH - 1) * ST + R;
+    constexpr int PWR = (TW - 1) * ST + S;          // columns that hold data
+    constexpr int PW = (TW - 1) * ST + 16;          // the 16-tap column block reads up to here
+    constexpr int CS = PH * PW;
+    constexpr int XE = C * CS;
+    constexpr int YS = TH * TW + 2;                 // dy row stride in LDS: 2 mod 4 keeps the A reads conflict-free
+    constexpr int YE = 64 * TH * TW;
+    constexpr int XPT = (XE + NT - 1) / NT, YPT = (YE + NT - 1) / NT;
+    constexpr int STAGE = XE + 64 * YS;
+    constexpr int NROW = C * R;                     // accumulator blocks per wave
+    constexpr int OUTSZ = 64 * NROW * 16;
+    constexpr int LDSF = 2 * STAGE > OUTSZ ? 2 * STAGE : OUTSZ;
+    static_assert(LDSF * 4 <= 160 * 1024, "LDS budget");
+    static_assert((TH * TW) % 4 == 0, "whole MFMA steps");
+
+    __shared__ float lds[LDSF];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 15, kk = lane >> 4;
+    const int kb = blockIdx.x % a.kblocks, sp = blockIdx.x / a.kblocks;
+    const int s_begin = (int)((long long)a.stages * sp / a.nsplit);
+    const int s_end = (int)((long long)a.stages * (sp + 1) / a.nsplit);
+    const int tiles = a.tiles_h * a.tiles_w;
+    const T* const tnull = nullptr;
+    const rsrc_t xrs = make_rsrc(a.x, a.x_bytes);
+    const rsrc_t yrs = make_rsrc(a.w, a.w_bytes);   // dy
+
+    float xv[XPT], yv[YPT];
+    auto fetch = [&](int stage) {
+        const int n = stage / tiles, t = stage - n * tiles;
+        const int ti = t / a.tiles_w, tj = t - ti * a.tiles_w;
+        const int p0 = ti * TH, q0 = tj * TW;
+        const int h0 = p0 * ST - a.pad_h, v0 = q0 * ST - a.pad_w;
+        const bool live = stage < s_end;
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) {
+            const int e = tid + NT * m;
+            const int c = e / CS, rem = e - c * CS;
+            const int ph = rem / PW, pw = rem - ph * PW;
+            const int h = h0 + ph, v = v0 + pw;
+            const bool ok = live && e < XE && pw < PWR && h >= 0 && h < a.H && v >= 0 && v < a.W;
+            xv[m] = buf_load(xrs, ok ? (unsigned)(((n * C + c) * a.H + h) * a.W + v) * (unsigned)sizeof(T) : kOob, tnull);
+        }
+#pragma unroll
+        for (int m = 0; m < YPT; ++m) {
+            const int e = tid + NT * m;
+            const int kl = e / (TH * TW), px = e - kl * (TH * TW);
+            const int th = px / TW, tw = px - th * TW;
+            const int k = kb * 64 + kl, p = p0 + th, q = q0 + tw;
+            const bool ok = live && e < YE && k < a.K && p < a.P && q < a.Q;
+            yv[m] = buf_load(yrs, ok ? (unsigned)(((n * a.K + k) * a.P + p) * a.Q + q) * (unsigned)sizeof(T) : kOob, tnull);
+        }
+    };
+    auto stash = [&](int buf) {
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        float* xs = lds + buf * STAGE;
+        float* ys = xs + XE;
+#pragma unroll
+        for (int m = 0; m < XPT; ++m)
+            if (tid + NT * m < XE) xs[tid + NT * m] = xv[m];
+#pragma unroll
+        for (int m = 0; m < YPT; ++m) {
+            const int e = tid + NT * m;
+            const int kl = e / (TH * TW), px = e - kl * (TH * TW);
+            if (e < YE) ys[kl * YS + px] = yv[m];
+        }
+    };
+
+    v4f acc[NROW];
+#pragma unroll
+    for (int i = 0; i < NROW; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    // step = (output row th, column quad uq): pixel = th*TW + 4*uq + kk
+    constexpr int NSTEPS = TH * TQ4;
+    const int yoff = (wave * 16 + li) * YS + kk;    // A: dy[k = li][pixel]
+    const int xoff = kk * ST + li;                  // B: patch[.. + q*ST + s], q = 4*uq + kk, s = li
+    auto multiply = [&](const float* xs) {
+        const float* ys = xs + XE;
+        float av[2], bv[2][NROW];
+        auto read_ops = [&](int step, float& ao, float (&bo)[NROW], int m) {
+            const int th = step / TQ4, uq = step - th * TQ4;
+            if (m == 0) ao = ys[yoff + th * TW + 4 * uq];
+            const int c = m / R, r = m - c * R;
+            bo[m] = xs[xoff + c * CS + (th * ST + r) * PW + 4 * uq * ST];
+        };
+#pragma unroll
+        for (int m = 0; m < NROW; ++m) read_ops(0, av[0], bv[0], m);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int step = 0; step < NSTEPS; ++step) {
+#pragma unroll
+            for (int m = 0; m < NROW; ++m) {
+                if (step + 1 < NSTEPS) read_ops(step + 1, av[(step + 1) & 1], bv[(step + 1) & 1], m);
+                acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[step & 1], bv[step & 1][m], acc[m], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    if (s_begin < s_end) {
+        fetch(s_begin);
+        stash(0);
+        __syncthreads();
+        int buf = 0;
+        for (int stage = s_begin; stage < s_end; ++stage) {
+            fetch(stage + 1);   // past the end of this workgroup's run: all zeros, never used
+            multiply(lds + buf * STAGE);
+            if (stage + 1 < s_end) stash(buf ^ 1);
+            __syncthreads();
+            buf ^= 1;
+        }
+    }
+
+    // ---- write the block: LDS transpose to dw order [k][c][r][s], coalesced stores ----------------------
+    __syncthreads();
+#pragma unroll
+    for (int m = 0; m < NROW; ++m)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            lds[((wave * 16 + 4 * kk + v) * NROW + m) * 16 + li] = acc[m][v];   // [k local][c*R+r][s (16 wide)]
+    __syncthreads();
+    float* out = a.out + (a.nsplit > 1 ? (size_t)sp * a.K * C * R * S : 0);
+    for (int o = tid; o < 64 * NROW * S; o += NT) {
+        const int kl = o / (NROW * S), rem = o - kl * (NROW * S);
+        const int row = rem / S, s = rem - row * S;
+        const int k = kb * 64 + kl;
+        if (k < a.K) out[(size_t)k * NROW * S + rem] = lds[(kl * NROW + row) * 16 + s];
+    }
+}
+
+__global__ __launch_bounds__(256) void smallc_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
+                                                            int nsplit, int count) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    float sum = 0.f;
+    for (int s0 = 0; s0 < nsplit; s0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = s0 + k < nsplit ? part[(size_t)(s0 + k) * count + i] : 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sum += v[k];
+    }
+    dw[i] = sum;
+}
+
+bool shape_ok(const Problem& pr) {
+    const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
+    if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
+    return pr.groups == 1 && pr.C == 3 && pr.R == 11 && pr.S == 11 && pr.sh == 4 && pr.sw == 4;
+}
+
+constexpr int kFwdTH = 2, kFwdTW = 55;       // forward tile: two full rows of a 55-wide output
+constexpr int kWgTH = 2, kWgTQ4 = 14;        // backward-weight stage: two rows x 56 columns
+
+void fill(const Problem& pr, SmallArgs& a) {
+    a.N = pr.N; a.H = pr.H; a.W = pr.W; a.K = pr.K; a.P = pr.P; a.Q = pr.Q; a.pad_h = pr.ph; a.pad_w = pr.pw;
+    a.kblocks = (pr.K + 63) / 64;
+    const unsigned esz = pr.dtype == 0 ? 4 : 2;
+    a.x_bytes = (unsigned)((size_t)pr.N * pr.C * pr.H * pr.W * esz);
+}
+
+int wgrad_splits(const Problem& pr, const SmallArgs& a) {
+    int nsplit = 256 / a.kblocks;   // one workgroup per CU
+    if (nsplit > a.stages) nsplit = a.stages;
+    return nsplit < 1 ? 1 : nsplit;
+}
+
+}  // namespace
+
+bool smallc_supports(int pass, const Problem& pr) { return (pass == 0 || pass == 2) && shape_ok(pr); }
+
+size_t smallc_workspace_bytes(int pass, const Problem& pr) {
+    if (pass != 2 || !shape_ok(pr)) return 0;
+    SmallArgs a{};
+    fill(pr, a);
+    a.tiles_h = (pr.P + kWgTH - 1) / kWgTH; a.tiles_w = (pr.Q + 4 * kWgTQ4 - 1) / (4 * kWgTQ4);
+    a.stages = pr.N * a.tiles_h * a.tiles_w;
+    const int ns = wgrad_splits(pr, a);
+    return ns > 1 ? (size_t)ns * pr.K * pr.C * pr.R * pr.S * sizeof(float) : 0;
+}
+
+hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
+                      hipStream_t st) {
+    if (!smallc_supports(pass, pr)) return hipErrorNotSupported;
+    const unsigned esz = pr.dtype == 0 ? 4 : 2;
+    SmallArgs a{};
+    fill(pr, a);
+    a.x = in0;
+    if (pass == 0) {
+        a.w = in1; a.out = out;
+        a.w_bytes = (unsigned)((size_t)pr.K * pr.C * pr.R * pr.S * esz);
+        a.tiles_h = (pr.P + kFwdTH - 1) / kFwdTH; a.tiles_w = (pr.Q + kFwdTW - 1) / kFwdTW;
+        const int grid = pr.N * a.tiles_h * a.tiles_w * a.kblocks;
+        if (pr.dtype == 0) smallc_fwd_kernel<float, 3, 11, 11, 4, kFwdTH, kFwdTW><<<grid, 256, 0, st>>>(a);
+        else smallc_fwd_kernel<uint16_t, 3, 11, 11, 4, kFwdTH, kFwdTW><<<grid, 256, 0, st>>>(a);
+        return hipGetLastError();
+    }
+    a.w = in1;   // dy
+    a.w_bytes = (unsigned)((size_t)pr.N * pr.K * pr.P * pr.Q * esz);
+    a.tiles_h = (pr.P + kWgTH - 1) / kWgTH; a.tiles_w = (pr.Q + 4 * kWgTQ4 - 1) / (4 * kWgTQ4);
+    a.stages = pr.N * a.tiles_h * a.tiles_w;
+    a.nsplit = wgrad_splits(pr, a);
+    a.out = a.nsplit > 1 ? static_cast<float*>(ws) : out;
+    const int grid = a.kblocks * a.nsplit;
+    if (pr.dtype == 0) smallc_wgrad_kernel<float, 3, 11, 11, 4, kWgTH, kWgTQ4><<<grid, 256, 0, st>>>(a);
+    else smallc_wgrad_kernel<uint16_t, 3, 11, 11, 4, kWgTH, kWgTQ4><<<grid, 256, 0, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.nsplit == 1) return e;
+    const int count = pr.K * pr.C * pr.R * pr.S;
+    smallc_reduce_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, a.nsplit, count);
+    return hipGetLastError();
+}
+
+}  // namespace miconv

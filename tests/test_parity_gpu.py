@@ -98,6 +98,23 @@ def test_strided_bwd_data_phases(row, dtype):
     pu.check_layer_full(L, dtype, passes=("bwd_data",), algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
 
 
+SMALLC = [
+    # name      N   H    W    K  pad     3 input channels, 11x11 filter, stride 4 (AlexNet-style first layer)
+    ("a11a", 2, 63, 63, 64, 2),
+    ("a11b", 3, 51, 75, 40, 2),      # ragged tiles, K not a multiple of 64
+    ("a11c", 1, 227, 227, 16, 0),    # no padding, full-width rows
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("row", SMALLC, ids=[r[0] for r in SMALLC])
+def test_small_channel_large_filter(row, dtype):
+    from paper_1912_01703_amd import binding as mc
+    name, N, H, W, K, pd = row
+    L = wl.custom_layer(name, N, 3, H, W, K, 11, 11, 4, pd, 1, seed=5000 + SMALLC.index(row))
+    pu.check_layer_full(L, dtype, algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+
+
 DW = [
     # name    N   C   H   W  stride pad
     ("dw14", 3, 40, 14, 14, 1, 1),
