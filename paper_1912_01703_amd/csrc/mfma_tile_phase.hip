@@ -33,9 +33,11 @@ Phase make_phase(int a, int st, int R, int pad, int H) {
     return p;
 }
 
-template <typename T, int JH, int JW>
-hipError_t launch_phase(TileArgs a, hipStream_t st) {
-    constexpr int TH = 14, TW = 14, CK = 16, WF = 4, WP = 1;
+// WF x WP waves: 4 x 1 (64 destination channels per workgroup) or, when the layer has at most 16
+// destination channels per group (backward-data of a first layer), 1 x 4 so that no wave is idle.
+template <typename T, int JH, int JW, int WF, int WP>
+hipError_t launch_phase_waves(TileArgs a, hipStream_t st) {
+    constexpr int TH = 14, TW = 14, CK = 16;
     a.tiles_h = (a.OH + TH - 1) / TH;
     a.tiles_w = (a.OW + TW - 1) / TW;
     a.fblocks = (a.Fg + 16 * WF - 1) / (16 * WF);
@@ -43,6 +45,11 @@ hipError_t launch_phase(TileArgs a, hipStream_t st) {
     const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
     conv_tile_kernel<T, JH, JW, 1, TH, TW, CK, WF, WP, true, false, true><<<grid, 64 * WF * WP, 0, st>>>(a);
     return hipGetLastError();
+}
+
+template <typename T, int JH, int JW>
+hipError_t launch_phase(const TileArgs& a, hipStream_t st) {
+    return a.Fg <= 16 ? launch_phase_waves<T, JH, JW, 1, 4>(a, st) : launch_phase_waves<T, JH, JW, 4, 1>(a, st);
 }
 
 template <typename T>
