@@ -23,6 +23,12 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}   # dense MFMA, MI355X published
 PEAK_HBM_GBS = 8000.0
 PASSES = ("fwd", "bwd_data", "bwd_weight")
+# HBM bytes per launch (read + written), from rocprofv3 FETCH_SIZE / WRITE_SIZE runs scaled by a plain
+# copy of known size; see profiles/conv2d_hbm_traffic_pmc.md for the commands and the raw counters.
+MEASURED_TRAFFIC = {
+    ("2a", "f32"): {"fwd": 44.9e6, "bwd_data": 45.2e6, "bwd_weight": 79.7e6},
+    ("5a", "f32"): {"fwd": 102.9e6, "bwd_data": 102.9e6, "bwd_weight": 105.2e6},
+}
 METRIC = "conv fwd+bwd TFLOP/s and % FP32 MFMA peak (ResNet-50 3x3 layer)"
 
 
@@ -34,6 +40,9 @@ def parse():
     ap.add_argument("--layer", default="2a")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run --steps plain device-to-device copies of MIB mebibytes "
+                         "(a kernel of known HBM traffic, used to scale the rocprofv3 FETCH_SIZE/WRITE_SIZE counters)")
     ap.add_argument("--rotate", type=int, default=0,
                     help="number of distinct buffer sets cycled between steps (0: auto; "
                          "bandwidth-bound layers use enough to exceed the 256 MB Infinity Cache)")
@@ -90,6 +99,16 @@ def main():
     if not torch.cuda.is_available():
         sys.stderr.write("bench.py: no GPU visible\n")
         sys.exit(3)
+    if a.copy_calibration > 0:
+        nbytes = a.copy_calibration << 20
+        src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(a.steps):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": nbytes, "bytes_written_per_copy": nbytes,
+                          "copies": a.steps}), flush=True)
+        return
     L = wl.LAYERS[a.layer]
     code = mc.BF16_F32ACC if a.dtype == "bf16" else mc.F32
     in_bytes = 2 if a.dtype == "bf16" else 4
@@ -159,17 +178,19 @@ def main():
                         "tflops": L.flops / (pass_ms[p] * 1e-3) / 1e12,
                         "gbs": algorithmic_bytes(L, name, in_bytes) / (pass_ms[p] * 1e-3) / 1e9}
     dom = int(np.argmax(pass_ms))
+    traffic = MEASURED_TRAFFIC.get((a.layer, a.dtype), {}).get(PASSES[dom])
     if depthwise:
         ach = passes[PASSES[dom]]["gbs"]
         roof = {"bound": "hbm", "kernel": PASSES[dom], "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": None,
+                "frac": ach / PEAK_HBM_GBS, "traffic": traffic,
                 "algorithmic_bytes_per_launch": algorithmic_bytes(L, PASSES[dom], in_bytes),
                 "avg_launch_ms": pass_ms[dom], "buffer_sets_rotated": nsets}
     else:
         ach = passes[PASSES[dom]]["tflops"]
         peak = PEAK_TFLOPS[a.dtype]
         roof = {"bound": "mfma", "kernel": PASSES[dom], "achieved": ach, "peak": peak, "unit": "TFLOP/s",
-                "frac": ach / peak, "traffic": None, "algorithmic_flops_per_launch": L.flops,
+                "frac": ach / peak, "traffic": traffic, "algorithmic_flops_per_launch": L.flops,
+                "algorithmic_bytes_per_launch": algorithmic_bytes(L, PASSES[dom], in_bytes),
                 "avg_launch_ms": pass_ms[dom]}
 
     out = {

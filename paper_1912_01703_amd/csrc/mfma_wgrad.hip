@@ -39,6 +39,7 @@ struct WgradArgs {
     int nsplit, stages;    // stages = tiles_h*tiles_w*img_stages, ordered tile-major
     int img_stages;        // ceil(N / images per stage)
     int total_wgs;
+    int xk, xc;            // blocks of one XCD form an xk x xc rectangle of the (k, c) block grid (0: linear runs)
 };
 
 // Buffer loads return 0 for a byte offset at or beyond the descriptor's size: elements that must
@@ -92,14 +93,25 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     // ---- which output block / split ----------------------------------------------------------
     // Workgroup ids are dealt round-robin to the 8 XCDs; giving each XCD a contiguous run of
     // block ids makes the blocks that share dy tiles and x patches share an L2.
-    const int per_xcd = (a.total_wgs + 7) / 8;
-    const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (L >= a.total_wgs) return;
-    int u = L;
-    const int cbi = u % a.cblocks; u /= a.cblocks;
-    const int kbi = u % a.kblocks; u /= a.kblocks;
-    const int g = u % a.groups;
-    const int sp = u / a.groups;
+    // A rectangle of blocks reads xk dy tiles and xc x patches per stage, so the squarer it is the
+    // less each L2 has to fetch from memory.
+    int cbi, kbi, g, sp;
+    if (a.xk > 0) {
+        const int xcd = blockIdx.x & 7, l = blockIdx.x >> 3;   // l < xk * xc
+        const int across = a.cblocks / a.xc;                   // XCD rectangles per row of the block grid
+        kbi = (xcd / across) * a.xk + l / a.xc;
+        cbi = (xcd % across) * a.xc + l % a.xc;
+        g = 0; sp = 0;
+    } else {
+        const int per_xcd = (a.total_wgs + 7) / 8;
+        const int L = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+        if (L >= a.total_wgs) return;
+        int u = L;
+        cbi = u % a.cblocks; u /= a.cblocks;
+        kbi = u % a.kblocks; u /= a.kblocks;
+        g = u % a.groups;
+        sp = u / a.groups;
+    }
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 15, kk = lane >> 4;
@@ -383,6 +395,18 @@ Plan make_plan(const Problem& pr, WgradArgs& a) {
     if (nsplit < 1) nsplit = 1;
     a.nsplit = nsplit;
     a.total_wgs = blocks * nsplit;
+    // XCD rectangles: only when the block grid splits exactly into 8 equal rectangles.
+    a.xk = a.xc = 0;
+    if (nsplit == 1 && pr.groups == 1 && blocks % 8 == 0) {
+        const int per = blocks / 8;
+        int best = 0;
+        for (int xk = 1; xk * xk <= per; ++xk) {
+            if (per % xk) continue;
+            const int xc = per / xk;
+            if (a.kblocks % xk == 0 && a.cblocks % xc == 0 && (a.kblocks / xk) * (a.cblocks / xc) == 8) best = xk;
+        }
+        if (best) { a.xk = best; a.xc = per / best; }
+    }
     const size_t wbytes = (size_t)pr.K * pr.Cg * pr.R * pr.S * sizeof(float);
     return Plan{nsplit, nsplit > 1 ? nsplit * wbytes : 0};
 }
