@@ -20,6 +20,7 @@
 // buffer that reduce_splits_kernel sums in split order: no floating-point
 // atomics anywhere, so dw is bit-reproducible.
 #include "common.h"
+#include <type_traits>
 
 namespace miconv {
 namespace {
@@ -60,12 +61,19 @@ constexpr int next_2_mod_4(int v) { return v + ((6 - v % 4) % 4); }   // smalles
 constexpr int next_odd(int v) { return v | 1; }
 constexpr int cmax(int a, int b) { return a > b ? a : b; }
 
-// IMG: images per stage.  With 4 waves sharing the pixel steps of a stage, two 14x14 images (98 steps)
-// divide almost evenly (25/25/24/24) where one (49 steps) leaves three waves idle for a step in 13.
+// IMG: images per stage.  With the waves sharing the pixel steps of a stage, two 14x14 images (98 steps)
+// divide more evenly than one (49 steps).
 // WIDE: the tile is the whole output plane and the planes are multiples of 4 floats: dy rows and x
 // planes are then read as 16-byte pieces (a quarter of the address-unit work of 4-byte reads) and the
 // x values scattered into the zero-bordered patch, whose border words are written once.
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG, bool WIDE>
+// HI: see the step assignment below.
+//
+// Nothing but MFMAs, LDS accesses, loads and waits may sit in the multiply loop: an ordinary vector
+// instruction does not overlap with a running MFMA of its own SIMD, so every address the loop uses is
+// a register prepared outside plus an immediate.  That is why the two LDS buffers are handled by two
+// instances of the loop (buffer offsets become immediates) and why all LDS store addresses are kept
+// in registers.
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG, bool WIDE, int HI = 0>
 __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     constexpr int NT = 64 * WK * WC * WS;
     constexpr int RS = R * S;
@@ -79,14 +87,27 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     // LDS row strides: 16 lanes x 2 adjacent pixels must fall in 32 distinct banks.
     constexpr int DS = next_2_mod_4(NPX);
     constexpr int XS = ST == 1 ? next_2_mod_4(PSZ) : next_odd(PSZ);
-    constexpr int YE = 16 * KB * NPX, XE = 16 * CB * PSZ;               // per image
-    constexpr int YPT = WIDE ? (IMG * YE / 4 + NT - 1) / NT : (IMG * YE + NT - 1) / NT;   // load pieces per thread
-    constexpr int XPT = WIDE ? (IMG * 16 * CB * (NPX * ST * ST) / 4 + NT - 1) / NT : (IMG * XE + NT - 1) / NT;
-    constexpr int YIMG = 16 * KB * DS, XIMG = 16 * CB * XS;             // floats per image in LDS
-    constexpr int STAGE = IMG * (YIMG + XIMG);                          // floats per LDS buffer
+    constexpr int YROWS = 16 * KB, XROWS = 16 * CB;                     // channels per image
+    constexpr int YIMG = YROWS * DS, XIMG = XROWS * XS;                 // floats per image in LDS
+    constexpr int STAGE = IMG * (YIMG + XIMG);                          // floats of one stage
+    // Lanes with nothing to store write to a word of their own behind the stage (no branch around
+    // a store that sits between MFMAs); BSTR is the distance between the two stage buffers.
+    constexpr int TRASH = STAGE, BSTR = STAGE + 64;
+    static_assert(STAGE % 4 == 0, "16-byte alignment of the second buffer");
     constexpr int OUTSZ = 16 * KB * 16 * CB * RS;                       // accumulator elements of the workgroup
-    constexpr int LDSF = cmax(2 * STAGE, WS * OUTSZ);
+    constexpr int LDSF = cmax(2 * BSTR, WS * OUTSZ);
     static_assert(LDSF * 4 <= 160 * 1024, "LDS budget");
+    // Load pieces per thread.  WIDE: consecutive 16-byte pieces of the stage's dy rows and x planes.
+    // Otherwise single elements: thread (row, lane-in-row) walks along its row, so that the LDS address
+    // of piece m is the thread's base plus a constant.
+    constexpr int YLANES = NPX < 64 ? 32 : 64, XLANES = PW <= 16 ? 16 : (PW <= 32 ? 32 : 64);
+    static_assert(NT % YLANES == 0 && NT % XLANES == 0, "row walkers");
+    constexpr int YRPP = NT / YLANES, XRPP = NT / XLANES;               // rows covered per pass
+    constexpr int YCOLP = (NPX + YLANES - 1) / YLANES, YROWP = (IMG * YROWS + YRPP - 1) / YRPP;
+    constexpr int XROWP = (IMG * XROWS * PH + XRPP - 1) / XRPP;         // x rows are (image, channel, patch row)
+    constexpr int YPT = WIDE ? (IMG * YROWS * NPX / 4 + NT - 1) / NT : YCOLP * YROWP;
+    constexpr int XPT = WIDE ? (IMG * XROWS * (NPX * ST * ST) / 4 + NT - 1) / NT : XROWP;
+    static_assert(WIDE || PW <= 64, "one lane per patch column");
 
     __shared__ float lds[LDSF];
 
@@ -127,62 +148,96 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     const int xplane = a.H * a.W, yplane = a.P * a.Q;
     const T* const tnull = nullptr;
 
-    // ---- gather plans (depend on the tile position only) -----------------------------------------
-    // Offsets are relative to the first image of the stage; image i of the stage adds i whole images.
-    // Images past the end of the batch fall outside the descriptor and read as zero.
-    unsigned ygo[YPT], xgo[XPT];   // byte offsets, kOob = reads as zero
-    int ylo[WIDE ? YPT : 1], xlo[WIDE ? XPT : 1][4];   // wide path: where the pieces land in a stage's LDS buffer
-    auto plan = [&](int tile) {
+    // ---- gather plans ----------------------------------------------------------------------------
+    // Global byte offsets (relative to the first image of a stage; kOob = reads as zero; images past
+    // the end of the batch fall outside the descriptor and read as zero) depend on the tile position;
+    // the LDS store addresses (in buffer 0) never change.
+    unsigned ygo[YPT], xgo[XPT];
+    float* ysto[YPT];
+    float* xsto[XPT][WIDE ? 4 : 1];
+    if constexpr (WIDE) {
+#pragma unroll
+        for (int m = 0; m < YPT; ++m) {
+            const int f = tid + NT * m;
+            const int row = (4 * f) / NPX, px = 4 * f - row * NPX;       // row = image-major, then channel
+            const int im = row / YROWS, kl = row - im * YROWS;
+            // rows are 8-byte aligned in LDS (DS is even, px a multiple of 4)
+            ysto[m] = lds + (row < IMG * YROWS ? im * YIMG + kl * DS + px : TRASH + (lane & ~3));
+        }
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) {
+            const int f = tid + NT * m;
+            const int xq = xplane / 4;
+            const int pc = f / xq, rem = 4 * (f - pc * xq);
+            const int im = pc / XROWS, cl = pc - im * XROWS;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int ih = (rem + e) / a.W, iw = (rem + e) - ih * a.W;
+                const int ph = ih + a.pad_h, pw = iw + a.pad_w;
+                const bool in = pc < IMG * XROWS && ph >= 0 && ph < PH && pw >= 0 && pw < PW;
+                xsto[m][e] = lds + (in ? IMG * YIMG + im * XIMG + cl * XS + ph * PW + pw : TRASH + lane);
+            }
+        }
+    } else {
+        const int yr = tid / YLANES, yc = tid - yr * YLANES;
+#pragma unroll
+        for (int m = 0; m < YPT; ++m) {
+            const int row = yr + YRPP * (m / YCOLP), px = yc + YLANES * (m % YCOLP);
+            const int im = row / YROWS, kl = row - im * YROWS;
+            ysto[m] = lds + (row < IMG * YROWS && px < NPX ? im * YIMG + kl * DS + px : TRASH + lane);
+        }
+        const int xr = tid / XLANES, xc = tid - xr * XLANES;
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) {
+            const int row = xr + XRPP * m;                               // (image, channel, patch row)
+            const int pc = row / PH, ph = row - pc * PH;
+            const int im = pc / XROWS, cl = pc - im * XROWS;
+            xsto[m][0] = lds + (pc < IMG * XROWS && xc < PW ? IMG * YIMG + im * XIMG + cl * XS + ph * PW + xc : TRASH + lane);
+        }
+    }
+    auto plan = [&](int tile) __attribute__((always_inline)) {
         if constexpr (WIDE) {
             // whole planes: H*W == NPX*ST*ST is not required, only that an x plane is xplane floats
             const int xq = xplane / 4;   // float4 per x plane
 #pragma unroll
             for (int m = 0; m < YPT; ++m) {
                 const int f = tid + NT * m;
-                const int im = f / (YE / 4), ei = 4 * f - im * YE;
-                const int kl = ei / NPX, px = ei - kl * NPX;
-                const bool ok = f < IMG * YE / 4 && k0 + kl < a.Kg;
+                const int row = (4 * f) / NPX, px = 4 * f - row * NPX;
+                const int im = row / YROWS, kl = row - im * YROWS;
+                const bool ok = row < IMG * YROWS && k0 + kl < a.Kg;
                 ygo[m] = ok ? (unsigned)((im * a.K + g * a.Kg + k0 + kl) * yplane + px) * 4u : kOob;
-                ylo[m] = f < IMG * YE / 4 ? im * YIMG + kl * DS + px : -1;
             }
 #pragma unroll
             for (int m = 0; m < XPT; ++m) {
                 const int f = tid + NT * m;
                 const int pc = f / xq, rem = 4 * (f - pc * xq);      // plane (image-major, then channel), element
-                const int im = pc / (16 * CB), cl = pc - im * 16 * CB;
-                const bool ok = pc < IMG * 16 * CB && c0 + cl < a.Cg;
+                const int im = pc / XROWS, cl = pc - im * XROWS;
+                const bool ok = pc < IMG * XROWS && c0 + cl < a.Cg;
                 xgo[m] = ok ? (unsigned)((im * a.C + g * a.Cg + c0 + cl) * xplane + rem) * 4u : kOob;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int ih = (rem + e) / a.W, iw = (rem + e) - ih * a.W;
-                    const int ph = ih + a.pad_h, pw = iw + a.pad_w;
-                    const bool in = pc < IMG * 16 * CB && ph >= 0 && ph < PH && pw >= 0 && pw < PW;
-                    xlo[m][e] = in ? IMG * YIMG + im * XIMG + cl * XS + ph * PW + pw : -1;
-                }
             }
             return;
         }
         const int ti = tile / a.tiles_w, tj = tile - ti * a.tiles_w;
         const int p0 = ti * TH, q0 = tj * TW;
         const int h0 = p0 * ST - a.pad_h, v0 = q0 * ST - a.pad_w;
+        const int yr = tid / YLANES, yc = tid - yr * YLANES;
 #pragma unroll
         for (int m = 0; m < YPT; ++m) {
-            const int e = tid + NT * m;
-            const int im = e / YE, ei = e - im * YE;
-            const int kl = ei / NPX, px = ei - kl * NPX;
+            const int row = yr + YRPP * (m / YCOLP), px = yc + YLANES * (m % YCOLP);
+            const int im = row / YROWS, kl = row - im * YROWS;
             const int th = px / TW, tw = px - th * TW;
             const int p = p0 + th, q = q0 + tw;
-            const bool ok = e < IMG * YE && k0 + kl < a.Kg && p < a.P && q < a.Q;
+            const bool ok = row < IMG * YROWS && px < NPX && k0 + kl < a.Kg && p < a.P && q < a.Q;
             ygo[m] = ok ? (unsigned)((im * a.K + g * a.Kg + k0 + kl) * yplane + p * a.Q + q) * (unsigned)sizeof(T) : kOob;
         }
+        const int xr = tid / XLANES, xc = tid - xr * XLANES;
 #pragma unroll
         for (int m = 0; m < XPT; ++m) {
-            const int e = tid + NT * m;
-            const int im = e / XE, ei = e - im * XE;
-            const int cl = ei / PSZ, rem = ei - cl * PSZ;
-            const int ph = rem / PW, pw = rem - ph * PW;
-            const int h = h0 + ph, v = v0 + pw;
-            const bool ok = e < IMG * XE && c0 + cl < a.Cg && h >= 0 && h < a.H && v >= 0 && v < a.W;
+            const int row = xr + XRPP * m;
+            const int pc = row / PH, ph = row - pc * PH;
+            const int im = pc / XROWS, cl = pc - im * XROWS;
+            const int h = h0 + ph, v = v0 + xc;
+            const bool ok = pc < IMG * XROWS && xc < PW && c0 + cl < a.Cg && h >= 0 && h < a.H && v >= 0 && v < a.W;
             xgo[m] = ok ? (unsigned)((im * a.C + g * a.Cg + c0 + cl) * xplane + h * a.W + v) * (unsigned)sizeof(T) : kOob;
         }
     };
@@ -192,14 +247,26 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     float yreg[WIDE ? 1 : YPT], xreg[WIDE ? 1 : XPT];
     v4u yreg4[WIDE ? YPT : 1], xreg4[WIDE ? XPT : 1];
     constexpr int NPIECES = YPT + XPT;
-    auto descriptors = [&](int stage, rsrc_t& yrs, rsrc_t& xrs) {
-        const int n = (stage % a.img_stages) * IMG;          // first image of the stage
-        const int left = stage < s_end ? a.N - n : 0;        // images from here to the end of the batch
+    rsrc_t yrs, xrs;
+    // The stage being fetched runs ahead of the one being multiplied: (f_tile, f_img) is its position.
+    int f_stage = s_begin, f_tile = s_begin / a.img_stages, f_img = s_begin - f_tile * a.img_stages;
+    auto descriptors = [&]() __attribute__((always_inline)) {
+        const int n = f_img * IMG;                           // first image of the stage
+        const int left = f_stage < s_end ? a.N - n : 0;      // past the split's end: empty, every load reads zero
         const int have = left < IMG ? left : IMG;
         yrs = make_rsrc(dyg + (size_t)n * a.K * yplane, (unsigned)(have * a.K * yplane) * (unsigned)sizeof(T));
         xrs = make_rsrc(xg + (size_t)n * a.C * xplane, (unsigned)(have * a.C * xplane) * (unsigned)sizeof(T));
     };
-    auto issue = [&](int piece, const rsrc_t& yrs, const rsrc_t& xrs) {
+    auto advance = [&]() __attribute__((always_inline)) {   // to the next stage to fetch (wave-uniform arithmetic only)
+        ++f_stage;
+        if (++f_img == a.img_stages) {
+            f_img = 0;
+            ++f_tile;
+            if (f_stage < s_end) plan(f_tile);
+        }
+        descriptors();
+    };
+    auto issue = [&](int piece) __attribute__((always_inline)) {
         if constexpr (WIDE) {
             if (piece < YPT) yreg4[piece] = __builtin_amdgcn_raw_buffer_load_b128(yrs, ygo[piece], 0, 0);
             else xreg4[piece - YPT] = __builtin_amdgcn_raw_buffer_load_b128(xrs, xgo[piece - YPT], 0, 0);
@@ -208,38 +275,22 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
             else xreg[piece - YPT] = buf_load(xrs, xgo[piece - YPT], tnull);
         }
     };
-    auto stash = [&](int buf) {
-        // Everything fetched for the next stage was issued during the MFMA loop; retiring all of it
-        // here keeps waits on these loads out of the next MFMA loop.
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-        float* sb = lds + buf * STAGE;
+    // LDS stores of one fetched piece (its load must have completed) into buffer `buf` (a constant).
+    auto write_piece = [&](int piece, int buf) __attribute__((always_inline)) {
+        const int bo = buf * BSTR;
         if constexpr (WIDE) {
+            if (piece < YPT) {
+                const int m = piece;
+                *reinterpret_cast<float2*>(ysto[m] + bo) = make_float2(__uint_as_float(yreg4[m].x), __uint_as_float(yreg4[m].y));
+                *reinterpret_cast<float2*>(ysto[m] + bo + 2) = make_float2(__uint_as_float(yreg4[m].z), __uint_as_float(yreg4[m].w));
+            } else {
+                const int m = piece - YPT;
 #pragma unroll
-            for (int m = 0; m < YPT; ++m)
-                if (ylo[m] >= 0) {   // rows are 8-byte aligned in LDS (DS is even, px a multiple of 4)
-                    *reinterpret_cast<float2*>(sb + ylo[m]) = make_float2(__uint_as_float(yreg4[m].x), __uint_as_float(yreg4[m].y));
-                    *reinterpret_cast<float2*>(sb + ylo[m] + 2) = make_float2(__uint_as_float(yreg4[m].z), __uint_as_float(yreg4[m].w));
-                }
-#pragma unroll
-            for (int m = 0; m < XPT; ++m)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (xlo[m][e] >= 0) sb[xlo[m][e]] = __uint_as_float(xreg4[m][e]);
-            return;
-        }
-#pragma unroll
-        for (int m = 0; m < YPT; ++m) {
-            const int e = tid + NT * m;
-            const int im = e / YE, ei = e - im * YE;
-            const int kl = ei / NPX, px = ei - kl * NPX;
-            if (e < IMG * YE) sb[im * YIMG + kl * DS + px] = yreg[m];
-        }
-#pragma unroll
-        for (int m = 0; m < XPT; ++m) {
-            const int e = tid + NT * m;
-            const int im = e / XE, ei = e - im * XE;
-            const int cl = ei / PSZ, rem = ei - cl * PSZ;
-            if (e < IMG * XE) sb[IMG * YIMG + im * XIMG + cl * XS + rem] = xreg[m];
+                for (int e = 0; e < 4; ++e) xsto[m][e][bo] = __uint_as_float(xreg4[m][e]);
+            }
+        } else {
+            if (piece < YPT) ysto[piece][bo] = yreg[piece];
+            else xsto[piece - YPT][0][bo] = xreg[piece - YPT];
         }
     };
 
@@ -251,93 +302,132 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
 #pragma unroll
             for (int t = 0; t < RS; ++t) acc[i][j][t] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    // ---- this wave's pixel steps: t = ws, ws+WS, ...; the LDS offsets of its lanes never change ----
-    constexpr int IT_FULL = NSTEPS / WS, IT_REM = NSTEPS % WS, ITER = IT_FULL + (IT_REM ? 1 : 0);
-    int yoff[ITER], xoff[ITER];
+    // ---- this wave's pixel steps; the LDS addresses of its lanes never change -------------------
+    // HI == 0: wave ws takes steps ws, ws+WS, ...  HI > 0 (two waves per SIMD): the first WS/2 waves of
+    // the workgroup take HI consecutive steps each and the other WS/2 share the rest.
+    constexpr int HALF = WS / 2;
+    constexpr int REM = HI > 0 ? NSTEPS - HALF * HI : 0;
+    static_assert(HI == 0 || (WS % 2 == 0 && REM > 0 && REM <= HALF * HI), "uneven split");
+    constexpr int ITER = HI > 0 ? HI : (NSTEPS + WS - 1) / WS;
+    constexpr int MINCNT = HI > 0 ? REM / HALF : NSTEPS / WS;   // steps every wave runs
+    int mycnt, mystart;
+    if (HI > 0) {
+        const int j = ws - HALF, q = REM / HALF, r = REM % HALF;
+        mycnt = ws < HALF ? HI : q + (j < r ? 1 : 0);
+        mystart = ws < HALF ? ws * HI : HALF * HI + j * q + (j < r ? j : r);
+    } else {
+        mycnt = NSTEPS / WS + (ws < NSTEPS % WS ? 1 : 0);
+        mystart = ws;
+    }
+    mycnt = __builtin_amdgcn_readfirstlane(mycnt);
+    const float* yrd[ITER];
+    const float* xrd[ITER];
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-        int t = ws + WS * i;
-        if (t >= NSTEPS) t = NSTEPS - 1;   // only in the step that waves with ws >= IT_REM skip; keeps the read in range
+        int t = HI > 0 ? mystart + i : mystart + WS * i;
+        if (t >= NSTEPS) t = NSTEPS - 1;   // steps beyond this wave's count are skipped; keeps their reads in range
         const int im = t / SPI;
         const int px = 4 * (t - im * SPI) + kk;
         const int th = px / TW, tw = px - th * TW;
-        yoff[i] = im * YIMG + (16 * (wk * KBW) + li) * DS + px;
-        xoff[i] = IMG * YIMG + im * XIMG + (16 * (wc * CBW) + li) * XS + th * ST * PW + tw * ST;
+        yrd[i] = lds + im * YIMG + (16 * (wk * KBW) + li) * DS + px;
+        xrd[i] = lds + IMG * YIMG + im * XIMG + (16 * (wc * CBW) + li) * XS + th * ST * PW + tw * ST;
     }
 
     // One step = NM = KBW*CBW*RS MFMAs on NR = KBW + CBW*RS operands.  Operand r of step i+1 is read
-    // from LDS right before MFMA r of step i, so reads issue while the matrix pipe is busy and every
+    // from LDS in the slot of MFMA r of step i, so reads issue while the matrix pipe is busy and every
     // operand is requested a full step before its use; scheduling fences pin that order.
     constexpr int NM = KBW * CBW * RS, NR = KBW + CBW * RS;
-    // The next stage's pieces all go out in the first third of the steps, so that the rest of the
-    // stage's MFMA work covers their latency before stash() waits for them.
+    // Software pipeline over stages, all inside the MFMA loop so that no wave ever leaves it for a
+    // separate copy phase: while stage s is multiplied, the registers hold stage s+1 (fetched during
+    // stage s-1); the first third of the steps stores them, a few LDS stores behind each MFMA, into
+    // the other LDS buffer; the second third refills the registers with the loads of stage s+2; the
+    // last third covers the latency of those loads.
+    constexpr int SLOTS = NM > NR ? NM : NR;
+    constexpr int WSTEPS = ITER >= 3 ? ITER / 3 : 1;
     constexpr int ISSUE_STEPS = ITER >= 3 ? ITER / 3 : 1;
-    auto multiply = [&](const float* sb, const rsrc_t& yrs, const rsrc_t& xrs) {
+    static_assert(ITER == 1 || WSTEPS + ISSUE_STEPS <= ITER, "store steps, then load steps");
+    static_assert(WSTEPS <= MINCNT, "the stores lie in steps every wave runs");
+    // buf: the LDS buffer multiplied (a constant at each call site); the other one is stored to.
+    auto multiply = [&](auto bufc) __attribute__((always_inline)) {
+        constexpr int buf = decltype(bufc)::value;
+        constexpr int bo = buf * BSTR;
         float ops[2][NR];   // [0..KBW): dy operands, then CBW*RS x operands
-        auto read_op = [&](int i, int r) -> float {
-            if (r < KBW) return sb[yoff[i] + r * 16 * DS];
+        auto read_op = [&](int i, int r) __attribute__((always_inline)) -> float {
+            if (r < KBW) return yrd[i][bo + r * 16 * DS];
             const int q = r - KBW, j = q / RS, t = q % RS;
-            return sb[xoff[i] + j * 16 * XS + (t / S) * PW + (t % S)];
+            return xrd[i][bo + j * 16 * XS + (t / S) * PW + (t % S)];
         };
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the held stage was requested two thirds of a stage ago
 #pragma unroll
         for (int r = 0; r < NR; ++r) ops[0][r] = read_op(0, r);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < ITER; ++i) {
-#pragma unroll
-            for (int piece = 0; piece < NPIECES; ++piece)
-                if (piece * ISSUE_STEPS / NPIECES == i) issue(piece, yrs, xrs);
-            __builtin_amdgcn_sched_barrier(0);
+            // Steps past MINCNT exist only for some waves (wave-uniform test).  Once the stores and loads
+            // of the stage are out, such a wave leaves the loop; before that it only skips the MFMAs.
+            if (i >= MINCNT && i >= WSTEPS + ISSUE_STEPS && i >= mycnt) break;
             const bool next = i + 1 < ITER;
-            if (i < IT_FULL || ws < IT_REM) {  // wave-uniform; false only in the last step
+            if (i < MINCNT || i >= WSTEPS + ISSUE_STEPS || i < mycnt) {
 #pragma unroll
-                for (int m = 0; m < (NM > NR ? NM : NR); ++m) {
-                    // The read goes first: the register it fills must differ from the ones the MFMA
-                    // behind it still reads (a read that overwrote an operand of the MFMA just issued
-                    // would have to wait for that MFMA to fetch it).
+                for (int m = 0; m < SLOTS; ++m) {
                     if (next && m < NR) ops[(i + 1) & 1][m] = read_op(i + 1, m);
                     if (m < NM) {
                         const int j = m / (RS * KBW), t = (m / KBW) % RS, ib = m % KBW;
                         acc[ib][j][t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ops[i & 1][ib], ops[i & 1][KBW + j * RS + t],
                                                                              acc[ib][j][t], 0, 0, 0);
                     }
+                    {   // pieces p with floor(p * WACT / NPIECES) == this slot's index
+                        constexpr int WACT = WSTEPS * SLOTS;
+                        const int act = i * SLOTS + m;
+                        const int lo = (act * NPIECES + WACT - 1) / WACT, hi = ((act + 1) * NPIECES + WACT - 1) / WACT;
+#pragma unroll
+                        for (int d = 0; d < (NPIECES + WACT - 1) / WACT + 1; ++d)
+                            if (act < WACT && lo + d < hi && lo + d < NPIECES) write_piece(lo + d, buf ^ 1);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
+            // loads go out behind the stores of the same registers
+            {   // pieces p with floor(p * ISSUE_STEPS / NPIECES) == k
+                const int k = ITER == 1 ? 0 : i - WSTEPS;
+                const int lo = (k * NPIECES + ISSUE_STEPS - 1) / ISSUE_STEPS, hi = ((k + 1) * NPIECES + ISSUE_STEPS - 1) / ISSUE_STEPS;
+#pragma unroll
+                for (int d = 0; d < (NPIECES + ISSUE_STEPS - 1) / ISSUE_STEPS + 1; ++d)
+                    if (k >= 0 && k < ISSUE_STEPS && lo + d < hi && lo + d < NPIECES) issue(lo + d);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
-    if constexpr (WIDE) {
-        // patch borders (and everything else) start as zero; the scatter only writes interior words
-        for (int e = tid; e < 2 * STAGE; e += NT) lds[e] = 0.f;
-        __syncthreads();
-    }
+    // patch borders (and everything else) start as zero; the wide scatter only writes interior words
+    for (int e = tid; e < LDSF; e += NT) lds[e] = 0.f;
+    __syncthreads();
     if (s_begin < s_end) {
-        int tile = s_begin / a.img_stages;
-        plan(tile);
-        rsrc_t yrs, xrs;
-        descriptors(s_begin, yrs, xrs);
+        plan(f_tile);
+        descriptors();
 #pragma unroll
-        for (int piece = 0; piece < NPIECES; ++piece) issue(piece, yrs, xrs);
-        stash(0);
+        for (int piece = 0; piece < NPIECES; ++piece) issue(piece);
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+#pragma unroll
+        for (int piece = 0; piece < NPIECES; ++piece) write_piece(piece, 0);
+        advance();   // stage s_begin+1 into the registers
+#pragma unroll
+        for (int piece = 0; piece < NPIECES; ++piece) issue(piece);
         __syncthreads();
-        int buf = 0;
-        for (int stage = s_begin; stage < s_end; ++stage) {
-            const bool more = stage + 1 < s_end;
-            if (more) {
-                const int nt = (stage + 1) / a.img_stages;
-                if (nt != tile) { tile = nt; plan(tile); }
-            }
-            descriptors(stage + 1, yrs, xrs);   // past the split's end: empty descriptors, every load reads zero
-            multiply(lds + buf * STAGE, yrs, xrs);
-            if (more) stash(buf ^ 1);
+        for (int stage = s_begin; stage < s_end; stage += 2) {
+            advance();
+            multiply(std::integral_constant<int, 0>{});
             __syncthreads();
-            buf ^= 1;
+            if (stage + 1 >= s_end) break;
+            advance();
+            multiply(std::integral_constant<int, 1>{});
+            __syncthreads();
         }
     }
 
     // ---- combine the WS pixel-step shares and write out ---------------------------------------------
     // LDS layout of one share: [k local][c local][tap], i.e. the order of dw within the block.
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // loads fetched past the last stage still target registers
     __syncthreads();
     constexpr int ROW = 16 * CB * RS;
 #pragma unroll
@@ -413,7 +503,7 @@ Plan make_plan(const Problem& pr, WgradArgs& a) {
 
 // WS: pixel-step shares (waves) on the 16-byte fetch path; WSN: on the 4-byte path, which needs more
 // registers per thread and therefore runs one wave per SIMD.
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int WSN, int IMG>
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int WSN, int IMG, int HI = 0>
 hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st,
                         bool dry, size_t* ws_bytes) {
     WgradArgs a{};
@@ -427,7 +517,7 @@ hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float*
     const int grid = ((a.total_wgs + 7) / 8) * 8;
     const bool wide = sizeof(T) == 4 && pr.P == TH && pr.Q == TW && (pr.H * pr.W) % 4 == 0 &&
                       pr.H * pr.W == TH * TW * ST * ST;
-    if (wide) wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, true><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
+    if (wide) wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, true, HI><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
     else wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WSN, IMG, false><<<grid, 64 * WK * WC * WSN, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.nsplit == 1) return e;
@@ -444,7 +534,7 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
     *ws_bytes = 0;
     if (pr.sh != pr.sw) return false;
     if (pr.R == 3 && pr.S == 3 && pr.sh == 1) {
-        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 8, 4, 2>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 8, 4, 2, 15>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 3 && pr.S == 3 && pr.sh == 2) {
