@@ -112,7 +112,8 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     const int n = u / a.groups;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // tells the compiler it is wave-uniform
     const int wf = wave % WF, wp = wave / WF;
     const int li = lane & 15, kk = lane >> 4;
 
@@ -179,7 +180,8 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     auto prepare = [&](int ch, rsrc_t& xrs, unsigned (&wvo)[KQ]) {
         const int left = a.Rg - ch * CK;  // reduction channels from this chunk on (<= 0: no such chunk)
         const int have = left <= 0 ? 0 : (left < CK ? left : CK);
-        xrs = make_rsrc(src + (size_t)ch * CK * plane, (unsigned)(have * plane) * (unsigned)sizeof(T));
+        xrs = make_rsrc(src + (size_t)ch * CK * plane,
+                        (unsigned)__builtin_amdgcn_readfirstlane(have * plane) * (unsigned)sizeof(T));
         const int wb = wbase + ch * wstep_chunk;
 #pragma unroll
         for (int k4 = 0; k4 < KQ; ++k4)

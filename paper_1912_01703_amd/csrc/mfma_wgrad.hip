@@ -66,14 +66,13 @@ constexpr int cmax(int a, int b) { return a > b ? a : b; }
 // WIDE: the tile is the whole output plane and the planes are multiples of 4 floats: dy rows and x
 // planes are then read as 16-byte pieces (a quarter of the address-unit work of 4-byte reads) and the
 // x values scattered into the zero-bordered patch, whose border words are written once.
-// HI: see the step assignment below.
 //
 // Nothing but MFMAs, LDS accesses, loads and waits may sit in the multiply loop: an ordinary vector
 // instruction does not overlap with a running MFMA of its own SIMD, so every address the loop uses is
 // a register prepared outside plus an immediate.  That is why the two LDS buffers are handled by two
 // instances of the loop (buffer offsets become immediates) and why all LDS store addresses are kept
 // in registers.
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG, bool WIDE, int HI = 0>
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG, bool WIDE>
 __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
     constexpr int NT = 64 * WK * WC * WS;
     constexpr int RS = R * S;
@@ -303,28 +302,15 @@ __global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
             for (int t = 0; t < RS; ++t) acc[i][j][t] = v4f{0.f, 0.f, 0.f, 0.f};
 
     // ---- this wave's pixel steps; the LDS addresses of its lanes never change -------------------
-    // HI == 0: wave ws takes steps ws, ws+WS, ...  HI > 0 (two waves per SIMD): the first WS/2 waves of
-    // the workgroup take HI consecutive steps each and the other WS/2 share the rest.
-    constexpr int HALF = WS / 2;
-    constexpr int REM = HI > 0 ? NSTEPS - HALF * HI : 0;
-    static_assert(HI == 0 || (WS % 2 == 0 && REM > 0 && REM <= HALF * HI), "uneven split");
-    constexpr int ITER = HI > 0 ? HI : (NSTEPS + WS - 1) / WS;
-    constexpr int MINCNT = HI > 0 ? REM / HALF : NSTEPS / WS;   // steps every wave runs
-    int mycnt, mystart;
-    if (HI > 0) {
-        const int j = ws - HALF, q = REM / HALF, r = REM % HALF;
-        mycnt = ws < HALF ? HI : q + (j < r ? 1 : 0);
-        mystart = ws < HALF ? ws * HI : HALF * HI + j * q + (j < r ? j : r);
-    } else {
-        mycnt = NSTEPS / WS + (ws < NSTEPS % WS ? 1 : 0);
-        mystart = ws;
-    }
-    mycnt = __builtin_amdgcn_readfirstlane(mycnt);
+    // Wave ws takes steps ws, ws+WS, ...
+    constexpr int ITER = (NSTEPS + WS - 1) / WS;
+    constexpr int MINCNT = NSTEPS / WS;   // steps every wave runs
+    const int mycnt = __builtin_amdgcn_readfirstlane(NSTEPS / WS + (ws < NSTEPS % WS ? 1 : 0));
     const float* yrd[ITER];
     const float* xrd[ITER];
 #pragma unroll
     for (int i = 0; i < ITER; ++i) {
-        int t = HI > 0 ? mystart + i : mystart + WS * i;
+        int t = ws + WS * i;
         if (t >= NSTEPS) t = NSTEPS - 1;   // steps beyond this wave's count are skipped; keeps their reads in range
         const int im = t / SPI;
         const int px = 4 * (t - im * SPI) + kk;
@@ -503,7 +489,7 @@ Plan make_plan(const Problem& pr, WgradArgs& a) {
 
 // WS: pixel-step shares (waves) on the 16-byte fetch path; WSN: on the 4-byte path, which needs more
 // registers per thread and therefore runs one wave per SIMD.
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int WSN, int IMG, int HI = 0>
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int WSN, int IMG>
 hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st,
                         bool dry, size_t* ws_bytes) {
     WgradArgs a{};
@@ -517,7 +503,7 @@ hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float*
     const int grid = ((a.total_wgs + 7) / 8) * 8;
     const bool wide = sizeof(T) == 4 && pr.P == TH && pr.Q == TW && (pr.H * pr.W) % 4 == 0 &&
                       pr.H * pr.W == TH * TW * ST * ST;
-    if (wide) wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, true, HI><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
+    if (wide) wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, true><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
     else wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WSN, IMG, false><<<grid, 64 * WK * WC * WSN, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.nsplit == 1) return e;
@@ -534,7 +520,7 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
     *ws_bytes = 0;
     if (pr.sh != pr.sw) return false;
     if (pr.R == 3 && pr.S == 3 && pr.sh == 1) {
-        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 8, 4, 2, 15>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 8, 4, 2>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 3 && pr.S == 3 && pr.sh == 2) {
