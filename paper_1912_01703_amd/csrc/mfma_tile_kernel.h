@@ -20,9 +20,17 @@
 //   * MFMA roles: M = 16 filters, N = 16 output pixels, K = 4 reduction channels.
 //     Lane l holds A[f = l%16][k = l/16], B[k = l/16][pixel = l%16] and
 //     D[f = 4*(l/16)+v][pixel = l%16] in accumulator register v.
-//   * Global loads for chunk i+1 are issued before the MFMA work of chunk i and
-//     land in the other LDS buffer afterwards: one barrier per chunk.
+//   * The patch is pipelined through NBUF LDS buffers entirely inside the MFMA loop: while chunk i
+//     is multiplied, the registers that hold the patch of chunk i+NBUF-1 (loaded during chunk i-1)
+//     are stored to its buffer, then refilled with the loads of chunk i+NBUF; the filters of chunk
+//     i+1 are loaded into the second register set.  One barrier per chunk and no separate copy phase.
+//     With three buffers the next chunk's patch was complete a barrier earlier, so the first LDS
+//     operands of chunk i+1 are requested before the barrier and the MFMA stream runs through it.
+//   * An ordinary vector instruction does not overlap with a running MFMA of its own SIMD, so the
+//     loop holds only MFMAs, LDS accesses, loads and waits: every address is a register prepared
+//     outside the loop plus an immediate.
 #include "common.h"
+#include <type_traits>
 
 namespace miconv {
 namespace tile {
@@ -79,7 +87,8 @@ constexpr int lds_channel_stride(int v, int kq) {
 // WF: waves along filters (16 filters each).  WP: waves along pixel blocks.  BWD: backward-data operand mapping.
 // WV: the reduction channels per group are a multiple of 4 (forward filters can be read four values at a time).
 // PHASE: one output phase of a strided backward-data pass (R, S are the sub-filter's size; BWD is set).
-template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, bool WV, bool PHASE>
+// NBUF: LDS patch buffers (2 or 3).
+template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, bool WV, bool PHASE, int NBUF = 3>
 __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int NT = 64 * WF * WP;
     constexpr int RS = R * S;
@@ -94,7 +103,11 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int NB = (NPX + 15) / 16;      // 16-pixel blocks in the tile
     constexpr int NBW = (NB + WP - 1) / WP;  // blocks per wave
 
-    __shared__ float xs[2][CK * CS];
+    static_assert(NBUF == 2 || NBUF == 3, "two or three patch buffers");
+    // Each buffer is followed by 64 words that lanes without an element store to (no branch around a
+    // store that sits between MFMAs).
+    constexpr int BUFSZ = ((CK * CS + 3) & ~3) + 64, TRASH = BUFSZ - 64;
+    __shared__ float xs[NBUF * BUFSZ];
 
     // ---- which unit of work -------------------------------------------------------------
     // Consecutive workgroup ids land on different XCDs (8 of them, one L2 each).  All filter
@@ -127,7 +140,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 
     // ---- per-thread gather plan for the source patch (same for every chunk) ---------------
     unsigned goff[XPT];  // byte offset inside the chunk's channels, kOob where the patch lies outside the image
-    int loff[XPT];
+    int loff[XPT];       // word offset inside a patch buffer
 #pragma unroll
     for (int m = 0; m < XPT; ++m) {
         const int e = tid + NT * m;
@@ -136,7 +149,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         const int ih = ih0 + ph, iw = iw0 + pw;
         const bool ok = (e < XE) && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
         goff[m] = ok ? (unsigned)(c * plane + ih * a.IW + iw) * (unsigned)sizeof(T) : kOob;
-        loff[m] = (e < XE) ? c * CS + rem : -1;
+        loff[m] = (e < XE) ? c * CS + rem : TRASH + lane;
     }
 
     // ---- per-lane filter addressing ---------------------------------------------------------
@@ -176,23 +189,25 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr bool W4 = WV && !BWD && sizeof(T) == 4 && (RS * KQ) % 4 == 0;   // 4 filter values per load
     constexpr bool W3 = !W4 && !PHASE && sizeof(T) == 4 && RS % 3 == 0;       // 3 filter values per load
     constexpr int WPIECES = W4 ? RS * KQ / 4 : (W3 ? RS * KQ / 3 : RS * KQ);
-    constexpr int NPIECES = XPT + WPIECES;
-    auto prepare = [&](int ch, rsrc_t& xrs, unsigned (&wvo)[KQ]) {
+    // Descriptor of chunk ch's patch: it covers exactly the channels the chunk has, so a partial last
+    // chunk (or a chunk past the end: zero channels) reads zeros without any per-element test.
+    auto patch_rsrc = [&](int ch) __attribute__((always_inline)) -> rsrc_t {
         const int left = a.Rg - ch * CK;  // reduction channels from this chunk on (<= 0: no such chunk)
         const int have = left <= 0 ? 0 : (left < CK ? left : CK);
-        xrs = make_rsrc(src + (size_t)ch * CK * plane,
-                        (unsigned)__builtin_amdgcn_readfirstlane(have * plane) * (unsigned)sizeof(T));
+        return make_rsrc(src + (size_t)ch * CK * plane,
+                         (unsigned)__builtin_amdgcn_readfirstlane(have * plane) * (unsigned)sizeof(T));
+    };
+    auto filter_offsets = [&](int ch, unsigned (&wvo)[KQ]) __attribute__((always_inline)) {
+        const int left = a.Rg - ch * CK;
         const int wb = wbase + ch * wstep_chunk;
 #pragma unroll
         for (int k4 = 0; k4 < KQ; ++k4)
             wvo[k4] = (f_ok && kk * KQ + k4 < left) ? (unsigned)(wb + k4 * wstep_k) * (unsigned)sizeof(T) : kOob;
     };
-    auto issue = [&](int piece, const rsrc_t& xrs, const unsigned (&wvo)[KQ], float (&an)[RS * KQ]) {
-        if (piece < XPT) {
-            xreg[piece] = buf_load(xrs, goff[piece], tnull);
-            return;
-        }
-        const int q = piece - XPT;
+    auto issue_x = [&](int piece, const rsrc_t& xrs) __attribute__((always_inline)) {
+        xreg[piece] = buf_load(xrs, goff[piece], tnull);
+    };
+    auto issue_w = [&](int q, const unsigned (&wvo)[KQ], float (&an)[RS * KQ]) __attribute__((always_inline)) {
         if constexpr (W4) {
             // forward: the lane's KQ channels x RS taps are RS*KQ consecutive floats (Rg is a multiple
             // of KQ, so they are all present or all absent)
@@ -217,70 +232,118 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
                 an[k4 * RS + (BWD ? RS - 1 - t : t)] = buf_load(wrs, wvo[k4] + (unsigned)(t * sizeof(T)), tnull);
         }
     };
-    auto store_patch = [&](float* buf) {
-        // Everything fetched for the next chunk (patch and filters) was issued during the MFMA loop;
-        // retiring all of it here keeps waits on these loads out of the next MFMA loop.
+
+    // One "group" = one (tap, reduction channel) pair = NBW MFMAs sharing an A operand; a chunk is G
+    // groups.  Slot i of group g: the LDS read of operand i of group g+1, then MFMA i of group g (the
+    // read issues while the matrix pipe is busy, every operand is requested a full group before its
+    // use and, being issued first, is not given a register the MFMA still reads), then this slot's
+    // share of the patch stores.
+    constexpr int G = RS * KQ;
+    static_assert(G >= 2, "a chunk needs a group for the stores and one for the loads");
+    constexpr int SG = G >= 3 ? G / 3 : 1;      // groups that carry the patch stores
+    constexpr int LG = G >= 3 ? G / 3 : 1;      // groups (after those) that carry the patch loads
+    constexpr int WG = G >= 2 ? G / 2 : 1;      // groups that carry the filter loads
+    constexpr int D = NBUF - 1;                 // the patch stored during chunk i belongs to chunk i + D
+    float bq[2][NBW];
+    // ac: filters of this chunk; an: register set the next chunk's filters are loaded into.
+    // rd: this chunk's patch buffer; nx: the next chunk's; wr: the buffer stored to (word offsets in xs).
+    // PAR: which half of bq holds group 0's operands (the halves alternate with the groups).
+    auto compute = [&](auto parc, int ch, const float (&ac)[RS * KQ], float (&an)[RS * KQ], int rd, int nx, int wr)
+                       __attribute__((always_inline)) {
+        constexpr int PAR = decltype(parc)::value;
+        // All loads in flight were issued at least a third of a chunk ago: the patch held in xreg and
+        // this chunk's filters.  Retiring them here keeps waits on loads out of the loop.
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+        const rsrc_t xrs = patch_rsrc(ch + D + 1);
+        unsigned wvo[KQ];
+        filter_offsets(ch + 1, wvo);
+        const float* pr[NBW];     // per-block read bases in this chunk's buffer
+        const float* pn[NBW];     // ... and in the next chunk's
+        float* ps[XPT];           // store addresses
 #pragma unroll
-        for (int m = 0; m < XPT; ++m)
-            if (loff[m] >= 0) buf[loff[m]] = xreg[m];
-    };
-    // One "group" = one (tap, reduction channel) pair = NBW MFMAs sharing an A operand.  While chunk i
-    // is multiplied out of xb/ac, the pieces of chunk i+1 are issued into xreg/an.
-    auto compute = [&](const float* xb, const float (&ac)[RS * KQ], const rsrc_t& xrs, const unsigned (&wvo)[KQ],
-                       float (&an)[RS * KQ]) {
-        constexpr int G = RS * KQ;
-        // The next chunk's pieces all go out in the first half of the groups, so that the remaining MFMA
-        // work covers their latency before store_patch() waits for them.
-        constexpr int ISSUE_GROUPS = G >= 2 ? G / 2 : 1;
-        float bq[2][NBW];
+        for (int i = 0; i < NBW; ++i) { pr[i] = xs + rd + pixoff[i]; pn[i] = xs + nx + pixoff[i]; }
 #pragma unroll
-        for (int i = 0; i < NBW; ++i) bq[0][i] = xb[pixoff[i]];
+        for (int m = 0; m < XPT; ++m) ps[m] = xs + wr + loff[m];
+        if (NBUF == 2) {   // the buffer was completed by the barrier just passed: group 0's operands cannot be requested earlier
+#pragma unroll
+            for (int i = 0; i < NBW; ++i) bq[PAR][i] = pr[i][0];
+        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
 #pragma unroll
-            for (int piece = 0; piece < NPIECES; ++piece)
-                if (piece * ISSUE_GROUPS / NPIECES == g) issue(piece, xrs, wvo, an);
+            for (int q = 0; q < WPIECES; ++q)
+                if (q * WG / WPIECES == g) issue_w(q, wvo, an);
+#pragma unroll
+            for (int m = 0; m < XPT; ++m)
+                if (SG + m * LG / XPT == g) issue_x(m, xrs);   // behind the store of the same register
             __builtin_amdgcn_sched_barrier(0);
             const int k4n = (g + 1) % KQ, tn = (g + 1) / KQ;
             const int off = k4n * CS + (tn / S) * PW + (tn % S);
             const float av = ac[(g % KQ) * RS + g / KQ];
-            // The LDS read of operand i of the next group, then MFMA i of this group: the read issues while
-            // the matrix pipe is busy with MFMA i-1, every operand is requested a full group before its
-            // use, and (being issued first) the read cannot be given a register the MFMA still reads.
 #pragma unroll
             for (int i = 0; i < NBW; ++i) {
-                if (NB % WP != 0 && i == NBW - 1 && !last_ok) continue;   // wave-uniform: this wave has one block fewer
-                if (g + 1 < G) bq[(g + 1) & 1][i] = xb[pixoff[i] + off];
-                acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[g & 1][i], acc[i], 0, 0, 0);
+                const bool mine = !(NB % WP != 0 && i == NBW - 1 && !last_ok);   // wave-uniform: this wave may have one block fewer
+                if (mine) {
+                    if (g + 1 < G) bq[(PAR + g + 1) & 1][i] = pr[i][off];
+                    else if (NBUF == 3) bq[(PAR + g + 1) & 1][i] = pn[i][0];      // group 0 of the next chunk
+                    acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[(PAR + g) & 1][i], acc[i], 0, 0, 0);
+                }
+                {   // patch stores m with floor(m * SG*NBW / XPT) == this slot
+                    constexpr int SACT = SG * NBW;
+                    const int act = g * NBW + i;
+                    const int lo = (act * XPT + SACT - 1) / SACT, hi = ((act + 1) * XPT + SACT - 1) / SACT;
+#pragma unroll
+                    for (int d = 0; d < (XPT + SACT - 1) / SACT + 1; ++d)
+                        if (act < SACT && lo + d < hi && lo + d < XPT) *ps[lo + d] = xreg[lo + d];
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
 
-    // Two register sets for the filters and two LDS buffers for the patch alternate, so the loop
-    // is written out for an even and an odd chunk: no register copies, LDS addresses are immediates.
+    // Two register sets for the filters alternate, so the loop is written out for an even and an odd
+    // chunk (no register copies); the LDS buffers rotate through word offsets.
     float A0[RS * KQ], A1[RS * KQ];
     const int nchunks = (a.Rg + CK - 1) / CK;
-    rsrc_t xrs;
-    unsigned wvo[KQ];
-    prepare(0, xrs, wvo);
+    {   // prologue: chunks 0 .. D-1 into their buffers, chunk D into the registers, filters of chunk 0
+        unsigned wvo[KQ];
+        filter_offsets(0, wvo);
 #pragma unroll
-    for (int piece = 0; piece < NPIECES; ++piece) issue(piece, xrs, wvo, A0);
-    store_patch(xs[0]);
-    __syncthreads();
-    for (int ch = 0; ch < nchunks; ch += 2) {
-        prepare(ch + 1, xrs, wvo);
-        compute(xs[0], A0, xrs, wvo, A1);
-        if (ch + 1 >= nchunks) break;
-        store_patch(xs[1]);
+        for (int q = 0; q < WPIECES; ++q) issue_w(q, wvo, A0);
+#pragma unroll
+        for (int c = 0; c <= D; ++c) {
+            const rsrc_t xrs = patch_rsrc(c);
+#pragma unroll
+            for (int m = 0; m < XPT; ++m) issue_x(m, xrs);
+            if (c < D) {
+                __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+#pragma unroll
+                for (int m = 0; m < XPT; ++m) xs[c * BUFSZ + loff[m]] = xreg[m];
+            }
+        }
         __syncthreads();
-        prepare(ch + 2, xrs, wvo);
-        compute(xs[1], A1, xrs, wvo, A0);
-        if (ch + 2 < nchunks) store_patch(xs[0]);
-        __syncthreads();
+        if (NBUF == 3) {
+#pragma unroll
+            for (int i = 0; i < NBW; ++i) bq[0][i] = xs[pixoff[i]];
+        }
     }
+    int rd = 0, nx = BUFSZ, wr = D * BUFSZ;
+    auto rotate = [&]() __attribute__((always_inline)) {
+        rd = nx;
+        nx = nx + BUFSZ == NBUF * BUFSZ ? 0 : nx + BUFSZ;
+        wr = wr + BUFSZ == NBUF * BUFSZ ? 0 : wr + BUFSZ;
+    };
+    for (int ch = 0; ch < nchunks; ch += 2) {
+        compute(std::integral_constant<int, 0>{}, ch, A0, A1, rd, nx, wr);
+        __syncthreads();
+        rotate();
+        if (ch + 1 >= nchunks) break;
+        compute(std::integral_constant<int, G & 1>{}, ch + 1, A1, A0, rd, nx, wr);
+        __syncthreads();
+        rotate();
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // loads fetched past the last chunk still target registers
 
     // ---- epilogue: D[f = 4*kk+v][pixel = li] ---------------------------------------------------
     const int fq = fblk * (16 * WF) + wf * 16 + 4 * kk;
