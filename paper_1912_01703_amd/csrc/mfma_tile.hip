@@ -1,24 +1,35 @@
 // Host side of the tiled forward / stride-1 backward-data path: which instantiation of the kernel in
 // mfma_tile_kernel.h serves which filter size and stride.
 #include "mfma_tile_kernel.h"
+#ifndef TILE_1X1
+#define TILE_1X1 32, 4, 2, BWD, 3
+#endif
 
 namespace miconv {
 namespace {
 using namespace tile;
 
-template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD>
+template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, int NBUF = 3>
 hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
-    static_assert(CK == 16 || CK == 8, "the four-at-a-time filter read assumes whole lane groups of channels");
     TileArgs a = base;
     a.tiles_h = (a.OH + TH - 1) / TH;
     a.tiles_w = (a.OW + TW - 1) / TW;
     a.fblocks = (a.Fg + 16 * WF - 1) / (16 * WF);
     a.units = a.N * a.groups * a.tiles_h * a.tiles_w;
     const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
-    if (a.Rg % (CK / 4) == 0 && a.Rg % 4 == 0)
-        conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true, false><<<grid, 64 * WF * WP, 0, st>>>(a);
-    else
-        conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, false, false><<<grid, 64 * WF * WP, 0, st>>>(a);
+    const bool wv = a.Rg % (CK / 4) == 0 && a.Rg % 4 == 0;   // forward filters can be read four values at a time
+    if constexpr (R == 1 && S == 1 && ST == 1 && sizeof(T) == 4 && (TH * TW) % 4 == 0) {
+        // patch == plane: contiguous chunks, 16 bytes per lane
+        const bool plane_patch = a.pad_h == 0 && a.pad_w == 0 && a.IH == TH && a.IW == TW && a.OH == TH && a.OW == TW &&
+                                 reinterpret_cast<uintptr_t>(a.src) % 16 == 0;
+        if (plane_patch) {
+            if (wv) conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true, false, NBUF, true><<<grid, 64 * WF * WP, 0, st>>>(a);
+            else conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, false, false, NBUF, true><<<grid, 64 * WF * WP, 0, st>>>(a);
+            return hipGetLastError();
+        }
+    }
+    if (wv) conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true, false, NBUF><<<grid, 64 * WF * WP, 0, st>>>(a);
+    else conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, false, false, NBUF><<<grid, 64 * WF * WP, 0, st>>>(a);
     return hipGetLastError();
 }
 
@@ -32,7 +43,7 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
         return true;
     }
     if (R == 1 && S == 1 && stride == 1) {
-        if (!dry) *err = launch_tile<T, 1, 1, 1, 14, 14, 16, 4, 1, BWD>(a, st);
+        if (!dry) *err = launch_tile<T, 1, 1, 1, 14, 14, TILE_1X1>(a, st);
         return true;
     }
     if (!BWD && R == 3 && S == 3 && stride == 2) {

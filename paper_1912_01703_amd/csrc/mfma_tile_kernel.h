@@ -88,17 +88,21 @@ constexpr int lds_channel_stride(int v, int kq) {
 // WV: the reduction channels per group are a multiple of 4 (forward filters can be read four values at a time).
 // PHASE: one output phase of a strided backward-data pass (R, S are the sub-filter's size; BWD is set).
 // NBUF: LDS patch buffers (2 or 3).
-template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, bool WV, bool PHASE, int NBUF = 3>
+// XW: the patch is the whole source plane (1x1 filter, no padding, one tile per image) and planes are
+//     multiples of 16 bytes: a chunk's patch is then one contiguous run of CK planes, read 16 bytes per lane.
+template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, bool WV, bool PHASE, int NBUF = 3,
+          bool XW = false>
 __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int NT = 64 * WF * WP;
     constexpr int RS = R * S;
     constexpr int PH = (TH - 1) * ST + R, PW = (TW - 1) * ST + S;
     constexpr int PSZ = PH * PW;
     constexpr int KQ = CK / 4;  // channels per lane group: lane group kk owns channels [kk*KQ, kk*KQ+KQ) of a chunk
-    static_assert(CK == 4 || CK == 8 || CK == 16 || CK == 32, "CK must be 4, 8, 16 or 32");
+    static_assert(CK == 4 || CK == 8 || CK == 16 || CK == 32 || CK == 64, "CK must be 4, 8, 16, 32 or 64");
+    static_assert(!XW || (R == 1 && S == 1 && ST == 1 && PSZ % 4 == 0 && sizeof(T) == 4), "whole-plane patches only");
     constexpr int CS = lds_channel_stride(PSZ, KQ);
     constexpr int XE = CK * PSZ;
-    constexpr int XPT = (XE + NT - 1) / NT;
+    constexpr int XPT = XW ? (XE / 4 + NT - 1) / NT : (XE + NT - 1) / NT;   // load pieces per thread
     constexpr int NPX = TH * TW;
     constexpr int NB = (NPX + 15) / 16;      // 16-pixel blocks in the tile
     constexpr int NBW = (NB + WP - 1) / WP;  // blocks per wave
@@ -143,13 +147,20 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     int loff[XPT];       // word offset inside a patch buffer
 #pragma unroll
     for (int m = 0; m < XPT; ++m) {
-        const int e = tid + NT * m;
-        const int c = e / PSZ, rem = e - c * PSZ;
-        const int ph = rem / PW, pw = rem - ph * PW;
-        const int ih = ih0 + ph, iw = iw0 + pw;
-        const bool ok = (e < XE) && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
-        goff[m] = ok ? (unsigned)(c * plane + ih * a.IW + iw) * (unsigned)sizeof(T) : kOob;
-        loff[m] = (e < XE) ? c * CS + rem : TRASH + lane;
+        if constexpr (XW) {
+            const int f = tid + NT * m;                       // 16-byte piece of the chunk's CK planes
+            const int c = (4 * f) / PSZ, rem = 4 * f - c * PSZ;
+            goff[m] = f < XE / 4 ? (unsigned)(4 * f) * 4u : kOob;
+            loff[m] = f < XE / 4 ? c * CS + rem : TRASH + (lane & ~3);   // 8-byte aligned: CS is even, rem a multiple of 4
+        } else {
+            const int e = tid + NT * m;
+            const int c = e / PSZ, rem = e - c * PSZ;
+            const int ph = rem / PW, pw = rem - ph * PW;
+            const int ih = ih0 + ph, iw = iw0 + pw;
+            const bool ok = (e < XE) && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
+            goff[m] = ok ? (unsigned)(c * plane + ih * a.IW + iw) * (unsigned)sizeof(T) : kOob;
+            loff[m] = (e < XE) ? c * CS + rem : TRASH + lane;
+        }
     }
 
     // ---- per-lane filter addressing ---------------------------------------------------------
@@ -179,7 +190,8 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 #pragma unroll
     for (int i = 0; i < NBW; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    float xreg[XPT];
+    float xreg[XW ? 1 : XPT];
+    v4u xreg4[XW ? XPT : 1];
 
     // ---- fetching a chunk -------------------------------------------------------------------------
     // The patch descriptor covers exactly the channels the chunk still has, so a partial last chunk
@@ -205,7 +217,16 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
             wvo[k4] = (f_ok && kk * KQ + k4 < left) ? (unsigned)(wb + k4 * wstep_k) * (unsigned)sizeof(T) : kOob;
     };
     auto issue_x = [&](int piece, const rsrc_t& xrs) __attribute__((always_inline)) {
-        xreg[piece] = buf_load(xrs, goff[piece], tnull);
+        if constexpr (XW) xreg4[piece] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[piece], 0, 0);
+        else xreg[piece] = buf_load(xrs, goff[piece], tnull);
+    };
+    auto store_x = [&](int piece, float* dst) __attribute__((always_inline)) {
+        if constexpr (XW) {
+            *reinterpret_cast<float2*>(dst) = make_float2(__uint_as_float(xreg4[piece].x), __uint_as_float(xreg4[piece].y));
+            *reinterpret_cast<float2*>(dst + 2) = make_float2(__uint_as_float(xreg4[piece].z), __uint_as_float(xreg4[piece].w));
+        } else {
+            *dst = xreg[piece];
+        }
     };
     auto issue_w = [&](int q, const unsigned (&wvo)[KQ], float (&an)[RS * KQ]) __attribute__((always_inline)) {
         if constexpr (W4) {
@@ -295,7 +316,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
                     const int lo = (act * XPT + SACT - 1) / SACT, hi = ((act + 1) * XPT + SACT - 1) / SACT;
 #pragma unroll
                     for (int d = 0; d < (XPT + SACT - 1) / SACT + 1; ++d)
-                        if (act < SACT && lo + d < hi && lo + d < XPT) *ps[lo + d] = xreg[lo + d];
+                        if (act < SACT && lo + d < hi && lo + d < XPT) store_x(lo + d, ps[lo + d]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -319,7 +340,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
             if (c < D) {
                 __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
 #pragma unroll
-                for (int m = 0; m < XPT; ++m) xs[c * BUFSZ + loff[m]] = xreg[m];
+                for (int m = 0; m < XPT; ++m) store_x(m, xs + c * BUFSZ + loff[m]);
             }
         }
         __syncthreads();

@@ -72,8 +72,9 @@ constexpr int cmax(int a, int b) { return a > b ? a : b; }
 // a register prepared outside plus an immediate.  That is why the two LDS buffers are handled by two
 // instances of the loop (buffer offsets become immediates) and why all LDS store addresses are kept
 // in registers.
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG, bool WIDE>
-__global__ __launch_bounds__(64 * WK * WC * WS) void wgrad_kernel(WgradArgs a) {
+// OCC: waves per SIMD the register allocation must allow.
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int IMG, bool WIDE, int OCC>
+__global__ __launch_bounds__(64 * WK * WC * WS, OCC) void wgrad_kernel(WgradArgs a) {
     constexpr int NT = 64 * WK * WC * WS;
     constexpr int RS = R * S;
     constexpr int PH = (TH - 1) * ST + R, PW = (TW - 1) * ST + S, PSZ = PH * PW;
@@ -456,7 +457,7 @@ struct Plan {
     size_t ws_bytes;
 };
 
-template <int TH, int TW, int KB, int CB, int IMG>
+template <int TH, int TW, int KB, int CB, int IMG, int OCC>
 Plan make_plan(const Problem& pr, WgradArgs& a) {
     a.tiles_h = (pr.P + TH - 1) / TH;
     a.tiles_w = (pr.Q + TW - 1) / TW;
@@ -465,8 +466,8 @@ Plan make_plan(const Problem& pr, WgradArgs& a) {
     a.img_stages = (pr.N + IMG - 1) / IMG;
     a.stages = a.tiles_h * a.tiles_w * a.img_stages;
     const int blocks = a.kblocks * a.cblocks * pr.groups;
-    // Enough workgroups to cover the 256 CUs, but never more partial buffers than stages.
-    int nsplit = (256 + blocks - 1) / blocks;
+    // Enough workgroups to cover the 256 CUs OCC times, but never more partial buffers than stages.
+    int nsplit = (256 * OCC + blocks - 1) / blocks;
     if (nsplit > a.stages) nsplit = a.stages;
     if (nsplit < 1) nsplit = 1;
     a.nsplit = nsplit;
@@ -489,22 +490,22 @@ Plan make_plan(const Problem& pr, WgradArgs& a) {
 
 // WS: pixel-step shares (waves) on the 16-byte fetch path; WSN: on the 4-byte path, which needs more
 // registers per thread and therefore runs one wave per SIMD.
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int WSN, int IMG>
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int WSN, int IMG, int OCC = 1>
 hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st,
                         bool dry, size_t* ws_bytes) {
     WgradArgs a{};
     a.x = x; a.dy = dy;
     a.N = pr.N; a.C = pr.C; a.H = pr.H; a.W = pr.W; a.K = pr.K; a.P = pr.P; a.Q = pr.Q;
     a.Cg = pr.Cg; a.Kg = pr.Kg; a.groups = pr.groups; a.pad_h = pr.ph; a.pad_w = pr.pw;
-    const Plan pl = make_plan<TH, TW, KB, CB, IMG>(pr, a);
+    const Plan pl = make_plan<TH, TW, KB, CB, IMG, OCC>(pr, a);
     *ws_bytes = pl.ws_bytes;
     if (dry) return hipSuccess;
     a.out = pl.nsplit > 1 ? static_cast<float*>(ws) : dw;
     const int grid = ((a.total_wgs + 7) / 8) * 8;
     const bool wide = sizeof(T) == 4 && pr.P == TH && pr.Q == TW && (pr.H * pr.W) % 4 == 0 &&
                       pr.H * pr.W == TH * TW * ST * ST;
-    if (wide) wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, true><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
-    else wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WSN, IMG, false><<<grid, 64 * WK * WC * WSN, 0, st>>>(a);
+    if (wide) wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, true, (WK * WC * WS + 3) / 4 * OCC><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
+    else wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WSN, IMG, false, (WK * WC * WSN + 3) / 4><<<grid, 64 * WK * WC * WSN, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.nsplit == 1) return e;
     const size_t count = (size_t)pr.K * pr.Cg * pr.R * pr.S;
