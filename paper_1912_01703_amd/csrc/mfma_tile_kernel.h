@@ -209,12 +209,24 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         return make_rsrc(src + (size_t)ch * CK * plane,
                          (unsigned)__builtin_amdgcn_readfirstlane(have * plane) * (unsigned)sizeof(T));
     };
+    // Byte offsets of the lane's KQ filter rows for chunk ch, kOob for an absent filter or channel.
+    // Chunks are visited in order, so the offsets of full chunks are running sums (one add each); only
+    // a partial last chunk needs the per-channel test.
+    unsigned wrun[KQ];
+#pragma unroll
+    for (int k4 = 0; k4 < KQ; ++k4) wrun[k4] = f_ok ? (unsigned)(wbase + k4 * wstep_k) * (unsigned)sizeof(T) : kOob;
     auto filter_offsets = [&](int ch, unsigned (&wvo)[KQ]) __attribute__((always_inline)) {
         const int left = a.Rg - ch * CK;
-        const int wb = wbase + ch * wstep_chunk;
+        if (left >= CK) {
 #pragma unroll
-        for (int k4 = 0; k4 < KQ; ++k4)
-            wvo[k4] = (f_ok && kk * KQ + k4 < left) ? (unsigned)(wb + k4 * wstep_k) * (unsigned)sizeof(T) : kOob;
+            for (int k4 = 0; k4 < KQ; ++k4) wvo[k4] = wrun[k4];
+        } else {
+#pragma unroll
+            for (int k4 = 0; k4 < KQ; ++k4) wvo[k4] = kk * KQ + k4 < left ? wrun[k4] : kOob;
+        }
+        // an absent filter stays out of range: kOob plus the whole tensor is still below 2^32
+#pragma unroll
+        for (int k4 = 0; k4 < KQ; ++k4) wrun[k4] += (unsigned)wstep_chunk * (unsigned)sizeof(T);
     };
     auto issue_x = [&](int piece, const rsrc_t& xrs) __attribute__((always_inline)) {
         if constexpr (XW) xreg4[piece] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[piece], 0, 0);
