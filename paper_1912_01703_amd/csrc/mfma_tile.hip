@@ -47,7 +47,11 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
         return true;
     }
     if (!BWD && R == 3 && S == 3 && stride == 2) {
-        if (!dry) *err = launch_tile<T, 3, 3, 2, 14, 14, 8, 4, 1, false>(a, st);
+        if (dry) return true;
+        // 64 filters per workgroup unless that leaves CUs without one; then 32 filters on twice the workgroups
+        const long long wgs64 = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
+        if (wgs64 >= 200) *err = launch_tile<T, 3, 3, 2, 14, 14, 8, 4, 1, false>(a, st);
+        else *err = launch_tile<T, 3, 3, 2, 14, 14, 8, 2, 4, false>(a, st);
         return true;
     }
     return false;

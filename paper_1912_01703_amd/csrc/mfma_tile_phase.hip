@@ -33,8 +33,8 @@ Phase make_phase(int a, int st, int R, int pad, int H) {
     return p;
 }
 
-// WF x WP waves: 4 x 1 (64 destination channels per workgroup) or, when the layer has at most 16
-// destination channels per group (backward-data of a first layer), 1 x 4 so that no wave is idle.
+// WF x WP waves: 4 x 1 (64 destination channels per workgroup), 2 x 4 for small grids or, when the layer
+// has at most 16 destination channels per group (backward-data of a first layer), 1 x 4 so that no wave is idle.
 template <typename T, int JH, int JW, int WF, int WP>
 hipError_t launch_phase_waves(TileArgs a, hipStream_t st) {
     constexpr int TH = 14, TW = 14, CK = 16;
@@ -49,7 +49,10 @@ hipError_t launch_phase_waves(TileArgs a, hipStream_t st) {
 
 template <typename T, int JH, int JW>
 hipError_t launch_phase(const TileArgs& a, hipStream_t st) {
-    return a.Fg <= 16 ? launch_phase_waves<T, JH, JW, 1, 4>(a, st) : launch_phase_waves<T, JH, JW, 4, 1>(a, st);
+    if (a.Fg <= 16) return launch_phase_waves<T, JH, JW, 1, 4>(a, st);
+    // 64 destination channels per workgroup unless that leaves CUs without one; then 32 on twice the workgroups
+    const long long wgs64 = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
+    return wgs64 >= 200 ? launch_phase_waves<T, JH, JW, 4, 1>(a, st) : launch_phase_waves<T, JH, JW, 2, 4>(a, st);
 }
 
 template <typename T>
