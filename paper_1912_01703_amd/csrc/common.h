@@ -39,6 +39,12 @@ hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, f
 bool tile_supports(int pass, const Problem& pr);
 hipError_t tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, hipStream_t st);
 
+// bf16 matrix-core forward / stride-1 backward-data for 3x3 filters (mfma_bf16.hip); needs workspace.
+bool bf16_tile_supports(int pass, const Problem& pr);
+size_t bf16_tile_workspace_bytes(int pass, const Problem& pr);
+hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
+                         hipStream_t st);
+
 // Strided backward-data on the tiled kernel, one launch per output phase (mfma_tile_phase.hip).
 bool tile_phase_supports(const Problem& pr);
 hipError_t tile_phase_run(const Problem& pr, const void* dy, const void* w, float* dx, hipStream_t st);

@@ -1,0 +1,355 @@
+// Forward and stride-1 backward-data 3x3 convolution of bf16 tensors on the bf16 matrix cores
+// (v_mfma_f32_16x16x32_bf16, fp32 accumulate, fp32 output), gfx950.
+//
+//   dst[n, f, oh, ow] = sum_{c, r, s} src[n, c, oh-pad_h+r, ow-pad_w+s] * Wt(f, c, r, s)
+//   forward        src = x,  Wt(f,c,r,s) = w[f][c][r][s]
+//   backward-data  src = dy, Wt(f,c,r,s) = w[c][f][2-r][2-s], pad' = 2-pad
+//
+// One MFMA contracts 32 reduction channels, and a lane supplies 8 consecutive channels of its
+// pixel (B operand) or filter (A operand) as one 16-byte register group.  NCHW keeps a pixel's
+// channels a whole plane apart, so two small pre-passes rewrite the operands into the caller's
+// workspace with channels innermost: src as [N][H][W][C], the filters as [tap][f][c] (for
+// backward-data already transposed and rotated).  They move each input byte once; the main
+// kernel then copies 64-byte runs (32 channels of a pixel) from global memory to LDS and reads
+// every operand with one 16-byte access.
+//
+// Main kernel.  A workgroup owns one image, one 14x14 rectangle of output pixels and 16*FB*WF
+// filters and walks the reduction channels in chunks of 32.  Wave (wf, wp) owns 16*FB filters and
+// every WP-th 16-pixel block.  Filters live in registers in A-operand layout; the 16x16-pixel
+// patch of a chunk sits in LDS as [pixel][32 channels] with 80-byte rows (16-byte reads of 8
+// consecutive pixels then fall in distinct banks) and the tap shift is an address immediate.
+// One B operand feeds FB MFMAs: LDS bandwidth (128 B/cycle per CU against 4 KB of operands per
+// MFMA pair) is what bounds this kernel, not the matrix pipe.
+// Everything is pipelined inside the MFMA loop, which holds no vector-ALU instruction: B operands
+// are read 7 slots ahead into a ring of 9 register groups, the patch of chunk i+2 is stored to
+// its LDS buffer (three buffers) and the registers refilled with chunk i+3, and the filters of
+// chunk i+1 replace those of chunk i tap by tap as soon as a tap's MFMAs are issued.
+#include "common.h"
+
+namespace miconv {
+namespace {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr unsigned kOob = 0x80000000u;  // tensors handled here are smaller than 2 GiB
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+
+// ---- pre-pass 1: [N][C][HW] -> [N][HW][C], 32 channels x 256 pixels per workgroup ----------
+struct PackXArgs {
+    const uint16_t* src;
+    uint16_t* dst;
+    int N, C, HW;          // C % 32 == 0, HW % 8 == 0
+    unsigned src_bytes;
+};
+
+__global__ __launch_bounds__(256) void pack_nhwc_kernel(PackXArgs a) {
+    constexpr int LS = 264;   // LDS row stride in elements (16-byte aligned rows)
+    __shared__ __attribute__((aligned(16))) uint16_t tile[32 * LS];
+    const int t = threadIdx.x;
+    const int p0 = blockIdx.x * 256, c0 = blockIdx.y * 32, n = blockIdx.z;
+    const rsrc_t rs = make_rsrc(a.src, a.src_bytes);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int q = t + 256 * i;
+        const int c = q >> 5, pc = q & 31;
+        const int p = p0 + 8 * pc;   // 8 consecutive pixels of one channel; all inside the plane or none
+        const unsigned off = p < a.HW ? (unsigned)((n * a.C + c0 + c) * a.HW + p) * 2u : kOob;
+        const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
+        *reinterpret_cast<v4u*>(&tile[c * LS + 8 * pc]) = v;
+    }
+    __syncthreads();
+    const int p = p0 + t;
+    if (p >= a.HW) return;
+    unsigned d[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        d[j] = (unsigned)tile[(2 * j) * LS + t] | ((unsigned)tile[(2 * j + 1) * LS + t] << 16);
+    v4u* o = reinterpret_cast<v4u*>(a.dst + ((size_t)n * a.HW + p) * a.C + c0);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) o[j] = v4u{d[4 * j], d[4 * j + 1], d[4 * j + 2], d[4 * j + 3]};
+}
+
+// ---- pre-pass 2: filters -> [tap][f][c] ---------------------------------------------------
+struct PackWArgs {
+    const uint16_t* w;   // [K][C][3][3]
+    uint16_t* dst;       // [9][F][Cs]
+    int F, Cs, bwd;      // forward: F = K, Cs = C; backward-data: F = C, Cs = K
+};
+
+__global__ __launch_bounds__(256) void pack_w_kernel(PackWArgs a) {
+    const int idx = blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.F * a.Cs) return;
+    const int f = idx / a.Cs, c = idx - f * a.Cs;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+        const size_t s = a.bwd ? ((size_t)c * a.F + f) * 9 + (8 - tap) : ((size_t)f * a.Cs + c) * 9 + tap;
+        a.dst[((size_t)tap * a.F + f) * a.Cs + c] = a.w[s];
+    }
+}
+
+// ---- main kernel ---------------------------------------------------------------------------
+struct BfArgs {
+    const uint16_t* xt;   // [N][IH][IW][Cs]
+    const uint16_t* wp;   // [9][F][Cs]
+    float* dst;           // [N][F][OH][OW]
+    int N, Cs, IH, IW, F, OH, OW;
+    int pad_h, pad_w;
+    int tiles_h, tiles_w, fblocks, units;
+    unsigned wp_bytes;
+};
+
+template <int FB, int WF, int WP>
+__global__ __launch_bounds__(64 * WF * WP, 2) void bf16_tile_kernel(BfArgs a) {
+    constexpr int TH = 14, TW = 14, PW = 16, PSZ = 256, NPX = TH * TW;
+    constexpr int NT = 64 * WF * WP;
+    constexpr int NB = (NPX + 15) / 16, NBW = (NB + WP - 1) / WP;
+    constexpr int ROWB = 80;                 // bytes per patch pixel in LDS: 64 of data, 16 of padding
+    constexpr int BUFB = PSZ * ROWB;         // one patch buffer
+    constexpr int NBUF = 3, D = NBUF - 1;
+    constexpr int XPT = PSZ * 4 / NT;        // 16-byte pieces per thread and chunk
+    static_assert(PSZ * 4 % NT == 0, "whole pieces");
+    constexpr int SLOTS = 9 * NBW;           // one slot = one B operand = FB MFMAs
+    constexpr int RING = 9, PF = 7;          // B operands are requested PF slots ahead; RING divides SLOTS
+    static_assert(SLOTS % RING == 0 && PF < RING, "ring");
+
+    __shared__ __attribute__((aligned(16))) unsigned char xs[NBUF * BUFB];
+
+    const int b = blockIdx.x;
+    const int xcd = b & 7, rest = b >> 3;
+    const int fblk = rest % a.fblocks;
+    const int unit = (rest / a.fblocks) * 8 + xcd;   // the filter blocks of one (image, tile) share an XCD
+    if (unit >= a.units) return;
+    int u = unit;
+    const int tj = u % a.tiles_w; u /= a.tiles_w;
+    const int ti = u % a.tiles_h;
+    const int n = u / a.tiles_h;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wf = wave % WF, wp = wave / WF;
+    const int li = lane & 15, kk = lane >> 4;
+
+    const int oh0 = ti * TH, ow0 = tj * TW;
+    const int ih0 = oh0 - a.pad_h, iw0 = ow0 - a.pad_w;
+    const uint16_t* src = a.xt + (size_t)n * a.IH * a.IW * a.Cs;
+    const unsigned img_bytes = (unsigned)(a.IH * a.IW * a.Cs) * 2u;
+    const int nchunks = a.Cs / 32;
+
+    // patch gather plan: piece = (pixel, quarter of its 32 channels)
+    unsigned goff[XPT];
+    int loff[XPT];
+#pragma unroll
+    for (int m = 0; m < XPT; ++m) {
+        const int e = tid + NT * m;
+        const int pix = e >> 2, q = e & 3;
+        const int ph = pix / PW, pw = pix - ph * PW;
+        const int ih = ih0 + ph, iw = iw0 + pw;
+        const bool ok = ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
+        goff[m] = ok ? (unsigned)((ih * a.IW + iw) * a.Cs + 8 * q) * 2u : kOob;
+        loff[m] = pix * ROWB + q * 16;
+    }
+    // filter rows of this lane: filter f, channels 8*kk .. 8*kk+7 of the chunk
+    const int fbase = fblk * (16 * FB * WF) + wf * (16 * FB);
+    unsigned wofs[FB];              // tap 0; tap t lies t * tap_bytes further (a wave-uniform offset)
+    const unsigned tap_bytes = (unsigned)(a.F * a.Cs) * 2u;
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb) {
+        const int f = fbase + 16 * fb + li;
+        wofs[fb] = f < a.F ? (unsigned)(f * a.Cs + 8 * kk) * 2u : kOob;
+    }
+    // B operand addresses of this lane's pixel in each of its blocks (tap (0,0), buffer 0)
+    int pixb[NBW];
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) {
+        int j = 16 * (wp + WP * i) + li;
+        if (j >= NPX) j = 0;   // padding lanes read a valid address; their results are never stored
+        const int th = j / TW, tw = j - th * TW;
+        pixb[i] = (th * PW + tw) * ROWB + kk * 16;
+    }
+    const bool last_ok = wp + WP * (NBW - 1) < NB;   // does this wave own a block in its last slot?
+
+    v4f acc[FB][NBW];
+#pragma unroll
+    for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) acc[fb][i] = v4f{0.f, 0.f, 0.f, 0.f};
+
+    auto patch_rsrc = [&](int ch) __attribute__((always_inline)) -> rsrc_t {
+        const bool have = ch < nchunks;   // a chunk past the end reads zeros
+        return make_rsrc(src + (have ? ch * 32 : 0), have ? img_bytes - (unsigned)ch * 64u : 0u);
+    };
+    auto filter_rsrc = [&](int ch) __attribute__((always_inline)) -> rsrc_t {
+        const bool have = ch < nchunks;
+        return make_rsrc(a.wp + (have ? ch * 32 : 0), have ? a.wp_bytes - (unsigned)ch * 64u : 0u);
+    };
+    auto mine = [&](int i) __attribute__((always_inline)) -> bool { return !(NB % WP != 0 && i == NBW - 1 && !last_ok); };
+    auto tapoff = [](int tap) { return ((tap / 3) * PW + tap % 3) * ROWB; };
+
+    v4u A[9][FB];
+    v4u xreg[XPT];
+    v4u ring[RING];
+
+    // ---- prologue: filters of chunk 0; patches of chunks 0..D-1 to LDS, chunk D to registers --------
+    {
+        const rsrc_t wrs = filter_rsrc(0);
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+            for (int fb = 0; fb < FB; ++fb) A[tap][fb] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs[fb], tap * tap_bytes, 0);
+#pragma unroll
+        for (int c = 0; c <= D; ++c) {
+            const rsrc_t xrs = patch_rsrc(c);
+#pragma unroll
+            for (int m = 0; m < XPT; ++m) xreg[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
+            if (c < D) {
+#pragma unroll
+                for (int m = 0; m < XPT; ++m) *reinterpret_cast<v4u*>(xs + c * BUFB + loff[m]) = xreg[m];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < PF; ++s)
+            if (mine(s % NBW)) ring[s % RING] = *reinterpret_cast<const v4u*>(xs + pixb[s % NBW] + tapoff(s / NBW));
+    }
+
+    int rd = 0, nx = BUFB, wr = D * BUFB;
+    for (int ch = 0; ch < nchunks; ++ch) {
+        const rsrc_t xrs = patch_rsrc(ch + D + 1);
+        const rsrc_t wrs = filter_rsrc(ch + 1);
+        const unsigned char* pr[NBW];
+        const unsigned char* pn[NBW];
+        unsigned char* ps[XPT];
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) { pr[i] = xs + rd + pixb[i]; pn[i] = xs + nx + pixb[i]; }
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) ps[m] = xs + wr + loff[m];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+            const int tap = s / NBW, i = s % NBW;
+            {   // request the B operand of slot s + PF (of the next chunk's buffer past the end of this one)
+                const int s2 = s + PF;
+                const int t2 = (s2 % SLOTS) / NBW, i2 = s2 % NBW;
+                if (mine(i2)) {
+                    const unsigned char* base = s2 < SLOTS ? pr[i2] : pn[i2];
+                    ring[s2 % RING] = *reinterpret_cast<const v4u*>(base + tapoff(t2));
+                }
+            }
+            if (mine(i)) {
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb)
+                    acc[fb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, A[tap][fb]),
+                                                                         __builtin_bit_cast(v8bf, ring[s % RING]),
+                                                                         acc[fb][i], 0, 0, 0);
+            }
+            // patch of chunk ch+D: registers -> LDS in the first third of the slots; the loads of
+            // chunk ch+D+1 refill the same registers in the second third
+#pragma unroll
+            for (int m = 0; m < XPT; ++m) {
+                if (m * (SLOTS / 3) / XPT == s) *reinterpret_cast<v4u*>(ps[m]) = xreg[m];
+                if (SLOTS / 3 + m * (SLOTS / 3) / XPT == s) xreg[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
+            }
+            // this tap's filters are no longer needed: fetch the next chunk's into the same registers
+            if (i == NBW - 1) {
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb) A[tap][fb] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs[fb], tap * tap_bytes, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+        rd = nx;
+        nx = nx + BUFB == NBUF * BUFB ? 0 : nx + BUFB;
+        wr = wr + BUFB == NBUF * BUFB ? 0 : wr + BUFB;
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // loads fetched past the last chunk still target registers
+
+    // ---- epilogue: D[f = 4*kk+v][pixel = li] ---------------------------------------------------
+    const int dplane = a.OH * a.OW;
+    float* dst = a.dst + (size_t)n * a.F * dplane;
+#pragma unroll
+    for (int i = 0; i < NBW; ++i) {
+        const int j = 16 * (wp + WP * i) + li;
+        if (j >= NPX) continue;
+        const int th = j / TW, tw = j - th * TW;
+        const int oh = oh0 + th, ow = ow0 + tw;
+        if (oh >= a.OH || ow >= a.OW) continue;
+#pragma unroll
+        for (int fb = 0; fb < FB; ++fb)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int f = fbase + 16 * fb + 4 * kk + v;
+                if (f < a.F) dst[(size_t)f * dplane + oh * a.OW + ow] = acc[fb][i][v];
+            }
+    }
+}
+
+constexpr int kFB = 2, kWF = 2, kWP = 2;
+
+size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+struct Shape {
+    int Cs, F, IH, IW, OH, OW, pad_h, pad_w;
+};
+
+bool shape_of(int pass, const Problem& pr, Shape& s) {
+    if (pr.dtype != 1 || pr.R != 3 || pr.S != 3 || pr.sh != 1 || pr.sw != 1 || pr.groups != 1) return false;
+    if (pr.ph > 2 || pr.pw > 2) return false;
+    if (pass == 0) s = Shape{pr.C, pr.K, pr.H, pr.W, pr.P, pr.Q, pr.ph, pr.pw};
+    else if (pass == 1) s = Shape{pr.K, pr.C, pr.P, pr.Q, pr.H, pr.W, 2 - pr.ph, 2 - pr.pw};
+    else return false;
+    if (s.Cs % 32 != 0 || (s.IH * s.IW) % 8 != 0) return false;
+    const size_t lim = (size_t)1 << 31;
+    if ((size_t)pr.N * s.Cs * s.IH * s.IW * 2 >= lim || (size_t)pr.N * s.F * s.OH * s.OW * 4 >= ((size_t)1 << 33)) return false;
+    if ((size_t)9 * s.F * s.Cs * 2 >= lim) return false;
+    return true;
+}
+
+}  // namespace
+
+bool bf16_tile_supports(int pass, const Problem& pr) {
+    Shape s;
+    return shape_of(pass, pr, s);
+}
+
+size_t bf16_tile_workspace_bytes(int pass, const Problem& pr) {
+    Shape s;
+    if (!shape_of(pass, pr, s)) return 0;
+    return round256((size_t)pr.N * s.IH * s.IW * s.Cs * 2) + round256((size_t)9 * s.F * s.Cs * 2);
+}
+
+hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
+                         hipStream_t st) {
+    Shape s;
+    if (!shape_of(pass, pr, s)) return hipErrorNotSupported;
+    uint16_t* xt = static_cast<uint16_t*>(ws);
+    uint16_t* wp = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(ws) + round256((size_t)pr.N * s.IH * s.IW * s.Cs * 2));
+    const int HW = s.IH * s.IW;
+
+    PackXArgs px{static_cast<const uint16_t*>(in0), xt, pr.N, s.Cs, HW, (unsigned)((size_t)pr.N * s.Cs * HW * 2)};
+    pack_nhwc_kernel<<<dim3((HW + 255) / 256, s.Cs / 32, pr.N), 256, 0, st>>>(px);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    PackWArgs pw{static_cast<const uint16_t*>(in1), wp, s.F, s.Cs, pass == 1 ? 1 : 0};
+    pack_w_kernel<<<(s.F * s.Cs + 255) / 256, 256, 0, st>>>(pw);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+
+    BfArgs a{};
+    a.xt = xt; a.wp = wp; a.dst = out;
+    a.N = pr.N; a.Cs = s.Cs; a.IH = s.IH; a.IW = s.IW; a.F = s.F; a.OH = s.OH; a.OW = s.OW;
+    a.pad_h = s.pad_h; a.pad_w = s.pad_w;
+    a.tiles_h = (s.OH + 13) / 14; a.tiles_w = (s.OW + 13) / 14;
+    a.fblocks = (s.F + 16 * kFB * kWF - 1) / (16 * kFB * kWF);
+    a.units = pr.N * a.tiles_h * a.tiles_w;
+    a.wp_bytes = (unsigned)((size_t)9 * s.F * s.Cs * 2);
+    const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
+    bf16_tile_kernel<kFB, kWF, kWP><<<grid, 64 * kWF * kWP, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace miconv

@@ -80,6 +80,28 @@ def test_mfma_shapes(row, dtype):
     pu.check_layer_full(L, dtype, algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
 
 
+BF16MM = [
+    # name     N   C    H   W   K   pad    3x3 stride 1, bf16: forward (C % 32 == 0, H*W % 8 == 0) and/or
+    #                                      backward-data (K % 32 == 0, P*Q % 8 == 0) run on the bf16 matrix cores
+    ("b3x3a", 2, 32, 16, 16, 64, 1),
+    ("b3x3b", 3, 64, 20, 18, 48, 1),       # 48 filters: partial filter block; backward-data takes the widened path
+    ("b3x3c", 1, 96, 30, 28, 96, 0),       # no padding; backward-data sees pad' = 2
+    ("b3x3d", 2, 32, 12, 24, 32, 2),       # padding 2
+    ("b3x3e", 1, 160, 28, 28, 128, 1),     # five chunks, four tiles, two filter blocks
+    ("b3x3f", 5, 32, 8, 8, 16, 1),         # one partial tile, one partial filter block
+]
+
+
+@pytest.mark.parametrize("row", BF16MM, ids=[r[0] for r in BF16MM])
+def test_bf16_matrix_core_path(row):
+    from paper_1912_01703_amd import binding as mc
+    name, N, C, H, W, K, pd = row
+    L = wl.custom_layer(name, N, C, H, W, K, 3, 3, 1, pd, 1, seed=6000 + BF16MM.index(row))
+    # the layout pre-passes of that path are what needs a workspace in a forward pass
+    assert mc.conv2d_workspace_bytes(0, *L.conv_args(), mc.BF16_F32ACC) > 0
+    pu.check_layer_full(L, "bf16", passes=("fwd", "bwd_data"), algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+
+
 PHASED = [
     # name      N   C   H   W   K   R   S  stride pad groups      backward-data only (per-phase MFMA launches)
     ("p5x5s2", 2, 16, 20, 20, 16, 5, 5, 2, 2, 1),
