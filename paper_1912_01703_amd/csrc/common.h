@@ -45,6 +45,11 @@ size_t bf16_tile_workspace_bytes(int pass, const Problem& pr);
 hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
                          hipStream_t st);
 
+// bf16 matrix-core backward-weight for 3x3 stride-1 filters (mfma_bf16_wgrad.hip); needs workspace.
+bool bf16_wgrad_supports(const Problem& pr);
+size_t bf16_wgrad_workspace_bytes(const Problem& pr);
+hipError_t bf16_wgrad_run(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st);
+
 // Strided backward-data on the tiled kernel, one launch per output phase (mfma_tile_phase.hip).
 bool tile_phase_supports(const Problem& pr);
 hipError_t tile_phase_run(const Problem& pr, const void* dy, const void* w, float* dx, hipStream_t st);

@@ -8,6 +8,7 @@ bool mfma_supports(int pass, const Problem& pr) {
     if (is_depthwise(pr)) return false;  // one input channel per filter: nothing to contract
     if (smallc_supports(pass, pr)) return true;
     if (bf16_tile_supports(pass, pr)) return true;
+    if (pass == 2 && bf16_wgrad_supports(pr)) return true;
     if (pass == 0) return tile_supports(pass, pr);
     if (pass == 1) return tile_supports(pass, pr) || tile_phase_supports(pr);
     size_t ws;
@@ -19,6 +20,7 @@ size_t mfma_workspace_bytes(int pass, const Problem& pr) {
     if (is_depthwise(pr)) return 0;
     if (smallc_supports(pass, pr)) return smallc_workspace_bytes(pass, pr);
     if (bf16_tile_supports(pass, pr)) return bf16_tile_workspace_bytes(pass, pr);
+    if (pass == 2 && bf16_wgrad_supports(pr)) return bf16_wgrad_workspace_bytes(pr);
     if (pass == 2) wgrad_supports(pr, &ws);
     return ws;
 }
@@ -26,6 +28,7 @@ size_t mfma_workspace_bytes(int pass, const Problem& pr) {
 hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws, hipStream_t st) {
     if (smallc_supports(pass, pr)) return smallc_run(pass, pr, a, b, out, ws, st);
     if (bf16_tile_supports(pass, pr)) return bf16_tile_run(pass, pr, a, b, out, ws, st);
+    if (pass == 2 && bf16_wgrad_supports(pr)) return bf16_wgrad_run(pr, a, b, out, ws, st);
     if (pass == 0) return tile_run(pass, pr, a, b, out, st);
     if (pass == 1) return tile_supports(pass, pr) ? tile_run(pass, pr, a, b, out, st) : tile_phase_run(pr, a, b, out, st);
     return wgrad_run(pr, a, b, out, ws, st);

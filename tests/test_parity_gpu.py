@@ -102,6 +102,25 @@ def test_bf16_matrix_core_path(row):
     pu.check_layer_full(L, "bf16", passes=("fwd", "bwd_data"), algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
 
 
+BF16WG = [
+    # name     N   C    H   W   K   pad    3x3 stride 1, bf16, H*W % 8 == 0 and P*Q % 8 == 0, N*P*Q >= 4096:
+    #                                      backward-weight on the bf16 matrix cores (rows streamed through LDS)
+    ("w3x3a", 16, 32, 16, 16, 64, 1),
+    ("w3x3b", 9, 40, 32, 32, 72, 1),       # N not a multiple of 8, partial channel blocks, two strips
+    ("w3x3c", 8, 32, 30, 28, 64, 0),       # no padding
+    ("w3x3d", 8, 16, 24, 24, 16, 2),       # padding 2
+    ("w3x3e", 3, 64, 120, 40, 64, 1),      # three row segments
+]
+
+
+@pytest.mark.parametrize("row", BF16WG, ids=[r[0] for r in BF16WG])
+def test_bf16_matrix_core_bwd_weight(row):
+    from paper_1912_01703_amd import binding as mc
+    name, N, C, H, W, K, pd = row
+    L = wl.custom_layer(name, N, C, H, W, K, 3, 3, 1, pd, 1, seed=6100 + BF16WG.index(row))
+    pu.check_layer_full(L, "bf16", passes=("bwd_weight",), algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+
+
 PHASED = [
     # name      N   C   H   W   K   R   S  stride pad groups      backward-data only (per-phase MFMA launches)
     ("p5x5s2", 2, 16, 20, 20, 16, 5, 5, 2, 2, 1),
