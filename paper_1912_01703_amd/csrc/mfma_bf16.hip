@@ -102,8 +102,8 @@ struct BfArgs {
     unsigned wp_bytes;
 };
 
-template <int FB, int WF, int WP>
-__global__ __launch_bounds__(64 * WF * WP, 2) void bf16_tile_kernel(BfArgs a) {
+template <int FB, int WF, int WP, int OCC>
+__global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) {
     constexpr int TH = 14, TW = 14, PW = 16, PSZ = 256, NPX = TH * TW;
     constexpr int NT = 64 * WF * WP;
     constexpr int NB = (NPX + 15) / 16, NBW = (NB + WP - 1) / WP;
@@ -287,7 +287,11 @@ __global__ __launch_bounds__(64 * WF * WP, 2) void bf16_tile_kernel(BfArgs a) {
     }
 }
 
-constexpr int kFB = 2, kWF = 2, kWP = 2;
+#ifndef BF_CFG
+#define BF_CFG 2, 2, 2, 2
+#endif
+constexpr int kCfg[4] = {BF_CFG};
+constexpr int kFB = kCfg[0], kWF = kCfg[1], kWP = kCfg[2], kOCC = kCfg[3];
 
 size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -348,7 +352,7 @@ hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const voi
     a.units = pr.N * a.tiles_h * a.tiles_w;
     a.wp_bytes = (unsigned)((size_t)9 * s.F * s.Cs * 2);
     const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
-    bf16_tile_kernel<kFB, kWF, kWP><<<grid, 64 * kWF * kWP, 0, st>>>(a);
+    bf16_tile_kernel<kFB, kWF, kWP, kOCC><<<grid, 64 * kWF * kWP, 0, st>>>(a);
     return hipGetLastError();
 }
 
