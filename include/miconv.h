@@ -29,7 +29,10 @@
  *             reaches (they become 0).
  *  workspace  scratch of at least conv2d_workspace_bytes(...) bytes for the
  *             same arguments, 256-byte aligned; may be NULL when that size
- *             is 0.  Its contents are undefined afterwards.
+ *             is 0.  Its contents are undefined afterwards.  It holds the
+ *             partial sums of a split backward-weight reduction and, for
+ *             bfloat16 inputs on the bf16 matrix-core kernels, re-laid-out
+ *             copies of the operands (up to the size of the inputs).
  *  stream     a hipStream_t passed as void* (NULL = the default stream).  All
  *             work is enqueued on it; the call returns without synchronising,
  *             so the host can run ahead of the device as in the paper's
