@@ -8,8 +8,8 @@
 // One MFMA contracts 32 reduction channels, and a lane supplies 8 consecutive channels of its
 // pixel (B operand) or filter (A operand) as one 16-byte register group.  NCHW keeps a pixel's
 // channels a whole plane apart, so two small pre-passes rewrite the operands into the caller's
-// workspace with channels innermost: src as [N][H][W][C], the filters as [tap][f][c] (for
-// backward-data already transposed and rotated).  They move each input byte once; the main
+// workspace with channels innermost: src as [N][H][W][C], the filters as [chunk][tap][f][32 channels]
+// (for backward-data already transposed and rotated; a wave's 16 filters are then 1 KB of whole cache lines).  They move each input byte once; the main
 // kernel then copies 64-byte runs (32 channels of a pixel) from global memory to LDS and reads
 // every operand with one 16-byte access.
 //
@@ -25,6 +25,9 @@
 // its LDS buffer (three buffers) and the registers refilled with chunk i+3, and the filters of
 // chunk i+1 replace those of chunk i tap by tap as soon as a tap's MFMAs are issued.
 #include "common.h"
+#ifndef BF_EXP
+#define BF_EXP 0
+#endif
 
 namespace miconv {
 namespace {
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(256) void pack_nhwc_kernel(PackXArgs a) {
 // ---- pre-pass 2: filters -> [tap][f][c] ---------------------------------------------------
 struct PackWArgs {
     const uint16_t* w;   // [K][C][3][3]
-    uint16_t* dst;       // [9][F][Cs]
+    uint16_t* dst;       // [Cs/32][9][F][32]: the 32 channels of a chunk are 64 contiguous bytes per (tap, filter)
     int F, Cs, bwd;      // forward: F = K, Cs = C; backward-data: F = C, Cs = K
 };
 
@@ -87,14 +90,14 @@ __global__ __launch_bounds__(256) void pack_w_kernel(PackWArgs a) {
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
         const size_t s = a.bwd ? ((size_t)c * a.F + f) * 9 + (8 - tap) : ((size_t)f * a.Cs + c) * 9 + tap;
-        a.dst[((size_t)tap * a.F + f) * a.Cs + c] = a.w[s];
+        a.dst[(((size_t)(c >> 5) * 9 + tap) * a.F + f) * 32 + (c & 31)] = a.w[s];
     }
 }
 
 // ---- main kernel ---------------------------------------------------------------------------
 struct BfArgs {
     const uint16_t* xt;   // [N][IH][IW][Cs]
-    const uint16_t* wp;   // [9][F][Cs]
+    const uint16_t* wp;   // [Cs/32][9][F][32]
     float* dst;           // [N][F][OH][OW]
     int N, Cs, IH, IW, F, OH, OW;
     int pad_h, pad_w;
@@ -102,13 +105,19 @@ struct BfArgs {
     unsigned wp_bytes;
 };
 
-template <int FB, int WF, int WP, int OCC>
+// ALDS: the filters of taps 1..8 go through LDS once per workgroup instead of being loaded by every wave.
+template <int FB, int WF, int WP, int OCC, bool ALDS>
 __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) {
     constexpr int TH = 14, TW = 14, PW = 16, PSZ = 256, NPX = TH * TW;
     constexpr int NT = 64 * WF * WP;
     constexpr int NB = (NPX + 15) / 16, NBW = (NB + WP - 1) / WP;
     constexpr int ROWB = 80;                 // bytes per patch pixel in LDS: 64 of data, 16 of padding
-    constexpr int BUFB = PSZ * ROWB;         // one patch buffer
+    // A 16-pixel block of the 14-wide tile wraps to the next patch row.  With this row pitch the
+    // wrap continues the 80-byte progression modulo 128 bytes (14 * 80 = 96 mod 128), so the 8 lanes
+    // the LDS serves together still hit distinct banks.
+    constexpr int RPB = 16 * ROWB + 96;
+    static_assert((RPB - TW * ROWB) % 128 == 0, "row pitch keeps wrapped blocks conflict-free");
+    constexpr int BUFB = 16 * RPB;           // one patch buffer
     constexpr int NBUF = 3, D = NBUF - 1;
     constexpr int XPT = PSZ * 4 / NT;        // 16-byte pieces per thread and chunk
     static_assert(PSZ * 4 % NT == 0, "whole pieces");
@@ -116,7 +125,13 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     constexpr int RING = 9, PF = 7;          // B operands are requested PF slots ahead; RING divides SLOTS
     static_assert(SLOTS % RING == 0 && PF < RING, "ring");
 
-    __shared__ __attribute__((aligned(16))) unsigned char xs[NBUF * BUFB];
+    constexpr int FW = 16 * FB * WF;                      // filters per workgroup
+    constexpr int ABUF = 8 * FW * ROWB;                   // taps 1..8 of a chunk's filters: [tap-1][f][32 channels], 80-byte rows
+    constexpr int APT = ALDS ? 8 * FW * 4 / NT : 1;       // 16-byte filter pieces per thread and chunk
+    static_assert(!ALDS || 8 * FW * 4 % NT == 0, "whole filter pieces");
+    constexpr int ABASE = NBUF * BUFB;
+
+    __shared__ __attribute__((aligned(16))) unsigned char xs[NBUF * BUFB + (ALDS ? 2 * ABUF : 0)];
 
     const int b = blockIdx.x;
     const int xcd = b & 7, rest = b >> 3;
@@ -150,16 +165,16 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
         const int ih = ih0 + ph, iw = iw0 + pw;
         const bool ok = ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
         goff[m] = ok ? (unsigned)((ih * a.IW + iw) * a.Cs + 8 * q) * 2u : kOob;
-        loff[m] = pix * ROWB + q * 16;
+        loff[m] = ph * RPB + pw * ROWB + q * 16;
     }
     // filter rows of this lane: filter f, channels 8*kk .. 8*kk+7 of the chunk
     const int fbase = fblk * (16 * FB * WF) + wf * (16 * FB);
     unsigned wofs[FB];              // tap 0; tap t lies t * tap_bytes further (a wave-uniform offset)
-    const unsigned tap_bytes = (unsigned)(a.F * a.Cs) * 2u;
+    const unsigned tap_bytes = (unsigned)a.F * 64u;
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb) {
         const int f = fbase + 16 * fb + li;
-        wofs[fb] = f < a.F ? (unsigned)(f * a.Cs + 8 * kk) * 2u : kOob;
+        wofs[fb] = f < a.F ? (unsigned)(f * 32 + 8 * kk) * 2u : kOob;
     }
     // B operand addresses of this lane's pixel in each of its blocks (tap (0,0), buffer 0)
     int pixb[NBW];
@@ -168,7 +183,7 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
         int j = 16 * (wp + WP * i) + li;
         if (j >= NPX) j = 0;   // padding lanes read a valid address; their results are never stored
         const int th = j / TW, tw = j - th * TW;
-        pixb[i] = (th * PW + tw) * ROWB + kk * 16;
+        pixb[i] = th * RPB + tw * ROWB + kk * 16;
     }
     const bool last_ok = wp + WP * (NBW - 1) < NB;   // does this wave own a block in its last slot?
 
@@ -184,12 +199,28 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     };
     auto filter_rsrc = [&](int ch) __attribute__((always_inline)) -> rsrc_t {
         const bool have = ch < nchunks;
-        return make_rsrc(a.wp + (have ? ch * 32 : 0), have ? a.wp_bytes - (unsigned)ch * 64u : 0u);
+        const unsigned chunk_bytes = 9u * tap_bytes;
+        return make_rsrc(reinterpret_cast<const unsigned char*>(a.wp) + (have ? (size_t)ch * chunk_bytes : 0), have ? chunk_bytes : 0u);
     };
     auto mine = [&](int i) __attribute__((always_inline)) -> bool { return !(NB % WP != 0 && i == NBW - 1 && !last_ok); };
-    auto tapoff = [](int tap) { return ((tap / 3) * PW + tap % 3) * ROWB; };
+    auto tapoff = [](int tap) { return (tap / 3) * RPB + (tap % 3) * ROWB; };
 
-    v4u A[9][FB];
+    v4u A[ALDS ? 1 : 9][FB];   // filters in registers: all taps, or tap 0 only
+    v4u Ar[2][FB];             // ALDS: filters of the current and the next tap, read from LDS
+    v4u areg[APT];             // ALDS: filter pieces on their way from global memory to LDS
+    unsigned ago[APT];
+    int aoff[APT];
+    if constexpr (ALDS) {
+#pragma unroll
+        for (int m = 0; m < APT; ++m) {
+            const int e = tid + NT * m;
+            const int q = e & 3, fl = (e >> 2) % FW, tap = 1 + (e >> 2) / FW;
+            const int f = fblk * FW + fl;
+            ago[m] = f < a.F ? (unsigned)((tap * a.F + f) * 32 + 8 * q) * 2u : kOob;
+            aoff[m] = ABASE + ((tap - 1) * FW + fl) * ROWB + q * 16;
+        }
+    }
+    const int alane = ABASE + (wf * 16 * FB + li) * ROWB + kk * 16;   // this lane's row in a filter buffer (tap 1, block 0)
     v4u xreg[XPT];
     v4u ring[RING];
 
@@ -197,9 +228,18 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     {
         const rsrc_t wrs = filter_rsrc(0);
 #pragma unroll
-        for (int tap = 0; tap < 9; ++tap)
+        for (int tap = 0; tap < (ALDS ? 1 : 9); ++tap)
 #pragma unroll
             for (int fb = 0; fb < FB; ++fb) A[tap][fb] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs[fb], tap * tap_bytes, 0);
+        if constexpr (ALDS) {
+#pragma unroll
+            for (int m = 0; m < APT; ++m) areg[m] = __builtin_amdgcn_raw_buffer_load_b128(wrs, ago[m], 0, 0);
+#pragma unroll
+            for (int m = 0; m < APT; ++m) *reinterpret_cast<v4u*>(xs + aoff[m]) = areg[m];
+            const rsrc_t wrs1 = filter_rsrc(1);
+#pragma unroll
+            for (int m = 0; m < APT; ++m) areg[m] = __builtin_amdgcn_raw_buffer_load_b128(wrs1, ago[m], 0, 0);
+        }
 #pragma unroll
         for (int c = 0; c <= D; ++c) {
             const rsrc_t xrs = patch_rsrc(c);
@@ -220,6 +260,13 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     for (int ch = 0; ch < nchunks; ++ch) {
         const rsrc_t xrs = patch_rsrc(ch + D + 1);
         const rsrc_t wrs = filter_rsrc(ch + 1);
+        const rsrc_t wrs2 = filter_rsrc(ch + 2);
+        const unsigned char* ar = xs + alane + (ch & 1) * ABUF;            // filters of this chunk
+        unsigned char* aw[APT];                                           // ... and where the next chunk's go
+        if constexpr (ALDS) {
+#pragma unroll
+            for (int m = 0; m < APT; ++m) aw[m] = xs + aoff[m] + ((ch + 1) & 1) * ABUF;
+        }
         const unsigned char* pr[NBW];
         const unsigned char* pn[NBW];
         unsigned char* ps[XPT];
@@ -239,22 +286,36 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
                     ring[s2 % RING] = *reinterpret_cast<const v4u*>(base + tapoff(t2));
                 }
             }
-            if (mine(i)) {
+            if (ALDS && i == 1 && tap < 8) {   // the next tap's filters, a few slots before they are needed
 #pragma unroll
                 for (int fb = 0; fb < FB; ++fb)
-                    acc[fb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, A[tap][fb]),
+                    Ar[(tap + 1) & 1][fb] = *reinterpret_cast<const v4u*>(ar + (tap * FW + 16 * fb) * ROWB);
+            }
+            if (mine(i)) {
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb) {
+                    const v4u av = !ALDS ? A[tap][fb] : (tap == 0 ? A[0][fb] : Ar[tap & 1][fb]);
+                    acc[fb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, av),
                                                                          __builtin_bit_cast(v8bf, ring[s % RING]),
                                                                          acc[fb][i], 0, 0, 0);
+                }
+            }
+            if constexpr (ALDS) {   // filter pieces of chunk ch+1: registers -> LDS, then refilled with chunk ch+2
+#pragma unroll
+                for (int m = 0; m < APT; ++m) {
+                    if (1 + 2 * m == s) *reinterpret_cast<v4u*>(aw[m]) = areg[m];
+                    if (SLOTS / 3 + 1 + 2 * m == s) areg[m] = __builtin_amdgcn_raw_buffer_load_b128(wrs2, ago[m], 0, 0);
+                }
             }
             // patch of chunk ch+D: registers -> LDS in the first third of the slots; the loads of
             // chunk ch+D+1 refill the same registers in the second third
 #pragma unroll
             for (int m = 0; m < XPT; ++m) {
-                if (m * (SLOTS / 3) / XPT == s) *reinterpret_cast<v4u*>(ps[m]) = xreg[m];
-                if (SLOTS / 3 + m * (SLOTS / 3) / XPT == s) xreg[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
+                if (!(BF_EXP & 2) && m * (SLOTS / 3) / XPT == s) *reinterpret_cast<v4u*>(ps[m]) = xreg[m];
+                if (!(BF_EXP & 2) && SLOTS / 3 + m * (SLOTS / 3) / XPT == s) xreg[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
             }
             // this tap's filters are no longer needed: fetch the next chunk's into the same registers
-            if (i == NBW - 1) {
+            if (!(BF_EXP & 1) && i == NBW - 1 && (!ALDS || tap == 0)) {
 #pragma unroll
                 for (int fb = 0; fb < FB; ++fb) A[tap][fb] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs[fb], tap * tap_bytes, 0);
             }
@@ -288,9 +349,9 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
 }
 
 #ifndef BF_CFG
-#define BF_CFG 2, 2, 2, 2
+#define BF_CFG 2, 2, 2, 2, 0
 #endif
-constexpr int kCfg[4] = {BF_CFG};
+constexpr int kCfg[5] = {BF_CFG};
 constexpr int kFB = kCfg[0], kWF = kCfg[1], kWP = kCfg[2], kOCC = kCfg[3];
 
 size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -352,7 +413,7 @@ hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const voi
     a.units = pr.N * a.tiles_h * a.tiles_w;
     a.wp_bytes = (unsigned)((size_t)9 * s.F * s.Cs * 2);
     const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
-    bf16_tile_kernel<kFB, kWF, kWP, kOCC><<<grid, 64 * kWF * kWP, 0, st>>>(a);
+    bf16_tile_kernel<kFB, kWF, kWP, kOCC, kCfg[4] != 0><<<grid, 64 * kWF * kWP, 0, st>>>(a);
     return hipGetLastError();
 }
 
