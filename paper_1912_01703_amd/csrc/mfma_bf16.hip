@@ -25,9 +25,6 @@
 // its LDS buffer (three buffers) and the registers refilled with chunk i+3, and the filters of
 // chunk i+1 replace those of chunk i tap by tap as soon as a tap's MFMAs are issued.
 #include "common.h"
-#ifndef BF_EXP
-#define BF_EXP 0
-#endif
 
 namespace miconv {
 namespace {
@@ -102,11 +99,14 @@ struct BfArgs {
     int N, Cs, IH, IW, F, OH, OW;
     int pad_h, pad_w;
     int tiles_h, tiles_w, fblocks, units;
-    unsigned wp_bytes;
+    int items;            // work items: units rounded up to a multiple of 8, times fblocks
 };
 
-// ALDS: the filters of taps 1..8 go through LDS once per workgroup instead of being loaded by every wave.
-template <int FB, int WF, int WP, int OCC, bool ALDS>
+// The kernel is persistent: a workgroup walks a list of work items (image, tile, filter block), and
+// the chunk pipeline runs across item boundaries, so the loads of the next item's first chunks
+// overlap the MFMAs of the current one.  Layers with few reduction channels (two chunks per item at
+// 64 channels) would otherwise spend most of their time filling and draining the pipeline.
+template <int FB, int WF, int WP, int OCC>
 __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) {
     constexpr int TH = 14, TW = 14, PW = 16, PSZ = 256, NPX = TH * TW;
     constexpr int NT = 64 * WF * WP;
@@ -117,6 +117,7 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     // the LDS serves together still hit distinct banks.
     constexpr int RPB = 16 * ROWB + 96;
     static_assert((RPB - TW * ROWB) % 128 == 0, "row pitch keeps wrapped blocks conflict-free");
+
     constexpr int BUFB = 16 * RPB;           // one patch buffer
     constexpr int NBUF = 3, D = NBUF - 1;
     constexpr int XPT = PSZ * 4 / NT;        // 16-byte pieces per thread and chunk
@@ -124,58 +125,97 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     constexpr int SLOTS = 9 * NBW;           // one slot = one B operand = FB MFMAs
     constexpr int RING = 9, PF = 7;          // B operands are requested PF slots ahead; RING divides SLOTS
     static_assert(SLOTS % RING == 0 && PF < RING, "ring");
+    constexpr int FW = 16 * FB * WF;         // filters per work item
 
-    constexpr int FW = 16 * FB * WF;                      // filters per workgroup
-    constexpr int ABUF = 8 * FW * ROWB;                   // taps 1..8 of a chunk's filters: [tap-1][f][32 channels], 80-byte rows
-    constexpr int APT = ALDS ? 8 * FW * 4 / NT : 1;       // 16-byte filter pieces per thread and chunk
-    static_assert(!ALDS || 8 * FW * 4 % NT == 0, "whole filter pieces");
-    constexpr int ABASE = NBUF * BUFB;
-
-    __shared__ __attribute__((aligned(16))) unsigned char xs[NBUF * BUFB + (ALDS ? 2 * ABUF : 0)];
-
-    const int b = blockIdx.x;
-    const int xcd = b & 7, rest = b >> 3;
-    const int fblk = rest % a.fblocks;
-    const int unit = (rest / a.fblocks) * 8 + xcd;   // the filter blocks of one (image, tile) share an XCD
-    if (unit >= a.units) return;
-    int u = unit;
-    const int tj = u % a.tiles_w; u /= a.tiles_w;
-    const int ti = u % a.tiles_h;
-    const int n = u / a.tiles_h;
+    __shared__ __attribute__((aligned(16))) unsigned char xs[NBUF * BUFB];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wf = wave % WF, wp = wave / WF;
     const int li = lane & 15, kk = lane >> 4;
-
-    const int oh0 = ti * TH, ow0 = tj * TW;
-    const int ih0 = oh0 - a.pad_h, iw0 = ow0 - a.pad_w;
-    const uint16_t* src = a.xt + (size_t)n * a.IH * a.IW * a.Cs;
-    const unsigned img_bytes = (unsigned)(a.IH * a.IW * a.Cs) * 2u;
     const int nchunks = a.Cs / 32;
+    const unsigned img_bytes = (unsigned)(a.IH * a.IW * a.Cs) * 2u;
+    const unsigned tap_bytes = (unsigned)a.F * 64u;
+    const int tiles = a.tiles_h * a.tiles_w;
 
-    // patch gather plan: piece = (pixel, quarter of its 32 channels)
-    unsigned goff[XPT];
+    // Work item j of this workgroup is number blockIdx.x + j * gridDim.x (gridDim.x is a multiple of 8).
+    // Consecutive numbers land on different XCDs; the filter blocks of one (image, tile) are given
+    // numbers that differ by multiples of 8, run at about the same time and share an L2.
+    const int nitems = __builtin_amdgcn_readfirstlane(a.items > (int)blockIdx.x ? (a.items - 1 - (int)blockIdx.x) / (int)gridDim.x + 1 : 0);
+    struct Item { int ok, fblk, n, oh0, ow0; };
+    auto item = [&](int j) __attribute__((always_inline)) -> Item {
+        Item it{0, 0, 0, 0, 0};
+        if (j >= nitems) return it;
+        const int w = blockIdx.x + j * gridDim.x;
+        const int xcd = w & 7, rest = w >> 3;
+        it.fblk = rest % a.fblocks;
+        const int unit = __builtin_amdgcn_readfirstlane((rest / a.fblocks) * 8 + xcd);
+        if (unit >= a.units) return it;
+        // integer division goes through the vector ALU: tell the compiler the results are wave-uniform
+        const int t = unit % tiles;
+        it.ok = 1;
+        it.fblk = __builtin_amdgcn_readfirstlane(it.fblk);
+        it.n = __builtin_amdgcn_readfirstlane(unit / tiles);
+        it.oh0 = __builtin_amdgcn_readfirstlane((t / a.tiles_w) * TH);
+        it.ow0 = __builtin_amdgcn_readfirstlane((t % a.tiles_w) * TW);
+        return it;
+    };
+
+    // ---- the three positions of the pipeline ---------------------------------------------------------
+    // patch loads run D+1 chunks ahead of the MFMAs, filter loads one chunk ahead
+    int xj = 0, xch = 0;            // item and chunk the next patch load fetches
+    unsigned goff[XPT];             // its gather plan: piece = (pixel, quarter of the chunk's 32 channels)
+    const uint16_t* xsrc = a.xt;
+    int xok = 0;
+    auto plan_patch = [&]() __attribute__((always_inline)) {
+        const Item it = item(xj);
+        xok = it.ok;
+        xsrc = a.xt + (size_t)it.n * a.IH * a.IW * a.Cs;
+        const int ih0 = it.oh0 - a.pad_h, iw0 = it.ow0 - a.pad_w;
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) {
+            const int e = tid + NT * m;
+            const int pix = e >> 2, q = e & 3;
+            const int ph = pix / PW, pw = pix - ph * PW;
+            const int ih = ih0 + ph, iw = iw0 + pw;
+            const bool ok = ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
+            goff[m] = ok ? (unsigned)((ih * a.IW + iw) * a.Cs + 8 * q) * 2u : kOob;
+        }
+    };
+    auto patch_rsrc = [&]() __attribute__((always_inline)) -> rsrc_t {   // past the last item: reads zeros
+        return make_rsrc(xsrc + xch * 32, xok ? img_bytes - (unsigned)xch * 64u : 0u);
+    };
+    auto advance_patch = [&]() __attribute__((always_inline)) {
+        if (++xch == nchunks) { xch = 0; ++xj; plan_patch(); }
+    };
     int loff[XPT];
 #pragma unroll
     for (int m = 0; m < XPT; ++m) {
         const int e = tid + NT * m;
         const int pix = e >> 2, q = e & 3;
-        const int ph = pix / PW, pw = pix - ph * PW;
-        const int ih = ih0 + ph, iw = iw0 + pw;
-        const bool ok = ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
-        goff[m] = ok ? (unsigned)((ih * a.IW + iw) * a.Cs + 8 * q) * 2u : kOob;
-        loff[m] = ph * RPB + pw * ROWB + q * 16;
+        loff[m] = (pix / PW) * RPB + (pix % PW) * ROWB + q * 16;
     }
-    // filter rows of this lane: filter f, channels 8*kk .. 8*kk+7 of the chunk
-    const int fbase = fblk * (16 * FB * WF) + wf * (16 * FB);
-    unsigned wofs[FB];              // tap 0; tap t lies t * tap_bytes further (a wave-uniform offset)
-    const unsigned tap_bytes = (unsigned)a.F * 64u;
+
+    int wj = 0, wch = 0;            // item and chunk the next filter load fetches
+    unsigned wofs[FB];              // this lane's filter rows: filter f, channels 8*kk .. 8*kk+7 of the chunk (tap 0)
+    int wok = 0;
+    auto plan_filters = [&]() __attribute__((always_inline)) {
+        const Item it = item(wj);
+        wok = it.ok;
 #pragma unroll
-    for (int fb = 0; fb < FB; ++fb) {
-        const int f = fbase + 16 * fb + li;
-        wofs[fb] = f < a.F ? (unsigned)(f * 32 + 8 * kk) * 2u : kOob;
-    }
+        for (int fb = 0; fb < FB; ++fb) {
+            const int f = it.fblk * FW + wf * (16 * FB) + 16 * fb + li;
+            wofs[fb] = f < a.F ? (unsigned)(f * 32 + 8 * kk) * 2u : kOob;
+        }
+    };
+    auto filter_rsrc = [&]() __attribute__((always_inline)) -> rsrc_t {
+        const unsigned chunk_bytes = 9u * tap_bytes;
+        return make_rsrc(reinterpret_cast<const unsigned char*>(a.wp) + (size_t)wch * chunk_bytes, wok ? chunk_bytes : 0u);
+    };
+    auto advance_filters = [&]() __attribute__((always_inline)) {
+        if (++wch == nchunks) { wch = 0; ++wj; plan_filters(); }
+    };
+
     // B operand addresses of this lane's pixel in each of its blocks (tap (0,0), buffer 0)
     int pixb[NBW];
 #pragma unroll
@@ -186,65 +226,35 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
         pixb[i] = th * RPB + tw * ROWB + kk * 16;
     }
     const bool last_ok = wp + WP * (NBW - 1) < NB;   // does this wave own a block in its last slot?
+    auto mine = [&](int i) __attribute__((always_inline)) -> bool { return !(NB % WP != 0 && i == NBW - 1 && !last_ok); };
+    auto tapoff = [](int tap) { return (tap / 3) * RPB + (tap % 3) * ROWB; };
 
     v4f acc[FB][NBW];
 #pragma unroll
     for (int fb = 0; fb < FB; ++fb)
 #pragma unroll
         for (int i = 0; i < NBW; ++i) acc[fb][i] = v4f{0.f, 0.f, 0.f, 0.f};
-
-    auto patch_rsrc = [&](int ch) __attribute__((always_inline)) -> rsrc_t {
-        const bool have = ch < nchunks;   // a chunk past the end reads zeros
-        return make_rsrc(src + (have ? ch * 32 : 0), have ? img_bytes - (unsigned)ch * 64u : 0u);
-    };
-    auto filter_rsrc = [&](int ch) __attribute__((always_inline)) -> rsrc_t {
-        const bool have = ch < nchunks;
-        const unsigned chunk_bytes = 9u * tap_bytes;
-        return make_rsrc(reinterpret_cast<const unsigned char*>(a.wp) + (have ? (size_t)ch * chunk_bytes : 0), have ? chunk_bytes : 0u);
-    };
-    auto mine = [&](int i) __attribute__((always_inline)) -> bool { return !(NB % WP != 0 && i == NBW - 1 && !last_ok); };
-    auto tapoff = [](int tap) { return (tap / 3) * RPB + (tap % 3) * ROWB; };
-
-    v4u A[ALDS ? 1 : 9][FB];   // filters in registers: all taps, or tap 0 only
-    v4u Ar[2][FB];             // ALDS: filters of the current and the next tap, read from LDS
-    v4u areg[APT];             // ALDS: filter pieces on their way from global memory to LDS
-    unsigned ago[APT];
-    int aoff[APT];
-    if constexpr (ALDS) {
-#pragma unroll
-        for (int m = 0; m < APT; ++m) {
-            const int e = tid + NT * m;
-            const int q = e & 3, fl = (e >> 2) % FW, tap = 1 + (e >> 2) / FW;
-            const int f = fblk * FW + fl;
-            ago[m] = f < a.F ? (unsigned)((tap * a.F + f) * 32 + 8 * q) * 2u : kOob;
-            aoff[m] = ABASE + ((tap - 1) * FW + fl) * ROWB + q * 16;
-        }
-    }
-    const int alane = ABASE + (wf * 16 * FB + li) * ROWB + kk * 16;   // this lane's row in a filter buffer (tap 1, block 0)
+    v4u A[9][FB];
     v4u xreg[XPT];
     v4u ring[RING];
 
-    // ---- prologue: filters of chunk 0; patches of chunks 0..D-1 to LDS, chunk D to registers --------
+    if (nitems == 0) return;
+    // ---- prologue: filters of the first chunk; patches of chunks 0..D-1 to LDS, chunk D to registers ----
+    plan_patch();
+    plan_filters();
     {
-        const rsrc_t wrs = filter_rsrc(0);
+        const rsrc_t wrs = filter_rsrc();
 #pragma unroll
-        for (int tap = 0; tap < (ALDS ? 1 : 9); ++tap)
+        for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
             for (int fb = 0; fb < FB; ++fb) A[tap][fb] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs[fb], tap * tap_bytes, 0);
-        if constexpr (ALDS) {
-#pragma unroll
-            for (int m = 0; m < APT; ++m) areg[m] = __builtin_amdgcn_raw_buffer_load_b128(wrs, ago[m], 0, 0);
-#pragma unroll
-            for (int m = 0; m < APT; ++m) *reinterpret_cast<v4u*>(xs + aoff[m]) = areg[m];
-            const rsrc_t wrs1 = filter_rsrc(1);
-#pragma unroll
-            for (int m = 0; m < APT; ++m) areg[m] = __builtin_amdgcn_raw_buffer_load_b128(wrs1, ago[m], 0, 0);
-        }
+        advance_filters();
 #pragma unroll
         for (int c = 0; c <= D; ++c) {
-            const rsrc_t xrs = patch_rsrc(c);
+            const rsrc_t xrs = patch_rsrc();
 #pragma unroll
             for (int m = 0; m < XPT; ++m) xreg[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
+            advance_patch();
             if (c < D) {
 #pragma unroll
                 for (int m = 0; m < XPT; ++m) *reinterpret_cast<v4u*>(xs + c * BUFB + loff[m]) = xreg[m];
@@ -257,16 +267,11 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     }
 
     int rd = 0, nx = BUFB, wr = D * BUFB;
-    for (int ch = 0; ch < nchunks; ++ch) {
-        const rsrc_t xrs = patch_rsrc(ch + D + 1);
-        const rsrc_t wrs = filter_rsrc(ch + 1);
-        const rsrc_t wrs2 = filter_rsrc(ch + 2);
-        const unsigned char* ar = xs + alane + (ch & 1) * ABUF;            // filters of this chunk
-        unsigned char* aw[APT];                                           // ... and where the next chunk's go
-        if constexpr (ALDS) {
-#pragma unroll
-            for (int m = 0; m < APT; ++m) aw[m] = xs + aoff[m] + ((ch + 1) & 1) * ABUF;
-        }
+    int cj = 0, cch = 0;            // item and chunk being multiplied
+    const int total = nitems * nchunks;
+    for (int g = 0; g < total; ++g) {
+        const rsrc_t xrs = patch_rsrc();
+        const rsrc_t wrs = filter_rsrc();
         const unsigned char* pr[NBW];
         const unsigned char* pn[NBW];
         unsigned char* ps[XPT];
@@ -286,40 +291,53 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
                     ring[s2 % RING] = *reinterpret_cast<const v4u*>(base + tapoff(t2));
                 }
             }
-            if (ALDS && i == 1 && tap < 8) {   // the next tap's filters, a few slots before they are needed
-#pragma unroll
-                for (int fb = 0; fb < FB; ++fb)
-                    Ar[(tap + 1) & 1][fb] = *reinterpret_cast<const v4u*>(ar + (tap * FW + 16 * fb) * ROWB);
-            }
             if (mine(i)) {
 #pragma unroll
-                for (int fb = 0; fb < FB; ++fb) {
-                    const v4u av = !ALDS ? A[tap][fb] : (tap == 0 ? A[0][fb] : Ar[tap & 1][fb]);
-                    acc[fb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, av),
+                for (int fb = 0; fb < FB; ++fb)
+                    acc[fb][i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, A[tap][fb]),
                                                                          __builtin_bit_cast(v8bf, ring[s % RING]),
                                                                          acc[fb][i], 0, 0, 0);
-                }
             }
-            if constexpr (ALDS) {   // filter pieces of chunk ch+1: registers -> LDS, then refilled with chunk ch+2
-#pragma unroll
-                for (int m = 0; m < APT; ++m) {
-                    if (1 + 2 * m == s) *reinterpret_cast<v4u*>(aw[m]) = areg[m];
-                    if (SLOTS / 3 + 1 + 2 * m == s) areg[m] = __builtin_amdgcn_raw_buffer_load_b128(wrs2, ago[m], 0, 0);
-                }
-            }
-            // patch of chunk ch+D: registers -> LDS in the first third of the slots; the loads of
-            // chunk ch+D+1 refill the same registers in the second third
+            // patch D chunks ahead: registers -> LDS in the first third of the slots; the loads of
+            // the chunk after it refill the same registers in the second third
 #pragma unroll
             for (int m = 0; m < XPT; ++m) {
-                if (!(BF_EXP & 2) && m * (SLOTS / 3) / XPT == s) *reinterpret_cast<v4u*>(ps[m]) = xreg[m];
-                if (!(BF_EXP & 2) && SLOTS / 3 + m * (SLOTS / 3) / XPT == s) xreg[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
+                if (m * (SLOTS / 3) / XPT == s) *reinterpret_cast<v4u*>(ps[m]) = xreg[m];
+                if (SLOTS / 3 + m * (SLOTS / 3) / XPT == s) xreg[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
             }
             // this tap's filters are no longer needed: fetch the next chunk's into the same registers
-            if (!(BF_EXP & 1) && i == NBW - 1 && (!ALDS || tap == 0)) {
+            if (i == NBW - 1) {
 #pragma unroll
                 for (int fb = 0; fb < FB; ++fb) A[tap][fb] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs[fb], tap * tap_bytes, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
+        }
+        advance_patch();
+        advance_filters();
+        if (++cch == nchunks) {
+            // ---- the item is complete: D[f = 4*kk+v][pixel = li] to memory, accumulators back to zero ----
+            const Item it = item(cj);
+            const int dplane = a.OH * a.OW;
+            float* dst = a.dst + (size_t)it.n * a.F * dplane;
+            const int fbase = it.fblk * FW + wf * (16 * FB);
+#pragma unroll
+            for (int i = 0; i < NBW; ++i) {
+                const int j = 16 * (wp + WP * i) + li;
+                const int th = j / TW, tw = j - th * TW;
+                const int oh = it.oh0 + th, ow = it.ow0 + tw;
+                const bool pix_ok = it.ok && j < NPX && oh < a.OH && ow < a.OW;
+#pragma unroll
+                for (int fb = 0; fb < FB; ++fb) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int f = fbase + 16 * fb + 4 * kk + v;
+                        if (pix_ok && f < a.F) dst[(size_t)f * dplane + oh * a.OW + ow] = acc[fb][i][v];
+                    }
+                    acc[fb][i] = v4f{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+            cch = 0;
+            ++cj;
         }
         __syncthreads();
         rd = nx;
@@ -327,31 +345,12 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
         wr = wr + BUFB == NBUF * BUFB ? 0 : wr + BUFB;
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // loads fetched past the last chunk still target registers
-
-    // ---- epilogue: D[f = 4*kk+v][pixel = li] ---------------------------------------------------
-    const int dplane = a.OH * a.OW;
-    float* dst = a.dst + (size_t)n * a.F * dplane;
-#pragma unroll
-    for (int i = 0; i < NBW; ++i) {
-        const int j = 16 * (wp + WP * i) + li;
-        if (j >= NPX) continue;
-        const int th = j / TW, tw = j - th * TW;
-        const int oh = oh0 + th, ow = ow0 + tw;
-        if (oh >= a.OH || ow >= a.OW) continue;
-#pragma unroll
-        for (int fb = 0; fb < FB; ++fb)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int f = fbase + 16 * fb + 4 * kk + v;
-                if (f < a.F) dst[(size_t)f * dplane + oh * a.OW + ow] = acc[fb][i][v];
-            }
-    }
 }
 
 #ifndef BF_CFG
-#define BF_CFG 2, 2, 2, 2, 0
+#define BF_CFG 2, 2, 2, 2
 #endif
-constexpr int kCfg[5] = {BF_CFG};
+constexpr int kCfg[4] = {BF_CFG};
 constexpr int kFB = kCfg[0], kWF = kCfg[1], kWP = kCfg[2], kOCC = kCfg[3];
 
 size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -411,9 +410,10 @@ hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const voi
     a.tiles_h = (s.OH + 13) / 14; a.tiles_w = (s.OW + 13) / 14;
     a.fblocks = (s.F + 16 * kFB * kWF - 1) / (16 * kFB * kWF);
     a.units = pr.N * a.tiles_h * a.tiles_w;
-    a.wp_bytes = (unsigned)((size_t)9 * s.F * s.Cs * 2);
-    const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
-    bf16_tile_kernel<kFB, kWF, kWP, kOCC, kCfg[4] != 0><<<grid, 64 * kWF * kWP, 0, st>>>(a);
+    a.items = ((a.units + 7) / 8) * 8 * a.fblocks;
+    // two workgroups fit a CU: at most that many are launched and each walks its share of the items
+    const int grid = a.items < 256 * kOCC ? a.items : 256 * kOCC;
+    bf16_tile_kernel<kFB, kWF, kWP, kOCC><<<grid, 64 * kWF * kWP, 0, st>>>(a);
     return hipGetLastError();
 }
 
