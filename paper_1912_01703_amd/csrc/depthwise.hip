@@ -432,6 +432,7 @@ struct DwStripWArgs {
     int PB, NSEG, UPP, passes, lds_per_wave, w_off, o_off;
     float inv_ppw, inv_pps, inv_q, inv_nseg, inv_xplane, inv_w, inv_yplane;
     int nsplit;
+    int fuse;          // the nsplit waves of a channel sit in one workgroup and are summed there (nsplit divides 4)
     unsigned x_bytes, y_bytes;
 };
 
@@ -450,10 +451,20 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
     const int xplane = a.H * a.W, yplane = a.P * a.Q;
     const T* const tnull = nullptr;
     float* my = lds + wave * a.lds_per_wave;
-    const int unit = blockIdx.x * (kThreads / 64) + wave;   // = sp * C + c
-    if (unit >= a.C * a.nsplit) return;
-    const int c = unit % a.C, sp = unit / a.C;
-    const int n0 = (int)((long long)a.N * sp / a.nsplit), n1 = (int)((long long)a.N * (sp + 1) / a.nsplit);
+    int c, sp;
+    if (a.fuse) {   // the splits of a channel are the waves of one workgroup
+        c = blockIdx.x * ((kThreads / 64) / a.nsplit) + wave / a.nsplit;
+        sp = wave % a.nsplit;
+    } else {
+        const int unit = blockIdx.x * (kThreads / 64) + wave;   // = sp * C + c
+        if (unit >= a.C * a.nsplit) return;
+        c = unit % a.C;
+        sp = unit / a.C;
+    }
+    const bool valid = c < a.C;   // a fused workgroup may hold waves past the last channel: they only join the barrier
+    if (!valid) c = 0;
+    const int n0 = valid ? (int)((long long)a.N * sp / a.nsplit) : 0;
+    const int n1 = valid ? (int)((long long)a.N * (sp + 1) / a.nsplit) : 0;
 
     float* yl = my + a.o_off;   // wide path: the batch's dy planes, unpadded
 
@@ -602,6 +613,21 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
 #pragma unroll
         for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
         acc[t] = v;
+    }
+    if (a.fuse) {
+        // partial sums of the channel's waves meet in LDS and are added in split order
+        __syncthreads();   // every wave is done with its LDS region
+        if (lane == 0) {
+#pragma unroll
+            for (int t = 0; t < 9; ++t) lds[wave * 9 + t] = acc[t];
+        }
+        __syncthreads();
+        if (valid && sp == 0 && lane < 9) {
+            float sum = lds[wave * 9 + lane];
+            for (int s2 = 1; s2 < a.nsplit; ++s2) sum += lds[(wave + s2) * 9 + lane];
+            a.out[(size_t)c * 9 + lane] = sum;
+        }
+        return;
     }
     if (lane == 0) {
         float* out = a.out + (size_t)sp * a.C * 9 + (size_t)c * 9;
@@ -769,7 +795,9 @@ bool strip_wgrad_args(const Problem& pr, const void* x, const void* dy, DwStripW
     int nsplit = (2048 + pr.C - 1) / pr.C;
     if (nsplit > pr.N) nsplit = pr.N;
     if (nsplit < 1) nsplit = 1;
+    if (nsplit == 3) nsplit = 4 <= pr.N ? 4 : 2;   // 2 and 4 divide the four waves of a workgroup
     a.nsplit = nsplit;
+    a.fuse = nsplit > 1 && (kThreads / 64) % nsplit == 0;
     a.x_bytes = (unsigned)((size_t)pr.N * pr.C * pr.H * pr.W * esz);
     a.y_bytes = (unsigned)((size_t)pr.N * pr.C * pr.P * pr.Q * esz);
     return true;
@@ -777,7 +805,8 @@ bool strip_wgrad_args(const Problem& pr, const void* x, const void* dy, DwStripW
 
 template <typename T, int ST>
 hipError_t launch_strip_wgrad(const DwStripWArgs& a, hipStream_t st) {
-    const int grid = (a.C * a.nsplit + 3) / 4;
+    const int per_wg = a.fuse ? 4 / a.nsplit : 4;   // channels (fused) or (channel, split) pairs per workgroup
+    const int grid = a.fuse ? (a.C + per_wg - 1) / per_wg : (a.C * a.nsplit + 3) / 4;
     const size_t smem = (size_t)4 * a.lds_per_wave * sizeof(float);
     const bool wide = sizeof(T) == 4 && (a.H * a.W) % 4 == 0 && (a.P * a.Q) % 4 == 0 &&
                       reinterpret_cast<uintptr_t>(a.x) % 16 == 0 && reinterpret_cast<uintptr_t>(a.dy) % 16 == 0;
@@ -802,7 +831,7 @@ bool depthwise_supports(int pass, const Problem& pr) {
 size_t depthwise_workspace_bytes(int pass, const Problem& pr) {
     if (pass != 2) return 0;
     DwStripWArgs b{};
-    if (strip_wgrad_args(pr, nullptr, nullptr, b)) return b.nsplit > 1 ? (size_t)b.nsplit * pr.C * 9 * sizeof(float) : 0;
+    if (strip_wgrad_args(pr, nullptr, nullptr, b)) return b.nsplit > 1 && !b.fuse ? (size_t)b.nsplit * pr.C * 9 * sizeof(float) : 0;
     DwWArgs a{};
     if (!wgrad_args(pr, nullptr, nullptr, a)) return 0;
     return a.nsplit > 1 ? (size_t)a.nsplit * pr.C * 9 * sizeof(float) : 0;
@@ -814,11 +843,11 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
     if (pass == 2) {
         DwStripWArgs b{};
         if (strip_wgrad_args(pr, in0, in1, b)) {
-            b.out = b.nsplit > 1 ? static_cast<float*>(ws) : out;
+            b.out = b.nsplit > 1 && !b.fuse ? static_cast<float*>(ws) : out;
             hipError_t e;
             if (pr.dtype == 0) e = pr.sh == 1 ? launch_strip_wgrad<float, 1>(b, st) : launch_strip_wgrad<float, 2>(b, st);
             else e = pr.sh == 1 ? launch_strip_wgrad<uint16_t, 1>(b, st) : launch_strip_wgrad<uint16_t, 2>(b, st);
-            if (e != hipSuccess || b.nsplit == 1) return e;
+            if (e != hipSuccess || b.nsplit == 1 || b.fuse) return e;
             dw_reduce_splits_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, b.nsplit, count);
             return hipGetLastError();
         }
