@@ -37,7 +37,8 @@ struct WgradArgs {
     int pad_h, pad_w;
     int tiles_h, tiles_w;
     int kblocks, cblocks;  // per group
-    int nsplit, stages;    // stages = tiles_h*tiles_w*img_stages, ordered tile-major
+    int nsplit, stages;    // stages = tiles_h*tiles_w*img_stages, ordered tile-major (image-major when tile_fastest)
+    int tile_fastest;      // wide 1x1 path: consecutive stages are the tiles of one image group
     int img_stages;        // ceil(N / images per stage)
     int total_wgs;
     int xk, xc;            // blocks of one XCD form an xk x xc rectangle of the (k, c) block grid (0: linear runs)
@@ -140,8 +141,9 @@ __global__ __launch_bounds__(64 * WK * WC * WS, OCC) void wgrad_kernel(WgradArgs
 
     const int k0 = kbi * 16 * KB, c0 = cbi * 16 * CB;   // within the group
     // a stage = IMG consecutive images of one tile; stages are ordered tile-major
-    const int s_begin = (int)((long long)a.stages * sp / a.nsplit);
-    const int s_end = (int)((long long)a.stages * (sp + 1) / a.nsplit);
+    // (integer division goes through the vector ALU: readfirstlane tells the compiler the results are wave-uniform)
+    const int s_begin = __builtin_amdgcn_readfirstlane((int)((long long)a.stages * sp / a.nsplit));
+    const int s_end = __builtin_amdgcn_readfirstlane((int)((long long)a.stages * (sp + 1) / a.nsplit));
 
     const T* xg = static_cast<const T*>(a.x);
     const T* dyg = static_cast<const T*>(a.dy);
@@ -167,7 +169,7 @@ __global__ __launch_bounds__(64 * WK * WC * WS, OCC) void wgrad_kernel(WgradArgs
 #pragma unroll
         for (int m = 0; m < XPT; ++m) {
             const int f = tid + NT * m;
-            const int xq = xplane / 4;
+            constexpr int xq = NPX * ST * ST / 4;   // 16-byte pieces of one channel's share of a stage
             const int pc = f / xq, rem = 4 * (f - pc * xq);
             const int im = pc / XROWS, cl = pc - im * XROWS;
 #pragma unroll
@@ -197,8 +199,9 @@ __global__ __launch_bounds__(64 * WK * WC * WS, OCC) void wgrad_kernel(WgradArgs
     }
     auto plan = [&](int tile) __attribute__((always_inline)) {
         if constexpr (WIDE) {
-            // whole planes: H*W == NPX*ST*ST is not required, only that an x plane is xplane floats
-            const int xq = xplane / 4;   // float4 per x plane
+            // a channel's share of a stage is contiguous: the whole plane, or TH full rows of a 1x1 layer
+            // (then the tile's offset inside the plane is part of the descriptor base)
+            constexpr int xq = NPX * ST * ST / 4;
 #pragma unroll
             for (int m = 0; m < YPT; ++m) {
                 const int f = tid + NT * m;
@@ -249,21 +252,30 @@ __global__ __launch_bounds__(64 * WK * WC * WS, OCC) void wgrad_kernel(WgradArgs
     constexpr int NPIECES = YPT + XPT;
     rsrc_t yrs, xrs;
     // The stage being fetched runs ahead of the one being multiplied: (f_tile, f_img) is its position.
-    int f_stage = s_begin, f_tile = s_begin / a.img_stages, f_img = s_begin - f_tile * a.img_stages;
+    const int ntiles = a.tiles_h * a.tiles_w;
+    int f_stage = s_begin;
+    int f_tile = __builtin_amdgcn_readfirstlane(a.tile_fastest ? s_begin % ntiles : s_begin / a.img_stages);
+    int f_img = __builtin_amdgcn_readfirstlane(a.tile_fastest ? s_begin / ntiles : s_begin - f_tile * a.img_stages);
     auto descriptors = [&]() __attribute__((always_inline)) {
-        const int n = f_img * IMG;                           // first image of the stage
+        const int n = __builtin_amdgcn_readfirstlane(f_img * IMG);   // first image of the stage
         const int left = f_stage < s_end ? a.N - n : 0;      // past the split's end: empty, every load reads zero
         const int have = left < IMG ? left : IMG;
-        yrs = make_rsrc(dyg + (size_t)n * a.K * yplane, (unsigned)(have * a.K * yplane) * (unsigned)sizeof(T));
-        xrs = make_rsrc(xg + (size_t)n * a.C * xplane, (unsigned)(have * a.C * xplane) * (unsigned)sizeof(T));
+        const int toff = __builtin_amdgcn_readfirstlane(WIDE ? f_tile * NPX : 0);   // wide path: the tile is a contiguous run of each plane
+        const int ybytes = (have * a.K * yplane - toff) * (int)sizeof(T), xbytes = (have * a.C * xplane - toff * ST * ST) * (int)sizeof(T);
+        yrs = make_rsrc(dyg + (size_t)n * a.K * yplane + toff, (unsigned)__builtin_amdgcn_readfirstlane(ybytes > 0 ? ybytes : 0));
+        xrs = make_rsrc(xg + (size_t)n * a.C * xplane + toff * ST * ST, (unsigned)__builtin_amdgcn_readfirstlane(xbytes > 0 ? xbytes : 0));
     };
     auto advance = [&]() __attribute__((always_inline)) {   // to the next stage to fetch (wave-uniform arithmetic only)
         ++f_stage;
-        if (++f_img == a.img_stages) {
-            f_img = 0;
-            ++f_tile;
-            if (f_stage < s_end) plan(f_tile);
-        }
+        // (written with selects on values: a select between the two counters' addresses would put them in memory)
+        const bool tf = a.tile_fastest != 0;
+        const int inner = (tf ? f_tile : f_img) + 1;
+        const bool wrap = inner == (tf ? ntiles : a.img_stages);
+        const int inner2 = wrap ? 0 : inner;
+        const int outer2 = (tf ? f_img : f_tile) + (wrap ? 1 : 0);
+        f_tile = tf ? inner2 : outer2;
+        f_img = tf ? outer2 : inner2;
+        if (!WIDE && wrap && f_stage < s_end) plan(f_tile);
         descriptors();
     };
     auto issue = [&](int piece) __attribute__((always_inline)) {
@@ -502,8 +514,14 @@ hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float*
     if (dry) return hipSuccess;
     a.out = pl.nsplit > 1 ? static_cast<float*>(ws) : dw;
     const int grid = ((a.total_wgs + 7) / 8) * 8;
-    const bool wide = sizeof(T) == 4 && pr.P == TH && pr.Q == TW && (pr.H * pr.W) % 4 == 0 &&
-                      pr.H * pr.W == TH * TW * ST * ST;
+    const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(dy) % 16 == 0;
+    // 16-byte fetch path: a channel's share of a stage is one contiguous run - the whole plane, or (1x1
+    // filters without padding) TH full rows of it
+    const bool whole = pr.P == TH && pr.Q == TW && pr.H * pr.W == TH * TW * ST * ST;
+    const bool rows = R == 1 && S == 1 && ST == 1 && pr.ph == 0 && pr.pw == 0 && pr.Q == TW && pr.P % TH == 0;
+    const bool wide = sizeof(T) == 4 && aligned && (pr.H * pr.W) % 4 == 0 && (pr.P * pr.Q) % 4 == 0 && (TH * TW) % 4 == 0 &&
+                      (whole || rows);
+    a.tile_fastest = wide && !whole;
     if (wide) wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, true, (WK * WC * WS + 3) / 4 * OCC><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
     else wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WSN, IMG, false, (WK * WC * WSN + 3) / 4><<<grid, 64 * WK * WC * WSN, 0, st>>>(a);
     hipError_t e = hipGetLastError();
