@@ -300,6 +300,109 @@ __global__ __launch_bounds__(256) void smallc_reduce_kernel(const float* __restr
     dw[i] = sum;
 }
 
+
+// ---- backward-data on the vector ALU ------------------------------------------------------------
+//   dx[n, c, h, v] = sum_{k, r, s : (h+PAD-r) % ST == 0, (v+PAD-s) % ST == 0} dy[n, k, (h+PAD-r)/ST, (v+PAD-s)/ST] * w[k, c, r, s]
+// With C = 3 destination channels an MFMA would use 3 of its 16 rows; the vector ALU has the same
+// fp32 peak and no such granularity.  A lane owns an ST x ST block of dx pixels (all C channels):
+// each filter tap (r, s) feeds exactly one pixel of that block, from the dy value at a block offset
+// that depends on the tap only.  Per output channel k the lane therefore loads the ND x ND dy values
+// around its block once (bounds-checked buffer loads: zero outside) and issues C*R*S fused
+// multiply-adds whose weight is wave-uniform and comes through the scalar unit (a scalar load feeds
+// an SGPR operand).  Nothing is shared between lanes, so a wave needs no LDS and no barrier.
+struct SmallBwdArgs {
+    const float* dy;
+    const float* w;
+    float* dx;
+    int N, K, H, W, P, Q;
+    int btiles_h, btiles_w;   // 8 x 8 blocks of ST x ST pixels per wave
+    unsigned dy_bytes;
+};
+
+template <int C, int R, int S, int ST, int PAD>
+__global__ __launch_bounds__(64) void smallc_bwd_data_kernel(SmallBwdArgs a) {
+    // Tap r lands on row phase (r - PAD) mod ST of the block and reads dy row (block row) + dp(r).
+    constexpr auto phase = [](int r) { return ((r - PAD) % ST + ST) % ST; };
+    constexpr auto dpos = [](int r) { return (((r - PAD) % ST + ST) % ST + PAD - r) / ST; };
+    constexpr int DMIN = dpos(R > S ? R - 1 : S - 1), DMAX = dpos(0);   // dpos decreases with r
+    constexpr int ND = DMAX - DMIN + 1;
+    static_assert(R == S, "square filters");
+
+    int u = blockIdx.x;
+    const int tj = u % a.btiles_w; u /= a.btiles_w;
+    const int ti = u % a.btiles_h;
+    const int n = u / a.btiles_h;
+    const int lane = threadIdx.x;
+    const int bi = ti * 8 + (lane >> 3), bj = tj * 8 + (lane & 7);   // this lane's block of dx
+
+    const rsrc_t yrs = make_rsrc(a.dy, a.dy_bytes);
+    unsigned off[ND][ND];
+#pragma unroll
+    for (int dr = 0; dr < ND; ++dr)
+#pragma unroll
+        for (int dc = 0; dc < ND; ++dc) {
+            const int p = bi + DMIN + dr, q = bj + DMIN + dc;
+            off[dr][dc] = p >= 0 && p < a.P && q >= 0 && q < a.Q ? (unsigned)(p * a.Q + q) * 4u : kOob;
+        }
+    float acc[C][ST][ST];
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int i = 0; i < ST; ++i)
+#pragma unroll
+            for (int j = 0; j < ST; ++j) acc[c][i][j] = 0.f;
+
+    const unsigned plane = (unsigned)(a.P * a.Q) * 4u;
+    unsigned kbase = (unsigned)(n * a.K) * plane;   // byte offset of dy[n, k] (wave-uniform)
+    float v[ND][ND], vn[ND][ND];
+#pragma unroll
+    for (int dr = 0; dr < ND; ++dr)
+#pragma unroll
+        for (int dc = 0; dc < ND; ++dc)
+            v[dr][dc] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(yrs, off[dr][dc], kbase, 0));
+    for (int k = 0; k < a.K; ++k) {
+        kbase += plane;
+        if (k + 1 < a.K) {
+#pragma unroll
+            for (int dr = 0; dr < ND; ++dr)
+#pragma unroll
+                for (int dc = 0; dc < ND; ++dc)
+                    vn[dr][dc] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(yrs, off[dr][dc], kbase, 0));
+        }
+        const float* __restrict__ wk = a.w + (size_t)k * (C * R * S);
+#pragma unroll
+        for (int c = 0; c < C; ++c)
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int s2 = 0; s2 < S; ++s2)
+                    acc[c][phase(r)][phase(s2)] =
+                        fmaf(v[dpos(r) - DMIN][dpos(s2) - DMIN], wk[(c * R + r) * S + s2], acc[c][phase(r)][phase(s2)]);
+#pragma unroll
+        for (int dr = 0; dr < ND; ++dr)
+#pragma unroll
+            for (int dc = 0; dc < ND; ++dc) v[dr][dc] = vn[dr][dc];
+    }
+
+    const int h0 = bi * ST, v0 = bj * ST;
+    const bool vec = ST == 4 && (a.W & 3) == 0 && (reinterpret_cast<uintptr_t>(a.dx) & 15) == 0;
+#pragma unroll
+    for (int c = 0; c < C; ++c)
+#pragma unroll
+        for (int i = 0; i < ST; ++i) {
+            const int h = h0 + i;
+            if (h >= a.H) continue;
+            float* row = a.dx + ((size_t)(n * C + c) * a.H + h) * a.W;
+            if (vec && v0 + ST <= a.W) {
+                *reinterpret_cast<float4*>(row + v0) = make_float4(acc[c][i][0], acc[c][i][1], acc[c][i][2], acc[c][i][3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < ST; ++j)
+                    if (v0 + j < a.W) row[v0 + j] = acc[c][i][j];
+            }
+        }
+}
+
 bool shape_ok(const Problem& pr) {
     const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
     if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
@@ -322,9 +425,12 @@ int wgrad_splits(const Problem& pr, const SmallArgs& a) {
     return nsplit < 1 ? 1 : nsplit;
 }
 
+// Backward-data: fp32 tensors with the padding the kernel is instantiated for.
+bool bwd_ok(const Problem& pr) { return shape_ok(pr) && pr.dtype == 0 && pr.ph == 2 && pr.pw == 2; }
+
 }  // namespace
 
-bool smallc_supports(int pass, const Problem& pr) { return (pass == 0 || pass == 2) && shape_ok(pr); }
+bool smallc_supports(int pass, const Problem& pr) { return pass == 1 ? bwd_ok(pr) : shape_ok(pr); }
 
 size_t smallc_workspace_bytes(int pass, const Problem& pr) {
     if (pass != 2 || !shape_ok(pr)) return 0;
@@ -339,6 +445,15 @@ size_t smallc_workspace_bytes(int pass, const Problem& pr) {
 hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
                       hipStream_t st) {
     if (!smallc_supports(pass, pr)) return hipErrorNotSupported;
+    if (pass == 1) {
+        SmallBwdArgs b{};
+        b.dy = static_cast<const float*>(in0); b.w = static_cast<const float*>(in1); b.dx = out;
+        b.N = pr.N; b.K = pr.K; b.H = pr.H; b.W = pr.W; b.P = pr.P; b.Q = pr.Q;
+        b.btiles_h = ((pr.H + 3) / 4 + 7) / 8; b.btiles_w = ((pr.W + 3) / 4 + 7) / 8;
+        b.dy_bytes = (unsigned)((size_t)pr.N * pr.K * pr.P * pr.Q * 4);
+        smallc_bwd_data_kernel<3, 11, 11, 4, 2><<<pr.N * b.btiles_h * b.btiles_w, 64, 0, st>>>(b);
+        return hipGetLastError();
+    }
     const unsigned esz = pr.dtype == 0 ? 4 : 2;
     SmallArgs a{};
     fill(pr, a);
