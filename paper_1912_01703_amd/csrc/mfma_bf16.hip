@@ -249,17 +249,25 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
 #pragma unroll
             for (int fb = 0; fb < FB; ++fb) A[tap][fb] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs[fb], tap * tap_bytes, 0);
         advance_filters();
+        // the patches of chunks 0..D are all requested before the first one is waited for
+        v4u pre[D][XPT];
 #pragma unroll
-        for (int c = 0; c <= D; ++c) {
+        for (int c = 0; c < D; ++c) {
+            const rsrc_t xrs = patch_rsrc();
+#pragma unroll
+            for (int m = 0; m < XPT; ++m) pre[c][m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
+            advance_patch();
+        }
+        {
             const rsrc_t xrs = patch_rsrc();
 #pragma unroll
             for (int m = 0; m < XPT; ++m) xreg[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
             advance_patch();
-            if (c < D) {
-#pragma unroll
-                for (int m = 0; m < XPT; ++m) *reinterpret_cast<v4u*>(xs + c * BUFB + loff[m]) = xreg[m];
-            }
         }
+#pragma unroll
+        for (int c = 0; c < D; ++c)
+#pragma unroll
+            for (int m = 0; m < XPT; ++m) *reinterpret_cast<v4u*>(xs + c * BUFB + loff[m]) = pre[c][m];
         __syncthreads();
 #pragma unroll
         for (int s = 0; s < PF; ++s)

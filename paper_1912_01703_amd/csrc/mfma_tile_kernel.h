@@ -228,17 +228,25 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 #pragma unroll
         for (int k4 = 0; k4 < KQ; ++k4) wrun[k4] += (unsigned)wstep_chunk * (unsigned)sizeof(T);
     };
+    auto load_piece = [&](int piece, const rsrc_t& xrs) __attribute__((always_inline)) {
+        if constexpr (XW) return __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[piece], 0, 0);
+        else return buf_load(xrs, goff[piece], tnull);
+    };
+    auto store_piece = [&](auto v, float* dst) __attribute__((always_inline)) {
+        if constexpr (XW) {
+            *reinterpret_cast<float2*>(dst) = make_float2(__uint_as_float(v[0]), __uint_as_float(v[1]));
+            *reinterpret_cast<float2*>(dst + 2) = make_float2(__uint_as_float(v[2]), __uint_as_float(v[3]));
+        } else {
+            *dst = v;
+        }
+    };
     auto issue_x = [&](int piece, const rsrc_t& xrs) __attribute__((always_inline)) {
-        if constexpr (XW) xreg4[piece] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[piece], 0, 0);
-        else xreg[piece] = buf_load(xrs, goff[piece], tnull);
+        if constexpr (XW) xreg4[piece] = load_piece(piece, xrs);
+        else xreg[piece] = load_piece(piece, xrs);
     };
     auto store_x = [&](int piece, float* dst) __attribute__((always_inline)) {
-        if constexpr (XW) {
-            *reinterpret_cast<float2*>(dst) = make_float2(__uint_as_float(xreg4[piece].x), __uint_as_float(xreg4[piece].y));
-            *reinterpret_cast<float2*>(dst + 2) = make_float2(__uint_as_float(xreg4[piece].z), __uint_as_float(xreg4[piece].w));
-        } else {
-            *dst = xreg[piece];
-        }
+        if constexpr (XW) store_piece(xreg4[piece], dst);
+        else store_piece(xreg[piece], dst);
     };
     auto issue_w = [&](int q, const unsigned (&wvo)[KQ], float (&an)[RS * KQ]) __attribute__((always_inline)) {
         if constexpr (W4) {
@@ -344,17 +352,23 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         filter_offsets(0, wvo);
 #pragma unroll
         for (int q = 0; q < WPIECES; ++q) issue_w(q, wvo, A0);
+        // all of them are requested before the first one is waited for
+        decltype(load_piece(0, patch_rsrc(0))) pre[D][XPT];
 #pragma unroll
-        for (int c = 0; c <= D; ++c) {
+        for (int c = 0; c < D; ++c) {
             const rsrc_t xrs = patch_rsrc(c);
 #pragma unroll
-            for (int m = 0; m < XPT; ++m) issue_x(m, xrs);
-            if (c < D) {
-                __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-#pragma unroll
-                for (int m = 0; m < XPT; ++m) store_x(m, xs + c * BUFSZ + loff[m]);
-            }
+            for (int m = 0; m < XPT; ++m) pre[c][m] = load_piece(m, xrs);
         }
+        {
+            const rsrc_t xrs = patch_rsrc(D);
+#pragma unroll
+            for (int m = 0; m < XPT; ++m) issue_x(m, xrs);
+        }
+#pragma unroll
+        for (int c = 0; c < D; ++c)
+#pragma unroll
+            for (int m = 0; m < XPT; ++m) store_piece(pre[c][m], xs + c * BUFSZ + loff[m]);
         __syncthreads();
         if (NBUF == 3) {
 #pragma unroll
