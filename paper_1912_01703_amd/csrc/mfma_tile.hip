@@ -9,14 +9,16 @@ namespace miconv {
 namespace {
 using namespace tile;
 
-template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, int NBUF = 3>
+template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, int NBUF = 3, bool PERSIST = false>
 hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
     TileArgs a = base;
     a.tiles_h = (a.OH + TH - 1) / TH;
     a.tiles_w = (a.OW + TW - 1) / TW;
     a.fblocks = (a.Fg + 16 * WF - 1) / (16 * WF);
     a.units = a.N * a.groups * a.tiles_h * a.tiles_w;
-    const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
+    a.items = ((a.units + 7) / 8) * 8 * a.fblocks;
+    // persistent: one workgroup per CU walks its share of the items
+    const int grid = PERSIST && a.items > 256 ? 256 : a.items;
     const bool wv = a.Rg % (CK / 4) == 0 && a.Rg % 4 == 0;   // forward filters can be read four values at a time
     if constexpr (R == 1 && S == 1 && ST == 1 && sizeof(T) == 4 && (TH * TW) % 4 == 0) {
         // patch == plane: contiguous chunks, 16 bytes per lane
@@ -28,8 +30,8 @@ hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
             return hipGetLastError();
         }
     }
-    if (wv) conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true, false, NBUF><<<grid, 64 * WF * WP, 0, st>>>(a);
-    else conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, false, false, NBUF><<<grid, 64 * WF * WP, 0, st>>>(a);
+    if (wv) conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true, false, NBUF, false, PERSIST><<<grid, 64 * WF * WP, 0, st>>>(a);
+    else conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, false, false, NBUF, false, PERSIST><<<grid, 64 * WF * WP, 0, st>>>(a);
     return hipGetLastError();
 }
 
@@ -39,7 +41,11 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
     *err = hipSuccess;
     if (R == 3 && S == 3 && stride == 1) {
         // eight waves: two per SIMD, so one wave's LDS and barrier waits are covered by the other's MFMAs
-        if (!dry) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD>(a, st);
+        if (dry) return true;
+        // Few chunks per item and many items: persistent workgroups hide each item's start-up and write-out
+        const long long ids = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
+        if (a.Rg <= 128 && ids >= 1024) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD, 3, true>(a, st);
+        else *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD>(a, st);
         return true;
     }
     if (R == 1 && S == 1 && stride == 1) {

@@ -56,6 +56,7 @@ struct TileArgs {
     int DH, DW;            // full destination plane
     int w_rs;              // taps of the full filter (R*S of the layer)
     int tapoff[9];         // phase mode: offset of sub-filter tap t inside a (k, c) filter plane
+    int items;             // work item ids: units rounded up to a multiple of 8, times fblocks
 };
 
 // Buffer loads: the hardware compares the byte offset with the descriptor's size and returns 0
@@ -88,10 +89,14 @@ constexpr int lds_channel_stride(int v, int kq) {
 // WV: the reduction channels per group are a multiple of 4 (forward filters can be read four values at a time).
 // PHASE: one output phase of a strided backward-data pass (R, S are the sub-filter's size; BWD is set).
 // NBUF: LDS patch buffers (2 or 3).
+// PERSIST: the grid is smaller than the number of work items; a workgroup walks items blockIdx.x,
+//     blockIdx.x + gridDim.x, ... and the chunk pipeline runs across item boundaries, so that the
+//     start-up loads and the write-out of one item overlap the MFMAs of its neighbours (layers with
+//     few chunks per item and many items).
 // XW: the patch is the whole source plane (1x1 filter, no padding, one tile per image) and planes are
 //     multiples of 16 bytes: a chunk's patch is then one contiguous run of CK planes, read 16 bytes per lane.
 template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, bool WV, bool PHASE, int NBUF = 3,
-          bool XW = false>
+          bool XW = false, bool PERSIST = false>
 __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int NT = 64 * WF * WP;
     constexpr int RS = R * S;
@@ -116,17 +121,32 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     // ---- which unit of work -------------------------------------------------------------
     // Consecutive workgroup ids land on different XCDs (8 of them, one L2 each).  All filter
     // blocks of one (image, tile) are given ids that differ by multiples of 8 so that they share an L2.
-    const int b = blockIdx.x;
-    const int xcd = b & 7;
-    const int rest = b >> 3;
-    const int fblk = rest % a.fblocks;
-    const int unit = (rest / a.fblocks) * 8 + xcd;
-    if (unit >= a.units) return;
-    int u = unit;
-    const int tj = u % a.tiles_w; u /= a.tiles_w;
-    const int ti = u % a.tiles_h; u /= a.tiles_h;
-    const int g = u % a.groups;
-    const int n = u / a.groups;
+    struct Item { int ok, fblk, n, g, oh0, ow0; };
+    auto decode = [&](int b) __attribute__((always_inline)) -> Item {
+        Item it{0, 0, 0, 0, 0, 0};
+        const int xcd = b & 7;
+        const int rest = b >> 3;
+        it.fblk = __builtin_amdgcn_readfirstlane(rest % a.fblocks);
+        const int unit = __builtin_amdgcn_readfirstlane((rest / a.fblocks) * 8 + xcd);
+        if (b >= a.items || unit >= a.units) return it;
+        // (integer division goes through the vector ALU: readfirstlane tells the compiler the results are wave-uniform)
+        int u = unit;
+        const int tj = u % a.tiles_w; u /= a.tiles_w;
+        const int ti = u % a.tiles_h; u /= a.tiles_h;
+        it.ok = 1;
+        it.g = __builtin_amdgcn_readfirstlane(u % a.groups);
+        it.n = __builtin_amdgcn_readfirstlane(u / a.groups);
+        it.oh0 = __builtin_amdgcn_readfirstlane(ti * TH);
+        it.ow0 = __builtin_amdgcn_readfirstlane(tj * TW);
+        return it;
+    };
+    // items of this workgroup: one, or (PERSIST) every gridDim.x-th id (gridDim.x is a multiple of 8)
+    const int nitems = PERSIST ? __builtin_amdgcn_readfirstlane(((int)a.items - 1 - (int)blockIdx.x) / (int)gridDim.x + 1) : 1;
+    auto item = [&](int j) __attribute__((always_inline)) -> Item {
+        return j < nitems ? decode(blockIdx.x + j * gridDim.x) : Item{0, 0, 0, 0, 0, 0};
+    };
+    const Item it0 = item(0);
+    if (!PERSIST && !it0.ok) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -134,46 +154,67 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     const int wf = wave % WF, wp = wave / WF;
     const int li = lane & 15, kk = lane >> 4;
 
-    const int oh0 = ti * TH, ow0 = tj * TW;
-    const int ih0 = oh0 * ST - a.pad_h, iw0 = ow0 * ST - a.pad_w;
     const int plane = a.IH * a.IW;
-
-    const T* src = static_cast<const T*>(a.src) + (size_t)(n * a.Csrc + g * a.Rg) * plane;
     const T* const tnull = nullptr;
     const rsrc_t wrs = make_rsrc(a.wgt, a.wgt_bytes);
 
-    // ---- per-thread gather plan for the source patch (same for every chunk) ---------------
+    // ---- per-thread gather plan for the source patch of an item (same for every chunk) ------------
     unsigned goff[XPT];  // byte offset inside the chunk's channels, kOob where the patch lies outside the image
     int loff[XPT];       // word offset inside a patch buffer
+    const T* src = static_cast<const T*>(a.src);
+    int xok = 0;
+    auto plan_patch = [&](const Item& it) __attribute__((always_inline)) {
+        xok = it.ok;
+        src = static_cast<const T*>(a.src) + (size_t)(it.n * a.Csrc + it.g * a.Rg) * plane;
+        const int ih0 = it.oh0 * ST - a.pad_h, iw0 = it.ow0 * ST - a.pad_w;
+#pragma unroll
+        for (int m = 0; m < XPT; ++m) {
+            if constexpr (XW) {
+                const int f = tid + NT * m;                       // 16-byte piece of the chunk's CK planes
+                goff[m] = f < XE / 4 ? (unsigned)(4 * f) * 4u : kOob;
+            } else {
+                const int e = tid + NT * m;
+                const int c = e / PSZ, rem = e - c * PSZ;
+                const int ph = rem / PW, pw = rem - ph * PW;
+                const int ih = ih0 + ph, iw = iw0 + pw;
+                const bool ok = (e < XE) && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
+                goff[m] = ok ? (unsigned)(c * plane + ih * a.IW + iw) * (unsigned)sizeof(T) : kOob;
+            }
+        }
+    };
 #pragma unroll
     for (int m = 0; m < XPT; ++m) {
         if constexpr (XW) {
-            const int f = tid + NT * m;                       // 16-byte piece of the chunk's CK planes
+            const int f = tid + NT * m;
             const int c = (4 * f) / PSZ, rem = 4 * f - c * PSZ;
-            goff[m] = f < XE / 4 ? (unsigned)(4 * f) * 4u : kOob;
             loff[m] = f < XE / 4 ? c * CS + rem : TRASH + (lane & ~3);   // 8-byte aligned: CS is even, rem a multiple of 4
         } else {
             const int e = tid + NT * m;
             const int c = e / PSZ, rem = e - c * PSZ;
-            const int ph = rem / PW, pw = rem - ph * PW;
-            const int ih = ih0 + ph, iw = iw0 + pw;
-            const bool ok = (e < XE) && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
-            goff[m] = ok ? (unsigned)(c * plane + ih * a.IW + iw) * (unsigned)sizeof(T) : kOob;
             loff[m] = (e < XE) ? c * CS + rem : TRASH + lane;
         }
     }
 
-    // ---- per-lane filter addressing ---------------------------------------------------------
+    // ---- per-lane filter addressing of an item ----------------------------------------------
     // This wave's 16 filters; lane li owns filter f, lane group kk owns KQ consecutive channels.
-    const int f = fblk * (16 * WF) + wf * 16 + li;
-    const bool f_ok = f < a.Fg;
     // forward:  w[(g*Fg+f)][c][tap]       -> contiguous over (c, tap) for a fixed filter
     // backward: w[(g*Rg+c)][f][RS-1-tap]  -> one run of RS values per reduction channel
     const int WRS = PHASE ? a.w_rs : RS;       // taps per (k, c) filter plane in memory
-    const int wbase = BWD ? ((g * a.Rg + kk * KQ) * a.Fg + (f_ok ? f : 0)) * WRS
-                          : ((g * a.Fg + (f_ok ? f : 0)) * a.Rg + kk * KQ) * WRS;
     const int wstep_k = BWD ? a.Fg * WRS : WRS;  // next reduction channel
     const int wstep_chunk = CK * wstep_k;      // next chunk
+    // Byte offsets of the lane's KQ filter rows, kOob for an absent filter or channel.  Chunks are
+    // visited in order, so the offsets of full chunks are running sums (one add each); only a
+    // partial last chunk needs the per-channel test.
+    unsigned wrun[KQ];
+    bool f_ok = false;
+    auto plan_filters = [&](const Item& it) __attribute__((always_inline)) {
+        const int f = it.fblk * (16 * WF) + wf * 16 + li;
+        f_ok = it.ok && f < a.Fg;
+        const int wbase = BWD ? ((it.g * a.Rg + kk * KQ) * a.Fg + (f_ok ? f : 0)) * WRS
+                              : ((it.g * a.Fg + (f_ok ? f : 0)) * a.Rg + kk * KQ) * WRS;
+#pragma unroll
+        for (int k4 = 0; k4 < KQ; ++k4) wrun[k4] = f_ok ? (unsigned)(wbase + k4 * wstep_k) * (unsigned)sizeof(T) : kOob;
+    };
 
     // ---- per-lane pixel offsets into the LDS patch -----------------------------------------
     int pixoff[NBW];
@@ -204,17 +245,11 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     // Descriptor of chunk ch's patch: it covers exactly the channels the chunk has, so a partial last
     // chunk (or a chunk past the end: zero channels) reads zeros without any per-element test.
     auto patch_rsrc = [&](int ch) __attribute__((always_inline)) -> rsrc_t {
-        const int left = a.Rg - ch * CK;  // reduction channels from this chunk on (<= 0: no such chunk)
+        const int left = xok ? a.Rg - ch * CK : 0;  // reduction channels from this chunk on (<= 0: no such chunk)
         const int have = left <= 0 ? 0 : (left < CK ? left : CK);
         return make_rsrc(src + (size_t)ch * CK * plane,
                          (unsigned)__builtin_amdgcn_readfirstlane(have * plane) * (unsigned)sizeof(T));
     };
-    // Byte offsets of the lane's KQ filter rows for chunk ch, kOob for an absent filter or channel.
-    // Chunks are visited in order, so the offsets of full chunks are running sums (one add each); only
-    // a partial last chunk needs the per-channel test.
-    unsigned wrun[KQ];
-#pragma unroll
-    for (int k4 = 0; k4 < KQ; ++k4) wrun[k4] = f_ok ? (unsigned)(wbase + k4 * wstep_k) * (unsigned)sizeof(T) : kOob;
     auto filter_offsets = [&](int ch, unsigned (&wvo)[KQ]) __attribute__((always_inline)) {
         const int left = a.Rg - ch * CK;
         if (left >= CK) {
@@ -289,15 +324,16 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     // ac: filters of this chunk; an: register set the next chunk's filters are loaded into.
     // rd: this chunk's patch buffer; nx: the next chunk's; wr: the buffer stored to (word offsets in xs).
     // PAR: which half of bq holds group 0's operands (the halves alternate with the groups).
-    auto compute = [&](auto parc, int ch, const float (&ac)[RS * KQ], float (&an)[RS * KQ], int rd, int nx, int wr)
+    // xch, wch: the chunks whose patch / filters are fetched during this one.
+    auto compute = [&](auto parc, int xch, int wch, const float (&ac)[RS * KQ], float (&an)[RS * KQ], int rd, int nx, int wr)
                        __attribute__((always_inline)) {
         constexpr int PAR = decltype(parc)::value;
         // All loads in flight were issued at least a third of a chunk ago: the patch held in xreg and
         // this chunk's filters.  Retiring them here keeps waits on loads out of the loop.
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-        const rsrc_t xrs = patch_rsrc(ch + D + 1);
+        const rsrc_t xrs = patch_rsrc(xch);
         unsigned wvo[KQ];
-        filter_offsets(ch + 1, wvo);
+        filter_offsets(wch, wvo);
         const float* pr[NBW];     // per-block read bases in this chunk's buffer
         const float* pn[NBW];     // ... and in the next chunk's
         float* ps[XPT];           // store addresses
@@ -343,27 +379,62 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         }
     };
 
+    // ---- write-out of an item: D[f = 4*kk+v][pixel = li] ---------------------------------------
+    auto write_out = [&](const Item& it) __attribute__((always_inline)) {
+        const int fq = it.fblk * (16 * WF) + wf * 16 + 4 * kk;
+        const int dplane = PHASE ? a.DH * a.DW : a.OH * a.OW;
+        float* dst = a.dst + (size_t)(it.n * a.Cdst + it.g * a.Fg) * dplane;
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
+            const int j = 16 * (wp + WP * i) + li;
+            const int th = j / TW, tw = j - th * TW;
+            const int oh = it.oh0 + th, ow = it.ow0 + tw;
+            if (!it.ok || j >= NPX || oh >= a.OH || ow >= a.OW) continue;
+            const int pix = PHASE ? (oh * a.o_sh + a.o_oh) * a.DW + ow * a.o_sw + a.o_ow : oh * a.OW + ow;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (fq + v < a.Fg) dst[(size_t)(fq + v) * dplane + pix] = acc[i][v];
+        }
+    };
+
     // Two register sets for the filters alternate, so the loop is written out for an even and an odd
     // chunk (no register copies); the LDS buffers rotate through word offsets.
     float A0[RS * KQ], A1[RS * KQ];
     const int nchunks = (a.Rg + CK - 1) / CK;
+    // The three positions of the pipeline (item, chunk): patch loads run D+1 chunks ahead of the
+    // MFMAs, filter loads one chunk ahead.  Without PERSIST there is one item and chunks past its end
+    // read zeros.
+    int xj = 0, xch = 0, wj = 0, wch = 0, cj = 0, cch = 0;
+    auto advance_patch = [&]() __attribute__((always_inline)) {
+        ++xch;
+        if (PERSIST && xch == nchunks) { xch = 0; ++xj; plan_patch(item(xj)); }
+    };
+    auto advance_filters = [&]() __attribute__((always_inline)) {
+        ++wch;
+        if (PERSIST && wch == nchunks) { wch = 0; ++wj; plan_filters(item(wj)); }
+    };
+    plan_patch(it0);
+    plan_filters(it0);
     {   // prologue: chunks 0 .. D-1 into their buffers, chunk D into the registers, filters of chunk 0
         unsigned wvo[KQ];
-        filter_offsets(0, wvo);
+        filter_offsets(wch, wvo);
+        advance_filters();
 #pragma unroll
         for (int q = 0; q < WPIECES; ++q) issue_w(q, wvo, A0);
         // all of them are requested before the first one is waited for
         decltype(load_piece(0, patch_rsrc(0))) pre[D][XPT];
 #pragma unroll
         for (int c = 0; c < D; ++c) {
-            const rsrc_t xrs = patch_rsrc(c);
+            const rsrc_t xrs = patch_rsrc(xch);
 #pragma unroll
             for (int m = 0; m < XPT; ++m) pre[c][m] = load_piece(m, xrs);
+            advance_patch();
         }
         {
-            const rsrc_t xrs = patch_rsrc(D);
+            const rsrc_t xrs = patch_rsrc(xch);
 #pragma unroll
             for (int m = 0; m < XPT; ++m) issue_x(m, xrs);
+            advance_patch();
         }
 #pragma unroll
         for (int c = 0; c < D; ++c)
@@ -376,38 +447,32 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         }
     }
     int rd = 0, nx = BUFSZ, wr = D * BUFSZ;
-    auto rotate = [&]() __attribute__((always_inline)) {
+    // after a chunk: move the fetch positions on; an item whose last chunk this was is written out
+    auto chunk_done = [&]() __attribute__((always_inline)) {
+        advance_patch();
+        advance_filters();
+        if (PERSIST && ++cch == nchunks) {
+            write_out(item(cj));
+#pragma unroll
+            for (int i = 0; i < NBW; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
+            cch = 0;
+            ++cj;
+        }
+        __syncthreads();
         rd = nx;
         nx = nx + BUFSZ == NBUF * BUFSZ ? 0 : nx + BUFSZ;
         wr = wr + BUFSZ == NBUF * BUFSZ ? 0 : wr + BUFSZ;
     };
-    for (int ch = 0; ch < nchunks; ch += 2) {
-        compute(std::integral_constant<int, 0>{}, ch, A0, A1, rd, nx, wr);
-        __syncthreads();
-        rotate();
-        if (ch + 1 >= nchunks) break;
-        compute(std::integral_constant<int, G & 1>{}, ch + 1, A1, A0, rd, nx, wr);
-        __syncthreads();
-        rotate();
+    const int total = nitems * nchunks;
+    for (int ch = 0; ch < total; ch += 2) {
+        compute(std::integral_constant<int, 0>{}, xch, wch, A0, A1, rd, nx, wr);
+        chunk_done();
+        if (ch + 1 >= total) break;
+        compute(std::integral_constant<int, G & 1>{}, xch, wch, A1, A0, rd, nx, wr);
+        chunk_done();
     }
     __builtin_amdgcn_s_waitcnt(0x0F70);   // loads fetched past the last chunk still target registers
-
-    // ---- epilogue: D[f = 4*kk+v][pixel = li] ---------------------------------------------------
-    const int fq = fblk * (16 * WF) + wf * 16 + 4 * kk;
-    const int dplane = PHASE ? a.DH * a.DW : a.OH * a.OW;
-    float* dst = a.dst + (size_t)(n * a.Cdst + g * a.Fg) * dplane;
-#pragma unroll
-    for (int i = 0; i < NBW; ++i) {
-        const int j = 16 * (wp + WP * i) + li;
-        if (j >= NPX) continue;
-        const int th = j / TW, tw = j - th * TW;
-        const int oh = oh0 + th, ow = ow0 + tw;
-        if (oh >= a.OH || ow >= a.OW) continue;
-        const int pix = PHASE ? (oh * a.o_sh + a.o_oh) * a.DW + ow * a.o_sw + a.o_ow : oh * a.OW + ow;
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-            if (fq + v < a.Fg) dst[(size_t)(fq + v) * dplane + pix] = acc[i][v];
-    }
+    if (!PERSIST) write_out(it0);
 }
 
 

@@ -42,7 +42,8 @@ hipError_t launch_phase_waves(TileArgs a, hipStream_t st) {
     a.tiles_w = (a.OW + TW - 1) / TW;
     a.fblocks = (a.Fg + 16 * WF - 1) / (16 * WF);
     a.units = a.N * a.groups * a.tiles_h * a.tiles_w;
-    const int grid = ((a.units + 7) / 8) * 8 * a.fblocks;
+    a.items = ((a.units + 7) / 8) * 8 * a.fblocks;
+    const int grid = a.items;
     conv_tile_kernel<T, JH, JW, 1, TH, TW, CK, WF, WP, true, false, true><<<grid, 64 * WF * WP, 0, st>>>(a);
     return hipGetLastError();
 }
