@@ -141,9 +141,14 @@ __global__ __launch_bounds__(64 * WK * WC * WS, OCC) void wgrad_kernel(WgradArgs
 
     const int k0 = kbi * 16 * KB, c0 = cbi * 16 * CB;   // within the group
     // a stage = IMG consecutive images of one tile; stages are ordered tile-major
-    // (integer division goes through the vector ALU: readfirstlane tells the compiler the results are wave-uniform)
-    const int s_begin = __builtin_amdgcn_readfirstlane((int)((long long)a.stages * sp / a.nsplit));
-    const int s_end = __builtin_amdgcn_readfirstlane((int)((long long)a.stages * (sp + 1) / a.nsplit));
+    // FLAT (1x1 filters on the 16-byte path): a tile is TH full rows, a contiguous run inside each plane whose
+    // offset goes into the descriptor base; stages may then be ordered image-major (a.tile_fastest).
+    constexpr bool FLAT = WIDE && R == 1 && S == 1 && ST == 1;
+    // (integer division goes through the vector ALU: readfirstlane tells the compiler the results are
+    // wave-uniform, which the descriptor arithmetic of the FLAT path needs)
+    const int s_begin0 = (int)((long long)a.stages * sp / a.nsplit), s_end0 = (int)((long long)a.stages * (sp + 1) / a.nsplit);
+    const int s_begin = FLAT ? __builtin_amdgcn_readfirstlane(s_begin0) : s_begin0;
+    const int s_end = FLAT ? __builtin_amdgcn_readfirstlane(s_end0) : s_end0;
 
     const T* xg = static_cast<const T*>(a.x);
     const T* dyg = static_cast<const T*>(a.dy);
@@ -254,28 +259,39 @@ __global__ __launch_bounds__(64 * WK * WC * WS, OCC) void wgrad_kernel(WgradArgs
     // The stage being fetched runs ahead of the one being multiplied: (f_tile, f_img) is its position.
     const int ntiles = a.tiles_h * a.tiles_w;
     int f_stage = s_begin;
-    int f_tile = __builtin_amdgcn_readfirstlane(a.tile_fastest ? s_begin % ntiles : s_begin / a.img_stages);
-    int f_img = __builtin_amdgcn_readfirstlane(a.tile_fastest ? s_begin / ntiles : s_begin - f_tile * a.img_stages);
+    int f_tile = FLAT ? __builtin_amdgcn_readfirstlane(a.tile_fastest ? s_begin % ntiles : s_begin / a.img_stages) : s_begin / a.img_stages;
+    int f_img = FLAT ? __builtin_amdgcn_readfirstlane(a.tile_fastest ? s_begin / ntiles : s_begin - f_tile * a.img_stages)
+                     : s_begin - f_tile * a.img_stages;
     auto descriptors = [&]() __attribute__((always_inline)) {
-        const int n = __builtin_amdgcn_readfirstlane(f_img * IMG);   // first image of the stage
+        const int n = f_img * IMG;                           // first image of the stage
         const int left = f_stage < s_end ? a.N - n : 0;      // past the split's end: empty, every load reads zero
         const int have = left < IMG ? left : IMG;
-        const int toff = __builtin_amdgcn_readfirstlane(WIDE ? f_tile * NPX : 0);   // wide path: the tile is a contiguous run of each plane
-        const int ybytes = (have * a.K * yplane - toff) * (int)sizeof(T), xbytes = (have * a.C * xplane - toff * ST * ST) * (int)sizeof(T);
-        yrs = make_rsrc(dyg + (size_t)n * a.K * yplane + toff, (unsigned)__builtin_amdgcn_readfirstlane(ybytes > 0 ? ybytes : 0));
-        xrs = make_rsrc(xg + (size_t)n * a.C * xplane + toff * ST * ST, (unsigned)__builtin_amdgcn_readfirstlane(xbytes > 0 ? xbytes : 0));
+        if constexpr (FLAT) {
+            const int toff = __builtin_amdgcn_readfirstlane(f_tile * NPX);
+            const int ybytes = (have * a.K * yplane - toff) * (int)sizeof(T), xbytes = (have * a.C * xplane - toff) * (int)sizeof(T);
+            yrs = make_rsrc(dyg + (size_t)n * a.K * yplane + toff, (unsigned)__builtin_amdgcn_readfirstlane(ybytes > 0 ? ybytes : 0));
+            xrs = make_rsrc(xg + (size_t)n * a.C * xplane + toff, (unsigned)__builtin_amdgcn_readfirstlane(xbytes > 0 ? xbytes : 0));
+        } else {
+            yrs = make_rsrc(dyg + (size_t)n * a.K * yplane, (unsigned)(have * a.K * yplane) * (unsigned)sizeof(T));
+            xrs = make_rsrc(xg + (size_t)n * a.C * xplane, (unsigned)(have * a.C * xplane) * (unsigned)sizeof(T));
+        }
     };
     auto advance = [&]() __attribute__((always_inline)) {   // to the next stage to fetch (wave-uniform arithmetic only)
         ++f_stage;
-        // (written with selects on values: a select between the two counters' addresses would put them in memory)
-        const bool tf = a.tile_fastest != 0;
-        const int inner = (tf ? f_tile : f_img) + 1;
-        const bool wrap = inner == (tf ? ntiles : a.img_stages);
-        const int inner2 = wrap ? 0 : inner;
-        const int outer2 = (tf ? f_img : f_tile) + (wrap ? 1 : 0);
-        f_tile = tf ? inner2 : outer2;
-        f_img = tf ? outer2 : inner2;
-        if (!WIDE && wrap && f_stage < s_end) plan(f_tile);
+        if constexpr (FLAT) {
+            // (written with selects on values: a select between the two counters' addresses would put them in memory)
+            const bool tf = a.tile_fastest != 0;
+            const int inner = (tf ? f_tile : f_img) + 1;
+            const bool wrap = inner == (tf ? ntiles : a.img_stages);
+            const int inner2 = wrap ? 0 : inner;
+            const int outer2 = (tf ? f_img : f_tile) + (wrap ? 1 : 0);
+            f_tile = tf ? inner2 : outer2;
+            f_img = tf ? outer2 : inner2;
+        } else if (++f_img == a.img_stages) {
+            f_img = 0;
+            ++f_tile;
+            if (!WIDE && f_stage < s_end) plan(f_tile);
+        }
         descriptors();
     };
     auto issue = [&](int piece) __attribute__((always_inline)) {
