@@ -53,6 +53,9 @@ hipError_t bf16_wgrad_run(const Problem& pr, const void* x, const void* dy, floa
 // Strided backward-data on the tiled kernel, one launch per output phase (mfma_tile_phase.hip).
 bool tile_phase_supports(const Problem& pr);
 hipError_t tile_phase_run(const Problem& pr, const void* dy, const void* w, float* dx, hipStream_t st);
+// ... and, for 3x3 stride-2 padding-1 layers, in one launch whose four phases share the dy patch.
+bool tile_merge2_supports(const Problem& pr);
+hipError_t tile_merge2_run(const Problem& pr, const void* dy, const void* w, float* dx, hipStream_t st);
 
 // Few-input-channel, large strided filter layers (mfma_smallc.hip): forward and backward-weight.
 bool smallc_supports(int pass, const Problem& pr);

@@ -30,7 +30,10 @@ hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, f
     if (bf16_tile_supports(pass, pr)) return bf16_tile_run(pass, pr, a, b, out, ws, st);
     if (pass == 2 && bf16_wgrad_supports(pr)) return bf16_wgrad_run(pr, a, b, out, ws, st);
     if (pass == 0) return tile_run(pass, pr, a, b, out, st);
-    if (pass == 1) return tile_supports(pass, pr) ? tile_run(pass, pr, a, b, out, st) : tile_phase_run(pr, a, b, out, st);
+    if (pass == 1) {
+        if (tile_supports(pass, pr)) return tile_run(pass, pr, a, b, out, st);
+        return tile_merge2_supports(pr) ? tile_merge2_run(pr, a, b, out, st) : tile_phase_run(pr, a, b, out, st);
+    }
     return wgrad_run(pr, a, b, out, ws, st);
 }
 

@@ -93,14 +93,20 @@ constexpr int lds_channel_stride(int v, int kq) {
 //     blockIdx.x + gridDim.x, ... and the chunk pipeline runs across item boundaries, so that the
 //     start-up loads and the write-out of one item overlap the MFMAs of its neighbours (layers with
 //     few chunks per item and many items).
+// MERGE2: backward-data of a 3x3 stride-2 padding-1 layer in one launch (BWD set, R = S = 3, ST = 1).  Output
+//     pixel (h, v) belongs to phase (a, b) = ((h+1) % 2, (v+1) % 2) and only taps r = a (mod 2), s = b (mod 2)
+//     reach it, so the nine taps of the filter split over four accumulator sets that all read the same dy
+//     patch: a work item is a 14x14 rectangle of the half-resolution grid (28x28 dx pixels).  With
+//     h = 2*i + 1 - a for grid row i, tap r reads dy row i + (r == 0), see roff() below.
 // XW: the patch is the whole source plane (1x1 filter, no padding, one tile per image) and planes are
 //     multiples of 16 bytes: a chunk's patch is then one contiguous run of CK planes, read 16 bytes per lane.
 template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, bool WV, bool PHASE, int NBUF = 3,
-          bool XW = false, bool PERSIST = false>
+          bool XW = false, bool PERSIST = false, bool MERGE2 = false>
 __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int NT = 64 * WF * WP;
     constexpr int RS = R * S;
-    constexpr int PH = (TH - 1) * ST + R, PW = (TW - 1) * ST + S;
+    static_assert(!MERGE2 || (BWD && !PHASE && !XW && R == 3 && S == 3 && ST == 1), "merged stride-2 backward-data");
+    constexpr int PH = MERGE2 ? TH + 1 : (TH - 1) * ST + R, PW = MERGE2 ? TW + 1 : (TW - 1) * ST + S;
     constexpr int PSZ = PH * PW;
     constexpr int KQ = CK / 4;  // channels per lane group: lane group kk owns channels [kk*KQ, kk*KQ+KQ) of a chunk
     static_assert(CK == 4 || CK == 8 || CK == 16 || CK == 32 || CK == 64, "CK must be 4, 8, 16, 32 or 64");
@@ -227,9 +233,18 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     }
 
     const bool last_ok = wp + WP * (NBW - 1) < NB;   // does this wave own a block in its last slot?
-    v4f acc[NBW];
+    // Per-tap LDS offset and accumulator set.  Plain correlation: tap (r, s) reads patch row r, column s.
+    // MERGE2: tap index r reads patch row roff(r) = (r == 0) and belongs to row phase a = r % 2.
+    constexpr auto tap_off = [](int t) {
+        return MERGE2 ? ((t / S) == 0 ? PW : 0) + ((t % S) == 0 ? 1 : 0) : (t / S) * PW + (t % S);
+    };
+    constexpr auto tap_set = [](int t) { return MERGE2 ? ((t / S) % 2) * 2 + (t % S) % 2 : 0; };
+    constexpr int NSET = MERGE2 ? 4 : 1;
+    v4f acc[NSET][NBW];
 #pragma unroll
-    for (int i = 0; i < NBW; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int q = 0; q < NSET; ++q)
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) acc[q][i] = v4f{0.f, 0.f, 0.f, 0.f};
 
     float xreg[XW ? 1 : XPT];
     v4u xreg4[XW ? XPT : 1];
@@ -298,14 +313,14 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 #pragma unroll
             for (int e = 0; e < 3; ++e) {
                 const int t = 3 * j + e;   // tap as stored; backward-data uses it rotated by 180 degrees
-                an[k4 * RS + (BWD ? RS - 1 - t : t)] = __uint_as_float(v[e]);
+                an[k4 * RS + (BWD && !MERGE2 ? RS - 1 - t : t)] = __uint_as_float(v[e]);
             }
         } else {
             const int k4 = q / RS, t = q % RS;
             if constexpr (PHASE)   // the table already lists the taps in correlation order
                 an[k4 * RS + t] = buf_load(wrs, wvo[k4] + (unsigned)(a.tapoff[t] * sizeof(T)), tnull);
             else
-                an[k4 * RS + (BWD ? RS - 1 - t : t)] = buf_load(wrs, wvo[k4] + (unsigned)(t * sizeof(T)), tnull);
+                an[k4 * RS + (BWD && !MERGE2 ? RS - 1 - t : t)] = buf_load(wrs, wvo[k4] + (unsigned)(t * sizeof(T)), tnull);
         }
     };
 
@@ -343,7 +358,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         for (int m = 0; m < XPT; ++m) ps[m] = xs + wr + loff[m];
         if (NBUF == 2) {   // the buffer was completed by the barrier just passed: group 0's operands cannot be requested earlier
 #pragma unroll
-            for (int i = 0; i < NBW; ++i) bq[PAR][i] = pr[i][0];
+            for (int i = 0; i < NBW; ++i) bq[PAR][i] = pr[i][tap_off(0)];
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -356,15 +371,15 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
                 if (SG + m * LG / XPT == g) issue_x(m, xrs);   // behind the store of the same register
             __builtin_amdgcn_sched_barrier(0);
             const int k4n = (g + 1) % KQ, tn = (g + 1) / KQ;
-            const int off = k4n * CS + (tn / S) * PW + (tn % S);
+            const int off = k4n * CS + tap_off(tn);
             const float av = ac[(g % KQ) * RS + g / KQ];
 #pragma unroll
             for (int i = 0; i < NBW; ++i) {
                 const bool mine = !(NB % WP != 0 && i == NBW - 1 && !last_ok);   // wave-uniform: this wave may have one block fewer
                 if (mine) {
                     if (g + 1 < G) bq[(PAR + g + 1) & 1][i] = pr[i][off];
-                    else if (NBUF == 3) bq[(PAR + g + 1) & 1][i] = pn[i][0];      // group 0 of the next chunk
-                    acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[(PAR + g) & 1][i], acc[i], 0, 0, 0);
+                    else if (NBUF == 3) bq[(PAR + g + 1) & 1][i] = pn[i][tap_off(0)];      // group 0 of the next chunk
+                    acc[tap_set(g / KQ)][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[(PAR + g) & 1][i], acc[tap_set(g / KQ)][i], 0, 0, 0);
                 }
                 {   // patch stores m with floor(m * SG*NBW / XPT) == this slot
                     constexpr int SACT = SG * NBW;
@@ -382,7 +397,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     // ---- write-out of an item: D[f = 4*kk+v][pixel = li] ---------------------------------------
     auto write_out = [&](const Item& it) __attribute__((always_inline)) {
         const int fq = it.fblk * (16 * WF) + wf * 16 + 4 * kk;
-        const int dplane = PHASE ? a.DH * a.DW : a.OH * a.OW;
+        const int dplane = PHASE || MERGE2 ? a.DH * a.DW : a.OH * a.OW;
         float* dst = a.dst + (size_t)(it.n * a.Cdst + it.g * a.Fg) * dplane;
 #pragma unroll
         for (int i = 0; i < NBW; ++i) {
@@ -390,10 +405,17 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
             const int th = j / TW, tw = j - th * TW;
             const int oh = it.oh0 + th, ow = it.ow0 + tw;
             if (!it.ok || j >= NPX || oh >= a.OH || ow >= a.OW) continue;
-            const int pix = PHASE ? (oh * a.o_sh + a.o_oh) * a.DW + ow * a.o_sw + a.o_ow : oh * a.OW + ow;
 #pragma unroll
-            for (int v = 0; v < 4; ++v)
-                if (fq + v < a.Fg) dst[(size_t)(fq + v) * dplane + pix] = acc[i][v];
+            for (int q = 0; q < NSET; ++q) {
+                // MERGE2: set (a, b) holds destination pixel (2*oh + 1 - a, 2*ow + 1 - b)
+                const int dh = 2 * oh + 1 - q / 2, dw = 2 * ow + 1 - q % 2;
+                if (MERGE2 && (dh >= a.DH || dw >= a.DW)) continue;
+                const int pix = MERGE2 ? dh * a.DW + dw
+                                       : (PHASE ? (oh * a.o_sh + a.o_oh) * a.DW + ow * a.o_sw + a.o_ow : oh * a.OW + ow);
+#pragma unroll
+                for (int v = 0; v < 4; ++v)
+                    if (fq + v < a.Fg) dst[(size_t)(fq + v) * dplane + pix] = acc[q][i][v];
+            }
         }
     };
 
@@ -443,7 +465,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         __syncthreads();
         if (NBUF == 3) {
 #pragma unroll
-            for (int i = 0; i < NBW; ++i) bq[0][i] = xs[pixoff[i]];
+            for (int i = 0; i < NBW; ++i) bq[0][i] = xs[pixoff[i] + tap_off(0)];
         }
     }
     int rd = 0, nx = BUFSZ, wr = D * BUFSZ;
@@ -454,7 +476,9 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         if (PERSIST && ++cch == nchunks) {
             write_out(item(cj));
 #pragma unroll
-            for (int i = 0; i < NBW; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
+            for (int q = 0; q < NSET; ++q)
+#pragma unroll
+                for (int i = 0; i < NBW; ++i) acc[q][i] = v4f{0.f, 0.f, 0.f, 0.f};
             cch = 0;
             ++cj;
         }

@@ -1,4 +1,5 @@
-// Backward-data for stride > 1 on the tiled MFMA kernel, one launch per output phase.
+// Backward-data for stride > 1 on the tiled MFMA kernel: one launch per output phase, or (3x3, stride 2,
+// padding 1) one launch in which all four phases share the dy patch.
 //
 //   dx[n,c,h,v] = sum_{k,r,s : (h+ph-r) % st == 0, (v+pw-s) % st == 0} dy[n,k,(h+ph-r)/st,(v+pw-s)/st] * w[k,c,r,s]
 //
@@ -72,7 +73,44 @@ hipError_t launch_phase_shape(int jh, int jw, const TileArgs& a, hipStream_t st)
     }
 }
 
+// 3x3, stride 2, padding 1: the merged kernel (MERGE2 in mfma_tile_kernel.h).
+template <typename T, int WF, int WP>
+hipError_t launch_merge2(TileArgs a, hipStream_t st) {
+    constexpr int TH = 14, TW = 14, CK = 16;
+    a.tiles_h = (a.OH + TH - 1) / TH;
+    a.tiles_w = (a.OW + TW - 1) / TW;
+    a.fblocks = (a.Fg + 16 * WF - 1) / (16 * WF);
+    a.units = a.N * a.groups * a.tiles_h * a.tiles_w;
+    a.items = ((a.units + 7) / 8) * 8 * a.fblocks;
+    conv_tile_kernel<T, 3, 3, 1, TH, TW, CK, WF, WP, true, false, false, 3, false, false, true><<<a.items, 64 * WF * WP, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+bool merge2_ok(const Problem& pr) {
+    if (pr.R != 3 || pr.S != 3 || pr.sh != 2 || pr.sw != 2 || pr.ph != 1 || pr.pw != 1) return false;
+    const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
+    return (size_t)pr.N * pr.C * pr.H * pr.W * esz < lim && (size_t)pr.N * pr.K * pr.P * pr.Q * esz < lim;
+}
+
 }  // namespace
+
+bool tile_merge2_supports(const Problem& pr) { return merge2_ok(pr); }
+
+hipError_t tile_merge2_run(const Problem& pr, const void* dy, const void* w, float* dx, hipStream_t st) {
+    if (!merge2_ok(pr)) return hipErrorNotSupported;
+    const unsigned esz = pr.dtype == 0 ? 4 : 2;
+    TileArgs t{};
+    t.src = dy; t.wgt = w; t.dst = dx;
+    t.N = pr.N; t.Csrc = pr.K; t.IH = pr.P; t.IW = pr.Q;
+    t.Cdst = pr.C; t.OH = (pr.H + 1) / 2; t.OW = (pr.W + 1) / 2;   // the half-resolution grid
+    t.Fg = pr.Cg; t.Rg = pr.Kg; t.groups = pr.groups;
+    t.pad_h = 0; t.pad_w = 0;                                     // patch row 0 is dy row (grid row of the tile)
+    t.wgt_bytes = (unsigned)((size_t)pr.K * pr.Cg * pr.R * pr.S * esz);
+    t.DH = pr.H; t.DW = pr.W;
+    t.w_rs = 9;
+    if (t.Fg <= 16) return pr.dtype == 0 ? launch_merge2<float, 1, 4>(t, st) : launch_merge2<uint16_t, 1, 4>(t, st);
+    return pr.dtype == 0 ? launch_merge2<float, 2, 4>(t, st) : launch_merge2<uint16_t, 2, 4>(t, st);
+}
 
 bool tile_phase_supports(const Problem& pr) {
     if (pr.sh < 2 && pr.sw < 2) return false;   // stride 1 runs on the plain path

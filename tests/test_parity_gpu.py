@@ -70,6 +70,7 @@ MFMA = [
     ("m3x3s2b", 1, 16, 31, 27, 20, 3, 3, 2, 1, 1),    # odd sizes: phases of different extent
     ("m3x3s2c", 2, 16, 16, 16, 24, 3, 3, 2, 0, 1),    # no padding: the last input row/column feeds nothing
     ("m3x3s2g", 1, 32, 14, 14, 32, 3, 3, 2, 1, 2),
+    ("m3x3s2d", 2, 24, 57, 60, 40, 3, 3, 2, 1, 1),    # merged-phase backward-data over several ragged tiles
 ]
 
 
