@@ -555,7 +555,7 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
     *ws_bytes = 0;
     if (pr.sh != pr.sw) return false;
     if (pr.R == 3 && pr.S == 3 && pr.sh == 1) {
-        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 8, 4, 2>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 8, 8, 2>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 3 && pr.S == 3 && pr.sh == 2) {
