@@ -559,7 +559,7 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
         return true;
     }
     if (pr.R == 3 && pr.S == 3 && pr.sh == 2) {
-        *err = launch_wgrad<T, 3, 3, 2, 14, 14, 1, 1, 1, 1, 4, 4, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 3, 3, 2, 14, 14, 1, 1, 1, 1, 8, 8, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1) {
