@@ -518,28 +518,35 @@ Plan make_plan(const Problem& pr, WgradArgs& a) {
 
 // WS: pixel-step shares (waves) on the 16-byte fetch path; WSN: on the 4-byte path, which needs more
 // registers per thread and therefore runs one wave per SIMD.
-template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int WSN, int IMG, int OCC = 1>
+// WS, IMG: pixel-step shares (waves) and images per stage on the 16-byte fetch path; WSN, IMGN: on the 4-byte path.
+template <typename T, int R, int S, int ST, int TH, int TW, int KB, int CB, int WK, int WC, int WS, int WSN, int IMG, int OCC = 1,
+          int IMGN = IMG>
 hipError_t launch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st,
                         bool dry, size_t* ws_bytes) {
     WgradArgs a{};
     a.x = x; a.dy = dy;
     a.N = pr.N; a.C = pr.C; a.H = pr.H; a.W = pr.W; a.K = pr.K; a.P = pr.P; a.Q = pr.Q;
     a.Cg = pr.Cg; a.Kg = pr.Kg; a.groups = pr.groups; a.pad_h = pr.ph; a.pad_w = pr.pw;
-    const Plan pl = make_plan<TH, TW, KB, CB, IMG, OCC>(pr, a);
-    *ws_bytes = pl.ws_bytes;
-    if (dry) return hipSuccess;
-    a.out = pl.nsplit > 1 ? static_cast<float*>(ws) : dw;
-    const int grid = ((a.total_wgs + 7) / 8) * 8;
-    const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(dy) % 16 == 0;
     // 16-byte fetch path: a channel's share of a stage is one contiguous run - the whole plane, or (1x1
     // filters without padding) TH full rows of it
     const bool whole = pr.P == TH && pr.Q == TW && pr.H * pr.W == TH * TW * ST * ST;
     const bool rows = R == 1 && S == 1 && ST == 1 && pr.ph == 0 && pr.pw == 0 && pr.Q == TW && pr.P % TH == 0;
-    const bool wide = sizeof(T) == 4 && aligned && (pr.H * pr.W) % 4 == 0 && (pr.P * pr.Q) % 4 == 0 && (TH * TW) % 4 == 0 &&
-                      (whole || rows);
+    const bool wide_shape = sizeof(T) == 4 && (pr.H * pr.W) % 4 == 0 && (pr.P * pr.Q) % 4 == 0 && (TH * TW) % 4 == 0 && (whole || rows);
+    if (dry) {   // the pointers (their alignment picks the path) are not known yet: report the larger need
+        WgradArgs b = a;
+        const Plan p1 = make_plan<TH, TW, KB, CB, IMG, OCC>(pr, a), p2 = make_plan<TH, TW, KB, CB, IMGN, 1>(pr, b);
+        *ws_bytes = p1.ws_bytes > p2.ws_bytes ? p1.ws_bytes : p2.ws_bytes;
+        return hipSuccess;
+    }
+    const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(dy) % 16 == 0;
+    const bool wide = wide_shape && aligned;
+    const Plan pl = wide ? make_plan<TH, TW, KB, CB, IMG, OCC>(pr, a) : make_plan<TH, TW, KB, CB, IMGN, 1>(pr, a);
+    *ws_bytes = pl.ws_bytes;
+    a.out = pl.nsplit > 1 ? static_cast<float*>(ws) : dw;
+    const int grid = ((a.total_wgs + 7) / 8) * 8;
     a.tile_fastest = wide && !whole;
     if (wide) wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WS, IMG, true, (WK * WC * WS + 3) / 4 * OCC><<<grid, 64 * WK * WC * WS, 0, st>>>(a);
-    else wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WSN, IMG, false, (WK * WC * WSN + 3) / 4><<<grid, 64 * WK * WC * WSN, 0, st>>>(a);
+    else wgrad_kernel<T, R, S, ST, TH, TW, KB, CB, WK, WC, WSN, IMGN, false, (WK * WC * WSN + 3) / 4><<<grid, 64 * WK * WC * WSN, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.nsplit == 1) return e;
     const size_t count = (size_t)pr.K * pr.Cg * pr.R * pr.S;
@@ -563,7 +570,7 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1) {
-        *err = launch_wgrad<T, 1, 1, 1, 2, 14, 8, 8, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 1, 1, 1, 2, 14, 8, 8, 2, 2, 2, 1, 2, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     return false;
