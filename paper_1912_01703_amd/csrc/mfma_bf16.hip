@@ -355,11 +355,9 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     __builtin_amdgcn_s_waitcnt(0x0F70);   // loads fetched past the last chunk still target registers
 }
 
-#ifndef BF_CFG
-#define BF_CFG 2, 2, 2, 2
-#endif
-constexpr int kCfg[4] = {BF_CFG};
-constexpr int kFB = kCfg[0], kWF = kCfg[1], kWP = kCfg[2], kOCC = kCfg[3];
+// 32 filters per wave (one B operand feeds two MFMAs), 2 x 2 waves, two workgroups per CU.  Wider waves
+// (64 filters, or all 13 pixel blocks) spill; four pixel-block waves leave too few MFMAs per chunk.
+constexpr int kFB = 2, kWF = 2, kWP = 2, kOCC = 2;
 
 size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
 

@@ -1,9 +1,6 @@
 // Host side of the tiled forward / stride-1 backward-data path: which instantiation of the kernel in
 // mfma_tile_kernel.h serves which filter size and stride.
 #include "mfma_tile_kernel.h"
-#ifndef TILE_1X1
-#define TILE_1X1 32, 4, 2, BWD, 3
-#endif
 
 namespace miconv {
 namespace {
@@ -25,8 +22,8 @@ hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
         const bool plane_patch = a.pad_h == 0 && a.pad_w == 0 && a.IH == TH && a.IW == TW && a.OH == TH && a.OW == TW &&
                                  reinterpret_cast<uintptr_t>(a.src) % 16 == 0;
         if (plane_patch) {
-            if (wv) conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true, false, NBUF, true><<<grid, 64 * WF * WP, 0, st>>>(a);
-            else conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, false, false, NBUF, true><<<grid, 64 * WF * WP, 0, st>>>(a);
+            if (wv) conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true, false, NBUF, true, PERSIST><<<grid, 64 * WF * WP, 0, st>>>(a);
+            else conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, false, false, NBUF, true, PERSIST><<<grid, 64 * WF * WP, 0, st>>>(a);
             return hipGetLastError();
         }
     }
@@ -49,7 +46,11 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
         return true;
     }
     if (R == 1 && S == 1 && stride == 1) {
-        if (!dry) *err = launch_tile<T, 1, 1, 1, 14, 14, TILE_1X1>(a, st);
+        if (dry) return true;
+        // 32-channel chunks on eight waves; persistent workgroups when there are many short items
+        const long long ids = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
+        if (a.Rg <= 256 && ids >= 1024) *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD, 3, true>(a, st);
+        else *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD>(a, st);
         return true;
     }
     if (!BWD && R == 3 && S == 3 && stride == 2) {
