@@ -80,3 +80,29 @@ def test_workspace_query_is_zero_for_invalid_arguments(mc):
     bad = dict(GOOD, groups=3)
     assert mc.conv2d_workspace_bytes(2, *bad.values()) == 0
     assert mc.conv2d_workspace_bytes(9, *GOOD.values()) == 0
+
+
+def test_workspace_sizes_of_the_benchmark_layers(mc):
+    """Host arithmetic only: which passes of which layers need scratch memory, and how much."""
+    from paper_1912_01703_amd import workloads as wl
+    L = wl.LAYERS
+    # layer 2a backward-weight: 256 workgroups without a split, nothing to reduce
+    assert mc.conv2d_workspace_bytes(2, *L["2a"].conv_args(), mc.F32) == 0
+    # depthwise: the splits of a channel are summed inside a workgroup
+    assert mc.conv2d_workspace_bytes(2, *L["5a"].conv_args(), mc.F32) == 0
+    for p in (0, 1):
+        assert mc.conv2d_workspace_bytes(p, *L["4b"].conv_args(), mc.F32) == 0
+    # a split reduction holds one partial dw per split
+    ws = mc.conv2d_workspace_bytes(2, *L["2b"].conv_args(), mc.F32)
+    dw_bytes = 4 * L["2b"].K * L["2b"].C
+    assert ws > 0 and ws % dw_bytes == 0
+    # bf16 inputs on the bf16 matrix cores: a channels-innermost copy of the source and the packed filters
+    l4 = L["4b"]
+    need = l4.N * l4.H * l4.W * l4.C * 2 + 9 * l4.K * l4.C * 2
+    got = mc.conv2d_workspace_bytes(0, *l4.conv_args(), mc.BF16_F32ACC)
+    assert need <= got <= need + 512
+    # ... and for backward-weight images-innermost copies of x and dy (N is a multiple of 8 here) plus the partials
+    got2 = mc.conv2d_workspace_bytes(2, *l4.conv_args(), mc.BF16_F32ACC)
+    assert got2 >= 2 * l4.N * l4.C * l4.H * l4.W * 2
+    # 14x14 planes are not a multiple of 8 elements: bf16 inputs take the widening path, no layout copies
+    assert mc.conv2d_workspace_bytes(0, *L["2a"].conv_args(), mc.BF16_F32ACC) == 0
