@@ -104,5 +104,9 @@ def test_workspace_sizes_of_the_benchmark_layers(mc):
     # ... and for backward-weight images-innermost copies of x and dy (N is a multiple of 8 here) plus the partials
     got2 = mc.conv2d_workspace_bytes(2, *l4.conv_args(), mc.BF16_F32ACC)
     assert got2 >= 2 * l4.N * l4.C * l4.H * l4.W * 2
+    # with few channels backward-weight transposes its operands on the way into LDS: only partial sums
+    l4a = L["4a"]
+    got3 = mc.conv2d_workspace_bytes(2, *l4a.conv_args(), mc.BF16_F32ACC)
+    assert 0 < got3 and got3 % (4 * 9 * l4a.K * l4a.C) == 0
     # 14x14 planes are not a multiple of 8 elements: bf16 inputs take the widening path, no layout copies
     assert mc.conv2d_workspace_bytes(0, *L["2a"].conv_args(), mc.BF16_F32ACC) == 0

@@ -106,13 +106,18 @@ def test_bf16_matrix_core_path(row):
 
 
 BF16WG = [
-    # name     N   C    H   W   K   pad    3x3 stride 1, bf16, H*W % 8 == 0 and P*Q % 8 == 0, N*P*Q >= 4096:
+    # name     N   C    H   W   K   pad    3x3 stride 1, bf16, N*P*Q >= 4096, Q % 4 == 0 and W even (few channels) or planes % 8 == 0:
     #                                      backward-weight on the bf16 matrix cores (rows streamed through LDS)
     ("w3x3a", 16, 32, 16, 16, 64, 1),
     ("w3x3b", 9, 40, 32, 32, 72, 1),       # N not a multiple of 8, partial channel blocks, two strips
     ("w3x3c", 8, 32, 30, 28, 64, 0),       # no padding
     ("w3x3d", 8, 16, 24, 24, 16, 2),       # padding 2
     ("w3x3e", 3, 64, 120, 40, 64, 1),      # three row segments
+    # many channels: x and dy are rewritten images-innermost by a pre-pass instead of inside the kernel
+    ("w3x3f", 16, 128, 16, 16, 128, 1),
+    ("w3x3g", 9, 136, 24, 32, 120, 1),     # N not a multiple of 8, partial channel blocks, two strips
+    ("w3x3h", 8, 128, 24, 30, 128, 0),     # no padding
+    ("w3x3i", 8, 128, 24, 26, 128, 2),     # padding 2, width not a multiple of 4
 ]
 
 
