@@ -470,7 +470,6 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
 
     // wide path: float4 f = lane + 64*i of the batch's x planes (and dy planes) and where the values land
     unsigned vgx[NLV], vgy[NLV];
-    int vpx[NLV], vpy[NLV];
     int lo[NLV][4];
     if constexpr (WIDE) {
 #pragma unroll
@@ -479,12 +478,10 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
             {
                 const int pl = fdiv(4 * f, a.inv_xplane), rem = 4 * f - pl * xplane;
                 vgx[i] = 4 * f < a.PB * xplane ? (unsigned)(pl * a.C * xplane + rem) * 4u : kOob;
-                vpx[i] = pl;
             }
             {
                 const int pl = fdiv(4 * f, a.inv_yplane), rem = 4 * f - pl * yplane;
                 vgy[i] = 4 * f < a.PB * yplane ? (unsigned)(pl * a.C * yplane + rem) * 4u : kOob;
-                vpy[i] = pl;
             }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -501,7 +498,6 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
 
     // image i of a batch is the plane (n+i)*C + c: offsets are relative to image n, channel c
     unsigned goff[NPIB];
-    int gpl[NPIB];
 #pragma unroll
     for (int i = 0; i < NPIB; ++i) {
         const int e = lane + 64 * i;
@@ -510,9 +506,8 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
         const int ih = ph - a.pad_h, iw = pw - a.pad_w;
         const bool ok = e < a.PB * PPS && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
         goff[i] = ok ? (unsigned)(pl * a.C * xplane + ih * a.W + iw) * ESZ : kOob;
-        gpl[i] = pl;
     }
-    int win[NPS], rows[NPS], ypl[NPS], yli[NPS];
+    int win[NPS], rows[NPS], yli[NPS];
     unsigned yo[NPS];
     {
         const int ul = fdiv(lane, a.inv_q), q = lane - ul * a.Q;
@@ -527,12 +522,13 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
             yo[ps] = (unsigned)(pl * a.C * yplane + p0 * a.Q + q) * ESZ;
             yli[ps] = pl * yplane + p0 * a.Q + q;
             rows[ps] = ok ? min(kSeg, a.P - p0) : 0;
-            ypl[ps] = pl;
         }
     }
 
-    const rsrc_t xrs = make_rsrc(a.x, a.x_bytes);
-    const rsrc_t yrs = make_rsrc(a.dy, a.y_bytes);
+    // The descriptors end with plane (n1 - 1, c): images of a batch past the wave's range read as zeros.
+    const int last = __builtin_amdgcn_readfirstlane((n1 - 1) * a.C + c + 1);
+    const rsrc_t xrs = make_rsrc(a.x, n1 > n0 ? (unsigned)(last * xplane) * ESZ : 0u);
+    const rsrc_t yrs = make_rsrc(a.dy, n1 > n0 ? (unsigned)(last * yplane) * ESZ : 0u);
     float acc[9];
 #pragma unroll
     for (int t = 0; t < 9; ++t) acc[t] = 0.f;
@@ -540,22 +536,21 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
     float xv[WIDE ? 1 : NPIB], yv[WIDE ? 1 : NPS][kSeg];
     v4u x4[WIDE ? NLV : 1], y4[WIDE ? NLV : 1];
     auto fetch = [&](int n) {
-        const int left = n1 - n;   // images of the range still to come: later ones read as zero
         const unsigned xb = (unsigned)((n * a.C + c) * xplane) * ESZ, yb = (unsigned)((n * a.C + c) * yplane) * ESZ;
         if constexpr (WIDE) {
 #pragma unroll
             for (int i = 0; i < NLV; ++i) {
-                x4[i] = __builtin_amdgcn_raw_buffer_load_b128(xrs, vpx[i] < left ? xb + vgx[i] : kOob, 0, 0);
-                y4[i] = __builtin_amdgcn_raw_buffer_load_b128(yrs, vpy[i] < left ? yb + vgy[i] : kOob, 0, 0);
+                x4[i] = __builtin_amdgcn_raw_buffer_load_b128(xrs, xb + vgx[i], 0, 0);   // kOob + xb stays out of range
+                y4[i] = __builtin_amdgcn_raw_buffer_load_b128(yrs, yb + vgy[i], 0, 0);
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < NPIB; ++i) xv[i] = buf_load(xrs, gpl[i] < left ? xb + goff[i] : kOob, tnull);
+            for (int i = 0; i < NPIB; ++i) xv[i] = buf_load(xrs, xb + goff[i], tnull);
 #pragma unroll
             for (int ps = 0; ps < NPS; ++ps)
 #pragma unroll
                 for (int i = 0; i < kSeg; ++i)
-                    yv[ps][i] = buf_load(yrs, (i < rows[ps] && ypl[ps] < left) ? yb + yo[ps] + (unsigned)(i * a.Q) * ESZ : kOob, tnull);
+                    yv[ps][i] = buf_load(yrs, i < rows[ps] ? yb + yo[ps] + (unsigned)(i * a.Q) * ESZ : kOob, tnull);
         }
     };
     if (n0 < n1) fetch(n0);
@@ -767,12 +762,18 @@ template <typename T, int ST>
 hipError_t launch_strip_stencil(const DwStripArgs& a, hipStream_t st) {
     // Persistent waves: each keeps one batch in flight while it computes the previous one.
     // The grid is what is resident at once (256 CUs x the occupancy the register budget allows).
-    int grid = (a.nbatches + 3) / 4;
-    const int resident = 256 * 3;
-    if (grid > resident) grid = resident;
     const size_t smem = (size_t)4 * a.lds_per_wave * sizeof(float);
     const bool wide = sizeof(T) == 4 && (a.IH * a.IW) % 4 == 0 && (a.OH * a.OW) % 4 == 0 &&
                       reinterpret_cast<uintptr_t>(a.src) % 16 == 0 && reinterpret_cast<uintptr_t>(a.dst) % 16 == 0;
+    // Workgroups per CU: registers allow 4 for the 16-byte stride-1 kernel (3 otherwise), LDS 160 KB.
+    int occ = wide && ST == 1 ? 4 : 3;
+    while (occ > 1 && occ * smem > 160 * 1024) --occ;
+    const int resident = 256 * occ;
+    // Every wave runs the same number of batches (a grid of `resident` would leave most waves idle in
+    // the last of ceil(5.33) rounds on a 16 384-batch layer).
+    const int wg_batches = (a.nbatches + 3) / 4;
+    const int rounds = (wg_batches + resident - 1) / resident;
+    const int grid = (wg_batches + rounds - 1) / rounds;
     if (wide) dw_strip_stencil_kernel<T, ST, 16, 2, true><<<grid, kThreads, smem, st>>>(a);
     else dw_strip_stencil_kernel<T, ST, 16, 2, false><<<grid, kThreads, smem, st>>>(a);
     return hipGetLastError();
@@ -791,7 +792,8 @@ bool strip_wgrad_args(const Problem& pr, const void* x, const void* dy, DwStripW
     a.inv_ppw = 1.0f / a.PPW; a.inv_pps = 1.0f / (a.PPH * a.PPW); a.inv_q = 1.0f / pr.Q; a.inv_nseg = 1.0f / sp.NSEG;
     a.inv_xplane = 1.0f / (pr.H * pr.W); a.inv_w = 1.0f / pr.W; a.inv_yplane = 1.0f / (pr.P * pr.Q);
     // One wave per (channel, split): two waves per SIMD (256 CUs x 4 SIMDs x 2) measured best, each
-    // running a long, prefetched image loop.
+    // running a long, prefetched image loop (four per SIMD, all resident: 29 instead of 26.5 us on the
+    // 14x14x1024 layer - more concurrent 784-byte streams, not more bytes in flight).
     int nsplit = (2048 + pr.C - 1) / pr.C;
     if (nsplit > pr.N) nsplit = pr.N;
     if (nsplit < 1) nsplit = 1;
