@@ -119,8 +119,11 @@ def main():
         x, w, dy = (wl.to_bf16_bits(t).view(np.int16) for t in (x, w, dy))
 
     depthwise = L.groups == L.C == L.K and L.groups > 1
-    set_bytes = sum(algorithmic_bytes(L, p, in_bytes) for p in PASSES)
-    nsets = a.rotate if a.rotate > 0 else (max(2, int(600e6 // max(1, set_bytes)) + 1) if depthwise else 1)
+    # HBM-bound layers rotate over buffer sets so that no launch finds its inputs in the 256 MB Infinity
+    # Cache: also within a group of launches of one pass, more than 256 MB are touched between two
+    # uses of a buffer.
+    pass_bytes = min(algorithmic_bytes(L, p, in_bytes) for p in PASSES)
+    nsets = a.rotate if a.rotate > 0 else (max(4, int(300e6 // max(1, pass_bytes)) + 2) if depthwise else 1)
     nsets = min(nsets, 64)
     sets = []
     for i in range(nsets):
@@ -157,19 +160,37 @@ def main():
     ms_per_step = wall * 1e3 / a.steps
     tflops = 3.0 * L.flops / (ms_per_step * 1e-3) / 1e12
 
-    # Second region, same launches: HIP events around every pass (recorded on the
-    # stream the kernels are launched on) give each pass's average duration.
+    # Second region, same launches: HIP events (recorded on the stream the kernels are launched on)
+    # around GROUP back-to-back launches of one pass, each on the next buffer set; the bracket's time
+    # divided by GROUP is that pass's average launch duration.  One launch per bracket would add the
+    # events' own cost (2-3 us) to kernels that run for 25 us.  MFMA-bound layers keep the order of a
+    # training step (fwd, bwd_data, bwd_weight groups alternate).  HBM-bound layers run pass by pass,
+    # each after a few untimed launches: in step order the pass that only reads (bwd_weight) is charged
+    # the write-back of the 256 MB of results that the passes before it left in the Infinity Cache
+    # (31 instead of 25 us on layer 5a).
+    GROUP = 4
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3)]
           for _ in range(a.steps)]
-    for i in range(a.steps):
-        s = sets[i % nsets]
+
+    def bracket(i, p):
+        ev[i][p][0].record()
+        for j in range(GROUP):
+            run_pass(p, sets[(i * GROUP + j) % nsets])
+        ev[i][p][1].record()
+
+    if depthwise:
         for p in range(3):
-            ev[i][p][0].record()
-            run_pass(p, s)
-            ev[i][p][1].record()
+            for j in range(2 * GROUP):
+                run_pass(p, sets[j % nsets])
+            for i in range(a.steps):
+                bracket(i, p)
+    else:
+        for i in range(a.steps):
+            for p in range(3):
+                bracket(i, p)
     torch.cuda.synchronize()
-    pass_ms = [float(np.mean([ev[i][p][0].elapsed_time(ev[i][p][1]) for i in range(a.steps)])) for p in range(3)]
-    pass_min = [float(np.min([ev[i][p][0].elapsed_time(ev[i][p][1]) for i in range(a.steps)])) for p in range(3)]
+    pass_ms = [float(np.mean([ev[i][p][0].elapsed_time(ev[i][p][1]) for i in range(a.steps)])) / GROUP for p in range(3)]
+    pass_min = [float(np.min([ev[i][p][0].elapsed_time(ev[i][p][1]) for i in range(a.steps)])) / GROUP for p in range(3)]
     algos = [mc.miconv_last_algo(p) for p in range(3)]
 
     passes = {}
@@ -184,14 +205,15 @@ def main():
         roof = {"bound": "hbm", "kernel": PASSES[dom], "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": ach / PEAK_HBM_GBS, "traffic": traffic,
                 "algorithmic_bytes_per_launch": algorithmic_bytes(L, PASSES[dom], in_bytes),
-                "avg_launch_ms": pass_ms[dom], "buffer_sets_rotated": nsets}
+                "avg_launch_ms": pass_ms[dom], "launches_per_event_pair": GROUP, "event_region_order": "pass by pass",
+                "buffer_sets_rotated": nsets}
     else:
         ach = passes[PASSES[dom]]["tflops"]
         peak = PEAK_TFLOPS[a.dtype]
         roof = {"bound": "mfma", "kernel": PASSES[dom], "achieved": ach, "peak": peak, "unit": "TFLOP/s",
                 "frac": ach / peak, "traffic": traffic, "algorithmic_flops_per_launch": L.flops,
                 "algorithmic_bytes_per_launch": algorithmic_bytes(L, PASSES[dom], in_bytes),
-                "avg_launch_ms": pass_ms[dom]}
+                "avg_launch_ms": pass_ms[dom], "launches_per_event_pair": GROUP, "event_region_order": "step by step"}
 
     out = {
         "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,

@@ -16,6 +16,8 @@
 // away from an integer, far more than fp32 rounding) instead of integer division.
 #include "common.h"
 
+#include <type_traits>
+
 namespace miconv {
 namespace {
 
@@ -283,40 +285,33 @@ struct DwStripArgs {
 // quarter of its peak with 4-byte ones, which is what bounds this kernel): the batch is read as
 // consecutive float4 and scattered into the padded planes, results are gathered from an LDS staging
 // area as float4.  Needs fp32 planes whose sizes are multiples of 4 and 16-byte aligned tensors.
-template <typename T, int ST, int NPIB, int NPS, bool WIDE>
+// PPWC, OWC: padded-plane and output widths known at compile time (0: taken from the arguments), which
+// turns every LDS offset of the compute step into an immediate.  Such an instance also assumes that the
+// output height is a multiple of kSeg: every lane owns kSeg rows or none, and the per-row checks go.
+template <typename T, int ST, int NPIB, int NPS, bool WIDE, int PPWC = 0, int OWC = 0>
 __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs a) {
     constexpr int NLV = 4;   // float4 passes over a batch's input / output (PB*plane/4 <= 256)
     extern __shared__ float lds[];
     constexpr unsigned ESZ = sizeof(T);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int PPS = a.PPH * a.PPW;
-    const int iplane = a.IH * a.IW, oplane = a.OH * a.OW;
+    constexpr bool WHOLE = PPWC != 0;
+    const int ppw = PPWC ? PPWC : a.PPW, ow = OWC ? OWC : a.OW;
+    const int PPS = a.PPH * ppw;
+    const int iplane = a.IH * a.IW, oplane = a.OH * ow;
     const T* const tnull = nullptr;
     float* my = lds + wave * a.lds_per_wave;
     float* wl = my + a.w_off;   // behind the planes and the slack rows masked strips read
     float* ol = my + a.o_off;
 
-    // wide path: lane's float4 f = lane + 64*i of the batch and where its four values land in LDS
+    // wide path: lane's float4 f = lane + 64*i of the batch
     unsigned vgo[NLV];
-    int lo[NLV][4];
     if constexpr (WIDE) {
 #pragma unroll
         for (int i = 0; i < NLV; ++i) {
             const int f = lane + 64 * i;
             vgo[i] = 4 * f < a.PB * iplane ? (unsigned)f * 16u : kOob;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int idx = 4 * f + k;
-                const int pl = fdiv(idx, a.inv_iplane), rem = idx - pl * iplane;
-                const int ih = fdiv(rem, a.inv_iw), iw = rem - ih * a.IW;
-                const int ph = ih + a.pad_h, pw = iw + a.pad_w;
-                const bool ok = idx < a.PB * iplane && ph >= 0 && ph < a.PPH && pw >= 0 && pw < a.PPW;
-                lo[i][k] = ok ? pl * PPS + ph * a.PPW + pw : -1;
-            }
         }
-        // borders (and the slack) are written once; the scatter only ever touches interior words
-        for (int e = lane; e < a.w_off; e += 64) my[e] = 0.f;
     }
 
     unsigned goff[NPIB];   // byte offset inside the batch, kOob = zero
@@ -324,14 +319,14 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
     for (int i = 0; i < NPIB; ++i) {
         const int e = lane + 64 * i;
         const int pl = fdiv(e, a.inv_pps), rem = e - pl * PPS;
-        const int ph = fdiv(rem, a.inv_ppw), pw = rem - ph * a.PPW;
+        const int ph = fdiv(rem, a.inv_ppw), pw = rem - ph * ppw;
         const int ih = ph - a.pad_h, iw = pw - a.pad_w;
         const bool ok = e < a.PB * PPS && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
         goff[i] = ok ? (unsigned)(pl * iplane + ih * a.IW + iw) * ESZ : kOob;
     }
     int win[NPS], oo[NPS], rows[NPS], wof[NPS];
     {
-        const int ul = fdiv(lane, a.inv_ow), q = lane - ul * a.OW;
+        const int ul = fdiv(lane, a.inv_ow), q = lane - ul * ow;
 #pragma unroll
         for (int ps = 0; ps < NPS; ++ps) {
             const int u = ps * a.UPP + ul;
@@ -339,8 +334,8 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
             const int uc = ok ? u : 0;
             const int pl = fdiv(uc, a.inv_nseg), seg = uc - pl * a.NSEG;
             const int p0 = seg * kSeg;
-            win[ps] = pl * PPS + p0 * ST * a.PPW + q * ST;
-            oo[ps] = pl * oplane + p0 * a.OW + q;
+            win[ps] = pl * PPS + p0 * ST * ppw + q * ST;
+            oo[ps] = pl * oplane + p0 * ow + q;
             rows[ps] = ok ? min(kSeg, a.OH - p0) : 0;
             wof[ps] = pl * 9;
         }
@@ -369,14 +364,33 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
         wreg = buf_load(wrs, (pl < a.PB && plane < a.planes) ? (unsigned)(c * 9 + (a.flip ? 8 - t : t)) * ESZ : kOob, tnull);
     };
     int b = blockIdx.x * (kThreads / 64) + wave;
-    if (b < a.nbatches) fetch(b);
+    if (b < a.nbatches) fetch(b);   // the first batch is on its way while the rest of the plan is made
+
+    // wide path: where the four values of float4 f land in LDS
+    int lo[NLV][4];
+    if constexpr (WIDE) {
+#pragma unroll
+        for (int i = 0; i < NLV; ++i) {
+            const int f = lane + 64 * i;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int idx = 4 * f + k;
+                const int pl = fdiv(idx, a.inv_iplane), rem = idx - pl * iplane;
+                const int ih = fdiv(rem, a.inv_iw), iw = rem - ih * a.IW;
+                const int ph = ih + a.pad_h, pw = iw + a.pad_w;
+                const bool ok = idx < a.PB * iplane && ph >= 0 && ph < a.PPH && pw >= 0 && pw < ppw;
+                lo[i][k] = ok ? pl * PPS + ph * ppw + pw : a.lds_per_wave - 1;   // values without a place land in a spare word
+            }
+        }
+        // borders (and the slack) are written once; the scatter only ever touches interior words
+        for (int e = lane; e < a.w_off; e += 64) my[e] = 0.f;
+    }
     for (; b < a.nbatches; b += nw) {
         if constexpr (WIDE) {
 #pragma unroll
             for (int i = 0; i < NLV; ++i)
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (lo[i][k] >= 0) my[lo[i][k]] = __uint_as_float(v4[i][k]);
+                for (int k = 0; k < 4; ++k) my[lo[i][k]] = __uint_as_float(v4[i][k]);
         } else {
 #pragma unroll
             for (int i = 0; i < NPIB; ++i)
@@ -386,9 +400,7 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
         if (b + nw < a.nbatches) fetch(b + nw);   // the next batch travels while this one is computed
         float* d = a.dst + (size_t)b * a.PB * oplane;
         const int live = min(a.PB, a.planes - b * a.PB) * oplane;   // outputs that exist in this batch
-#pragma unroll
-        for (int ps = 0; ps < NPS; ++ps) {
-            if (ps >= a.passes) break;
+        auto pass = [&](int ps) __attribute__((always_inline)) {
             const float* xq = my + win[ps];
             float wv[9];
 #pragma unroll
@@ -397,7 +409,7 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
 #pragma unroll
             for (int r = 0; r < (kSeg - 1) * ST + 3; ++r)
 #pragma unroll
-                for (int s = 0; s < 3; ++s) xw[r][s] = xq[r * a.PPW + s];
+                for (int s = 0; s < 3; ++s) xw[r][s] = xq[r * ppw + s];
 #pragma unroll
             for (int i = 0; i < kSeg; ++i) {
                 float acc = 0.f;
@@ -405,12 +417,21 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
                 for (int r = 0; r < 3; ++r)
 #pragma unroll
                     for (int s = 0; s < 3; ++s) acc = fmaf(xw[i * ST + r][s], wv[r * 3 + s], acc);
-                const int o = oo[ps] + i * a.OW;
+                const int o = oo[ps] + i * ow;
                 if constexpr (WIDE) {
-                    if (i < rows[ps]) ol[o] = acc;
+                    if (WHOLE || i < rows[ps]) ol[o] = acc;
                 } else {
-                    if (i < rows[ps] && o < live) d[o] = acc;
+                    if ((WHOLE || i < rows[ps]) && o < live) d[o] = acc;
                 }
+            }
+        };
+#pragma unroll
+        for (int ps = 0; ps < NPS; ++ps) {
+            if (ps >= a.passes) break;
+            if constexpr (WHOLE) {
+                if (rows[ps] != 0) pass(ps);
+            } else {
+                pass(ps);
             }
         }
         if constexpr (WIDE) {
@@ -426,91 +447,97 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
 struct DwStripWArgs {
     const void* x;
     const void* dy;
-    float* out;        // [nsplit][C*9] (or dw itself when nsplit == 1)
+    float* out;        // [wsplit][C*9] (dw itself when wsplit == 1)
     int N, C, H, W, P, Q, pad_h, pad_w;
     int PPH, PPW;
     int PB, NSEG, UPP, passes, lds_per_wave, w_off, o_off;
     float inv_ppw, inv_pps, inv_q, inv_nseg, inv_xplane, inv_w, inv_yplane;
-    int nsplit;
-    int fuse;          // the nsplit waves of a channel sit in one workgroup and are summed there (nsplit divides 4)
+    int CPB, IB;       // a batch of PB planes = IB consecutive images x CPB consecutive channels
+    int cgroups;       // groups of CPB consecutive channels
+    int waves;         // waves per workgroup = image ranges summed inside the workgroup
+    int wsplit;        // workgroups per channel group; their partial sums meet in the workspace
     unsigned x_bytes, y_bytes;
 };
 
-// One wave = one channel and a contiguous range of images, taken PB images at a time.  The nine
-// partial sums of every lane stay in registers over the whole range, the next images are fetched
-// while the current ones are multiplied, and the lanes are combined at the end by a fixed
-// butterfly: bit-reproducible, no atomics.
-template <typename T, int ST, int NPIB, int NPS, bool WIDE>
-__global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a) {
+
+// One wave = CPB consecutive channels and a contiguous range of images, IB images at a time.  The CPB
+// planes of an image are one contiguous run of memory, and neighbouring workgroups own neighbouring
+// channels, so that the waves in flight together sweep whole images.  The nine partial sums per
+// channel stay in the lanes' registers over the whole range, the next batch is fetched while the
+// current one is multiplied, and at the end lanes, then the waves of the workgroup (the image
+// ranges), are added in a fixed order: bit-reproducible, no atomics.
+// Most waves per workgroup (two per SIMD: the kernels use up to 209 registers).
+constexpr int kStripWgradWaves = 8;
+
+template <typename T, int ST, int NPIB, int NPS, bool WIDE, int PPWC = 0, int QC = 0>
+__global__ __launch_bounds__(64 * kStripWgradWaves) void dw_strip_wgrad_kernel(DwStripWArgs a) {
     constexpr int NLV = 4;   // float4 passes over a batch of x / dy planes
     extern __shared__ float lds[];
     constexpr unsigned ESZ = sizeof(T);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int PPS = a.PPH * a.PPW;
-    const int xplane = a.H * a.W, yplane = a.P * a.Q;
+    constexpr bool WHOLE = PPWC != 0;   // such an instance is only launched when P is a multiple of kSeg
+    const int ppw = PPWC ? PPWC : a.PPW, qw = QC ? QC : a.Q;   // widths, compile-time constants where given
+    const int PPS = a.PPH * ppw;
+    const int xplane = a.H * a.W, yplane = a.P * qw;
     const T* const tnull = nullptr;
     float* my = lds + wave * a.lds_per_wave;
-    int c, sp;
-    if (a.fuse) {   // the splits of a channel are the waves of one workgroup
-        c = blockIdx.x * ((kThreads / 64) / a.nsplit) + wave / a.nsplit;
-        sp = wave % a.nsplit;
-    } else {
-        const int unit = blockIdx.x * (kThreads / 64) + wave;   // = sp * C + c
-        if (unit >= a.C * a.nsplit) return;
-        c = unit % a.C;
-        sp = unit / a.C;
-    }
-    const bool valid = c < a.C;   // a fused workgroup may hold waves past the last channel: they only join the barrier
-    if (!valid) c = 0;
-    const int n0 = valid ? (int)((long long)a.N * sp / a.nsplit) : 0;
-    const int n1 = valid ? (int)((long long)a.N * (sp + 1) / a.nsplit) : 0;
+    float* wres = lds + a.waves * a.lds_per_wave;   // [wave][64]: per-wave sums
+    // Consecutive workgroup ids go to different XCDs (8, one L2 each).  The channel groups are dealt out so
+    // that an XCD owns a contiguous range of channels: the cache lines that two neighbouring groups share
+    // (planes are not multiples of 128 bytes) are then fetched from HBM once, not once per L2.
+    const int per_xcd = (a.cgroups + 7) / 8;
+    const int bid = blockIdx.x % (8 * per_xcd), ws = blockIdx.x / (8 * per_xcd);
+    const int cg = (bid & 7) * per_xcd + (bid >> 3);
+    if ((bid >> 3) >= per_xcd || cg >= a.cgroups) return;   // the whole workgroup: no barrier is missed
+    const int c0 = cg * a.CPB;
+    const int parts = a.wsplit * a.waves, part = ws * a.waves + wave;
+    const int nbat = (a.N + a.IB - 1) / a.IB;   // ranges are whole batches of IB images
+    const int n0 = (int)((long long)nbat * part / parts) * a.IB, n1 = min(a.N, (int)((long long)nbat * (part + 1) / parts) * a.IB);
+    const float inv_cpb = 1.0f / a.CPB;
+    // plane pl of a batch = image pl / CPB, channel pl % CPB; its offset from (image n, channel c0) in planes
+    auto plane_of = [&](int pl, int& ch) __attribute__((always_inline)) {
+        const int img = fdiv(pl, inv_cpb);
+        ch = pl - img * a.CPB;
+        return img * a.C + ch;
+    };
 
     float* yl = my + a.o_off;   // wide path: the batch's dy planes, unpadded
 
-    // wide path: float4 f = lane + 64*i of the batch's x planes (and dy planes) and where the values land
+    // wide path: float4 f = lane + 64*i of the batch's x planes (and dy planes); planes are multiples of
+    // 4 elements, so a float4 belongs to one plane
     unsigned vgx[NLV], vgy[NLV];
-    int lo[NLV][4];
+    int lo[NLV][4];   // filled once the first loads are on their way
     if constexpr (WIDE) {
 #pragma unroll
         for (int i = 0; i < NLV; ++i) {
             const int f = lane + 64 * i;
-            {
-                const int pl = fdiv(4 * f, a.inv_xplane), rem = 4 * f - pl * xplane;
-                vgx[i] = 4 * f < a.PB * xplane ? (unsigned)(pl * a.C * xplane + rem) * 4u : kOob;
-            }
-            {
-                const int pl = fdiv(4 * f, a.inv_yplane), rem = 4 * f - pl * yplane;
-                vgy[i] = 4 * f < a.PB * yplane ? (unsigned)(pl * a.C * yplane + rem) * 4u : kOob;
-            }
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int idx = 4 * f + k;
-                const int pl = fdiv(idx, a.inv_xplane), rem = idx - pl * xplane;
-                const int ih = fdiv(rem, a.inv_w), iw = rem - ih * a.W;
-                const int ph = ih + a.pad_h, pw = iw + a.pad_w;
-                const bool ok = idx < a.PB * xplane && ph >= 0 && ph < a.PPH && pw >= 0 && pw < a.PPW;
-                lo[i][k] = ok ? pl * PPS + ph * a.PPW + pw : -1;
-            }
+            const int plx = fdiv(4 * f, a.inv_xplane), ply = fdiv(4 * f, a.inv_yplane);
+            int chx, chy;
+            const int px = plane_of(plx, chx), py = plane_of(ply, chy);
+            vgx[i] = plx < a.PB && c0 + chx < a.C ? (unsigned)(px * xplane + (4 * f - plx * xplane)) * 4u : kOob;
+            vgy[i] = ply < a.PB && c0 + chy < a.C ? (unsigned)(py * yplane + (4 * f - ply * yplane)) * 4u : kOob;
         }
-        for (int e = lane; e < a.w_off; e += 64) my[e] = 0.f;   // borders and slack, written once
     }
 
-    // image i of a batch is the plane (n+i)*C + c: offsets are relative to image n, channel c
+    // offsets relative to (image n, channel c0); channels past the last one read as zeros, and so do images
+    // past the wave's range (the descriptors end there)
     unsigned goff[NPIB];
 #pragma unroll
     for (int i = 0; i < NPIB; ++i) {
         const int e = lane + 64 * i;
         const int pl = fdiv(e, a.inv_pps), rem = e - pl * PPS;
-        const int ph = fdiv(rem, a.inv_ppw), pw = rem - ph * a.PPW;
+        const int ph = fdiv(rem, a.inv_ppw), pw = rem - ph * ppw;
         const int ih = ph - a.pad_h, iw = pw - a.pad_w;
-        const bool ok = e < a.PB * PPS && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
-        goff[i] = ok ? (unsigned)(pl * a.C * xplane + ih * a.W + iw) * ESZ : kOob;
+        int ch;
+        const int po = plane_of(pl, ch);
+        const bool ok = e < a.PB * PPS && c0 + ch < a.C && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
+        goff[i] = ok ? (unsigned)(po * xplane + ih * a.W + iw) * ESZ : kOob;
     }
     int win[NPS], rows[NPS], yli[NPS];
     unsigned yo[NPS];
     {
-        const int ul = fdiv(lane, a.inv_q), q = lane - ul * a.Q;
+        const int ul = fdiv(lane, a.inv_q), q = lane - ul * qw;
 #pragma unroll
         for (int ps = 0; ps < NPS; ++ps) {
             const int u = ps * a.UPP + ul;
@@ -518,30 +545,39 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
             const int uc = ok ? u : 0;
             const int pl = fdiv(uc, a.inv_nseg), seg = uc - pl * a.NSEG;
             const int p0 = seg * kSeg;
-            win[ps] = pl * PPS + p0 * ST * a.PPW + q * ST;
-            yo[ps] = (unsigned)(pl * a.C * yplane + p0 * a.Q + q) * ESZ;
-            yli[ps] = pl * yplane + p0 * a.Q + q;
+            win[ps] = pl * PPS + p0 * ST * ppw + q * ST;
+            int ch;
+            const int po = plane_of(pl, ch);
+            yo[ps] = c0 + ch < a.C ? (unsigned)(po * yplane + p0 * qw + q) * ESZ : kOob;
+            yli[ps] = pl * yplane + p0 * qw + q;
             rows[ps] = ok ? min(kSeg, a.P - p0) : 0;
         }
     }
 
-    // The descriptors end with plane (n1 - 1, c): images of a batch past the wave's range read as zeros.
-    const int last = __builtin_amdgcn_readfirstlane((n1 - 1) * a.C + c + 1);
+    const int last = __builtin_amdgcn_readfirstlane((n1 - 1) * a.C + min(c0 + a.CPB, a.C));   // planes up to the range's end
     const rsrc_t xrs = make_rsrc(a.x, n1 > n0 ? (unsigned)(last * xplane) * ESZ : 0u);
     const rsrc_t yrs = make_rsrc(a.dy, n1 > n0 ? (unsigned)(last * yplane) * ESZ : 0u);
-    float acc[9];
+    float acc[NPS][9];
 #pragma unroll
-    for (int t = 0; t < 9; ++t) acc[t] = 0.f;
+    for (int ps = 0; ps < NPS; ++ps)
+#pragma unroll
+        for (int t = 0; t < 9; ++t) acc[ps][t] = 0.f;
 
+    // The 16-byte path keeps two batches in flight per wave (two register sets): with one, a wave's
+    // range is a chain of as many memory round trips as it has batches.
+    constexpr int DEPTH = WIDE ? 2 : 1;
     float xv[WIDE ? 1 : NPIB], yv[WIDE ? 1 : NPS][kSeg];
-    v4u x4[WIDE ? NLV : 1], y4[WIDE ? NLV : 1];
-    auto fetch = [&](int n) {
-        const unsigned xb = (unsigned)((n * a.C + c) * xplane) * ESZ, yb = (unsigned)((n * a.C + c) * yplane) * ESZ;
+    v4u x4[DEPTH][WIDE ? NLV : 1], y4[DEPTH][WIDE ? NLV : 1];
+    // Batches past the range lie beyond the descriptors: zeros, no traffic.
+    auto fetch = [&](int n, auto setc) __attribute__((always_inline)) {
+        constexpr int SET = decltype(setc)::value;
+        // kOob plus a byte offset below 2^31 is still beyond the descriptor
+        const unsigned xb = (unsigned)((n * a.C + c0) * xplane) * ESZ, yb = (unsigned)((n * a.C + c0) * yplane) * ESZ;
         if constexpr (WIDE) {
 #pragma unroll
             for (int i = 0; i < NLV; ++i) {
-                x4[i] = __builtin_amdgcn_raw_buffer_load_b128(xrs, xb + vgx[i], 0, 0);   // kOob + xb stays out of range
-                y4[i] = __builtin_amdgcn_raw_buffer_load_b128(yrs, yb + vgy[i], 0, 0);
+                x4[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(xrs, xb + vgx[i], 0, 0);
+                y4[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(yrs, yb + vgy[i], 0, 0);
             }
         } else {
 #pragma unroll
@@ -550,28 +586,43 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
             for (int ps = 0; ps < NPS; ++ps)
 #pragma unroll
                 for (int i = 0; i < kSeg; ++i)
-                    yv[ps][i] = buf_load(yrs, i < rows[ps] ? yb + yo[ps] + (unsigned)(i * a.Q) * ESZ : kOob, tnull);
+                    yv[ps][i] = buf_load(yrs, i < rows[ps] ? yb + yo[ps] + (unsigned)(i * qw) * ESZ : kOob, tnull);
         }
     };
-    if (n0 < n1) fetch(n0);
-    for (int n = n0; n < n1; n += a.PB) {
-        float yc[NPS][kSeg];
+    auto pass = [&](int ps) __attribute__((always_inline)) {
+        const float* xq = my + win[ps];
+        float yc[kSeg];
+#pragma unroll
+        for (int i = 0; i < kSeg; ++i) yc[i] = WHOLE || i < rows[ps] ? yl[yli[ps] + i * qw] : 0.f;
+        float xw[(kSeg - 1) * ST + 3][3];
+#pragma unroll
+        for (int r = 0; r < (kSeg - 1) * ST + 3; ++r)
+#pragma unroll
+            for (int s = 0; s < 3; ++s) xw[r][s] = xq[r * ppw + s];
+        // rows this lane does not own are skipped outright (their window may be another plane's data)
+#pragma unroll
+        for (int i = 0; i < kSeg; ++i) {
+            if (!WHOLE && i >= rows[ps]) continue;
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int s = 0; s < 3; ++s) acc[ps][r * 3 + s] = fmaf(yc[i], xw[i * ST + r][s], acc[ps][r * 3 + s]);
+        }
+    };
+    // One batch: registers -> LDS, refill the registers with the batch DEPTH ahead, multiply.
+    auto step = [&](int n, auto setc) __attribute__((always_inline)) {
+        constexpr int SET = decltype(setc)::value;
         if constexpr (WIDE) {
 #pragma unroll
             for (int i = 0; i < NLV; ++i) {
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
-                    if (lo[i][k] >= 0) my[lo[i][k]] = __uint_as_float(x4[i][k]);
+                for (int k = 0; k < 4; ++k) my[lo[i][k]] = __uint_as_float(x4[SET][i][k]);
                 const int f = lane + 64 * i;
                 if (4 * f < a.PB * yplane)
-                    *reinterpret_cast<float4*>(yl + 4 * f) = make_float4(__uint_as_float(y4[i].x), __uint_as_float(y4[i].y),
-                                                                         __uint_as_float(y4[i].z), __uint_as_float(y4[i].w));
+                    *reinterpret_cast<float4*>(yl + 4 * f) =
+                        make_float4(__uint_as_float(y4[SET][i].x), __uint_as_float(y4[SET][i].y), __uint_as_float(y4[SET][i].z),
+                                    __uint_as_float(y4[SET][i].w));
             }
-            if (n + a.PB < n1) fetch(n + a.PB);
-#pragma unroll
-            for (int ps = 0; ps < NPS; ++ps)
-#pragma unroll
-                for (int i = 0; i < kSeg; ++i) yc[ps][i] = i < rows[ps] ? yl[yli[ps] + i * a.Q] : 0.f;
         } else {
 #pragma unroll
             for (int i = 0; i < NPIB; ++i)
@@ -579,55 +630,85 @@ __global__ __launch_bounds__(kThreads) void dw_strip_wgrad_kernel(DwStripWArgs a
 #pragma unroll
             for (int ps = 0; ps < NPS; ++ps)
 #pragma unroll
-                for (int i = 0; i < kSeg; ++i) yc[ps][i] = yv[ps][i];
-            if (n + a.PB < n1) fetch(n + a.PB);
+                for (int i = 0; i < kSeg; ++i)
+                    if (i < rows[ps]) yl[yli[ps] + i * qw] = yv[ps][i];   // dy goes through LDS too: the registers are refilled next
         }
+        fetch(n + DEPTH * a.IB, setc);
 #pragma unroll
         for (int ps = 0; ps < NPS; ++ps) {
             if (ps >= a.passes) break;
-            const float* xq = my + win[ps];
-            float xw[(kSeg - 1) * ST + 3][3];
+            if constexpr (WHOLE) {
+                if (rows[ps] != 0) pass(ps);
+            } else {
+                pass(ps);
+            }
+        }
+    };
+    fetch(n0, std::integral_constant<int, 0>{});   // on their way while the rest of the plan is made
+    if constexpr (DEPTH == 2) fetch(n0 + a.IB, std::integral_constant<int, 1>{});
+
+    // wide path: where the four values of float4 f of the x planes land in LDS
+    if constexpr (WIDE) {
 #pragma unroll
-            for (int r = 0; r < (kSeg - 1) * ST + 3; ++r)
+        for (int i = 0; i < NLV; ++i) {
+            const int f = lane + 64 * i;
 #pragma unroll
-                for (int s = 0; s < 3; ++s) xw[r][s] = xq[r * a.PPW + s];
-            // rows this lane does not own are skipped outright (their window may be another plane's data)
+            for (int k = 0; k < 4; ++k) {
+                const int idx = 4 * f + k;
+                const int pl = fdiv(idx, a.inv_xplane), rem = idx - pl * xplane;
+                const int ih = fdiv(rem, a.inv_w), iw = rem - ih * a.W;
+                const int ph = ih + a.pad_h, pw = iw + a.pad_w;
+                const bool ok = idx < a.PB * xplane && ph >= 0 && ph < a.PPH && pw >= 0 && pw < ppw;
+                lo[i][k] = ok ? pl * PPS + ph * ppw + pw : a.lds_per_wave - 1;   // values without a place land in a spare word
+            }
+        }
+        for (int e = lane; e < a.w_off; e += 64) my[e] = 0.f;   // borders and slack, written once
+    }
+    for (int n = n0; n < n1; n += DEPTH * a.IB) {
+        step(n, std::integral_constant<int, 0>{});
+        if constexpr (DEPTH == 2) {
+            if (n + a.IB < n1) step(n + a.IB, std::integral_constant<int, 1>{});
+        }
+    }
+
+    // Lanes -> channels.  Every lane leaves its sums in the wave's own LDS region (operations of one wave
+    // on LDS run in program order).  The lanes that worked for plane pl in pass ps are those of the
+    // units [pl*NSEG, (pl+1)*NSEG) - ps*UPP, a contiguous run; lane 9*ch + t adds, in plane and lane order,
+    // the planes ch, ch + CPB, ... of its channel.
 #pragma unroll
-            for (int i = 0; i < kSeg; ++i) {
-                if (i >= rows[ps]) continue;
+    for (int ps = 0; ps < NPS; ++ps)
 #pragma unroll
-                for (int r = 0; r < 3; ++r)
+        for (int t = 0; t < 9; ++t) my[(ps * 64 + lane) * 9 + t] = acc[ps][t];
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    const int opl = lane / 9, ot = lane - opl * 9;
+    float sum = 0.f;
+    if (opl < a.CPB) {
+        for (int pl = opl; pl < a.PB; pl += a.CPB) {
 #pragma unroll
-                    for (int s = 0; s < 3; ++s) acc[r * 3 + s] = fmaf(yc[ps][i], xw[i * ST + r][s], acc[r * 3 + s]);
+            for (int ps = 0; ps < NPS; ++ps) {
+                if (ps >= a.passes) break;
+                const int ulo = min(max(pl * a.NSEG - ps * a.UPP, 0), a.UPP), uhi = min(max((pl + 1) * a.NSEG - ps * a.UPP, 0), a.UPP);
+                const float* src = my + ps * 64 * 9 + ot;
+                const int hi = uhi * qw;
+                for (int j = ulo * qw; j < hi; j += 4) {   // four independent reads per round
+                    const float v0 = src[j * 9];
+                    const float v1 = j + 1 < hi ? src[(j + 1) * 9] : 0.f;
+                    const float v2 = j + 2 < hi ? src[(j + 2) * 9] : 0.f;
+                    const float v3 = j + 3 < hi ? src[(j + 3) * 9] : 0.f;
+                    sum = (((sum + v0) + v1) + v2) + v3;
+                }
             }
         }
     }
-#pragma unroll
-    for (int t = 0; t < 9; ++t) {
-        float v = acc[t];
-#pragma unroll
-        for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
-        acc[t] = v;
-    }
-    if (a.fuse) {
-        // partial sums of the channel's waves meet in LDS and are added in split order
-        __syncthreads();   // every wave is done with its LDS region
-        if (lane == 0) {
-#pragma unroll
-            for (int t = 0; t < 9; ++t) lds[wave * 9 + t] = acc[t];
-        }
-        __syncthreads();
-        if (valid && sp == 0 && lane < 9) {
-            float sum = lds[wave * 9 + lane];
-            for (int s2 = 1; s2 < a.nsplit; ++s2) sum += lds[(wave + s2) * 9 + lane];
-            a.out[(size_t)c * 9 + lane] = sum;
-        }
-        return;
-    }
-    if (lane == 0) {
-        float* out = a.out + (size_t)sp * a.C * 9 + (size_t)c * 9;
-#pragma unroll
-        for (int t = 0; t < 9; ++t) out[t] = acc[t];
+    wres[wave * 64 + lane] = sum;
+    // Image ranges -> total, in range order.
+    __syncthreads();
+    if (wave == 0 && opl < a.CPB && c0 + opl < a.C) {
+        float total = wres[lane];
+        for (int w2 = 1; w2 < a.waves; ++w2) total += wres[w2 * 64 + lane];
+        a.out[(size_t)ws * a.C * 9 + (size_t)(c0 + opl) * 9 + ot] = total;
     }
 }
 
@@ -733,7 +814,7 @@ bool strip_plan(const Problem& pr, int oh, int ow, int pph, int ppw, int stride,
     sp.passes = (pb * sp.NSEG + sp.UPP - 1) / sp.UPP;
     sp.w_off = (pb * pps + (kSeg * stride + 3) * ppw + 3) & ~3;
     sp.o_off = (sp.w_off + 9 * pb + 3) & ~3;
-    sp.lds_per_wave = (sp.o_off + pb * oh * ow + 3) & ~3;
+    sp.lds_per_wave = ((sp.o_off + pb * oh * ow + 3) & ~3) + 4;   // the last word takes values that have no place
     return true;
 }
 
@@ -774,9 +855,29 @@ hipError_t launch_strip_stencil(const DwStripArgs& a, hipStream_t st) {
     const int wg_batches = (a.nbatches + 3) / 4;
     const int rounds = (wg_batches + resident - 1) / resident;
     const int grid = (wg_batches + rounds - 1) / rounds;
-    if (wide) dw_strip_stencil_kernel<T, ST, 16, 2, true><<<grid, kThreads, smem, st>>>(a);
+    if (wide && ST == 1 && a.PPW == 16 && a.OW == 14 && a.OH % kSeg == 0) dw_strip_stencil_kernel<T, 1, 16, 2, true, 16, 14><<<grid, kThreads, smem, st>>>(a);
+    else if (wide) dw_strip_stencil_kernel<T, ST, 16, 2, true><<<grid, kThreads, smem, st>>>(a);
     else dw_strip_stencil_kernel<T, ST, 16, 2, false><<<grid, kThreads, smem, st>>>(a);
     return hipGetLastError();
+}
+
+// One wave per (channel group, image range), about two waves per SIMD in total (256 CUs x 4 SIMDs x 2),
+// each running a prefetched image loop.  Up to wmax ranges are the waves of one workgroup; beyond that
+// several workgroups share a channel group and a second kernel adds their partial sums.
+void split_images(DwStripWArgs& a, int wmax) {
+    while (wmax > 1 && (size_t)wmax * (a.lds_per_wave + 64) * sizeof(float) > 160 * 1024) wmax /= 2;   // LDS of one CU
+    const int nbat = (a.N + a.IB - 1) / a.IB;
+    int parts = (2048 + a.cgroups - 1) / a.cgroups;
+    if (parts > nbat) parts = nbat;
+    if (parts < 1) parts = 1;
+    if (parts <= wmax) {
+        a.waves = parts;
+        a.wsplit = 1;
+    } else {
+        a.waves = wmax;
+        a.wsplit = (parts + wmax - 1) / wmax;
+        if (a.wsplit * wmax > nbat) a.wsplit = nbat / wmax;
+    }
 }
 
 bool strip_wgrad_args(const Problem& pr, const void* x, const void* dy, DwStripWArgs& a) {
@@ -791,29 +892,40 @@ bool strip_wgrad_args(const Problem& pr, const void* x, const void* dy, DwStripW
     a.w_off = sp.w_off; a.o_off = sp.o_off;
     a.inv_ppw = 1.0f / a.PPW; a.inv_pps = 1.0f / (a.PPH * a.PPW); a.inv_q = 1.0f / pr.Q; a.inv_nseg = 1.0f / sp.NSEG;
     a.inv_xplane = 1.0f / (pr.H * pr.W); a.inv_w = 1.0f / pr.W; a.inv_yplane = 1.0f / (pr.P * pr.Q);
-    // One wave per (channel, split): two waves per SIMD (256 CUs x 4 SIMDs x 2) measured best, each
-    // running a long, prefetched image loop (four per SIMD, all resident: 29 instead of 26.5 us on the
-    // 14x14x1024 layer - more concurrent 784-byte streams, not more bytes in flight).
-    int nsplit = (2048 + pr.C - 1) / pr.C;
-    if (nsplit > pr.N) nsplit = pr.N;
-    if (nsplit < 1) nsplit = 1;
-    if (nsplit == 3) nsplit = 4 <= pr.N ? 4 : 2;   // 2 and 4 divide the four waves of a workgroup
-    a.nsplit = nsplit;
-    a.fuse = nsplit > 1 && (kThreads / 64) % nsplit == 0;
+    if (a.lds_per_wave < 2 * 64 * 9) a.lds_per_wave = 2 * 64 * 9;   // the lane sums of both passes
+    // As many consecutive channels per wave as still leave a workgroup for every CU; the rest of the batch
+    // are further images of the same channels.
+    a.CPB = 1;
+    for (int d = 2; d <= sp.PB; ++d)
+        if (sp.PB % d == 0 && (pr.C + d - 1) / d >= 256) a.CPB = d;
+    a.IB = sp.PB / a.CPB;
+    a.cgroups = (pr.C + a.CPB - 1) / a.CPB;
+    split_images(a, kStripWgradWaves);
     a.x_bytes = (unsigned)((size_t)pr.N * pr.C * pr.H * pr.W * esz);
     a.y_bytes = (unsigned)((size_t)pr.N * pr.C * pr.P * pr.Q * esz);
     return true;
 }
 
+// Launches the kernel; *wsplit tells the caller how many partial sums per element it left in a.out.
 template <typename T, int ST>
-hipError_t launch_strip_wgrad(const DwStripWArgs& a, hipStream_t st) {
-    const int per_wg = a.fuse ? 4 / a.nsplit : 4;   // channels (fused) or (channel, split) pairs per workgroup
-    const int grid = a.fuse ? (a.C + per_wg - 1) / per_wg : (a.C * a.nsplit + 3) / 4;
-    const size_t smem = (size_t)4 * a.lds_per_wave * sizeof(float);
+hipError_t launch_strip_wgrad(DwStripWArgs a, float* dw, int* wsplit, hipStream_t st) {
     const bool wide = sizeof(T) == 4 && (a.H * a.W) % 4 == 0 && (a.P * a.Q) % 4 == 0 &&
                       reinterpret_cast<uintptr_t>(a.x) % 16 == 0 && reinterpret_cast<uintptr_t>(a.dy) % 16 == 0;
-    if (wide) dw_strip_wgrad_kernel<T, ST, 16, 2, true><<<grid, kThreads, smem, st>>>(a);
-    else dw_strip_wgrad_kernel<T, ST, 16, 2, false><<<grid, kThreads, smem, st>>>(a);
+    const bool fixed = wide && ST == 1 && a.PPW == 16 && a.Q == 14 && a.P % kSeg == 0;   // 14x14 planes, padding 1
+    split_images(a, kStripWgradWaves);
+    if (a.wsplit == 1) a.out = dw;
+    *wsplit = a.wsplit;
+    const int grid = 8 * ((a.cgroups + 7) / 8) * a.wsplit;
+    const size_t smem = ((size_t)a.waves * a.lds_per_wave + (size_t)a.waves * 64) * sizeof(float);
+    auto kernel = wide ? dw_strip_wgrad_kernel<T, ST, 16, 2, true> : dw_strip_wgrad_kernel<T, ST, 16, 2, false>;
+    if constexpr (ST == 1) {
+        if (fixed) kernel = dw_strip_wgrad_kernel<T, 1, 16, 2, true, 16, 14>;
+    }
+    if (smem > 64 * 1024) {   // dynamic LDS beyond 64 KB has to be granted first
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    kernel<<<grid, 64 * a.waves, smem, st>>>(a);
     return hipGetLastError();
 }
 
@@ -833,7 +945,7 @@ bool depthwise_supports(int pass, const Problem& pr) {
 size_t depthwise_workspace_bytes(int pass, const Problem& pr) {
     if (pass != 2) return 0;
     DwStripWArgs b{};
-    if (strip_wgrad_args(pr, nullptr, nullptr, b)) return b.nsplit > 1 && !b.fuse ? (size_t)b.nsplit * pr.C * 9 * sizeof(float) : 0;
+    if (strip_wgrad_args(pr, nullptr, nullptr, b)) return b.wsplit > 1 ? (size_t)b.wsplit * pr.C * 9 * sizeof(float) : 0;
     DwWArgs a{};
     if (!wgrad_args(pr, nullptr, nullptr, a)) return 0;
     return a.nsplit > 1 ? (size_t)a.nsplit * pr.C * 9 * sizeof(float) : 0;
@@ -845,12 +957,13 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
     if (pass == 2) {
         DwStripWArgs b{};
         if (strip_wgrad_args(pr, in0, in1, b)) {
-            b.out = b.nsplit > 1 && !b.fuse ? static_cast<float*>(ws) : out;
+            b.out = static_cast<float*>(ws);
+            int wsplit = 1;
             hipError_t e;
-            if (pr.dtype == 0) e = pr.sh == 1 ? launch_strip_wgrad<float, 1>(b, st) : launch_strip_wgrad<float, 2>(b, st);
-            else e = pr.sh == 1 ? launch_strip_wgrad<uint16_t, 1>(b, st) : launch_strip_wgrad<uint16_t, 2>(b, st);
-            if (e != hipSuccess || b.nsplit == 1 || b.fuse) return e;
-            dw_reduce_splits_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, b.nsplit, count);
+            if (pr.dtype == 0) e = pr.sh == 1 ? launch_strip_wgrad<float, 1>(b, out, &wsplit, st) : launch_strip_wgrad<float, 2>(b, out, &wsplit, st);
+            else e = pr.sh == 1 ? launch_strip_wgrad<uint16_t, 1>(b, out, &wsplit, st) : launch_strip_wgrad<uint16_t, 2>(b, out, &wsplit, st);
+            if (e != hipSuccess || wsplit == 1) return e;
+            dw_reduce_splits_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, wsplit, count);
             return hipGetLastError();
         }
         DwWArgs a{};

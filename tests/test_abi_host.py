@@ -88,7 +88,7 @@ def test_workspace_sizes_of_the_benchmark_layers(mc):
     L = wl.LAYERS
     # layer 2a backward-weight: 256 workgroups without a split, nothing to reduce
     assert mc.conv2d_workspace_bytes(2, *L["2a"].conv_args(), mc.F32) == 0
-    # depthwise: the splits of a channel are summed inside a workgroup
+    # depthwise: the image ranges of a channel pair are the eight waves of one workgroup and are summed there
     assert mc.conv2d_workspace_bytes(2, *L["5a"].conv_args(), mc.F32) == 0
     for p in (0, 1):
         assert mc.conv2d_workspace_bytes(p, *L["4b"].conv_args(), mc.F32) == 0
