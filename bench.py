@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run --steps plain device-to-device copies of MIB mebibytes "
                          "(a kernel of known HBM traffic, used to scale the rocprofv3 FETCH_SIZE/WRITE_SIZE counters)")
+    ap.add_argument("--settle-ms", type=float, default=60.0,
+                    help="untimed steps are run for this long before the warm-up steps so that the GPU clock has ramped up")
     ap.add_argument("--rotate", type=int, default=0,
                     help="number of distinct buffer sets cycled between steps (0: auto; "
                          "bandwidth-bound layers use enough to exceed the 256 MB Infinity Cache)")
@@ -149,6 +151,16 @@ def main():
         for p in range(3):
             run_pass(p, s)
 
+    # The GPU takes about 25 ms of sustained load to reach its full clock (layer 2a kernels go from 137 to
+    # 117 us over their first 200 launches): steps run untimed until that much time has passed, then the
+    # W warm-up steps, then the K timed ones.
+    t_settle = time.perf_counter()
+    i = 0
+    while (time.perf_counter() - t_settle) * 1e3 < a.settle_ms:
+        for _ in range(8):
+            step(i)
+            i += 1
+        torch.cuda.synchronize()
     for i in range(a.warmup):
         step(i)
     torch.cuda.synchronize()
