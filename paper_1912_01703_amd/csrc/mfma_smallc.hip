@@ -15,6 +15,8 @@
 //                    filters are summed afterwards in a fixed order.
 #include "common.h"
 
+#include <type_traits>
+
 namespace miconv {
 namespace {
 
@@ -44,9 +46,23 @@ struct SmallArgs {
 };
 
 // ---------------------------------------------------------------------------------------- forward
+// Persistent workgroups of eight waves.  A work item is one image x one tile of TH x TW output pixels
+// (all filters of the workgroup's 64-filter block); wave (wf, wp) owns 16 filters and half of the
+// tile's 16-pixel blocks.  The lane's weights (all C*R filter rows) are loaded once and stay in
+// registers.  The patch of item i+1 is requested before item i is multiplied and stored to the other
+// LDS buffer afterwards: one barrier per item.  Patch rows are dealt out to the waves, so a row's
+// validity and address are scalar (a zero-size descriptor for rows outside the image, the row's
+// offset in the scalar offset operand) and no vector ALU work is spent on them.
+__device__ __forceinline__ float buf_load_s(rsrc_t r, unsigned byte_off, unsigned soff, const float*) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, soff, 0));
+}
+__device__ __forceinline__ float buf_load_s(rsrc_t r, unsigned byte_off, unsigned soff, const uint16_t*) {
+    return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_raw_buffer_load_b16(r, byte_off, soff, 0)) << 16);
+}
+
 template <typename T, int C, int R, int S, int ST, int TH, int TW>
-__global__ __launch_bounds__(256) void smallc_fwd_kernel(SmallArgs a) {
-    constexpr int NT = 256;
+__global__ __launch_bounds__(512) void smallc_fwd_kernel(SmallArgs a) {
+    constexpr int NW = 8;
     constexpr int SU = (S + 3) / 4;                 // steps per filter row
     constexpr int NSTEP = C * R * SU;
     constexpr int PH = (TH - 1) * ST + R;
@@ -54,39 +70,27 @@ __global__ __launch_bounds__(256) void smallc_fwd_kernel(SmallArgs a) {
     constexpr int PW = (TW - 1) * ST + 4 * SU;      // ... plus the columns the zero-weight taps read
     constexpr int CS = PH * PW;
     constexpr int XE = C * CS;
-    constexpr int XPT = (XE + NT - 1) / NT;
+    constexpr int BUFSZ = XE + 64;                  // + words for lanes that have nothing to store
+    constexpr int ROWS = C * PH;                    // patch rows, dealt out to the waves
+    constexpr int RPW = (ROWS + NW - 1) / NW;
+    constexpr int CPL = (PW + 63) / 64;             // column chunks per lane
     constexpr int NPX = TH * TW;
     constexpr int NB = (NPX + 15) / 16;
+    constexpr int NB0 = (NB + 1) / 2;               // blocks of the waves with wp = 0; the others take NB - NB0
+    constexpr unsigned ESZ = sizeof(T);
 
-    __shared__ float patch[XE];
+    __shared__ float patch[2 * BUFSZ];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wf = wave & 3, wp = wave >> 2;
     const int li = lane & 15, kk = lane >> 4;
-    int u = blockIdx.x;
-    const int kb = u % a.kblocks; u /= a.kblocks;
-    const int tj = u % a.tiles_w; u /= a.tiles_w;
-    const int ti = u % a.tiles_h;
-    const int n = u / a.tiles_h;
-    const int p0 = ti * TH, q0 = tj * TW;
-    const int h0 = p0 * ST - a.pad_h, v0 = q0 * ST - a.pad_w;
+    const int kb = blockIdx.x % a.kblocks, slot = blockIdx.x / a.kblocks, nslots = gridDim.x / a.kblocks;
+    const int items = a.N * a.tiles_h * a.tiles_w;
     const T* const tnull = nullptr;
 
-    // ---- the tile's input patch, all channels: global -> registers -> LDS ---------------------------
-    const rsrc_t xrs = make_rsrc(static_cast<const T*>(a.x) + (size_t)n * C * a.H * a.W,
-                                 (unsigned)(C * a.H * a.W) * (unsigned)sizeof(T));
-    float xv[XPT];
-#pragma unroll
-    for (int m = 0; m < XPT; ++m) {
-        const int e = tid + NT * m;
-        const int c = e / CS, rem = e - c * CS;
-        const int ph = rem / PW, pw = rem - ph * PW;
-        const int h = h0 + ph, v = v0 + pw;
-        const bool ok = e < XE && pw < PWR && h >= 0 && h < a.H && v >= 0 && v < a.W;
-        xv[m] = buf_load(xrs, ok ? (unsigned)((c * a.H + h) * a.W + v) * (unsigned)sizeof(T) : kOob, tnull);
-    }
-
     // ---- this lane's filter values: w[f][c][r][4u+kk], zero past the end of a filter row -----------
-    const int f = kb * 64 + wave * 16 + li;
+    const int f = kb * 64 + wf * 16 + li;
     const rsrc_t wrs = make_rsrc(a.w, a.w_bytes);
     float wa[NSTEP];
 #pragma unroll
@@ -94,56 +98,119 @@ __global__ __launch_bounds__(256) void smallc_fwd_kernel(SmallArgs a) {
         const int cr = st / SU, uu = st - cr * SU;
         const int s = 4 * uu + kk;
         const bool ok = f < a.K && s < S;
-        wa[st] = buf_load(wrs, ok ? (unsigned)((f * C * R + cr) * S + s) * (unsigned)sizeof(T) : kOob, tnull);
+        wa[st] = buf_load(wrs, ok ? (unsigned)((f * C * R + cr) * S + s) * ESZ : kOob, tnull);
     }
-#pragma unroll
-    for (int m = 0; m < XPT; ++m)
-        if (tid + NT * m < XE) patch[tid + NT * m] = xv[m];
-    __syncthreads();
 
-    int pixoff[NB];
+    const rsrc_t xrs = make_rsrc(a.x, a.x_bytes), nors = make_rsrc(a.x, 0);
+    // where this lane's column chunks go inside a patch row (words); lanes past the row end use a spare word
+    int sto[CPL];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        int j = 16 * i + li;
+    for (int j = 0; j < CPL; ++j) sto[j] = lane + 64 * j < PW ? wave * PW + lane + 64 * j : XE + lane;
+
+    float xv[RPW][CPL];
+    struct Where { int n, p0, q0; };
+    auto decode = [&](int item) __attribute__((always_inline)) -> Where {
+        const int tj = item % a.tiles_w, r2 = item / a.tiles_w;
+        const int ti = r2 % a.tiles_h;
+        return Where{__builtin_amdgcn_readfirstlane(r2 / a.tiles_h), __builtin_amdgcn_readfirstlane(ti * TH),
+                     __builtin_amdgcn_readfirstlane(tj * TW)};
+    };
+    auto issue = [&](int item) __attribute__((always_inline)) {
+        const Where wh = decode(item);
+        const int h0 = wh.p0 * ST - a.pad_h, v0 = wh.q0 * ST - a.pad_w;
+        unsigned colv[CPL];
+#pragma unroll
+        for (int j = 0; j < CPL; ++j) {
+            const int pw = lane + 64 * j, v = v0 + pw;
+            colv[j] = pw < PWR && v >= 0 && v < a.W ? (unsigned)v * ESZ : kOob;
+        }
+#pragma unroll
+        for (int k = 0; k < RPW; ++k) {
+            const int rr = wave + NW * k;
+            const int c = rr / PH, ph = rr - c * PH;
+            const int h = h0 + ph;
+            const bool ok = rr < ROWS && h >= 0 && h < a.H;
+            const rsrc_t rs = ok ? xrs : nors;
+            const unsigned soff = ok ? (unsigned)(((wh.n * C + c) * a.H + h) * a.W) * ESZ : 0u;
+#pragma unroll
+            for (int j = 0; j < CPL; ++j) xv[k][j] = buf_load_s(rs, colv[j], soff, tnull);
+        }
+    };
+    auto store = [&](int buf) __attribute__((always_inline)) {
+        float* dst = patch + buf * BUFSZ;
+#pragma unroll
+        for (int k = 0; k < RPW; ++k) {
+            if (wave + NW * k >= ROWS) break;   // scalar
+#pragma unroll
+            for (int j = 0; j < CPL; ++j) dst[sto[j] + (sto[j] < XE ? k * NW * PW : 0)] = xv[k][j];
+        }
+    };
+
+    // pixel blocks of this wave: i0 .. i0 + NBW - 1
+    const int i0 = wp * NB0;
+    int pixoff[NB0];
+#pragma unroll
+    for (int ii = 0; ii < NB0; ++ii) {
+        int j = 16 * (i0 + ii) + li;
         if (j >= NPX) j = 0;
         const int th = j / TW, tw = j - th * TW;
-        pixoff[i] = th * ST * PW + tw * ST + kk;
+        pixoff[ii] = th * ST * PW + tw * ST + kk;
     }
-    v4f acc[NB];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
 
-    // Operand i of the next step is read from LDS right before MFMA i of this step.
-    float bq[2][NB];
+    // One item on NBW blocks: operand ii of the next step is read from LDS right before MFMA ii of this step.
+    auto compute = [&](const float* pb, const Where& wh, auto nbwc) __attribute__((always_inline)) {
+        constexpr int NBW = decltype(nbwc)::value;
+        v4f acc[NBW];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) bq[0][i] = patch[pixoff[i]];
-    __builtin_amdgcn_sched_barrier(0);
+        for (int ii = 0; ii < NBW; ++ii) acc[ii] = v4f{0.f, 0.f, 0.f, 0.f};
+        float bq[2][NBW];
 #pragma unroll
-    for (int st = 0; st < NSTEP; ++st) {
-        const int sn = st + 1;
-        const int crn = sn / SU, un = sn - crn * SU;
-        const int off = (crn / R) * CS + (crn % R) * PW + 4 * un;
+        for (int ii = 0; ii < NBW; ++ii) bq[0][ii] = pb[pixoff[ii]];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            if (sn < NSTEP) bq[sn & 1][i] = patch[pixoff[i] + off];
-            acc[i] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[st], bq[st & 1][i], acc[i], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int st = 0; st < NSTEP; ++st) {
+            const int sn = st + 1;
+            const int crn = sn / SU, un = sn - crn * SU;
+            const int off = (crn / R) * CS + (crn % R) * PW + 4 * un;
+#pragma unroll
+            for (int ii = 0; ii < NBW; ++ii) {
+                if (sn < NSTEP) bq[sn & 1][ii] = pb[pixoff[ii] + off];
+                acc[ii] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[st], bq[st & 1][ii], acc[ii], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-    }
+        // ---- D[f = 4*kk+v][pixel = li] -----------------------------------------------------------------
+        const int fq = kb * 64 + wf * 16 + 4 * kk;
+        float* y = a.out + (size_t)wh.n * a.K * a.P * a.Q;
+#pragma unroll
+        for (int ii = 0; ii < NBW; ++ii) {
+            const int j = 16 * (i0 + ii) + li;
+            if (j >= NPX) continue;
+            const int th = j / TW, tw = j - th * TW;
+            const int p = wh.p0 + th, q = wh.q0 + tw;
+            if (p >= a.P || q >= a.Q) continue;
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (fq + v < a.K) y[((size_t)(fq + v) * a.P + p) * a.Q + q] = acc[ii][v];
+        }
+    };
 
-    // ---- D[f = 4*kk+v][pixel = li] ---------------------------------------------------------------------
-    const int fq = kb * 64 + wave * 16 + 4 * kk;
-    float* y = a.out + (size_t)n * a.K * a.P * a.Q;
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        const int j = 16 * i + li;
-        if (j >= NPX) continue;
-        const int th = j / TW, tw = j - th * TW;
-        const int p = p0 + th, q = q0 + tw;
-        if (p >= a.P || q >= a.Q) continue;
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-            if (fq + v < a.K) y[((size_t)(fq + v) * a.P + p) * a.Q + q] = acc[i][v];
+    int item = slot, buf = 0;
+    if (item < items) {
+        issue(item);
+        store(0);
+    }
+    __syncthreads();
+    for (; item < items; item += nslots) {
+        const int next = item + nslots;
+        if (next < items) issue(next);   // travels while this item is multiplied
+        const Where wh = decode(item);
+        const float* pb = patch + buf * BUFSZ;
+        if (wp == 0) compute(pb, wh, std::integral_constant<int, NB0>{});
+        else compute(pb, wh, std::integral_constant<int, NB - NB0>{});
+        if (next < items) store(buf ^ 1);
+        __syncthreads();   // the next patch is complete, and every wave is done with this one
+        buf ^= 1;
     }
 }
 
@@ -462,9 +529,14 @@ hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* 
         a.w = in1; a.out = out;
         a.w_bytes = (unsigned)((size_t)pr.K * pr.C * pr.R * pr.S * esz);
         a.tiles_h = (pr.P + kFwdTH - 1) / kFwdTH; a.tiles_w = (pr.Q + kFwdTW - 1) / kFwdTW;
-        const int grid = pr.N * a.tiles_h * a.tiles_w * a.kblocks;
-        if (pr.dtype == 0) smallc_fwd_kernel<float, 3, 11, 11, 4, kFwdTH, kFwdTW><<<grid, 256, 0, st>>>(a);
-        else smallc_fwd_kernel<uint16_t, 3, 11, 11, 4, kFwdTH, kFwdTW><<<grid, 256, 0, st>>>(a);
+        // persistent workgroups, one per CU (two patch buffers take half of its LDS), shared out over the filter blocks
+        const int items = pr.N * a.tiles_h * a.tiles_w;
+        int slots = 256 / a.kblocks;
+        if (slots < 1) slots = 1;
+        if (slots > items) slots = items;
+        const int grid = slots * a.kblocks;
+        if (pr.dtype == 0) smallc_fwd_kernel<float, 3, 11, 11, 4, kFwdTH, kFwdTW><<<grid, 512, 0, st>>>(a);
+        else smallc_fwd_kernel<uint16_t, 3, 11, 11, 4, kFwdTH, kFwdTW><<<grid, 512, 0, st>>>(a);
         return hipGetLastError();
     }
     a.w = in1;   // dy

@@ -164,6 +164,14 @@ def test_small_channel_large_filter(row, dtype):
     pu.check_layer_full(L, dtype, algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
 
 
+def test_small_channel_forward_walks_several_items():
+    """Two filter blocks share the 256 persistent workgroups, and 140 work items per block exceed the 128
+    workgroups of each: some workgroups run a second item out of the other LDS buffer."""
+    from paper_1912_01703_amd import binding as mc
+    L = wl.custom_layer("a11d", 5, 3, 227, 227, 128, 11, 11, 4, 2, 1, seed=5010)
+    pu.check_layer_full(L, "f32", passes=("fwd",), algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+
+
 DW = [
     # name    N   C   H   W  stride pad
     ("dw14", 3, 40, 14, 14, 1, 1),
