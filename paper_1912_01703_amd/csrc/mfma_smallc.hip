@@ -9,8 +9,8 @@
 //
 //   forward          M = 16 filters (A: weights, held in registers for the whole kernel),
 //                    N = 16 output pixels (B: patch), K = 4 taps.
-//   backward-weight  M = 16 filters (A: dy), N = 16 taps of one (c, r) filter row (B: patch, 11 of
-//                    the 16 columns are real taps), K = 4 output pixels of one output row.
+//   backward-weight  M = 16 filters (A: dy), N = 16 consecutive taps of the flattened (c, r, s) order
+//                    (B: patch at a per-lane tap offset), K = 4 output pixels of one output row.
 //                    Stages (image x pixel tile) are shared out over the workgroups; the partial
 //                    filters are summed afterwards in a fixed order.
 #include "common.h"
@@ -215,105 +215,137 @@ __global__ __launch_bounds__(512) void smallc_fwd_kernel(SmallArgs a) {
 }
 
 // -------------------------------------------------------------------------------- backward-weight
-// Workgroup = 64 filters (one 16-filter block per wave) x all C*R filter rows, for a contiguous run
-// of stages; stage = one image x TH output rows x TQ4*4 output columns.
+// Workgroup = 64 filters x all C*R*S taps, for a contiguous run of stages; stage = one image x TH
+// output rows x TQ4*4 output columns.  The taps of a filter are numbered t = (c*R + r)*S + s and cut
+// into blocks of 16 for the MFMA N dimension (363 taps: 23 blocks, against 33 with one block per
+// 11-tap filter row).  Lane (li, kk) of block b reads x at "tap offset of 16 b + li" + 4 kk, a value
+// it keeps in a register per block; the step (output row, column quad) adds an immediate.  Eight
+// waves: wave (wf, wt) owns 16 filters and half of the tap blocks.  Rows of x and dy are dealt out to
+// the waves, so their validity and addresses are scalar; the next stage is requested before this one
+// is multiplied and stored to the other LDS buffer afterwards.
 template <typename T, int C, int R, int S, int ST, int TH, int TQ4>
-__global__ __launch_bounds__(256) void smallc_wgrad_kernel(SmallArgs a) {
-    constexpr int NT = 256;
-    static_assert(S <= 16, "one MFMA column block per filter row");
+__global__ __launch_bounds__(512) void smallc_wgrad_kernel(SmallArgs a) {
+    constexpr int NW = 8;
     constexpr int TW = 4 * TQ4;                     // output columns of a tile
     constexpr int PH = (TH - 1) * ST + R;
     constexpr int PWR = (TW - 1) * ST + S;          // columns that hold data
-    constexpr int PW = (TW - 1) * ST + 16;          // the 16-tap column block reads up to here
+    constexpr int PW = (PWR + 3) & ~3;
     constexpr int CS = PH * PW;
     constexpr int XE = C * CS;
     constexpr int YS = TH * TW + 2;                 // dy row stride in LDS: 2 mod 4 keeps the A reads conflict-free
-    constexpr int YE = 64 * TH * TW;
-    constexpr int XPT = (XE + NT - 1) / NT, YPT = (YE + NT - 1) / NT;
-    constexpr int STAGE = XE + 64 * YS;
-    constexpr int NROW = C * R;                     // accumulator blocks per wave
-    constexpr int OUTSZ = 64 * NROW * 16;
+    constexpr int STAGE = XE + 64 * YS + 64;        // + words for lanes that have nothing to store
+    constexpr int TRASH = XE + 64 * YS;
+    constexpr int NTAP = C * R * S;
+    constexpr int NBLK = (NTAP + 15) / 16;          // tap blocks
+    constexpr int NB0 = (NBLK + 1) / 2;             // blocks of the waves with wt = 0; the others take NBLK - NB0
+    constexpr int OUTSZ = 64 * NBLK * 16;
     constexpr int LDSF = 2 * STAGE > OUTSZ ? 2 * STAGE : OUTSZ;
+    constexpr int XROWS = C * PH, XRPW = (XROWS + NW - 1) / NW, XCPL = (PW + 63) / 64;
+    constexpr int YROWS = 64 * TH, YRPW = YROWS / NW;
+    constexpr unsigned ESZ = sizeof(T);
     static_assert(LDSF * 4 <= 160 * 1024, "LDS budget");
-    static_assert((TH * TW) % 4 == 0, "whole MFMA steps");
+    static_assert((TH * TW) % 4 == 0 && TW <= 64 && YROWS % NW == 0 && YRPW % TH == 0, "tile shape");
 
     __shared__ float lds[LDSF];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wf = wave & 3, wt = wave >> 2;
     const int li = lane & 15, kk = lane >> 4;
     const int kb = blockIdx.x % a.kblocks, sp = blockIdx.x / a.kblocks;
     const int s_begin = (int)((long long)a.stages * sp / a.nsplit);
     const int s_end = (int)((long long)a.stages * (sp + 1) / a.nsplit);
     const int tiles = a.tiles_h * a.tiles_w;
     const T* const tnull = nullptr;
-    const rsrc_t xrs = make_rsrc(a.x, a.x_bytes);
+    const rsrc_t xrs = make_rsrc(a.x, a.x_bytes), nors = make_rsrc(a.x, 0);
     const rsrc_t yrs = make_rsrc(a.w, a.w_bytes);   // dy
 
-    float xv[XPT], yv[YPT];
-    auto fetch = [&](int stage) {
-        const int n = stage / tiles, t = stage - n * tiles;
-        const int ti = t / a.tiles_w, tj = t - ti * a.tiles_w;
+    // where this lane's pieces go inside an x row / a dy row (words)
+    int xsto[XCPL];
+#pragma unroll
+    for (int j = 0; j < XCPL; ++j) xsto[j] = lane + 64 * j < PW ? wave * PW + lane + 64 * j : TRASH + lane;
+    // dy row d = wave*YRPW + m: filter d / TH, tile row d % TH
+    const int ysto = lane < TW ? XE + wave * (YRPW / TH) * YS + lane : TRASH + lane;
+
+    float xv[XRPW][XCPL], yv[YRPW];
+    auto fetch = [&](int stage) __attribute__((always_inline)) {
+        const int n = __builtin_amdgcn_readfirstlane(stage / tiles), t = stage - n * tiles;
+        const int ti = __builtin_amdgcn_readfirstlane(t / a.tiles_w), tj = t - ti * a.tiles_w;
         const int p0 = ti * TH, q0 = tj * TW;
         const int h0 = p0 * ST - a.pad_h, v0 = q0 * ST - a.pad_w;
         const bool live = stage < s_end;
+        unsigned colv[XCPL];
 #pragma unroll
-        for (int m = 0; m < XPT; ++m) {
-            const int e = tid + NT * m;
-            const int c = e / CS, rem = e - c * CS;
-            const int ph = rem / PW, pw = rem - ph * PW;
-            const int h = h0 + ph, v = v0 + pw;
-            const bool ok = live && e < XE && pw < PWR && h >= 0 && h < a.H && v >= 0 && v < a.W;
-            xv[m] = buf_load(xrs, ok ? (unsigned)(((n * C + c) * a.H + h) * a.W + v) * (unsigned)sizeof(T) : kOob, tnull);
+        for (int j = 0; j < XCPL; ++j) {
+            const int pw = lane + 64 * j, v = v0 + pw;
+            colv[j] = pw < PWR && v >= 0 && v < a.W ? (unsigned)v * ESZ : kOob;
         }
 #pragma unroll
-        for (int m = 0; m < YPT; ++m) {
-            const int e = tid + NT * m;
-            const int kl = e / (TH * TW), px = e - kl * (TH * TW);
-            const int th = px / TW, tw = px - th * TW;
-            const int k = kb * 64 + kl, p = p0 + th, q = q0 + tw;
-            const bool ok = live && e < YE && k < a.K && p < a.P && q < a.Q;
-            yv[m] = buf_load(yrs, ok ? (unsigned)(((n * a.K + k) * a.P + p) * a.Q + q) * (unsigned)sizeof(T) : kOob, tnull);
+        for (int k = 0; k < XRPW; ++k) {
+            const int rr = wave + NW * k;
+            const int c = rr / PH, ph = rr - c * PH;
+            const int h = h0 + ph;
+            const bool ok = live && rr < XROWS && h >= 0 && h < a.H;
+            const rsrc_t rs = ok ? xrs : nors;
+            const unsigned soff = ok ? (unsigned)(((n * C + c) * a.H + h) * a.W) * ESZ : 0u;
+#pragma unroll
+            for (int j = 0; j < XCPL; ++j) xv[k][j] = buf_load_s(rs, colv[j], soff, tnull);
+        }
+        const unsigned ycol = lane < TW && q0 + lane < a.Q ? (unsigned)(q0 + lane) * ESZ : kOob;
+#pragma unroll
+        for (int m = 0; m < YRPW; ++m) {
+            const int d = wave * YRPW + m;
+            const int k = kb * 64 + d / TH, p = p0 + d % TH;
+            const bool ok = live && k < a.K && p < a.P;
+            const rsrc_t rs = ok ? yrs : nors;
+            const unsigned soff = ok ? (unsigned)(((n * a.K + k) * a.P + p) * a.Q) * ESZ : 0u;
+            yv[m] = buf_load_s(rs, ycol, soff, tnull);
         }
     };
-    auto stash = [&](int buf) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-        float* xs = lds + buf * STAGE;
-        float* ys = xs + XE;
+    auto stash = [&](int buf) __attribute__((always_inline)) {
+        float* dst = lds + buf * STAGE;
 #pragma unroll
-        for (int m = 0; m < XPT; ++m)
-            if (tid + NT * m < XE) xs[tid + NT * m] = xv[m];
+        for (int k = 0; k < XRPW; ++k) {
+            if (wave + NW * k >= XROWS) break;   // scalar
 #pragma unroll
-        for (int m = 0; m < YPT; ++m) {
-            const int e = tid + NT * m;
-            const int kl = e / (TH * TW), px = e - kl * (TH * TW);
-            if (e < YE) ys[kl * YS + px] = yv[m];
+            for (int j = 0; j < XCPL; ++j) dst[xsto[j] + (xsto[j] < XE ? k * NW * PW : 0)] = xv[k][j];
         }
+#pragma unroll
+        for (int m = 0; m < YRPW; ++m) dst[ysto + (ysto < TRASH ? (m / TH) * YS + (m % TH) * TW : 0)] = yv[m];
     };
 
-    v4f acc[NROW];
+    // tap blocks of this wave: b0 .. ; tap t of a lane: offset of x[c][r][s] inside the patch, plus the lane's pixel
+    const int b0 = wt * NB0;
+    int tapoff[NB0];
 #pragma unroll
-    for (int i = 0; i < NROW; ++i) acc[i] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int m = 0; m < NB0; ++m) {
+        const int t = 16 * (b0 + m) + li;
+        const int c = t / (R * S), rem = t - c * (R * S);
+        const int r = rem / S, ss = rem - r * S;
+        tapoff[m] = kk * ST + (t < NTAP ? c * CS + r * PW + ss : 0);   // taps past the last: any valid word, their sums are dropped
+    }
+    v4f acc[NB0];
+#pragma unroll
+    for (int m = 0; m < NB0; ++m) acc[m] = v4f{0.f, 0.f, 0.f, 0.f};
 
     // step = (output row th, column quad uq): pixel = th*TW + 4*uq + kk
     constexpr int NSTEPS = TH * TQ4;
-    const int yoff = (wave * 16 + li) * YS + kk;    // A: dy[k = li][pixel]
-    const int xoff = kk * ST + li;                  // B: patch[.. + q*ST + s], q = 4*uq + kk, s = li
-    auto multiply = [&](const float* xs) {
-        const float* ys = xs + XE;
-        float av[2], bv[2][NROW];
-        auto read_ops = [&](int step, float& ao, float (&bo)[NROW], int m) {
+    const int yoff = XE + (wf * 16 + li) * YS + kk;    // A: dy[k = li][pixel]
+    auto multiply = [&](const float* xs, auto nbc) __attribute__((always_inline)) {
+        constexpr int NBW = decltype(nbc)::value;
+        float av[2], bv[2][NBW];
+        auto read_ops = [&](int step, float& ao, float (&bo)[NBW], int m) __attribute__((always_inline)) {
             const int th = step / TQ4, uq = step - th * TQ4;
-            if (m == 0) ao = ys[yoff + th * TW + 4 * uq];
-            const int c = m / R, r = m - c * R;
-            bo[m] = xs[xoff + c * CS + (th * ST + r) * PW + 4 * uq * ST];
+            if (m == 0) ao = xs[yoff + th * TW + 4 * uq];
+            bo[m] = xs[tapoff[m] + th * ST * PW + 4 * uq * ST];
         };
 #pragma unroll
-        for (int m = 0; m < NROW; ++m) read_ops(0, av[0], bv[0], m);
+        for (int m = 0; m < NBW; ++m) read_ops(0, av[0], bv[0], m);
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int step = 0; step < NSTEPS; ++step) {
 #pragma unroll
-            for (int m = 0; m < NROW; ++m) {
+            for (int m = 0; m < NBW; ++m) {
                 if (step + 1 < NSTEPS) read_ops(step + 1, av[(step + 1) & 1], bv[(step + 1) & 1], m);
                 acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[step & 1], bv[step & 1][m], acc[m], 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
@@ -327,28 +359,29 @@ __global__ __launch_bounds__(256) void smallc_wgrad_kernel(SmallArgs a) {
         __syncthreads();
         int buf = 0;
         for (int stage = s_begin; stage < s_end; ++stage) {
-            fetch(stage + 1);   // past the end of this workgroup's run: all zeros, never used
-            multiply(lds + buf * STAGE);
+            fetch(stage + 1);   // past the end of this workgroup's run: zero-size descriptors, nothing is read
+            if (wt == 0) multiply(lds + buf * STAGE, std::integral_constant<int, NB0>{});
+            else multiply(lds + buf * STAGE, std::integral_constant<int, NBLK - NB0>{});
             if (stage + 1 < s_end) stash(buf ^ 1);
             __syncthreads();
             buf ^= 1;
         }
     }
 
-    // ---- write the block: LDS transpose to dw order [k][c][r][s], coalesced stores ----------------------
+    // ---- write the block: LDS transpose to dw order [k][tap], coalesced stores -----------------------------
     __syncthreads();
 #pragma unroll
-    for (int m = 0; m < NROW; ++m)
+    for (int m = 0; m < NB0; ++m) {
+        if (b0 + m >= NBLK) break;   // scalar
 #pragma unroll
-        for (int v = 0; v < 4; ++v)
-            lds[((wave * 16 + 4 * kk + v) * NROW + m) * 16 + li] = acc[m][v];   // [k local][c*R+r][s (16 wide)]
+        for (int v = 0; v < 4; ++v) lds[(wf * 16 + 4 * kk + v) * (NBLK * 16) + 16 * (b0 + m) + li] = acc[m][v];
+    }
     __syncthreads();
-    float* out = a.out + (a.nsplit > 1 ? (size_t)sp * a.K * C * R * S : 0);
-    for (int o = tid; o < 64 * NROW * S; o += NT) {
-        const int kl = o / (NROW * S), rem = o - kl * (NROW * S);
-        const int row = rem / S, s = rem - row * S;
+    float* out = a.out + (a.nsplit > 1 ? (size_t)sp * a.K * NTAP : 0);
+    for (int o = tid; o < 64 * NTAP; o += 64 * NW) {
+        const int kl = o / NTAP, t = o - kl * NTAP;
         const int k = kb * 64 + kl;
-        if (k < a.K) out[(size_t)k * NROW * S + rem] = lds[(kl * NROW + row) * 16 + s];
+        if (k < a.K) out[(size_t)k * NTAP + t] = lds[kl * (NBLK * 16) + t];
     }
 }
 
@@ -546,8 +579,8 @@ hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* 
     a.nsplit = wgrad_splits(pr, a);
     a.out = a.nsplit > 1 ? static_cast<float*>(ws) : out;
     const int grid = a.kblocks * a.nsplit;
-    if (pr.dtype == 0) smallc_wgrad_kernel<float, 3, 11, 11, 4, kWgTH, kWgTQ4><<<grid, 256, 0, st>>>(a);
-    else smallc_wgrad_kernel<uint16_t, 3, 11, 11, 4, kWgTH, kWgTQ4><<<grid, 256, 0, st>>>(a);
+    if (pr.dtype == 0) smallc_wgrad_kernel<float, 3, 11, 11, 4, kWgTH, kWgTQ4><<<grid, 512, 0, st>>>(a);
+    else smallc_wgrad_kernel<uint16_t, 3, 11, 11, 4, kWgTH, kWgTQ4><<<grid, 512, 0, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.nsplit == 1) return e;
     const int count = pr.K * pr.C * pr.R * pr.S;
