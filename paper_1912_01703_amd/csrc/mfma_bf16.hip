@@ -100,6 +100,7 @@ struct BfArgs {
     int pad_h, pad_w;
     int tiles_h, tiles_w, fblocks, units;
     int items;            // work items: units rounded up to a multiple of 8, times fblocks
+    int pairs;            // OW is even and dst is 8-byte aligned: the write-out stores two pixels per lane
 };
 
 // The kernel is persistent: a workgroup walks a list of work items (image, tile, filter block), and
@@ -328,20 +329,48 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
             const int dplane = a.OH * a.OW;
             float* dst = a.dst + (size_t)it.n * a.F * dplane;
             const int fbase = it.fblk * FW + wf * (16 * FB);
+            if (a.pairs) {
+                // Neighbouring lanes hold neighbouring pixels of one row (tile width, block size and tile origin
+                // are even).  They trade two of their four filters, after which the even lane owns filters
+                // 4kk, 4kk+1 and the odd lane 4kk+2, 4kk+3 of both pixels: 8-byte stores, half as many.
+                const bool odd = li & 1;
 #pragma unroll
-            for (int i = 0; i < NBW; ++i) {
-                const int j = 16 * (wp + WP * i) + li;
-                const int th = j / TW, tw = j - th * TW;
-                const int oh = it.oh0 + th, ow = it.ow0 + tw;
-                const bool pix_ok = it.ok && j < NPX && oh < a.OH && ow < a.OW;
+                for (int i = 0; i < NBW; ++i) {
+                    const int j = 16 * (wp + WP * i) + li;
+                    const int th = j / TW, tw = j - th * TW;
+                    const int oh = it.oh0 + th, ow = it.ow0 + tw;
+                    const bool pix_ok = it.ok && j < NPX && oh < a.OH && ow < a.OW;   // the same for both lanes of a pair
 #pragma unroll
-                for (int fb = 0; fb < FB; ++fb) {
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const int f = fbase + 16 * fb + 4 * kk + v;
-                        if (pix_ok && f < a.F) dst[(size_t)f * dplane + oh * a.OW + ow] = acc[fb][i][v];
+                    for (int fb = 0; fb < FB; ++fb) {
+                        const v4f c = acc[fb][i];
+                        const float s0 = odd ? c[0] : c[2], s1 = odd ? c[1] : c[3];
+                        const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s0), 0xB1, 0xF, 0xF, true));
+                        const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s1), 0xB1, 0xF, 0xF, true));
+                        const float2 o0 = odd ? make_float2(r0, c[2]) : make_float2(c[0], r0);
+                        const float2 o1 = odd ? make_float2(r1, c[3]) : make_float2(c[1], r1);
+                        const int f = fbase + 16 * fb + 4 * kk + (odd ? 2 : 0);
+                        float* row = dst + (size_t)f * dplane + oh * a.OW + (ow - (odd ? 1 : 0));
+                        if (pix_ok && f < a.F) *reinterpret_cast<float2*>(row) = o0;
+                        if (pix_ok && f + 1 < a.F) *reinterpret_cast<float2*>(row + dplane) = o1;
+                        acc[fb][i] = v4f{0.f, 0.f, 0.f, 0.f};
                     }
-                    acc[fb][i] = v4f{0.f, 0.f, 0.f, 0.f};
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < NBW; ++i) {
+                    const int j = 16 * (wp + WP * i) + li;
+                    const int th = j / TW, tw = j - th * TW;
+                    const int oh = it.oh0 + th, ow = it.ow0 + tw;
+                    const bool pix_ok = it.ok && j < NPX && oh < a.OH && ow < a.OW;
+#pragma unroll
+                    for (int fb = 0; fb < FB; ++fb) {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            const int f = fbase + 16 * fb + 4 * kk + v;
+                            if (pix_ok && f < a.F) dst[(size_t)f * dplane + oh * a.OW + ow] = acc[fb][i][v];
+                        }
+                        acc[fb][i] = v4f{0.f, 0.f, 0.f, 0.f};
+                    }
                 }
             }
             cch = 0;
@@ -417,6 +446,7 @@ hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const voi
     a.fblocks = (s.F + 16 * kFB * kWF - 1) / (16 * kFB * kWF);
     a.units = pr.N * a.tiles_h * a.tiles_w;
     a.items = ((a.units + 7) / 8) * 8 * a.fblocks;
+    a.pairs = s.OW % 2 == 0 && reinterpret_cast<uintptr_t>(out) % 8 == 0;
     // two workgroups fit a CU: at most that many are launched and each walks its share of the items
     const int grid = a.items < 256 * kOCC ? a.items : 256 * kOCC;
     bf16_tile_kernel<kFB, kWF, kWP, kOCC><<<grid, 64 * kWF * kWP, 0, st>>>(a);
