@@ -180,7 +180,7 @@ def main():
     # each after a few untimed launches: in step order the pass that only reads (bwd_weight) is charged
     # the write-back of the 256 MB of results that the passes before it left in the Infinity Cache
     # (31 instead of 25 us on layer 5a).
-    GROUP = 4
+    GROUP = 16
     ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(3)]
           for _ in range(a.steps)]
 

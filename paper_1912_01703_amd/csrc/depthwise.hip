@@ -16,7 +16,10 @@
 // away from an integer, far more than fp32 rounding) instead of integer division.
 #include "common.h"
 
+#include <mutex>
 #include <type_traits>
+#include <utility>
+#include <vector>
 
 namespace miconv {
 namespace {
@@ -911,6 +914,21 @@ bool strip_wgrad_args(const Problem& pr, const void* x, const void* dy, DwStripW
     return true;
 }
 
+// Allows a kernel the whole 160 KB of a CU as dynamic LDS; asked of the runtime once per (device, kernel).
+hipError_t grant_lds(const void* kernel) {
+    static std::mutex mu;
+    static std::vector<std::pair<int, const void*>> granted;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const auto& g : granted)
+        if (g.first == dev && g.second == kernel) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e == hipSuccess) granted.emplace_back(dev, kernel);
+    return e;
+}
+
 // Launches the kernel; *wsplit tells the caller how many partial sums per element it left in a.out.
 template <typename T, int ST>
 hipError_t launch_strip_wgrad(DwStripWArgs a, float* dw, int* wsplit, hipStream_t st) {
@@ -927,7 +945,7 @@ hipError_t launch_strip_wgrad(DwStripWArgs a, float* dw, int* wsplit, hipStream_
         if (fixed) kernel = dw_strip_wgrad_kernel<T, 1, 16, 2, true, 16, 14>;
     }
     if (smem > 64 * 1024) {   // dynamic LDS beyond 64 KB has to be granted first
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        const hipError_t e = grant_lds(reinterpret_cast<const void*>(kernel));
         if (e != hipSuccess) return e;
     }
     kernel<<<grid, 64 * a.waves, smem, st>>>(a);
