@@ -503,6 +503,173 @@ __global__ __launch_bounds__(64) void smallc_bwd_data_kernel(SmallBwdArgs a) {
         }
 }
 
+// ------------------------------------------------------------------- backward-data on the matrix cores
+// dx[n, c, h, w] = sum_{k, r, s} dy[n, k, p, q] w[k, c, r, s] with h + 2 = 4 p + r, w + 2 = 4 q + s
+// (11x11, stride 4, padding 2).  Write h = 4 P' + a.  Rows a = 0, 1 see the taps r = a + 2 + 4 j at
+// p = P' - j, rows a = 2, 3 the taps r = a - 2 + 4 j at p = P' + 1 - j (j = 0, 1, 2; r = 11 does
+// not exist); the same holds for columns.  So the 16 pixel phases (a, b) fall into four groups
+// (a / 2, b / 2) whose members read the same dy values, and a group is one GEMM:
+//   M = 12 "virtual channels" (c, a % 2, b % 2) in a 16-row MFMA block,
+//   N = 16 positions (P', Q'),  K = (k, j_r, j_s) = 64 x 9, four filters per MFMA step.
+// 63 % of the multiplications are real (12 of 16 rows, and the taps that do not exist).
+// Eight waves: wave = group x half of the tile's position blocks; its A operands (144 per lane)
+// stay in registers.  Persistent workgroups walk (image, 2 x 56 positions) items; the dy patch of
+// the next item (64 filters x 5 rows x 59 columns) is requested before this one is multiplied and
+// stored to the other LDS buffer afterwards.  A lane ends up with 2 x 2 neighbouring pixels of one
+// channel and stores them as two 8-byte pairs.
+struct SmallBwdMArgs {
+    const void* dy;
+    const void* w;
+    float* dx;
+    int N, K, H, W, P, Q;
+    int tiles_h, tiles_w;   // tiles of 2 x 56 positions (a position = a 4 x 4 block of pixels)
+    int pairs;              // W is even and dx 8-byte aligned
+    unsigned dy_bytes, w_bytes;
+};
+
+template <typename T>
+__global__ __launch_bounds__(512) void smallc_bwd_data_mfma_kernel(SmallBwdMArgs a) {
+    constexpr int C = 3, R = 11, S = 11, NW = 8;
+    constexpr int TR = 2, TC = 56, NPOS = TR * TC, NB = NPOS / 16, NB0 = (NB + 1) / 2;
+    constexpr int PR = TR + 3, PC = TC + 3;         // patch rows p = P0 - 2 .. P0 + TR, columns likewise
+    constexpr int PWD = 60, KS = PR * PWD + 4;      // 304 = 16 mod 32: lane groups kk, kk + 1 hit different banks
+    constexpr int KF = 64;                          // filters (all of them: K <= 64)
+    constexpr int XE = KF * KS, BUFSZ = XE + 64;
+    constexpr int ROWS = KF * PR, RPW = ROWS / NW;  // patch rows per wave
+    constexpr int NSTEP = (KF / 4) * 9;
+    constexpr unsigned ESZ = sizeof(T);
+    static_assert(NPOS % 16 == 0 && ROWS % NW == 0 && PC <= 64, "tile shape");
+    static_assert(2 * BUFSZ * 4 <= 160 * 1024, "LDS budget");
+
+    __shared__ float patch[2 * BUFSZ];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave & 3, wp = wave >> 2;
+    const int sa = grp >> 1, sb = grp & 1;
+    const int li = lane & 15, kk = lane >> 4;
+    const int items = a.N * a.tiles_h * a.tiles_w;
+    const T* const tnull = nullptr;
+
+    // ---- A operands: w[k = 4 kq + kk][c][r][s] of virtual channel m = li, zero where the tap does not exist
+    const rsrc_t wrs = make_rsrc(a.w, a.w_bytes);
+    float wa[NSTEP];
+    {
+        const int c = li >> 2, al = (li >> 1) & 1, bl = li & 1;
+        const int r0 = (2 * sa + al + 2) & 3, s0 = (2 * sb + bl + 2) & 3;
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+            const int kq = st / 9, jr = (st % 9) / 3, js = st % 3;
+            const int k = 4 * kq + kk, r = r0 + 4 * jr, ss = s0 + 4 * js;
+            const bool ok = li < 12 && k < a.K && r < R && ss < S;
+            wa[st] = buf_load(wrs, ok ? (unsigned)(((k * C + c) * R + r) * S + ss) * ESZ : kOob, tnull);
+        }
+    }
+
+    const rsrc_t yrs = make_rsrc(a.dy, a.dy_bytes), nors = make_rsrc(a.dy, 0);
+    float xv[RPW];
+    struct Where { int n, P0, Q0; };
+    auto decode = [&](int item) __attribute__((always_inline)) -> Where {
+        const int tj = item % a.tiles_w, r2 = item / a.tiles_w;
+        const int ti = r2 % a.tiles_h;
+        return Where{__builtin_amdgcn_readfirstlane(r2 / a.tiles_h), __builtin_amdgcn_readfirstlane(ti * TR),
+                     __builtin_amdgcn_readfirstlane(tj * TC)};
+    };
+    auto issue = [&](int item) __attribute__((always_inline)) {
+        const Where wh = decode(item);
+        const int q = wh.Q0 - 2 + lane;
+        const unsigned colv = lane < PC && q >= 0 && q < a.Q ? (unsigned)q * ESZ : kOob;
+#pragma unroll
+        for (int j = 0; j < RPW; ++j) {
+            const int rr = wave + NW * j;
+            const int k = rr / PR, pr = rr - k * PR;
+            const int p = wh.P0 - 2 + pr;
+            const bool ok = k < a.K && p >= 0 && p < a.P;
+            xv[j] = buf_load_s(ok ? yrs : nors, colv, ok ? (unsigned)(((wh.n * a.K + k) * a.P + p) * a.Q) * ESZ : 0u, tnull);
+        }
+    };
+    auto store = [&](int buf) __attribute__((always_inline)) {
+        float* dst = patch + buf * BUFSZ;
+#pragma unroll
+        for (int j = 0; j < RPW; ++j) {
+            const int rr = wave + NW * j;
+            const int k = rr / PR, pr = rr - k * PR;   // scalar
+            dst[lane < PC ? k * KS + pr * PWD + lane : XE + lane] = xv[j];
+        }
+    };
+
+    // position blocks of this wave; lane's position (tr, tc) in block ii and where its dy values start
+    const int i0 = wp * NB0;
+    int pixoff[NB0];
+#pragma unroll
+    for (int ii = 0; ii < NB0; ++ii) {
+        const int j = 16 * (i0 + ii) + li;
+        const int tr = j / TC, tc = j - tr * TC;
+        pixoff[ii] = j < NPOS ? kk * KS + (tr + sa) * PWD + tc + sb : 0;
+    }
+
+    auto compute = [&](const float* pb, const Where& wh, auto nbwc) __attribute__((always_inline)) {
+        constexpr int NBW = decltype(nbwc)::value;
+        v4f acc[NBW];
+#pragma unroll
+        for (int ii = 0; ii < NBW; ++ii) acc[ii] = v4f{0.f, 0.f, 0.f, 0.f};
+        // step (kq, jr, js): dy[k][P' + sa - jr][Q' + sb - js] = patch[k][tr + sa - jr + 2][tc + sb - js + 2]
+        auto off_of = [](int st) { return (st / 9) * 4 * KS + (2 - (st % 9) / 3) * PWD + (2 - st % 3); };
+        float bq[2][NBW];
+#pragma unroll
+        for (int ii = 0; ii < NBW; ++ii) bq[0][ii] = pb[pixoff[ii] + off_of(0)];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st) {
+#pragma unroll
+            for (int ii = 0; ii < NBW; ++ii) {
+                if (st + 1 < NSTEP) bq[(st + 1) & 1][ii] = pb[pixoff[ii] + off_of(st + 1)];
+                acc[ii] = __builtin_amdgcn_mfma_f32_16x16x4f32(wa[st], bq[st & 1][ii], acc[ii], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // ---- D[(c = kk, al, bl) = 4 kk + v][position li]: rows h = 4 P' + 2 sa + al, columns w = 4 Q' + 2 sb + {0, 1}
+        if (kk < C) {
+            float* dxc = a.dx + ((size_t)wh.n * C + kk) * a.H * a.W;
+#pragma unroll
+            for (int ii = 0; ii < NBW; ++ii) {
+                const int j = 16 * (i0 + ii) + li;
+                const int tr = j / TC, tc = j - tr * TC;
+                const int h = 4 * (wh.P0 + tr) + 2 * sa, w = 4 * (wh.Q0 + tc) + 2 * sb;
+#pragma unroll
+                for (int al = 0; al < 2; ++al) {
+                    if (h + al >= a.H || w >= a.W) continue;
+                    float* row = dxc + (size_t)(h + al) * a.W + w;
+                    if (a.pairs) {
+                        *reinterpret_cast<float2*>(row) = make_float2(acc[ii][2 * al], acc[ii][2 * al + 1]);
+                    } else {
+                        row[0] = acc[ii][2 * al];
+                        if (w + 1 < a.W) row[1] = acc[ii][2 * al + 1];
+                    }
+                }
+            }
+        }
+    };
+
+    int item = blockIdx.x, buf = 0;
+    if (item < items) {
+        issue(item);
+        store(0);
+    }
+    __syncthreads();
+    for (; item < items; item += gridDim.x) {
+        const int next = item + gridDim.x;
+        if (next < items) issue(next);   // travels while this item is multiplied
+        const Where wh = decode(item);
+        const float* pb = patch + buf * BUFSZ;
+        if (wp == 0) compute(pb, wh, std::integral_constant<int, NB0>{});
+        else compute(pb, wh, std::integral_constant<int, NB - NB0>{});
+        if (next < items) store(buf ^ 1);
+        __syncthreads();   // the next patch is complete, and every wave is done with this one
+        buf ^= 1;
+    }
+}
+
 bool shape_ok(const Problem& pr) {
     const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
     if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
@@ -525,8 +692,10 @@ int wgrad_splits(const Problem& pr, const SmallArgs& a) {
     return nsplit < 1 ? 1 : nsplit;
 }
 
-// Backward-data: fp32 tensors with the padding the kernel is instantiated for.
-bool bwd_ok(const Problem& pr) { return shape_ok(pr) && pr.dtype == 0 && pr.ph == 2 && pr.pw == 2; }
+// Backward-data: the padding the kernels are written for; the matrix-core kernel holds all filters (K <= 64), the
+// vector-ALU kernel takes fp32 tensors with any number of filters.
+bool bwd_mfma_ok(const Problem& pr) { return shape_ok(pr) && pr.ph == 2 && pr.pw == 2 && pr.K <= 64; }
+bool bwd_ok(const Problem& pr) { return bwd_mfma_ok(pr) || (shape_ok(pr) && pr.dtype == 0 && pr.ph == 2 && pr.pw == 2); }
 
 }  // namespace
 
@@ -545,6 +714,21 @@ size_t smallc_workspace_bytes(int pass, const Problem& pr) {
 hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
                       hipStream_t st) {
     if (!smallc_supports(pass, pr)) return hipErrorNotSupported;
+    if (pass == 1 && bwd_mfma_ok(pr)) {
+        const unsigned esz = pr.dtype == 0 ? 4 : 2;
+        SmallBwdMArgs m{};
+        m.dy = in0; m.w = in1; m.dx = out;
+        m.N = pr.N; m.K = pr.K; m.H = pr.H; m.W = pr.W; m.P = pr.P; m.Q = pr.Q;
+        m.tiles_h = ((pr.H + 3) / 4 + 1) / 2; m.tiles_w = ((pr.W + 3) / 4 + 55) / 56;
+        m.pairs = pr.W % 2 == 0 && reinterpret_cast<uintptr_t>(out) % 8 == 0;
+        m.dy_bytes = (unsigned)((size_t)pr.N * pr.K * pr.P * pr.Q * esz);
+        m.w_bytes = (unsigned)((size_t)pr.K * pr.C * pr.R * pr.S * esz);
+        const int items = pr.N * m.tiles_h * m.tiles_w;
+        const int grid = items < 256 ? items : 256;   // persistent, one workgroup per CU (its two patch buffers fill the LDS)
+        if (pr.dtype == 0) smallc_bwd_data_mfma_kernel<float><<<grid, 512, 0, st>>>(m);
+        else smallc_bwd_data_mfma_kernel<uint16_t><<<grid, 512, 0, st>>>(m);
+        return hipGetLastError();
+    }
     if (pass == 1) {
         SmallBwdArgs b{};
         b.dy = static_cast<const float*>(in0); b.w = static_cast<const float*>(in1); b.dx = out;

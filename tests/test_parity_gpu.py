@@ -164,6 +164,14 @@ def test_small_channel_large_filter(row, dtype):
     pu.check_layer_full(L, dtype, algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
 
 
+def test_small_channel_backward_data_with_more_than_64_filters():
+    """The matrix-core backward-data kernel keeps all filters of a layer in LDS (K <= 64); with more, fp32
+    tensors take the vector-ALU kernel."""
+    from paper_1912_01703_amd import binding as mc
+    L = wl.custom_layer("a11e", 2, 3, 63, 67, 80, 11, 11, 4, 2, 1, seed=5011)
+    pu.check_layer_full(L, "f32", passes=("bwd_data",), algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+
+
 def test_small_channel_forward_walks_several_items():
     """Two filter blocks share the 256 persistent workgroups, and 140 work items per block exceed the 128
     workgroups of each: some workgroups run a second item out of the other LDS buffer."""
