@@ -152,6 +152,7 @@ SMALLC = [
     ("a11a", 2, 63, 63, 64, 2),
     ("a11b", 3, 51, 75, 40, 2),      # ragged tiles, K not a multiple of 64
     ("a11c", 1, 227, 227, 16, 0),    # no padding, full-width rows
+    ("a11f", 1, 35, 243, 16, 2),     # 60 output columns / 61 column positions: two tiles side by side in every pass
 ]
 
 
@@ -188,6 +189,10 @@ DW = [
     ("dw9x13", 5, 33, 9, 13, 1, 0),    # no padding, non-square
     ("dw15p2", 1, 17, 15, 15, 1, 2),   # padding wider than the filter reach
     ("dw56", 1, 8, 56, 56, 1, 1),
+    # backward-weight: 20 batches of 4 images on 4 channels = 8 waves x 2 workgroups per channel, partial sums reduced
+    ("dwsplit", 80, 4, 14, 14, 1, 1),
+    ("dwc1024", 2, 1024, 14, 14, 1, 1),   # backward-weight: a wave owns 4 consecutive channels
+    ("dwc513", 3, 513, 14, 14, 1, 1),     # ... 2 channels, the last pair half empty; 2 images per batch, the last half empty
 ]
 
 
