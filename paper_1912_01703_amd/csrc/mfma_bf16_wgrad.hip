@@ -123,8 +123,13 @@ __global__ __launch_bounds__(256) void bf16_wgrad_kernel(BwArgs a) {
     static_assert(SLOTS % RING == 0 && PF < RING, "ring");
     __shared__ __attribute__((aligned(16))) unsigned char lds[kLds];
 
+    // Workgroup ids that differ by multiples of 8 share an XCD (one L2 each).  Splits that follow each other work
+    // on neighbouring strips of the same rows; they are given to one XCD, where they run side by side, so that a
+    // cache line of a row, of which a 28-column strip covers 56 bytes, is fetched from HBM once and not once per strip
+    // (3.2 GB of fetches for 0.8 GB of operands on 224x224 planes otherwise).
     const int blocks = a.kblocks * a.cblocks;
-    const int blk = blockIdx.x % blocks, sp = blockIdx.x / blocks;
+    const int wg = gridDim.x % 8 == 0 ? (int)(blockIdx.x % 8) * (int)(gridDim.x / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+    const int blk = wg % blocks, sp = wg / blocks;
     const int kb = blk / a.cblocks, cb = blk - kb * a.cblocks;
     const int k0 = kb * kKB, c0 = cb * kCB;
     const int u0 = __builtin_amdgcn_readfirstlane((int)((long long)a.units * sp / a.nsplit));
