@@ -41,7 +41,10 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
         if (dry) return true;
         // Few chunks per item and many items: persistent workgroups hide each item's start-up and write-out
         const long long ids = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
-        if (a.Rg <= 128 && ids >= 1024) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD, 3, true>(a, st);
+        // Wide planes take 12 x 16 tiles: 12 pixel blocks without a ragged one (14 x 14 = 12.25 blocks run as 13), and
+        // output rows of 64 bytes that start on 64-byte boundaries
+        if (a.Rg <= 128 && ids >= 1024 && a.OW % 16 == 0 && a.OH >= 96) *err = launch_tile<T, 3, 3, 1, 12, 16, 16, 4, 2, BWD, 3, true>(a, st);
+        else if (a.Rg <= 128 && ids >= 1024) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD, 3, true>(a, st);
         else *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD>(a, st);
         return true;
     }

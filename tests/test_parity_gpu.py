@@ -66,6 +66,7 @@ MFMA = [
     ("m3x3n", 9, 16, 14, 14, 16, 3, 3, 1, 1, 1),      # more images than one split holds
     ("m3x3p", 5, 16, 210, 210, 24, 3, 3, 1, 1, 1),    # > 1024 work items of one chunk: persistent workgroups
     ("m3x3q", 3, 40, 200, 206, 72, 3, 3, 1, 1, 1),    # ... with two filter blocks, three chunks, ragged tiles
+    ("m3x3w", 9, 16, 100, 208, 24, 3, 3, 1, 1, 1),    # > 1024 items, width a multiple of 16: 12 x 16 tiles, last tile row ragged
     ("m3x3s2", 2, 32, 28, 28, 32, 3, 3, 2, 1, 1),     # stride 2: backward-data runs once per output phase
     ("m3x3s2b", 1, 16, 31, 27, 20, 3, 3, 2, 1, 1),    # odd sizes: phases of different extent
     ("m3x3s2c", 2, 16, 16, 16, 24, 3, 3, 2, 0, 1),    # no padding: the last input row/column feeds nothing
