@@ -107,22 +107,23 @@ struct BfArgs {
 // the chunk pipeline runs across item boundaries, so the loads of the next item's first chunks
 // overlap the MFMAs of the current one.  Layers with few reduction channels (two chunks per item at
 // 64 channels) would otherwise spend most of their time filling and draining the pipeline.
-template <int FB, int WF, int WP, int OCC>
+// TH x TW: the tile of output pixels, 14 x 14 or (wide planes) 12 x 16: 12 pixel blocks without a ragged one, and
+// output rows of 64 bytes on 64-byte boundaries where 14-pixel rows leave partly written cache lines behind.
+template <int TH, int TW, int FB, int WF, int WP, int OCC>
 __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) {
-    constexpr int TH = 14, TW = 14, PW = 16, PSZ = 256, NPX = TH * TW;
+    constexpr int PH = TH + 2, PW = TW + 2, PSZ = PH * PW, NPX = TH * TW;
     constexpr int NT = 64 * WF * WP;
     constexpr int NB = (NPX + 15) / 16, NBW = (NB + WP - 1) / WP;
     constexpr int ROWB = 80;                 // bytes per patch pixel in LDS: 64 of data, 16 of padding
-    // A 16-pixel block of the 14-wide tile wraps to the next patch row.  With this row pitch the
+    // A 16-pixel block of a 14-wide tile wraps to the next patch row.  With this row pitch the
     // wrap continues the 80-byte progression modulo 128 bytes (14 * 80 = 96 mod 128), so the 8 lanes
-    // the LDS serves together still hit distinct banks.
-    constexpr int RPB = 16 * ROWB + 96;
-    static_assert((RPB - TW * ROWB) % 128 == 0, "row pitch keeps wrapped blocks conflict-free");
+    // the LDS serves together still hit distinct banks.  A 16-wide tile has one block per row.
+    constexpr int RPB = TW == 14 ? 16 * ROWB + 96 : PW * ROWB + 16;
+    static_assert((TW == 14 && (RPB - TW * ROWB) % 128 == 0) || (TW == 16 && NPX % 16 == 0), "tile shapes the layout is made for");
 
-    constexpr int BUFB = 16 * RPB;           // one patch buffer
+    constexpr int XPT = (PSZ * 4 + NT - 1) / NT;   // 16-byte pieces per thread and chunk
+    constexpr int BUFB = PH * RPB + (XPT * NT - PSZ * 4) * 16;   // one patch buffer, and room for the pieces past the patch
     constexpr int NBUF = 3, D = NBUF - 1;
-    constexpr int XPT = PSZ * 4 / NT;        // 16-byte pieces per thread and chunk
-    static_assert(PSZ * 4 % NT == 0, "whole pieces");
     constexpr int SLOTS = 9 * NBW;           // one slot = one B operand = FB MFMAs
     constexpr int RING = 9, PF = 7;          // B operands are requested PF slots ahead; RING divides SLOTS
     static_assert(SLOTS % RING == 0 && PF < RING, "ring");
@@ -182,7 +183,7 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
             const int pix = e >> 2, q = e & 3;
             const int ph = pix / PW, pw = pix - ph * PW;
             const int ih = ih0 + ph, iw = iw0 + pw;
-            const bool ok = ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
+            const bool ok = pix < PSZ && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
             goff[m] = ok ? (unsigned)((ih * a.IW + iw) * a.Cs + 8 * q) * 2u : kOob;
         }
     };
@@ -197,7 +198,7 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     for (int m = 0; m < XPT; ++m) {
         const int e = tid + NT * m;
         const int pix = e >> 2, q = e & 3;
-        loff[m] = (pix / PW) * RPB + (pix % PW) * ROWB + q * 16;
+        loff[m] = pix < PSZ ? (pix / PW) * RPB + (pix % PW) * ROWB + q * 16 : PH * RPB + (e - PSZ * 4) * 16;
     }
 
     int wj = 0, wch = 0;            // item and chunk the next filter load fetches
@@ -445,14 +446,17 @@ hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const voi
     a.xt = xt; a.wp = wp; a.dst = out;
     a.N = pr.N; a.Cs = s.Cs; a.IH = s.IH; a.IW = s.IW; a.F = s.F; a.OH = s.OH; a.OW = s.OW;
     a.pad_h = s.pad_h; a.pad_w = s.pad_w;
-    a.tiles_h = (s.OH + 13) / 14; a.tiles_w = (s.OW + 13) / 14;
+    const bool wide = s.OW % 16 == 0 && s.OH >= 96;   // 12 x 16 tiles
+    const int th = wide ? 12 : 14, tw = wide ? 16 : 14;
+    a.tiles_h = (s.OH + th - 1) / th; a.tiles_w = (s.OW + tw - 1) / tw;
     a.fblocks = (s.F + 16 * kFB * kWF - 1) / (16 * kFB * kWF);
     a.units = pr.N * a.tiles_h * a.tiles_w;
     a.items = ((a.units + 7) / 8) * 8 * a.fblocks;
     a.pairs = s.OW % 2 == 0 && reinterpret_cast<uintptr_t>(out) % 8 == 0;
     // two workgroups fit a CU: at most that many are launched and each walks its share of the items
     const int grid = a.items < 256 * kOCC ? a.items : 256 * kOCC;
-    bf16_tile_kernel<kFB, kWF, kWP, kOCC><<<grid, 64 * kWF * kWP, 0, st>>>(a);
+    if (wide) bf16_tile_kernel<12, 16, kFB, kWF, kWP, kOCC><<<grid, 64 * kWF * kWP, 0, st>>>(a);
+    else bf16_tile_kernel<14, 14, kFB, kWF, kWP, kOCC><<<grid, 64 * kWF * kWP, 0, st>>>(a);
     return hipGetLastError();
 }
 

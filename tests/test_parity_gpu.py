@@ -94,6 +94,7 @@ BF16MM = [
     ("b3x3e", 1, 160, 28, 28, 128, 1),     # five chunks, four tiles, two filter blocks
     ("b3x3f", 5, 32, 8, 8, 16, 1),         # one partial tile, one partial filter block
     ("b3x3g", 2, 32, 8, 17, 32, 1),        # odd output width: the write-out stores single pixels
+    ("b3x3w", 1, 32, 100, 48, 64, 1),      # wide plane: 12 x 16 tiles, the last tile row ragged
 ]
 
 
