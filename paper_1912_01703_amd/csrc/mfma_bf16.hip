@@ -38,7 +38,9 @@ __device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
 }
 
-// ---- pre-pass 1: [N][C][HW] -> [N][HW][C], 32 channels x 256 pixels per workgroup ----------
+// ---- pre-pass 1: [N][C][HW] -> [N][HW][C], 64 channels x 128 pixels per workgroup ----------
+// 64 channels are the 128 bytes of one cache line of the destination: a workgroup writes whole lines
+// (with 32 channels the two halves of a line came from workgroups on different XCDs).
 struct PackXArgs {
     const uint16_t* src;
     uint16_t* dst;
@@ -47,28 +49,30 @@ struct PackXArgs {
 };
 
 __global__ __launch_bounds__(256) void pack_nhwc_kernel(PackXArgs a) {
-    constexpr int LS = 264;   // LDS row stride in elements (16-byte aligned rows)
-    __shared__ __attribute__((aligned(16))) uint16_t tile[32 * LS];
+    constexpr int LS = 136;   // LDS row stride in elements (16-byte aligned rows)
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * LS];
     const int t = threadIdx.x;
-    const int p0 = blockIdx.x * 256, c0 = blockIdx.y * 32, n = blockIdx.z;
+    const int p0 = blockIdx.x * 128, c0 = blockIdx.y * 64, n = blockIdx.z;
     const rsrc_t rs = make_rsrc(a.src, a.src_bytes);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int q = t + 256 * i;
-        const int c = q >> 5, pc = q & 31;
+        const int c = q >> 4, pc = q & 15;
         const int p = p0 + 8 * pc;   // 8 consecutive pixels of one channel; all inside the plane or none
-        const unsigned off = p < a.HW ? (unsigned)((n * a.C + c0 + c) * a.HW + p) * 2u : kOob;
+        const unsigned off = p < a.HW && c0 + c < a.C ? (unsigned)((n * a.C + c0 + c) * a.HW + p) * 2u : kOob;
         const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
         *reinterpret_cast<v4u*>(&tile[c * LS + 8 * pc]) = v;
     }
     __syncthreads();
-    const int p = p0 + t;
-    if (p >= a.HW) return;
+    // thread = (pixel, half of the 64 channels); the two halves of a pixel are waves of this workgroup
+    const int px = t & 127, h = t >> 7;
+    const int p = p0 + px;
+    if (p >= a.HW || c0 + 32 * h >= a.C) return;
     unsigned d[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j)
-        d[j] = (unsigned)tile[(2 * j) * LS + t] | ((unsigned)tile[(2 * j + 1) * LS + t] << 16);
-    v4u* o = reinterpret_cast<v4u*>(a.dst + ((size_t)n * a.HW + p) * a.C + c0);
+        d[j] = (unsigned)tile[(32 * h + 2 * j) * LS + px] | ((unsigned)tile[(32 * h + 2 * j + 1) * LS + px] << 16);
+    v4u* o = reinterpret_cast<v4u*>(a.dst + ((size_t)n * a.HW + p) * a.C + c0 + 32 * h);
 #pragma unroll
     for (int j = 0; j < 4; ++j) o[j] = v4u{d[4 * j], d[4 * j + 1], d[4 * j + 2], d[4 * j + 3]};
 }
@@ -433,7 +437,7 @@ hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const voi
     const int HW = s.IH * s.IW;
 
     PackXArgs px{static_cast<const uint16_t*>(in0), xt, pr.N, s.Cs, HW, (unsigned)((size_t)pr.N * s.Cs * HW * 2)};
-    pack_nhwc_kernel<<<dim3((HW + 255) / 256, s.Cs / 32, pr.N), 256, 0, st>>>(px);
+    pack_nhwc_kernel<<<dim3((HW + 127) / 128, (s.Cs + 63) / 64, pr.N), 256, 0, st>>>(px);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
 
