@@ -84,15 +84,30 @@ struct PackWArgs {
     int F, Cs, bwd;      // forward: F = K, Cs = C; backward-data: F = C, Cs = K
 };
 
+// A workgroup moves 8 filters x one chunk of 32 channels x 9 taps through LDS: contiguous runs on both sides
+// (forward: 576 bytes per filter in, 512 bytes per tap out).
 __global__ __launch_bounds__(256) void pack_w_kernel(PackWArgs a) {
-    const int idx = blockIdx.x * 256 + threadIdx.x;
-    if (idx >= a.F * a.Cs) return;
-    const int f = idx / a.Cs, c = idx - f * a.Cs;
+    __shared__ uint16_t t[8 * 288];   // [filter][channel][tap]
+    const int tid = threadIdx.x;
+    const int f0 = blockIdx.x * 8, chunk = blockIdx.y, c0 = chunk * 32;
 #pragma unroll
-    for (int tap = 0; tap < 9; ++tap) {
-        const size_t s = a.bwd ? ((size_t)c * a.F + f) * 9 + (8 - tap) : ((size_t)f * a.Cs + c) * 9 + tap;
-        a.dst[(((size_t)(c >> 5) * 9 + tap) * a.F + f) * 32 + (c & 31)] = a.w[s];
+    for (int k = 0; k < 9; ++k) {
+        const int e = tid + 256 * k;
+        if (!a.bwd) {   // w[f][c][tap]: per filter, the chunk's 32 x 9 values are one run
+            const int f = e / 288, r = e - f * 288;
+            if (f0 + f < a.F) t[e] = a.w[((size_t)(f0 + f) * a.Cs + c0) * 9 + r];
+        } else {        // w[c][f][8 - tap]: per reduction channel, the 8 x 9 values of the filters are one run
+            const int c = e / 72, r = e - c * 72;
+            const int f = r / 9, tap = r - f * 9;
+            if (f0 + f < a.F) t[f * 288 + c * 9 + (8 - tap)] = a.w[((size_t)(c0 + c) * a.F + f0) * 9 + r];
+        }
     }
+    __syncthreads();
+    const int f = tid >> 5, c = tid & 31;
+    if (f0 + f >= a.F) return;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+        a.dst[(((size_t)chunk * 9 + tap) * a.F + f0 + f) * 32 + c] = t[f * 288 + c * 9 + tap];
 }
 
 // ---- main kernel ---------------------------------------------------------------------------
@@ -442,7 +457,7 @@ hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const voi
     if (e != hipSuccess) return e;
 
     PackWArgs pw{static_cast<const uint16_t*>(in1), wp, s.F, s.Cs, pass == 1 ? 1 : 0};
-    pack_w_kernel<<<(s.F * s.Cs + 255) / 256, 256, 0, st>>>(pw);
+    pack_w_kernel<<<dim3((s.F + 7) / 8, s.Cs / 32), 256, 0, st>>>(pw);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
 
