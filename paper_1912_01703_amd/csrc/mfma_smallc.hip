@@ -1,5 +1,6 @@
 // Convolutions with very few input channels and a large, strided filter (the first layer of an
-// AlexNet-style network: C = 3, 11x11, stride 4) on the fp32 matrix cores.
+// AlexNet-style network: C = 3, 11x11, stride 4; forward and backward-weight also for the 7x7 stride-2
+// first layer of a ResNet) on the fp32 matrix cores.
 //
 // With C = 3 there is no channel dimension worth contracting over, so the MFMA K dimension runs
 // along the filter row instead: one step multiplies 4 consecutive taps s = 4u .. 4u+3 of one (c, r)
@@ -676,7 +677,15 @@ bool shape_ok(const Problem& pr) {
     return pr.groups == 1 && pr.C == 3 && pr.R == 11 && pr.S == 11 && pr.sh == 4 && pr.sw == 4;
 }
 
+// The 7x7 stride-2 first layer of a ResNet: the forward and backward-weight kernels are instantiated for it too.
+bool stem_ok(const Problem& pr) {
+    const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
+    if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
+    return pr.groups == 1 && pr.C == 3 && pr.R == 7 && pr.S == 7 && pr.sh == 2 && pr.sw == 2;
+}
+
 constexpr int kFwdTH = 2, kFwdTW = 55;       // forward tile: two full rows of a 55-wide output
+constexpr int kStemTW = 56;                  // ... half a row of the 112-wide output of the 7x7 stride-2 layer
 constexpr int kWgTH = 2, kWgTQ4 = 14;        // backward-weight stage: two rows x 56 columns
 
 void fill(const Problem& pr, SmallArgs& a) {
@@ -699,10 +708,10 @@ bool bwd_ok(const Problem& pr) { return bwd_mfma_ok(pr) || (shape_ok(pr) && pr.d
 
 }  // namespace
 
-bool smallc_supports(int pass, const Problem& pr) { return pass == 1 ? bwd_ok(pr) : shape_ok(pr); }
+bool smallc_supports(int pass, const Problem& pr) { return pass == 1 ? bwd_ok(pr) : (shape_ok(pr) || stem_ok(pr)); }
 
 size_t smallc_workspace_bytes(int pass, const Problem& pr) {
-    if (pass != 2 || !shape_ok(pr)) return 0;
+    if (pass != 2 || !(shape_ok(pr) || stem_ok(pr))) return 0;
     SmallArgs a{};
     fill(pr, a);
     a.tiles_h = (pr.P + kWgTH - 1) / kWgTH; a.tiles_w = (pr.Q + 4 * kWgTQ4 - 1) / (4 * kWgTQ4);
@@ -745,15 +754,22 @@ hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* 
     if (pass == 0) {
         a.w = in1; a.out = out;
         a.w_bytes = (unsigned)((size_t)pr.K * pr.C * pr.R * pr.S * esz);
-        a.tiles_h = (pr.P + kFwdTH - 1) / kFwdTH; a.tiles_w = (pr.Q + kFwdTW - 1) / kFwdTW;
+        const bool stem = pr.R == 7;
+        const int ftw = stem ? kStemTW : kFwdTW;
+        a.tiles_h = (pr.P + kFwdTH - 1) / kFwdTH; a.tiles_w = (pr.Q + ftw - 1) / ftw;
         // persistent workgroups, one per CU (two patch buffers take half of its LDS), shared out over the filter blocks
         const int items = pr.N * a.tiles_h * a.tiles_w;
         int slots = 256 / a.kblocks;
         if (slots < 1) slots = 1;
         if (slots > items) slots = items;
         const int grid = slots * a.kblocks;
-        if (pr.dtype == 0) smallc_fwd_kernel<float, 3, 11, 11, 4, kFwdTH, kFwdTW><<<grid, 512, 0, st>>>(a);
-        else smallc_fwd_kernel<uint16_t, 3, 11, 11, 4, kFwdTH, kFwdTW><<<grid, 512, 0, st>>>(a);
+        if (stem) {
+            if (pr.dtype == 0) smallc_fwd_kernel<float, 3, 7, 7, 2, kFwdTH, kStemTW><<<grid, 512, 0, st>>>(a);
+            else smallc_fwd_kernel<uint16_t, 3, 7, 7, 2, kFwdTH, kStemTW><<<grid, 512, 0, st>>>(a);
+        } else {
+            if (pr.dtype == 0) smallc_fwd_kernel<float, 3, 11, 11, 4, kFwdTH, kFwdTW><<<grid, 512, 0, st>>>(a);
+            else smallc_fwd_kernel<uint16_t, 3, 11, 11, 4, kFwdTH, kFwdTW><<<grid, 512, 0, st>>>(a);
+        }
         return hipGetLastError();
     }
     a.w = in1;   // dy
@@ -763,8 +779,13 @@ hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* 
     a.nsplit = wgrad_splits(pr, a);
     a.out = a.nsplit > 1 ? static_cast<float*>(ws) : out;
     const int grid = a.kblocks * a.nsplit;
-    if (pr.dtype == 0) smallc_wgrad_kernel<float, 3, 11, 11, 4, kWgTH, kWgTQ4><<<grid, 512, 0, st>>>(a);
-    else smallc_wgrad_kernel<uint16_t, 3, 11, 11, 4, kWgTH, kWgTQ4><<<grid, 512, 0, st>>>(a);
+    if (pr.R == 7) {
+        if (pr.dtype == 0) smallc_wgrad_kernel<float, 3, 7, 7, 2, kWgTH, kWgTQ4><<<grid, 512, 0, st>>>(a);
+        else smallc_wgrad_kernel<uint16_t, 3, 7, 7, 2, kWgTH, kWgTQ4><<<grid, 512, 0, st>>>(a);
+    } else {
+        if (pr.dtype == 0) smallc_wgrad_kernel<float, 3, 11, 11, 4, kWgTH, kWgTQ4><<<grid, 512, 0, st>>>(a);
+        else smallc_wgrad_kernel<uint16_t, 3, 11, 11, 4, kWgTH, kWgTQ4><<<grid, 512, 0, st>>>(a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.nsplit == 1) return e;
     const int count = pr.K * pr.C * pr.R * pr.S;

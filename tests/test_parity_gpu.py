@@ -168,6 +168,25 @@ def test_small_channel_large_filter(row, dtype):
     pu.check_layer_full(L, dtype, algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
 
 
+STEM = [
+    # name     N   H    W    K  pad     3 input channels, 7x7 filter, stride 2 (ResNet-style first layer): forward and
+    #                                   backward-weight on the matrix cores
+    ("s7a", 2, 64, 64, 64, 3),
+    ("s7b", 3, 51, 75, 40, 3),       # ragged tiles, K not a multiple of 64
+    ("s7c", 1, 230, 230, 16, 0),     # no padding, 112 output columns: two tiles side by side
+    ("s7d", 2, 37, 33, 72, 2),       # two filter blocks, padding 2
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("row", STEM, ids=[r[0] for r in STEM])
+def test_three_channel_7x7_stride_2(row, dtype):
+    from paper_1912_01703_amd import binding as mc
+    name, N, H, W, K, pd = row
+    L = wl.custom_layer(name, N, 3, H, W, K, 7, 7, 2, pd, 1, seed=5100 + STEM.index(row))
+    pu.check_layer_full(L, dtype, passes=("fwd", "bwd_weight"), algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+
+
 def test_small_channel_backward_data_with_more_than_64_filters():
     """The matrix-core backward-data kernel keeps all filters of a layer in LDS (K <= 64); with more, fp32
     tensors take the vector-ALU kernel."""
