@@ -9,7 +9,8 @@
 // a stride-1 correlation of dy with the J_a taps taken in reverse.  The same holds for columns, so a
 // stride-st backward pass is st*st stride-1 problems with sub-filters of J_a x J_b taps whose outputs
 // interleave in dx.  Gathering dy with zero-stuffing instead would spend st*st times the MFMA work on
-// structural zeros.  Phases without any tap (filter smaller than the stride) are not handled here.
+// structural zeros.  Phases without any tap (filter smaller than the stride, e.g. a 1x1 stride-2 shortcut) leave
+// zeros in dx: dx is cleared by a fill kernel first (no memset node: callers may capture the stream).
 #include "mfma_tile_kernel.h"
 
 namespace miconv {
@@ -86,6 +87,15 @@ hipError_t launch_merge2(TileArgs a, hipStream_t st) {
     return hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void zero_fill_kernel(float* __restrict__ dst, size_t count) {
+    const size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i + 4 <= count && reinterpret_cast<uintptr_t>(dst) % 16 == 0) {
+        *reinterpret_cast<float4*>(dst + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    } else {
+        for (size_t j = i; j < count && j < i + 4; ++j) dst[j] = 0.f;
+    }
+}
+
 bool merge2_ok(const Problem& pr) {
     if (pr.R != 3 || pr.S != 3 || pr.sh != 2 || pr.sw != 2 || pr.ph != 1 || pr.pw != 1) return false;
     const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
@@ -118,11 +128,11 @@ bool tile_phase_supports(const Problem& pr) {
     if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
     for (int a = 0; a < pr.sh; ++a) {
         const Phase p = make_phase(a, pr.sh, pr.R, pr.ph, pr.H);
-        if (p.cnt > 0 && (p.J < 1 || p.J > 3)) return false;
+        if (p.cnt > 0 && p.J > 3) return false;
     }
     for (int b = 0; b < pr.sw; ++b) {
         const Phase p = make_phase(b, pr.sw, pr.S, pr.pw, pr.W);
-        if (p.cnt > 0 && (p.J < 1 || p.J > 3)) return false;
+        if (p.cnt > 0 && p.J > 3) return false;
     }
     return true;
 }
@@ -130,12 +140,21 @@ bool tile_phase_supports(const Problem& pr) {
 hipError_t tile_phase_run(const Problem& pr, const void* dy, const void* w, float* dx, hipStream_t st) {
     if (!tile_phase_supports(pr)) return hipErrorNotSupported;
     const unsigned esz = pr.dtype == 0 ? 4 : 2;
+    bool empty = false;   // a phase that no tap reaches
+    for (int a = 0; a < pr.sh; ++a) empty |= make_phase(a, pr.sh, pr.R, pr.ph, pr.H).J == 0;
+    for (int b = 0; b < pr.sw; ++b) empty |= make_phase(b, pr.sw, pr.S, pr.pw, pr.W).J == 0;
+    if (empty) {
+        const size_t count = (size_t)pr.N * pr.C * pr.H * pr.W;
+        zero_fill_kernel<<<(unsigned)((count / 4 + 256) / 256), 256, 0, st>>>(dx, count);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     for (int a = 0; a < pr.sh; ++a) {
         const Phase ph = make_phase(a, pr.sh, pr.R, pr.ph, pr.H);
-        if (ph.cnt == 0) continue;
+        if (ph.cnt == 0 || ph.J == 0) continue;
         for (int b = 0; b < pr.sw; ++b) {
             const Phase pw = make_phase(b, pr.sw, pr.S, pr.pw, pr.W);
-            if (pw.cnt == 0) continue;
+            if (pw.cnt == 0 || pw.J == 0) continue;
             TileArgs t{};
             t.src = dy; t.wgt = w; t.dst = dx;
             t.N = pr.N; t.Csrc = pr.K; t.IH = pr.P; t.IW = pr.Q;
