@@ -952,17 +952,226 @@ hipError_t launch_strip_wgrad(DwStripWArgs a, float* dw, int* wsplit, hipStream_
     return hipGetLastError();
 }
 
+// ====================================================================================================
+// Row kernels: planes of any size, no LDS.  A thread produces four neighbouring outputs of one row
+// (one 16-byte store) from bounds-checked 4-byte buffer loads; a workgroup covers consecutive rows
+// of a plane, so the rows its threads share come out of the L1/L2 caches.  Used where a
+// padded plane does not fit the strip kernels' LDS regions (112x112, 56x56 planes) and for
+// backward-data at stride 2, which the LDS kernels do not do.
+// ====================================================================================================
+struct DwRowArgs {
+    const void* src;   // x (forward) or dy (backward-data)
+    const void* w;
+    float* dst;
+    int planes, C;
+    int IH, IW, OH, OW;    // source and destination plane sizes
+    int pad_h, pad_w;
+    int flip;              // stride-1 backward-data = forward with the filter rotated by 180 degrees
+    int bx;                // groups of four columns per row
+    long long items;       // planes * OH * bx
+    unsigned src_bytes, w_bytes;
+};
+
+// BWD2: backward-data of a stride-2 convolution, dst = dx, src = dy:
+//   dx[h][w] = sum over taps (r, s) with (h + pad - r) and (w + pad - s) even of dy[(h+pad-r)/2][(w+pad-s)/2] w[r][s];
+// otherwise dst[oh][ow] = sum_{r,s} src[oh*ST - pad + r][ow*ST - pad + s] w[r][s].
+template <typename T, int ST, bool BWD2>
+__global__ __launch_bounds__(256) void dw_rows_kernel(DwRowArgs a) {
+    constexpr unsigned ESZ = sizeof(T);
+    const T* const tnull = nullptr;
+    // items (plane, row, group of four columns) in row-major order, 256 per workgroup: small planes share a
+    // workgroup, large ones give it a band of rows
+    const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (item >= a.items) return;
+    const int qi = (int)(item % a.bx);
+    const long long rest = item / a.bx;
+    const int oh = (int)(rest % a.OH), plane = (int)(rest / a.OH);
+    const int ow0 = qi * 4;
+    const int c = plane % a.C;
+    const rsrc_t srs = make_rsrc(a.src, a.src_bytes), wrs = make_rsrc(a.w, a.w_bytes);
+    float wv[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) wv[t] = buf_load(wrs, (unsigned)(c * 9 + (a.flip ? 8 - t : t)) * ESZ, tnull);
+    const unsigned pbase = (unsigned)plane * (unsigned)(a.IH * a.IW);
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (!BWD2) {
+        constexpr int NC = 3 * ST + 3;   // source columns under four outputs
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int ih = oh * ST - a.pad_h + r;
+            const bool rok = ih >= 0 && ih < a.IH;
+            float xv[NC];
+#pragma unroll
+            for (int j = 0; j < NC; ++j) {
+                const int iw = ow0 * ST - a.pad_w + j;
+                xv[j] = buf_load(srs, rok && iw >= 0 && iw < a.IW ? (pbase + (unsigned)(ih * a.IW + iw)) * ESZ : kOob, tnull);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int ss = 0; ss < 3; ++ss) acc[i] = fmaf(xv[i * ST + ss], wv[r * 3 + ss], acc[i]);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int t = oh + a.pad_h - r;
+            const bool rok = t >= 0 && (t & 1) == 0 && (t >> 1) < a.IH;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int ss = 0; ss < 3; ++ss) {
+                    const int u = ow0 + i + a.pad_w - ss;
+                    const bool ok = rok && u >= 0 && (u & 1) == 0 && (u >> 1) < a.IW;
+                    const float v = buf_load(srs, ok ? (pbase + (unsigned)((t >> 1) * a.IW + (u >> 1))) * ESZ : kOob, tnull);
+                    acc[i] = fmaf(v, wv[r * 3 + ss], acc[i]);
+                }
+        }
+    }
+    float* o = a.dst + (size_t)plane * a.OH * a.OW + (size_t)oh * a.OW + ow0;
+    if (ow0 + 4 <= a.OW && reinterpret_cast<uintptr_t>(o) % 16 == 0) {
+        *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (ow0 + i < a.OW) o[i] = acc[i];
+    }
+}
+
+// false when the shape is not a 3x3 depthwise forward / backward-data this kernel family does.
+bool rows_args(int pass, const Problem& pr, const void* in0, const void* in1, float* out, DwRowArgs& a, int& st, bool& bwd2) {
+    if (!is_depthwise(pr) || pr.R != 3 || pr.S != 3 || pr.sh != pr.sw || pr.sh > 2 || pass > 1) return false;
+    const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
+    if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
+    a.src = in0; a.w = in1; a.dst = out;
+    a.planes = pr.N * pr.C; a.C = pr.C;
+    bwd2 = pass == 1 && pr.sh == 2;
+    if (pass == 0) {
+        a.IH = pr.H; a.IW = pr.W; a.OH = pr.P; a.OW = pr.Q; a.pad_h = pr.ph; a.pad_w = pr.pw; a.flip = 0;
+        st = pr.sh;
+    } else {
+        a.IH = pr.P; a.IW = pr.Q; a.OH = pr.H; a.OW = pr.W;
+        a.pad_h = bwd2 ? pr.ph : 2 - pr.ph; a.pad_w = bwd2 ? pr.pw : 2 - pr.pw;
+        a.flip = bwd2 ? 0 : 1;
+        st = bwd2 ? 2 : 1;
+    }
+    a.bx = (a.OW + 3) / 4;
+    a.items = (long long)a.planes * a.OH * a.bx;
+    if ((a.items + 255) / 256 >= (1ll << 31)) return false;
+    a.src_bytes = (unsigned)((size_t)a.planes * a.IH * a.IW * esz);
+    a.w_bytes = (unsigned)((size_t)pr.C * 9 * esz);
+    return true;
+}
+
+template <typename T>
+hipError_t launch_rows(const DwRowArgs& a, int st, bool bwd2, hipStream_t stream) {
+    const unsigned grid = (unsigned)((a.items + 255) / 256);
+    if (bwd2) dw_rows_kernel<T, 2, true><<<grid, 256, 0, stream>>>(a);
+    else if (st == 1) dw_rows_kernel<T, 1, false><<<grid, 256, 0, stream>>>(a);
+    else dw_rows_kernel<T, 2, false><<<grid, 256, 0, stream>>>(a);
+    return hipGetLastError();
+}
+
+// Backward-weight without LDS staging, for planes of any size.  A workgroup owns one channel and a contiguous
+// share of its (image, output row, group of four columns) items; a thread adds 4 x 9 products per item into
+// nine sums, which are then combined over the workgroup in a fixed order (lanes by butterfly, waves in order).
+// Partial sums of the workgroups of a channel go to the workspace and are added by a second kernel.
+struct DwRowWArgs {
+    const void* x;
+    const void* dy;
+    float* out;            // [nsplit][C*9], or dw when nsplit == 1
+    int N, C, H, W, P, Q, pad_h, pad_w;
+    int qd;                // groups of four output columns per row
+    int nsplit;
+    long long items;       // N * P * qd
+    unsigned x_bytes, y_bytes;
+};
+
+template <typename T, int ST>
+__global__ __launch_bounds__(256) void dw_rows_wgrad_kernel(DwRowWArgs a) {
+    constexpr unsigned ESZ = sizeof(T);
+    constexpr int NC = 3 * ST + 3;
+    __shared__ float red[4 * 9];
+    const T* const tnull = nullptr;
+    const int c = blockIdx.x % a.C, sp = blockIdx.x / a.C;
+    const long long e0 = a.items * sp / a.nsplit, e1 = a.items * (sp + 1) / a.nsplit;
+    const rsrc_t xrs = make_rsrc(a.x, a.x_bytes), yrs = make_rsrc(a.dy, a.y_bytes);
+    float acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) acc[t] = 0.f;
+    for (long long e = e0 + threadIdx.x; e < e1; e += 256) {
+        const int q0 = (int)(e % a.qd) * 4;
+        const long long rest = e / a.qd;
+        const int p = (int)(rest % a.P), n = (int)(rest / a.P);
+        const unsigned ybase = (unsigned)(((n * a.C + c) * a.P + p) * a.Q);
+        float yv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) yv[i] = buf_load(yrs, q0 + i < a.Q ? (ybase + (unsigned)(q0 + i)) * ESZ : kOob, tnull);
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            const int ih = p * ST - a.pad_h + r;
+            const bool rok = ih >= 0 && ih < a.H;
+            const unsigned xbase = (unsigned)(((n * a.C + c) * a.H + ih) * a.W);
+            float xv[NC];
+#pragma unroll
+            for (int j = 0; j < NC; ++j) {
+                const int iw = q0 * ST - a.pad_w + j;
+                xv[j] = buf_load(xrs, rok && iw >= 0 && iw < a.W ? (xbase + (unsigned)iw) * ESZ : kOob, tnull);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int ss = 0; ss < 3; ++ss) acc[r * 3 + ss] = fmaf(yv[i], xv[i * ST + ss], acc[r * 3 + ss]);
+        }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        float v = acc[t];
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+        if (lane == 0) red[wave * 9 + t] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < 9) {
+        const float sum = ((red[threadIdx.x] + red[9 + threadIdx.x]) + red[18 + threadIdx.x]) + red[27 + threadIdx.x];
+        a.out[(size_t)sp * a.C * 9 + (size_t)c * 9 + threadIdx.x] = sum;
+    }
+}
+
+bool rows_wgrad_args(const Problem& pr, const void* x, const void* dy, DwRowWArgs& a) {
+    if (!is_depthwise(pr) || pr.R != 3 || pr.S != 3 || pr.sh != pr.sw || pr.sh > 2) return false;
+    const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
+    if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
+    a.x = x; a.dy = dy;
+    a.N = pr.N; a.C = pr.C; a.H = pr.H; a.W = pr.W; a.P = pr.P; a.Q = pr.Q; a.pad_h = pr.ph; a.pad_w = pr.pw;
+    a.qd = (pr.Q + 3) / 4;
+    a.items = (long long)pr.N * pr.P * a.qd;
+    // about 4096 workgroups, each with at least four items per thread
+    long long ns = (4096 + pr.C - 1) / pr.C;
+    const long long most = a.items / 1024 > 0 ? a.items / 1024 : 1;
+    if (ns > most) ns = most;
+    a.nsplit = (int)ns;
+    a.x_bytes = (unsigned)((size_t)pr.N * pr.C * pr.H * pr.W * esz);
+    a.y_bytes = (unsigned)((size_t)pr.N * pr.C * pr.P * pr.Q * esz);
+    return true;
+}
+
 }  // namespace
 
 bool depthwise_supports(int pass, const Problem& pr) {
     if (pass == 2) {
         DwWArgs a{};
         DwStripWArgs b{};
-        return strip_wgrad_args(pr, nullptr, nullptr, b) || wgrad_args(pr, nullptr, nullptr, a);
+        DwRowWArgs r{};
+        return strip_wgrad_args(pr, nullptr, nullptr, b) || wgrad_args(pr, nullptr, nullptr, a) ||
+               rows_wgrad_args(pr, nullptr, nullptr, r);
     }
     DwArgs a{};
     int stride;
-    return stencil_args(pass, pr, nullptr, nullptr, nullptr, a, stride);
+    if (stencil_args(pass, pr, nullptr, nullptr, nullptr, a, stride)) return true;
+    DwRowArgs r{};
+    bool bwd2;
+    return rows_args(pass, pr, nullptr, nullptr, nullptr, r, stride, bwd2);
 }
 
 size_t depthwise_workspace_bytes(int pass, const Problem& pr) {
@@ -970,8 +1179,10 @@ size_t depthwise_workspace_bytes(int pass, const Problem& pr) {
     DwStripWArgs b{};
     if (strip_wgrad_args(pr, nullptr, nullptr, b)) return b.wsplit > 1 ? (size_t)b.wsplit * pr.C * 9 * sizeof(float) : 0;
     DwWArgs a{};
-    if (!wgrad_args(pr, nullptr, nullptr, a)) return 0;
-    return a.nsplit > 1 ? (size_t)a.nsplit * pr.C * 9 * sizeof(float) : 0;
+    if (wgrad_args(pr, nullptr, nullptr, a)) return a.nsplit > 1 ? (size_t)a.nsplit * pr.C * 9 * sizeof(float) : 0;
+    DwRowWArgs r{};
+    if (!rows_wgrad_args(pr, nullptr, nullptr, r)) return 0;
+    return r.nsplit > 1 ? (size_t)r.nsplit * pr.C * 9 * sizeof(float) : 0;
 }
 
 hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
@@ -990,7 +1201,23 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
             return hipGetLastError();
         }
         DwWArgs a{};
-        if (!wgrad_args(pr, in0, in1, a)) return hipErrorNotSupported;
+        if (!wgrad_args(pr, in0, in1, a)) {
+            DwRowWArgs r{};
+            if (!rows_wgrad_args(pr, in0, in1, r)) return hipErrorNotSupported;
+            r.out = r.nsplit > 1 ? static_cast<float*>(ws) : out;
+            const unsigned grid = (unsigned)(pr.C * r.nsplit);
+            if (pr.dtype == 0) {
+                if (pr.sh == 1) dw_rows_wgrad_kernel<float, 1><<<grid, 256, 0, st>>>(r);
+                else dw_rows_wgrad_kernel<float, 2><<<grid, 256, 0, st>>>(r);
+            } else {
+                if (pr.sh == 1) dw_rows_wgrad_kernel<uint16_t, 1><<<grid, 256, 0, st>>>(r);
+                else dw_rows_wgrad_kernel<uint16_t, 2><<<grid, 256, 0, st>>>(r);
+            }
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess || r.nsplit == 1) return e;
+            dw_reduce_splits_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, r.nsplit, count);
+            return hipGetLastError();
+        }
         a.out = a.nsplit > 1 ? static_cast<float*>(ws) : out;
         const int pps = a.PPH * a.PPW, yplane = pr.P * pr.Q;
         const int per_plane = pps + yplane > a.G4 * 9 ? pps + yplane : a.G4 * 9;
@@ -1014,9 +1241,15 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
         if (pr.dtype == 0) return stride == 1 ? launch_strip_stencil<float, 1>(sa, st) : launch_strip_stencil<float, 2>(sa, st);
         return stride == 1 ? launch_strip_stencil<uint16_t, 1>(sa, st) : launch_strip_stencil<uint16_t, 2>(sa, st);
     }
+    // planes that fit the LDS budget of a workgroup (56x56: 200 us where the row kernel takes 286)
     DwArgs a{};
-    if (!stencil_args(pass, pr, in0, in1, out, a, stride)) return hipErrorNotSupported;
-    return pr.dtype == 0 ? launch_stencil<float>(a, stride, st) : launch_stencil<uint16_t>(a, stride, st);
+    if (stencil_args(pass, pr, in0, in1, out, a, stride))
+        return pr.dtype == 0 ? launch_stencil<float>(a, stride, st) : launch_stencil<uint16_t>(a, stride, st);
+    // larger planes, and backward-data at stride 2: the row kernels
+    DwRowArgs ra{};
+    bool bwd2;
+    if (!rows_args(pass, pr, in0, in1, out, ra, stride, bwd2)) return hipErrorNotSupported;
+    return pr.dtype == 0 ? launch_rows<float>(ra, stride, bwd2, st) : launch_rows<uint16_t>(ra, stride, bwd2, st);
 }
 
 }  // namespace miconv

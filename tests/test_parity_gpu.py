@@ -209,7 +209,11 @@ DW = [
     # name    N   C   H   W  stride pad
     ("dw14", 3, 40, 14, 14, 1, 1),
     ("dw7", 2, 70, 7, 7, 1, 1),        # 49 outputs per plane: ragged groups of four, scalar stores
-    ("dw28s2", 2, 24, 28, 28, 2, 1),   # stride 2: forward and backward-weight only on this path
+    ("dw28s2", 2, 24, 28, 28, 2, 1),   # stride 2: backward-data on the row kernel
+    ("dw29s2", 2, 6, 29, 31, 2, 1),    # stride 2, odd sizes: the last row and column of dx see fewer taps
+    ("dw16s2p0", 1, 5, 16, 18, 2, 0),  # stride 2 without padding: the last input row and column feed nothing
+    ("dw112", 1, 3, 112, 112, 1, 1),   # planes too large for the LDS kernels: the row kernels
+    ("dw60x70s2", 1, 4, 60, 70, 2, 1), # ... at stride 2, ragged 16 x 64 blocks
     ("dw9x13", 5, 33, 9, 13, 1, 0),    # no padding, non-square
     ("dw15p2", 1, 17, 15, 15, 1, 2),   # padding wider than the filter reach
     ("dw56", 1, 8, 56, 56, 1, 1),
@@ -226,8 +230,7 @@ def test_depthwise_shapes(row, dtype):
     from paper_1912_01703_amd import binding as mc
     name, N, C, H, W, st, pd = row
     L = wl.custom_layer(name, N, C, H, W, C, 3, 3, st, pd, C, seed=3000 + DW.index(row))
-    passes = ("fwd", "bwd_weight") if st != 1 else pu.PASSES
-    pu.check_layer_full(L, dtype, passes=passes, algo=mc.ALGO_DEPTHWISE, expect_algo=mc.ALGO_DEPTHWISE)
+    pu.check_layer_full(L, dtype, algo=mc.ALGO_DEPTHWISE, expect_algo=mc.ALGO_DEPTHWISE)
 
 
 @pytest.mark.parametrize("name", ["2a", "2b", "2c", "3", "5a", "5b"])
