@@ -39,6 +39,11 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
     if (R == 3 && S == 3 && stride == 1) {
         // eight waves: two per SIMD, so one wave's LDS and barrier waits are covered by the other's MFMAs
         if (dry) return true;
+        // planes of at most 7 x 7 pixels: a 7 x 7 tile is 4 pixel blocks (a 14 x 14 tile would run 13 for 3.06)
+        if (a.OH <= 7 && a.OW <= 7) {
+            *err = launch_tile<T, 3, 3, 1, 7, 7, 16, 4, 2, BWD>(a, st);
+            return true;
+        }
         // Few chunks per item and many items: persistent workgroups hide each item's start-up and write-out
         const long long ids = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
         // Wide planes take 12 x 16 tiles: 12 pixel blocks without a ragged one (14 x 14 = 12.25 blocks run as 13), and
@@ -52,6 +57,10 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
         if (dry) return true;
         // 32-channel chunks on eight waves (64-channel chunks leave one workgroup per CU: 80 instead of 68 us on
         // the 1024 -> 256 channel layer); persistent workgroups when there are many short items
+        if (a.OH <= 7 && a.OW <= 7) {
+            *err = launch_tile<T, 1, 1, 1, 7, 7, 32, 4, 2, BWD>(a, st);
+            return true;
+        }
         const long long ids = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
         if (a.Rg <= 256 && ids >= 1024) *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD, 3, true>(a, st);
         else *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD>(a, st);

@@ -72,6 +72,9 @@ MFMA = [
     ("m3x3s2c", 2, 16, 16, 16, 24, 3, 3, 2, 0, 1),    # no padding: the last input row/column feeds nothing
     ("m3x3s2g", 1, 32, 14, 14, 32, 3, 3, 2, 1, 2),
     ("m3x3s2d", 2, 24, 57, 60, 40, 3, 3, 2, 1, 1),    # merged-phase backward-data over several ragged tiles
+    ("m3x3z", 5, 40, 7, 7, 72, 3, 3, 1, 1, 1),        # 7 x 7 planes: tiles of 7 x 7 pixels
+    ("m1x1z", 6, 72, 7, 7, 136, 1, 1, 1, 0, 1),
+    ("m3x3y", 3, 24, 6, 5, 24, 3, 3, 1, 1, 1),        # ... smaller than the tile
     ("m1x1s2", 3, 40, 28, 28, 72, 1, 1, 2, 0, 1),     # 1x1 stride 2: three of four dx phases receive nothing
     ("m1x1s2b", 2, 136, 15, 19, 24, 1, 1, 2, 0, 1),   # ... odd sizes, more than one 128-channel block
 ]
