@@ -561,6 +561,11 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
     *err = hipSuccess;
     *ws_bytes = 0;
     if (pr.sh != pr.sw) return false;
+    if (pr.R == 3 && pr.S == 3 && pr.sh == 1 && pr.P <= 7 && pr.Q <= 7) {
+        // planes of at most 7 x 7 pixels: stages of four images x 7 x 8 pixels (the eighth column lies outside the image)
+        *err = launch_wgrad<T, 3, 3, 1, 7, 8, 1, 1, 1, 1, 8, 8, 4>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        return true;
+    }
     if (pr.R == 3 && pr.S == 3 && pr.sh == 1) {
         *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 8, 8, 2>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
@@ -571,6 +576,10 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 2) {
         *err = launch_wgrad<T, 1, 1, 2, 2, 14, 8, 8, 2, 2, 1, 1, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        return true;
+    }
+    if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && pr.P <= 7 && pr.Q <= 7) {
+        *err = launch_wgrad<T, 1, 1, 1, 7, 8, 8, 8, 2, 2, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1) {
