@@ -19,8 +19,9 @@ hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
     const bool wv = a.Rg % (CK / 4) == 0 && a.Rg % 4 == 0;   // forward filters can be read four values at a time
     if constexpr (R == 1 && S == 1 && ST == 1 && sizeof(T) == 4 && (TH * TW) % 4 == 0) {
         // patch == plane: contiguous chunks, 16 bytes per lane
-        const bool plane_patch = a.pad_h == 0 && a.pad_w == 0 && a.IH == TH && a.IW == TW && a.OH == TH && a.OW == TW &&
-                                 reinterpret_cast<uintptr_t>(a.src) % 16 == 0;
+        // (a ragged last band reads rows of the next channel or zeros past the tensor; those pixels are not stored)
+        const bool plane_patch = a.pad_h == 0 && a.pad_w == 0 && a.IW == TW && a.OW == TW && a.IH == a.OH &&
+                                 (a.IH * a.IW) % 4 == 0 && reinterpret_cast<uintptr_t>(a.src) % 16 == 0;
         if (plane_patch) {
             if (wv) conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true, false, NBUF, true, PERSIST><<<grid, 64 * WF * WP, 0, st>>>(a);
             else conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, false, false, NBUF, true, PERSIST><<<grid, 64 * WF * WP, 0, st>>>(a);
@@ -60,6 +61,17 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
         if (a.OH <= 7 && a.OW <= 7) {
             *err = launch_tile<T, 1, 1, 1, 7, 7, 32, 4, 2, BWD>(a, st);
             return true;
+        }
+        // planes 28, 56 or 112 pixels wide: bands of full rows, 224 pixels = 14 blocks, fetched 16 bytes per lane; two
+        // patch buffers, so that two workgroups share a CU
+        if constexpr (sizeof(T) == 4) {
+            if (a.pad_h == 0 && a.pad_w == 0 && a.IH == a.OH && a.IW == a.OW && (a.OW == 28 || a.OW == 56 || a.OW == 112) &&
+                reinterpret_cast<uintptr_t>(a.src) % 16 == 0) {
+                if (a.OW == 28) *err = launch_tile<T, 1, 1, 1, 8, 28, 32, 4, 2, BWD, 2, true>(a, st);
+                else if (a.OW == 56) *err = launch_tile<T, 1, 1, 1, 4, 56, 32, 4, 2, BWD, 2, true>(a, st);
+                else *err = launch_tile<T, 1, 1, 1, 2, 112, 32, 4, 2, BWD, 2, true>(a, st);
+                return true;
+            }
         }
         const long long ids = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
         if (a.Rg <= 256 && ids >= 1024) *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD, 3, true>(a, st);

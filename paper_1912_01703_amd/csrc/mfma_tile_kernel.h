@@ -98,7 +98,7 @@ constexpr int lds_channel_stride(int v, int kq) {
 //     reach it, so the nine taps of the filter split over four accumulator sets that all read the same dy
 //     patch: a work item is a 14x14 rectangle of the half-resolution grid (28x28 dx pixels).  With
 //     h = 2*i + 1 - a for grid row i, tap r reads dy row i + (r == 0), see roff() below.
-// XW: the patch is the whole source plane (1x1 filter, no padding, one tile per image) and planes are
+// XW: the patch is TH full rows of the source plane (1x1 filter, no padding, tile as wide as the plane) and planes are
 //     multiples of 16 bytes: a chunk's patch is then one contiguous run of CK planes, read 16 bytes per lane.
 template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, bool WV, bool PHASE, int NBUF = 3,
           bool XW = false, bool PERSIST = false, bool MERGE2 = false>
@@ -178,8 +178,11 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 #pragma unroll
         for (int m = 0; m < XPT; ++m) {
             if constexpr (XW) {
-                const int f = tid + NT * m;                       // 16-byte piece of the chunk's CK planes
-                goff[m] = f < XE / 4 ? (unsigned)(4 * f) * 4u : kOob;
+                // 16-byte piece of the chunk's CK channels: TH full rows per channel, one contiguous run starting at
+                // the tile's first row (the whole plane when the tile is the plane)
+                const int f = tid + NT * m;
+                const int c = (4 * f) / PSZ, rem = 4 * f - c * PSZ;
+                goff[m] = f < XE / 4 ? (unsigned)(c * plane + it.oh0 * a.IW + rem) * 4u : kOob;
             } else {
                 const int e = tid + NT * m;
                 const int c = e / PSZ, rem = e - c * PSZ;

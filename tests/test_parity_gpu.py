@@ -63,7 +63,10 @@ MFMA = [
     ("m3x3t", 2, 3, 20, 20, 10, 3, 3, 1, 1, 1),       # reduction channels not a multiple of the chunk
     ("m3x3u", 2, 21, 14, 14, 35, 3, 3, 1, 1, 1),
     ("m1x1c", 3, 200, 14, 14, 136, 1, 1, 1, 0, 1),    # several 128-wide blocks with ragged edges
-    ("m1x1d", 2, 72, 20, 28, 40, 1, 1, 1, 0, 1),      # few filters: 64-wide blocks in backward-weight, two of them along C
+    ("m1x1d", 2, 72, 20, 28, 40, 1, 1, 1, 0, 1),      # few filters: 64-wide blocks in backward-weight, two of them along C;
+                                                      # 28 pixels wide: bands of 8 full rows, the last one ragged
+    ("m1x1e", 1, 72, 9, 56, 40, 1, 1, 1, 0, 1),       # 56 wide: bands of 4 rows, three chunks
+    ("m1x1f", 2, 16, 5, 112, 24, 1, 1, 1, 0, 1),      # 112 wide: bands of 2 rows, a partial chunk
     ("m3x3n", 9, 16, 14, 14, 16, 3, 3, 1, 1, 1),      # more images than one split holds
     ("m3x3p", 5, 16, 210, 210, 24, 3, 3, 1, 1, 1),    # > 1024 work items of one chunk: persistent workgroups
     ("m3x3q", 3, 40, 200, 206, 72, 3, 3, 1, 1, 1),    # ... with two filter blocks, three chunks, ragged tiles
