@@ -45,6 +45,9 @@ def parse():
                          "(a kernel of known HBM traffic, used to scale the rocprofv3 FETCH_SIZE/WRITE_SIZE counters)")
     ap.add_argument("--settle-ms", type=float, default=60.0,
                     help="untimed steps are run for this long before the warm-up steps so that the GPU clock has ramped up")
+    ap.add_argument("--sweep", action="store_true",
+                    help="instead of the benchmark, time further ResNet / VGG / MobileNet layer shapes (fp32) and print "
+                         "one JSON line with a list of per-pass timings")
     ap.add_argument("--rotate", type=int, default=0,
                     help="number of distinct buffer sets cycled between steps (0: auto; "
                          "bandwidth-bound layers use enough to exceed the 256 MB Infinity Cache)")
@@ -97,6 +100,48 @@ def cpu_baseline(L, dtype):
             "sample": f"layer {L.name} with N={n_sub} of {L.N} images, fwd+bwd_data+bwd_weight once, fp64 accumulate"}
 
 
+def sweep(mc, wl, torch):
+    """Times every pass of wl.MORE_SHAPES (fp32, random inputs, back-to-back launches between two events)."""
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream().cuda_stream
+    rows = []
+    for (name, N, C, H, W, K, R, st, pd, g) in wl.MORE_SHAPES:
+        L = wl.custom_layer(name, N, C, H, W, K, R, R, st, pd, g)
+        args = L.conv_args()
+        x = torch.randn(L.x_shape, device=dev)
+        w = torch.randn(L.w_shape, device=dev)
+        dy = torch.randn(L.y_shape, device=dev)
+        y, dx, dw = (torch.empty(sh, device=dev) for sh in (L.y_shape, L.x_shape, L.w_shape))
+        ws = torch.empty(max([256] + [mc.conv2d_workspace_bytes(p, *args, mc.F32) for p in range(3)]),
+                         dtype=torch.uint8, device=dev)
+        calls = [lambda: mc.conv2d_fwd(x, w, y, *args, mc.F32, ws, stream),
+                 lambda: mc.conv2d_bwd_data(dy, w, dx, *args, mc.F32, ws, stream),
+                 lambda: mc.conv2d_bwd_weight(x, dy, dw, *args, mc.F32, ws, stream)]
+        row = {"layer": name, "flops_per_pass": L.flops, "bytes_x_plus_y": (x.numel() + y.numel()) * 4}
+        for p, call in enumerate(calls):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            call()
+            torch.cuda.synchronize()
+            e0.record(); call(); e1.record()
+            torch.cuda.synchronize()
+            reps = max(3, min(200, int(30.0 / max(e0.elapsed_time(e1), 1e-3))))
+            for _ in range(reps):
+                call()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                call()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            row[PASSES[p]] = {"ms": ms, "tflops": L.flops / (ms * 1e-3) / 1e12, "algo": mc.miconv_last_algo(p)}
+        rows.append(row)
+        sys.stderr.write("%-32s " % name + " | ".join("%9.1f us %6.1f TF a%d" % (row[k]["ms"] * 1e3, row[k]["tflops"], row[k]["algo"])
+                                                     for k in PASSES) + "\n")
+        del x, w, dy, y, dx, dw, ws
+    print(json.dumps({"sweep": rows}), flush=True)
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -119,6 +164,9 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_calibration": True, "bytes_read_per_copy": nbytes, "bytes_written_per_copy": nbytes,
                           "copies": a.steps}), flush=True)
+        return
+    if a.sweep:
+        sweep(mc, wl, torch)
         return
     L = wl.LAYERS[a.layer]
     code = mc.BF16_F32ACC if a.dtype == "bf16" else mc.F32

@@ -144,3 +144,33 @@ def sample_indices(shape, count, seed):
         return np.arange(total, dtype=np.int64)
     extra = rng.integers(0, total, size=max(0, count - forced.size), dtype=np.int64)
     return np.unique(np.concatenate([forced, extra]))
+
+
+# Further layer shapes of the networks the benchmark layers come from (ResNet-50, VGG, MobileNet): a second
+# sweep for `bench.py --sweep`; not part of the nine benchmark layers.  (name, N, C, H, W, K, R, stride, pad, groups)
+MORE_SHAPES = [
+    ("resnet stem 7x7 s2 3->64 224", 64, 3, 224, 224, 64, 7, 2, 3, 1),
+    ("resnet 3x3 64 56x56", 64, 64, 56, 56, 64, 3, 1, 1, 1),
+    ("resnet 1x1 64->256 56x56", 64, 64, 56, 56, 256, 1, 1, 0, 1),
+    ("resnet 1x1 256->64 56x56", 64, 256, 56, 56, 64, 1, 1, 0, 1),
+    ("resnet 1x1 s2 256->512 56->28", 64, 256, 56, 56, 512, 1, 2, 0, 1),
+    ("resnet 3x3 128 28x28", 64, 128, 28, 28, 128, 3, 1, 1, 1),
+    ("resnet 1x1 512->128 28x28", 64, 512, 28, 28, 128, 1, 1, 0, 1),
+    ("resnet 3x3 s2 256 28->14", 64, 256, 28, 28, 256, 3, 2, 1, 1),
+    ("resnet 3x3 512 7x7", 64, 512, 7, 7, 512, 3, 1, 1, 1),
+    ("resnet 1x1 512->2048 7x7", 64, 512, 7, 7, 2048, 1, 1, 0, 1),
+    ("resnet 1x1 2048->512 7x7", 64, 2048, 7, 7, 512, 1, 1, 0, 1),
+    ("vgg 3x3 64->128 112x112", 32, 64, 112, 112, 128, 3, 1, 1, 1),
+    ("vgg 3x3 256 56x56", 32, 256, 56, 56, 256, 3, 1, 1, 1),
+    ("vgg 3x3 512 14x14", 64, 512, 14, 14, 512, 3, 1, 1, 1),
+    ("mobilenet dw 32 112x112", 128, 32, 112, 112, 32, 3, 1, 1, 32),
+    ("mobilenet dw s2 64 112->56", 128, 64, 112, 112, 64, 3, 2, 1, 64),
+    ("mobilenet dw 128 56x56", 128, 128, 56, 56, 128, 3, 1, 1, 128),
+    ("mobilenet dw s2 128 56->28", 128, 128, 56, 56, 128, 3, 2, 1, 128),
+    ("mobilenet dw 256 28x28", 128, 256, 28, 28, 256, 3, 1, 1, 256),
+    ("mobilenet dw s2 256 28->14", 128, 256, 28, 28, 256, 3, 2, 1, 256),
+    ("mobilenet dw s2 512 14->7", 128, 512, 14, 14, 512, 3, 2, 1, 512),
+    ("mobilenet dw 1024 7x7", 128, 1024, 7, 7, 1024, 3, 1, 1, 1024),
+    ("mobilenet pw 32->64 112x112", 128, 32, 112, 112, 64, 1, 1, 0, 1),
+    ("mobilenet pw 1024->1024 7x7", 128, 1024, 7, 7, 1024, 1, 1, 0, 1),
+]
