@@ -81,7 +81,7 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
     if (!BWD && R == 1 && S == 1 && stride == 2) {
         // the 1x1 stride-2 shortcut of a residual network: every other pixel of every other row
         if (dry) return true;
-        *err = launch_tile<T, 1, 1, 2, 14, 14, 8, 4, 2, false>(a, st);
+        *err = launch_tile<T, 1, 1, 2, 14, 14, 32, 4, 2, false>(a, st);
         return true;
     }
     if (!BWD && R == 3 && S == 3 && stride == 2) {

@@ -106,7 +106,12 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int NT = 64 * WF * WP;
     constexpr int RS = R * S;
     static_assert(!MERGE2 || (BWD && !PHASE && !XW && R == 3 && S == 3 && ST == 1), "merged stride-2 backward-data");
-    constexpr int PH = MERGE2 ? TH + 1 : (TH - 1) * ST + R, PW = MERGE2 ? TW + 1 : (TW - 1) * ST + S;
+    // A strided 1x1 filter only ever reads the pixels (oh*ST, ow*ST): the patch holds just those (SPARSE), not the
+    // (TH-1)*ST+1 rows and columns between them.
+    constexpr bool SPARSE = R == 1 && S == 1 && ST > 1 && !MERGE2;
+    constexpr int PST = SPARSE ? 1 : ST;     // pixel stride inside the LDS patch
+    constexpr int GST = SPARSE ? ST : 1;     // source stride between neighbouring patch elements
+    constexpr int PH = MERGE2 ? TH + 1 : (TH - 1) * PST + R, PW = MERGE2 ? TW + 1 : (TW - 1) * PST + S;
     constexpr int PSZ = PH * PW;
     constexpr int KQ = CK / 4;  // channels per lane group: lane group kk owns channels [kk*KQ, kk*KQ+KQ) of a chunk
     static_assert(CK == 4 || CK == 8 || CK == 16 || CK == 32 || CK == 64, "CK must be 4, 8, 16, 32 or 64");
@@ -187,7 +192,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
                 const int e = tid + NT * m;
                 const int c = e / PSZ, rem = e - c * PSZ;
                 const int ph = rem / PW, pw = rem - ph * PW;
-                const int ih = ih0 + ph, iw = iw0 + pw;
+                const int ih = ih0 + ph * GST, iw = iw0 + pw * GST;
                 const bool ok = (e < XE) && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
                 goff[m] = ok ? (unsigned)(c * plane + ih * a.IW + iw) * (unsigned)sizeof(T) : kOob;
             }
@@ -234,7 +239,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         int j = 16 * (wp + WP * i) + li;
         if (j >= NPX) j = 0;  // padding lanes read a valid address; their results are never stored
         const int th = j / TW, tw = j - th * TW;
-        pixoff[i] = kk * KQ * CS + th * ST * PW + tw * ST;
+        pixoff[i] = kk * KQ * CS + th * PST * PW + tw * PST;
     }
 
     const bool last_ok = wp + WP * (NBW - 1) < NB;   // does this wave own a block in its last slot?
