@@ -29,6 +29,7 @@ constexpr int kThreads = 256;
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 constexpr int kStream = 2;   // cache policy "non-temporal": data that is read once (3 % on the backward-weight kernel)
 constexpr unsigned kOob = 0x80000000u;
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
@@ -1001,10 +1002,35 @@ __global__ __launch_bounds__(256) void dw_rows_kernel(DwRowArgs a) {
             const int ih = oh * ST - a.pad_h + r;
             const bool rok = ih >= 0 && ih < a.IH;
             float xv[NC];
+            const int iw0 = ow0 * ST - a.pad_w;
+            const long long first = (long long)pbase + (long long)ih * a.IW + iw0;   // element index of the window's first column
+            if (sizeof(T) == 4 && first >= 0) {
+                // 16-byte loads (they need no more than 4-byte alignment; words past the end of the tensor read as
+                // zero one by one); columns left or right of the row hold the neighbouring rows' values: cleared.
+                const unsigned off = rok ? (unsigned)first * 4u : kOob;
 #pragma unroll
-            for (int j = 0; j < NC; ++j) {
-                const int iw = ow0 * ST - a.pad_w + j;
-                xv[j] = buf_load(srs, rok && iw >= 0 && iw < a.IW ? (pbase + (unsigned)(ih * a.IW + iw)) * ESZ : kOob, tnull);
+                for (int j0 = 0; j0 < NC; j0 += 4) {
+                    if (NC - j0 >= 4) {
+                        const v4u v = __builtin_amdgcn_raw_buffer_load_b128(srs, off + 4u * j0, 0, 0);
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) xv[j0 + k] = __uint_as_float(v[k]);
+                    } else if (NC - j0 >= 2) {
+                        const v2u v = __builtin_amdgcn_raw_buffer_load_b64(srs, off + 4u * j0, 0, 0);
+                        xv[j0] = __uint_as_float(v[0]); xv[j0 + 1] = __uint_as_float(v[1]);
+                        if (NC - j0 == 3) xv[j0 + 2] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(srs, off + 4u * (j0 + 2), 0, 0));
+                    } else {
+                        xv[j0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(srs, off + 4u * j0, 0, 0));
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < NC; ++j)
+                    if (iw0 + j < 0 || iw0 + j >= a.IW) xv[j] = 0.f;
+            } else {
+#pragma unroll
+                for (int j = 0; j < NC; ++j) {
+                    const int iw = iw0 + j;
+                    xv[j] = buf_load(srs, rok && iw >= 0 && iw < a.IW ? (pbase + (unsigned)(ih * a.IW + iw)) * ESZ : kOob, tnull);
+                }
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -1241,15 +1267,16 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
         if (pr.dtype == 0) return stride == 1 ? launch_strip_stencil<float, 1>(sa, st) : launch_strip_stencil<float, 2>(sa, st);
         return stride == 1 ? launch_strip_stencil<uint16_t, 1>(sa, st) : launch_strip_stencil<uint16_t, 2>(sa, st);
     }
-    // planes that fit the LDS budget of a workgroup (56x56: 200 us where the row kernel takes 286)
+    // bf16 planes that fit the LDS budget of a workgroup: the row kernel reads bf16 two bytes at a time
     DwArgs a{};
-    if (stencil_args(pass, pr, in0, in1, out, a, stride))
-        return pr.dtype == 0 ? launch_stencil<float>(a, stride, st) : launch_stencil<uint16_t>(a, stride, st);
+    if (pr.dtype != 0 && stencil_args(pass, pr, in0, in1, out, a, stride)) return launch_stencil<uint16_t>(a, stride, st);
     // larger planes, and backward-data at stride 2: the row kernels
     DwRowArgs ra{};
     bool bwd2;
-    if (!rows_args(pass, pr, in0, in1, out, ra, stride, bwd2)) return hipErrorNotSupported;
-    return pr.dtype == 0 ? launch_rows<float>(ra, stride, bwd2, st) : launch_rows<uint16_t>(ra, stride, bwd2, st);
+    if (rows_args(pass, pr, in0, in1, out, ra, stride, bwd2))
+        return pr.dtype == 0 ? launch_rows<float>(ra, stride, bwd2, st) : launch_rows<uint16_t>(ra, stride, bwd2, st);
+    if (!stencil_args(pass, pr, in0, in1, out, a, stride)) return hipErrorNotSupported;
+    return pr.dtype == 0 ? launch_stencil<float>(a, stride, st) : launch_stencil<uint16_t>(a, stride, st);
 }
 
 }  // namespace miconv
