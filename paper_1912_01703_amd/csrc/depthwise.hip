@@ -960,6 +960,30 @@ hipError_t launch_strip_wgrad(DwStripWArgs a, float* dw, int* wsplit, hipStream_
 // padded plane does not fit the strip kernels' LDS regions (112x112, 56x56 planes) and for
 // backward-data at stride 2, which the LDS kernels do not do.
 // ====================================================================================================
+// NC consecutive floats of a row starting at byte offset `off` (kOob: none), as 16-, 8- and 4-byte loads.  They need no
+// more than 4-byte alignment, and words past the end of the tensor read as zero one by one.  Columns left or right of
+// the row (iw0 + j outside [0, IW)) hold the neighbouring rows' values and are cleared.
+template <int NC>
+__device__ __forceinline__ void load_window(rsrc_t srs, unsigned off, int iw0, int IW, float (&xv)[NC]) {
+#pragma unroll
+    for (int j0 = 0; j0 < NC; j0 += 4) {
+        if (NC - j0 >= 4) {
+            const v4u v = __builtin_amdgcn_raw_buffer_load_b128(srs, off + 4u * j0, 0, 0);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) xv[j0 + k] = __uint_as_float(v[k]);
+        } else if (NC - j0 >= 2) {
+            const v2u v = __builtin_amdgcn_raw_buffer_load_b64(srs, off + 4u * j0, 0, 0);
+            xv[j0] = __uint_as_float(v[0]); xv[j0 + 1] = __uint_as_float(v[1]);
+            if (NC - j0 == 3) xv[j0 + 2] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(srs, off + 4u * (j0 + 2), 0, 0));
+        } else {
+            xv[j0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(srs, off + 4u * j0, 0, 0));
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < NC; ++j)
+        if (iw0 + j < 0 || iw0 + j >= IW) xv[j] = 0.f;
+}
+
 struct DwRowArgs {
     const void* src;   // x (forward) or dy (backward-data)
     const void* w;
@@ -1005,26 +1029,7 @@ __global__ __launch_bounds__(256) void dw_rows_kernel(DwRowArgs a) {
             const int iw0 = ow0 * ST - a.pad_w;
             const long long first = (long long)pbase + (long long)ih * a.IW + iw0;   // element index of the window's first column
             if (sizeof(T) == 4 && first >= 0) {
-                // 16-byte loads (they need no more than 4-byte alignment; words past the end of the tensor read as
-                // zero one by one); columns left or right of the row hold the neighbouring rows' values: cleared.
-                const unsigned off = rok ? (unsigned)first * 4u : kOob;
-#pragma unroll
-                for (int j0 = 0; j0 < NC; j0 += 4) {
-                    if (NC - j0 >= 4) {
-                        const v4u v = __builtin_amdgcn_raw_buffer_load_b128(srs, off + 4u * j0, 0, 0);
-#pragma unroll
-                        for (int k = 0; k < 4; ++k) xv[j0 + k] = __uint_as_float(v[k]);
-                    } else if (NC - j0 >= 2) {
-                        const v2u v = __builtin_amdgcn_raw_buffer_load_b64(srs, off + 4u * j0, 0, 0);
-                        xv[j0] = __uint_as_float(v[0]); xv[j0 + 1] = __uint_as_float(v[1]);
-                        if (NC - j0 == 3) xv[j0 + 2] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(srs, off + 4u * (j0 + 2), 0, 0));
-                    } else {
-                        xv[j0] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(srs, off + 4u * j0, 0, 0));
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < NC; ++j)
-                    if (iw0 + j < 0 || iw0 + j >= a.IW) xv[j] = 0.f;
+                load_window<NC>(srs, rok ? (unsigned)first * 4u : kOob, iw0, a.IW, xv);
             } else {
 #pragma unroll
                 for (int j = 0; j < NC; ++j) {
@@ -1130,18 +1135,28 @@ __global__ __launch_bounds__(256) void dw_rows_wgrad_kernel(DwRowWArgs a) {
         const int p = (int)(rest % a.P), n = (int)(rest / a.P);
         const unsigned ybase = (unsigned)(((n * a.C + c) * a.P + p) * a.Q);
         float yv[4];
+        if (sizeof(T) == 4) {
+            load_window<4>(yrs, (ybase + (unsigned)q0) * 4u, q0, a.Q, yv);
+        } else {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) yv[i] = buf_load(yrs, q0 + i < a.Q ? (ybase + (unsigned)(q0 + i)) * ESZ : kOob, tnull);
+            for (int i = 0; i < 4; ++i) yv[i] = buf_load(yrs, q0 + i < a.Q ? (ybase + (unsigned)(q0 + i)) * ESZ : kOob, tnull);
+        }
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
             const int ih = p * ST - a.pad_h + r;
             const bool rok = ih >= 0 && ih < a.H;
-            const unsigned xbase = (unsigned)(((n * a.C + c) * a.H + ih) * a.W);
+            const int iw0 = q0 * ST - a.pad_w;
+            const long long first = ((long long)(n * a.C + c) * a.H + ih) * a.W + iw0;
             float xv[NC];
+            if (sizeof(T) == 4 && first >= 0) {
+                load_window<NC>(xrs, rok ? (unsigned)first * 4u : kOob, iw0, a.W, xv);
+            } else {
+                const unsigned xbase = (unsigned)(((n * a.C + c) * a.H + ih) * a.W);
 #pragma unroll
-            for (int j = 0; j < NC; ++j) {
-                const int iw = q0 * ST - a.pad_w + j;
-                xv[j] = buf_load(xrs, rok && iw >= 0 && iw < a.W ? (xbase + (unsigned)iw) * ESZ : kOob, tnull);
+                for (int j = 0; j < NC; ++j) {
+                    const int iw = iw0 + j;
+                    xv[j] = buf_load(xrs, rok && iw >= 0 && iw < a.W ? (xbase + (unsigned)iw) * ESZ : kOob, tnull);
+                }
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i)
@@ -1205,7 +1220,7 @@ size_t depthwise_workspace_bytes(int pass, const Problem& pr) {
     DwStripWArgs b{};
     if (strip_wgrad_args(pr, nullptr, nullptr, b)) return b.wsplit > 1 ? (size_t)b.wsplit * pr.C * 9 * sizeof(float) : 0;
     DwWArgs a{};
-    if (wgrad_args(pr, nullptr, nullptr, a)) return a.nsplit > 1 ? (size_t)a.nsplit * pr.C * 9 * sizeof(float) : 0;
+    if (pr.dtype != 0 && wgrad_args(pr, nullptr, nullptr, a)) return a.nsplit > 1 ? (size_t)a.nsplit * pr.C * 9 * sizeof(float) : 0;
     DwRowWArgs r{};
     if (!rows_wgrad_args(pr, nullptr, nullptr, r)) return 0;
     return r.nsplit > 1 ? (size_t)r.nsplit * pr.C * 9 * sizeof(float) : 0;
@@ -1227,7 +1242,7 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
             return hipGetLastError();
         }
         DwWArgs a{};
-        if (!wgrad_args(pr, in0, in1, a)) {
+        if (pr.dtype == 0 || !wgrad_args(pr, in0, in1, a)) {   // fp32: the row kernel (16-byte loads) also beats the LDS kernel
             DwRowWArgs r{};
             if (!rows_wgrad_args(pr, in0, in1, r)) return hipErrorNotSupported;
             r.out = r.nsplit > 1 ? static_cast<float*>(ws) : out;
