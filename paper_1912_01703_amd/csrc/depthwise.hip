@@ -960,6 +960,16 @@ hipError_t launch_strip_wgrad(DwStripWArgs a, float* dw, int* wsplit, hipStream_
 // padded plane does not fit the strip kernels' LDS regions (112x112, 56x56 planes) and for
 // backward-data at stride 2, which the LDS kernels do not do.
 // ====================================================================================================
+// n / d for n < 2^31 through a double-precision reciprocal (the integer divide of the compiler takes some forty
+// instructions, and 64-bit ones far more, which bounded the row kernels: they run one short thread per four outputs).
+__device__ __forceinline__ unsigned udiv(unsigned n, unsigned d, double inv) {
+    unsigned q = (unsigned)((double)n * inv);
+    const int r = (int)(n - q * d);
+    if (r < 0) --q;
+    else if ((unsigned)r >= d) ++q;
+    return q;
+}
+
 // NC consecutive floats of a row starting at byte offset `off` (kOob: none), as 16-, 8- and 4-byte loads.  They need no
 // more than 4-byte alignment, and words past the end of the tensor read as zero one by one.  Columns left or right of
 // the row (iw0 + j outside [0, IW)) hold the neighbouring rows' values and are cleared.
@@ -993,6 +1003,7 @@ struct DwRowArgs {
     int pad_h, pad_w;
     int flip;              // stride-1 backward-data = forward with the filter rotated by 180 degrees
     int bx;                // groups of four columns per row
+    double inv_bx, inv_oh; // reciprocals for the item decoding
     long long items;       // planes * OH * bx
     unsigned src_bytes, w_bytes;
 };
@@ -1008,15 +1019,30 @@ __global__ __launch_bounds__(256) void dw_rows_kernel(DwRowArgs a) {
     // workgroup, large ones give it a band of rows
     const long long item = (long long)blockIdx.x * 256 + threadIdx.x;
     if (item >= a.items) return;
-    const int qi = (int)(item % a.bx);
-    const long long rest = item / a.bx;
-    const int oh = (int)(rest % a.OH), plane = (int)(rest / a.OH);
+    int qi, oh, plane;
+    if (a.items < (1ll << 31)) {   // the usual case: 32-bit quotients through a double-precision reciprocal
+        const unsigned rest = udiv((unsigned)item, (unsigned)a.bx, a.inv_bx);
+        qi = (int)((unsigned)item - rest * (unsigned)a.bx);
+        plane = (int)udiv(rest, (unsigned)a.OH, a.inv_oh);
+        oh = (int)(rest - (unsigned)plane * (unsigned)a.OH);
+    } else {
+        qi = (int)(item % a.bx);
+        const long long rest = item / a.bx;
+        oh = (int)(rest % a.OH); plane = (int)(rest / a.OH);
+    }
     const int ow0 = qi * 4;
     const int c = plane % a.C;
     const rsrc_t srs = make_rsrc(a.src, a.src_bytes), wrs = make_rsrc(a.w, a.w_bytes);
     float wv[9];
+    if (sizeof(T) == 4) {   // the channel's nine weights as 16 + 16 + 4 bytes
+        float wr[9];
+        load_window<9>(wrs, (unsigned)(c * 9) * 4u, 0, 9, wr);
 #pragma unroll
-    for (int t = 0; t < 9; ++t) wv[t] = buf_load(wrs, (unsigned)(c * 9 + (a.flip ? 8 - t : t)) * ESZ, tnull);
+        for (int t = 0; t < 9; ++t) wv[t] = a.flip ? wr[8 - t] : wr[t];
+    } else {
+#pragma unroll
+        for (int t = 0; t < 9; ++t) wv[t] = buf_load(wrs, (unsigned)(c * 9 + (a.flip ? 8 - t : t)) * ESZ, tnull);
+    }
     const unsigned pbase = (unsigned)plane * (unsigned)(a.IH * a.IW);
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     if constexpr (!BWD2) {
@@ -1042,6 +1068,28 @@ __global__ __launch_bounds__(256) void dw_rows_kernel(DwRowArgs a) {
 #pragma unroll
                 for (int ss = 0; ss < 3; ++ss) acc[i] = fmaf(xv[i * ST + ss], wv[r * 3 + ss], acc[i]);
         }
+    } else if (sizeof(T) == 4 && (plane > 0 || ow0 + a.pad_w >= 2)) {   // (the window may start one column left of the row: not before the tensor)
+        // Column u = ow0 + i + pad_w - s of the stride-1 grid holds dy column u / 2 when u is even.  With
+        // ow0 + pad_w = 2 m + e the four outputs need dy columns m - 1 .. m + 2 at most: one 16-byte load per
+        // contributing row, element (e + i - s) / 2 + 1 of it for output i and tap s.
+        const int e = (ow0 + a.pad_w) & 1, m = (ow0 + a.pad_w) >> 1;
+        auto rows3 = [&](auto ec) __attribute__((always_inline)) {
+            constexpr int E = decltype(ec)::value;
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                const int t = oh + a.pad_h - r;
+                const bool rok = t >= 0 && (t & 1) == 0 && (t >> 1) < a.IH;
+                float yv[4];
+                load_window<4>(srs, rok ? (pbase + (unsigned)((t >> 1) * a.IW + m - 1)) * 4u : kOob, m - 1, a.IW, yv);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int ss = 0; ss < 3; ++ss)
+                        if ((E + i - ss) % 2 == 0) acc[i] = fmaf(yv[(E + i - ss) / 2 + 1], wv[r * 3 + ss], acc[i]);
+            }
+        };
+        if (e == 0) rows3(std::integral_constant<int, 0>{});
+        else rows3(std::integral_constant<int, 1>{});
     } else {
 #pragma unroll
         for (int r = 0; r < 3; ++r) {
@@ -1086,6 +1134,7 @@ bool rows_args(int pass, const Problem& pr, const void* in0, const void* in1, fl
         st = bwd2 ? 2 : 1;
     }
     a.bx = (a.OW + 3) / 4;
+    a.inv_bx = 1.0 / a.bx; a.inv_oh = 1.0 / a.OH;
     a.items = (long long)a.planes * a.OH * a.bx;
     if ((a.items + 255) / 256 >= (1ll << 31)) return false;
     a.src_bytes = (unsigned)((size_t)a.planes * a.IH * a.IW * esz);
@@ -1112,6 +1161,7 @@ struct DwRowWArgs {
     float* out;            // [nsplit][C*9], or dw when nsplit == 1
     int N, C, H, W, P, Q, pad_h, pad_w;
     int qd;                // groups of four output columns per row
+    double inv_qd, inv_p;  // reciprocals for the item decoding
     int nsplit;
     long long items;       // N * P * qd
     unsigned x_bytes, y_bytes;
@@ -1130,9 +1180,17 @@ __global__ __launch_bounds__(256) void dw_rows_wgrad_kernel(DwRowWArgs a) {
 #pragma unroll
     for (int t = 0; t < 9; ++t) acc[t] = 0.f;
     for (long long e = e0 + threadIdx.x; e < e1; e += 256) {
-        const int q0 = (int)(e % a.qd) * 4;
-        const long long rest = e / a.qd;
-        const int p = (int)(rest % a.P), n = (int)(rest / a.P);
+        int q0, p, n;
+        if (a.items < (1ll << 31)) {
+            const unsigned rest = udiv((unsigned)e, (unsigned)a.qd, a.inv_qd);
+            q0 = (int)((unsigned)e - rest * (unsigned)a.qd) * 4;
+            n = (int)udiv(rest, (unsigned)a.P, a.inv_p);
+            p = (int)(rest - (unsigned)n * (unsigned)a.P);
+        } else {
+            q0 = (int)(e % a.qd) * 4;
+            const long long rest = e / a.qd;
+            p = (int)(rest % a.P); n = (int)(rest / a.P);
+        }
         const unsigned ybase = (unsigned)(((n * a.C + c) * a.P + p) * a.Q);
         float yv[4];
         if (sizeof(T) == 4) {
@@ -1186,6 +1244,7 @@ bool rows_wgrad_args(const Problem& pr, const void* x, const void* dy, DwRowWArg
     a.x = x; a.dy = dy;
     a.N = pr.N; a.C = pr.C; a.H = pr.H; a.W = pr.W; a.P = pr.P; a.Q = pr.Q; a.pad_h = pr.ph; a.pad_w = pr.pw;
     a.qd = (pr.Q + 3) / 4;
+    a.inv_qd = 1.0 / a.qd; a.inv_p = 1.0 / pr.P;
     a.items = (long long)pr.N * pr.P * a.qd;
     // about 4096 workgroups, each with at least four items per thread
     long long ns = (4096 + pr.C - 1) / pr.C;
