@@ -1108,7 +1108,7 @@ __global__ __launch_bounds__(256) void dw_rows_kernel(DwRowArgs a) {
     }
     float* o = a.dst + (size_t)plane * a.OH * a.OW + (size_t)oh * a.OW + ow0;
     if (ow0 + 4 <= a.OW && reinterpret_cast<uintptr_t>(o) % 16 == 0) {
-        *reinterpret_cast<float4*>(o) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        __builtin_nontemporal_store(v4f{acc[0], acc[1], acc[2], acc[3]}, reinterpret_cast<v4f*>(o));   // streamed past the caches
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
