@@ -589,6 +589,12 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
         else *err = launch_wgrad<T, 1, 1, 1, 2, 56, 4, 4, 2, 2, 2, 1, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
+    if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && pr.ph == 0 && pr.pw == 0 && (pr.Q == 28 || pr.Q == 56) && pr.Cg > 64 && pr.Kg > 64) {
+        // many channels on wide planes: stages of 56 pixels in full rows
+        if (pr.Q == 28) *err = launch_wgrad<T, 1, 1, 1, 2, 28, 8, 8, 2, 2, 2, 1, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        else *err = launch_wgrad<T, 1, 1, 1, 1, 56, 8, 8, 2, 2, 2, 1, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        return true;
+    }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && (pr.Cg <= 64 || pr.Kg <= 64)) {
         // few channels: 64 x 64 channel blocks (a 128 x 128 block would be mostly empty)
         *err = launch_wgrad<T, 1, 1, 1, 2, 14, 4, 4, 2, 2, 2, 1, 2, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
