@@ -704,7 +704,10 @@ int wgrad_splits(const Problem& pr, const SmallArgs& a) {
 // Backward-data: the padding the kernels are written for; the matrix-core kernel holds all filters (K <= 64), the
 // vector-ALU kernel takes fp32 tensors with any number of filters.
 bool bwd_mfma_ok(const Problem& pr) { return shape_ok(pr) && pr.ph == 2 && pr.pw == 2 && pr.K <= 64; }
-bool bwd_ok(const Problem& pr) { return bwd_mfma_ok(pr) || (shape_ok(pr) && pr.dtype == 0 && pr.ph == 2 && pr.pw == 2); }
+bool stem_bwd_ok(const Problem& pr) { return stem_ok(pr) && pr.dtype == 0 && pr.ph == 3 && pr.pw == 3; }
+bool bwd_ok(const Problem& pr) {
+    return bwd_mfma_ok(pr) || (shape_ok(pr) && pr.dtype == 0 && pr.ph == 2 && pr.pw == 2) || stem_bwd_ok(pr);
+}
 
 }  // namespace
 
@@ -742,8 +745,13 @@ hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* 
         SmallBwdArgs b{};
         b.dy = static_cast<const float*>(in0); b.w = static_cast<const float*>(in1); b.dx = out;
         b.N = pr.N; b.K = pr.K; b.H = pr.H; b.W = pr.W; b.P = pr.P; b.Q = pr.Q;
-        b.btiles_h = ((pr.H + 3) / 4 + 7) / 8; b.btiles_w = ((pr.W + 3) / 4 + 7) / 8;
         b.dy_bytes = (unsigned)((size_t)pr.N * pr.K * pr.P * pr.Q * 4);
+        if (pr.R == 7) {   // 7x7 stride 2, padding 3: a lane owns a 2 x 2 block of dx pixels
+            b.btiles_h = ((pr.H + 1) / 2 + 7) / 8; b.btiles_w = ((pr.W + 1) / 2 + 7) / 8;
+            smallc_bwd_data_kernel<3, 7, 7, 2, 3><<<pr.N * b.btiles_h * b.btiles_w, 64, 0, st>>>(b);
+            return hipGetLastError();
+        }
+        b.btiles_h = ((pr.H + 3) / 4 + 7) / 8; b.btiles_w = ((pr.W + 3) / 4 + 7) / 8;
         smallc_bwd_data_kernel<3, 11, 11, 4, 2><<<pr.N * b.btiles_h * b.btiles_w, 64, 0, st>>>(b);
         return hipGetLastError();
     }

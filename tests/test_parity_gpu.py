@@ -198,6 +198,14 @@ def test_three_channel_7x7_stride_2(row, dtype):
     pu.check_layer_full(L, dtype, passes=("fwd", "bwd_weight"), algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
 
 
+def test_three_channel_7x7_stride_2_backward_data():
+    """Padding 3, fp32: the vector-ALU kernel with a 2 x 2 block of dx pixels per lane."""
+    from paper_1912_01703_amd import binding as mc
+    for i, (N, H, W, K) in enumerate([(2, 64, 64, 64), (1, 45, 51, 24)]):
+        L = wl.custom_layer("s7bd%d" % i, N, 3, H, W, K, 7, 7, 2, 3, 1, seed=5200 + i)
+        pu.check_layer_full(L, "f32", passes=("bwd_data",), algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+
+
 def test_small_channel_backward_data_with_more_than_64_filters():
     """The matrix-core backward-data kernel keeps all filters of a layer in LDS (K <= 64); with more, fp32
     tensors take the vector-ALU kernel."""
