@@ -4,7 +4,21 @@ namespace miconv {
 
 static bool is_depthwise(const Problem& pr) { return pr.groups == pr.C && pr.groups == pr.K && pr.groups > 1; }
 
-bool mfma_supports(int pass, const Problem& pr) {
+// A 1x1 filter at stride 1 without padding does not couple pixels: the plane may be given any shape with the same
+// number of pixels.  Planes whose width has no tuned instance are presented 56 pixels wide (112 x 112 = 224 x 56), which
+// puts them on the full-row 16-byte paths of all three passes.
+static Problem canonical(const Problem& in) {
+    Problem pr = in;
+    if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && pr.sw == 1 && pr.ph == 0 && pr.pw == 0 && pr.W != 14 && pr.W != 28 && pr.W != 56 &&
+        pr.W > 7 && (pr.H * pr.W) % 56 == 0) {
+        pr.H = pr.P = pr.H * pr.W / 56;
+        pr.W = pr.Q = 56;
+    }
+    return pr;
+}
+
+bool mfma_supports(int pass, const Problem& in) {
+    const Problem pr = canonical(in);
     if (is_depthwise(pr)) return false;  // one input channel per filter: nothing to contract
     if (smallc_supports(pass, pr)) return true;
     if (bf16_tile_supports(pass, pr)) return true;
@@ -15,7 +29,8 @@ bool mfma_supports(int pass, const Problem& pr) {
     return wgrad_supports(pr, &ws);
 }
 
-size_t mfma_workspace_bytes(int pass, const Problem& pr) {
+size_t mfma_workspace_bytes(int pass, const Problem& in) {
+    const Problem pr = canonical(in);
     size_t ws = 0;
     if (is_depthwise(pr)) return 0;
     if (smallc_supports(pass, pr)) return smallc_workspace_bytes(pass, pr);
@@ -25,7 +40,8 @@ size_t mfma_workspace_bytes(int pass, const Problem& pr) {
     return ws;
 }
 
-hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws, hipStream_t st) {
+hipError_t mfma_run(int pass, const Problem& in, const void* a, const void* b, float* out, void* ws, hipStream_t st) {
+    const Problem pr = canonical(in);
     if (smallc_supports(pass, pr)) return smallc_run(pass, pr, a, b, out, ws, st);
     if (bf16_tile_supports(pass, pr)) return bf16_tile_run(pass, pr, a, b, out, ws, st);
     if (pass == 2 && bf16_wgrad_supports(pr)) return bf16_wgrad_run(pr, a, b, out, ws, st);

@@ -66,6 +66,8 @@ MFMA = [
     ("m1x1d", 2, 72, 20, 28, 40, 1, 1, 1, 0, 1),      # few filters: 64-wide blocks in backward-weight, two of them along C;
                                                       # 28 pixels wide: bands of 8 full rows, the last one ragged
     ("m1x1e", 1, 72, 9, 56, 40, 1, 1, 1, 0, 1),       # 56 wide: bands of 4 rows, three chunks
+    ("m1x1i", 1, 24, 14, 112, 40, 1, 1, 1, 0, 1),     # 112 wide: handled as a plane of 28 x 56 pixels
+    ("m1x1j", 2, 72, 8, 21, 136, 1, 1, 1, 0, 1),      # 168 pixels = 3 x 56
     ("m1x1g", 2, 136, 10, 28, 200, 1, 1, 1, 0, 1),    # 28 wide, many channels: backward-weight stages of two full rows
     ("m1x1h", 1, 72, 7, 56, 136, 1, 1, 1, 0, 1),      # 56 wide, many channels: stages of one row
     ("m1x1f", 2, 16, 5, 112, 24, 1, 1, 1, 0, 1),      # 112 wide: bands of 2 rows, a partial chunk
