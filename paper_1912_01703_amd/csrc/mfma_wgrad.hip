@@ -579,7 +579,7 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && pr.P <= 7 && pr.Q <= 7) {
-        *err = launch_wgrad<T, 1, 1, 1, 7, 8, 8, 8, 2, 2, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 1, 1, 1, 7, 8, 4, 4, 2, 2, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && (pr.Cg <= 64 || pr.Kg <= 64) && pr.ph == 0 && pr.pw == 0 &&
