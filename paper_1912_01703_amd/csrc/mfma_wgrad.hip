@@ -575,7 +575,7 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 2) {
-        *err = launch_wgrad<T, 1, 1, 2, 2, 14, 8, 8, 2, 2, 1, 1, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        *err = launch_wgrad<T, 1, 1, 2, 2, 14, 4, 4, 2, 2, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && pr.P <= 7 && pr.Q <= 7) {
