@@ -57,6 +57,7 @@ struct TileArgs {
     int w_rs;              // taps of the full filter (R*S of the layer)
     int tapoff[9];         // phase mode: offset of sub-filter tap t inside a (k, c) filter plane
     int items;             // work item ids: units rounded up to a multiple of 8, times fblocks
+    int fill2;             // phase mode, 1x1 filter at stride 2: the three pixels next to every written one get zeros
 };
 
 // Buffer loads: the hardware compares the byte offset with the descriptor's size and returns 0
@@ -422,6 +423,25 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
                 if (MERGE2 && (dh >= a.DH || dw >= a.DW)) continue;
                 const int pix = MERGE2 ? dh * a.DW + dw
                                        : (PHASE ? (oh * a.o_sh + a.o_oh) * a.DW + ow * a.o_sw + a.o_ow : oh * a.OW + ow);
+                if (PHASE && a.fill2) {
+                    // pix = (2 oh, 2 ow): the 2 x 2 block it heads belongs to this lane alone (no tap reaches the other three)
+                    const bool right = 2 * ow + 1 < a.DW, below = 2 * oh + 1 < a.DH;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        if (fq + v >= a.Fg) continue;
+                        float* o = dst + (size_t)(fq + v) * dplane + pix;
+                        if (right && a.fill2 == 2) {   // even row length and aligned dx: 8-byte stores
+                            *reinterpret_cast<float2*>(o) = make_float2(acc[q][i][v], 0.f);
+                            if (below) *reinterpret_cast<float2*>(o + a.DW) = make_float2(0.f, 0.f);
+                        } else {
+                            o[0] = acc[q][i][v];
+                            if (right) o[1] = 0.f;
+                            if (below) o[a.DW] = 0.f;
+                            if (below && right) o[a.DW + 1] = 0.f;
+                        }
+                    }
+                    continue;
+                }
 #pragma unroll
                 for (int v = 0; v < 4; ++v)
                     if (fq + v < a.Fg) dst[(size_t)(fq + v) * dplane + pix] = acc[q][i][v];
