@@ -43,7 +43,8 @@
  *             exception crosses this boundary.
  *  Limits     every tensor must have fewer than 2^31 elements.
  *  Threads    calls may be made from several host threads; the algorithm
- *             override below is process-wide.
+ *             override, the last-algorithm record and the error text below
+ *             are kept per host thread.
  */
 #ifndef MICONV_H
 #define MICONV_H
@@ -80,6 +81,8 @@ typedef enum {
 } miconv_algo;
 
 /*
+ * The "2d convolution" of the paper's Section 4.1 (the operator behind the
+ * convolution layer of its Listing 1):
  * y[n,k,p,q] = sum_{c,r,s} x[n, g*Cg+c, p*stride_h-pad_h+r, q*stride_w-pad_w+s] * w[k,c,r,s]
  * (no filter flip; taps outside the image read zero).
  */
@@ -89,7 +92,8 @@ MICONV_API int conv2d_fwd(const void *x, const void *w, void *y,
                int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Vector-Jacobian product of conv2d_fwd with respect to x:
+ * Backward function of conv2d_fwd in the sense of the paper's Section 4.2: the
+ * vector-Jacobian product of conv2d_fwd with respect to x,
  * dx[n,c,h,w] = sum over all (k,p,q,r,s) with p*stride_h-pad_h+r == h and
  * q*stride_w-pad_w+s == w of dy[n,k,p,q] * w[k,c,r,s].  N,C,H,W describe dx.
  */
@@ -99,7 +103,8 @@ MICONV_API int conv2d_bwd_data(const void *dy, const void *w, void *dx,
                     int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
- * Vector-Jacobian product of conv2d_fwd with respect to w:
+ * Backward function of conv2d_fwd in the sense of the paper's Section 4.2: the
+ * vector-Jacobian product of conv2d_fwd with respect to w,
  * dw[k,c,r,s] = sum_{n,p,q} dy[n,k,p,q] * x[n, g*Cg+c, p*stride_h-pad_h+r, q*stride_w-pad_w+s].
  * The result does not depend on launch timing: partial sums are combined in a
  * fixed order (no floating-point atomics).
@@ -120,7 +125,22 @@ MICONV_API size_t conv2d_workspace_bytes(int pass,
                               int dtype);
 
 /*
- * Process-wide algorithm override for one pass (a miconv_algo).  With
+ * Host-only query: the kernel family the given pass would run for these
+ * arguments under the calling thread's algorithm override, as a string with
+ * static storage: "direct", "mfma/tile", "mfma/tile_phase", "mfma/tile_merge2",
+ * "mfma/wgrad", "mfma/smallc", "mfma/bf16_tile", "mfma/bf16_wgrad",
+ * "depthwise/strip", "depthwise/rows", "depthwise/lds"; "none" for invalid
+ * arguments or a forced algorithm that cannot run the problem.  Whenever the
+ * answer is not "none" the compute call has a kernel for the problem.
+ */
+MICONV_API const char *miconv_kernel_path(int pass,
+                                          int N, int C, int H, int W, int K, int R, int S,
+                                          int stride_h, int stride_w, int pad_h, int pad_w, int groups,
+                                          int dtype);
+
+/*
+ * Algorithm override for one pass (a miconv_algo), for the calling host thread
+ * only (other threads keep their own setting; meant for tests and profiling).  With
  * MICONV_ALGO_AUTO (the default) every valid problem runs on some kernel.  A
  * forced algorithm that cannot run a problem makes the compute call return
  * MICONV_ERR_UNSUPPORTED.  Returns MICONV_OK or MICONV_ERR_DTYPE.

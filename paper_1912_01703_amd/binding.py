@@ -38,6 +38,8 @@ for _name in ("conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight"):
     _fn.argtypes = [ctypes.c_void_p] * 3 + _dims + [_i, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.conv2d_workspace_bytes.restype = ctypes.c_size_t
 _lib.conv2d_workspace_bytes.argtypes = [_i] + _dims + [_i]
+_lib.miconv_kernel_path.restype = ctypes.c_char_p
+_lib.miconv_kernel_path.argtypes = [_i] + _dims + [_i]
 _lib.miconv_set_algo.restype = _i
 _lib.miconv_set_algo.argtypes = [_i, _i]
 _lib.miconv_last_algo.restype = _i
@@ -99,6 +101,11 @@ def conv2d_bwd_weight(x, dy, dw, N, C, H, W, K, R, S, stride_h, stride_w, pad_h,
 def conv2d_workspace_bytes(pass_, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype=F32):
     return int(_lib.conv2d_workspace_bytes(int(pass_), N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w,
                                            groups, int(dtype)))
+
+
+def miconv_kernel_path(pass_, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype=F32) -> str:
+    return _lib.miconv_kernel_path(int(pass_), N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,
+                                   int(dtype)).decode()
 
 
 def miconv_set_algo(pass_, algo):

@@ -3,7 +3,6 @@
 // Nothing here allocates device memory or synchronises.
 #include "../../include/miconv.h"
 
-#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 
@@ -15,7 +14,7 @@ using miconv::Problem;
 
 thread_local char g_err[256] = "";
 thread_local int g_last_algo[3] = {MICONV_ALGO_AUTO, MICONV_ALGO_AUTO, MICONV_ALGO_AUTO};
-std::atomic<int> g_forced[3] = {{MICONV_ALGO_AUTO}, {MICONV_ALGO_AUTO}, {MICONV_ALGO_AUTO}};
+thread_local int g_forced[3] = {MICONV_ALGO_AUTO, MICONV_ALGO_AUTO, MICONV_ALGO_AUTO};
 
 int fail(int code, const char* fmt, ...) {
     va_list ap;
@@ -40,10 +39,15 @@ int make_problem(Problem& pr, int N, int C, int H, int W, int K, int R, int S, i
         return fail(MICONV_ERR_SHAPE, "filter %dx%d larger than padded input %dx%d (+2*%d,+2*%d)", R, S, H, W, ph, pw);
     const long long P = hp / sh + 1, Q = wq / sw + 1;
     const long long lim = 1LL << 31;
-    const long long nx = (long long)N * C * H * W, ny = (long long)N * K * P * Q;
-    const long long nw = (long long)K * (C / groups) * R * S;
+    // products of four factors: each factor and the running product are clamped to 2^31, so nothing exceeds 2^62
+    const auto count = [lim](long long a, long long b, long long c, long long d) {
+        long long v = 1;
+        for (long long f : {a, b, c, d}) v = v >= lim ? lim : v * (f >= lim ? lim : f);
+        return v >= lim ? lim : v;
+    };
+    const long long nx = count(N, C, H, W), ny = count(N, K, P, Q), nw = count(K, C / groups, R, S);
     if (nx >= lim || ny >= lim || nw >= lim)
-        return fail(MICONV_ERR_SHAPE, "tensor too large: x=%lld y=%lld w=%lld elements (limit 2^31)", nx, ny, nw);
+        return fail(MICONV_ERR_SHAPE, "tensor too large: x=%lld y=%lld w=%lld elements (counts are capped at the limit, 2^31)", nx, ny, nw);
     pr.N = N; pr.C = C; pr.H = H; pr.W = W; pr.K = K; pr.R = R; pr.S = S;
     pr.sh = sh; pr.sw = sw; pr.ph = ph; pr.pw = pw; pr.groups = groups;
     pr.P = (int)P; pr.Q = (int)Q; pr.Cg = C / groups; pr.Kg = K / groups; pr.dtype = dtype;
@@ -52,7 +56,7 @@ int make_problem(Problem& pr, int N, int C, int H, int W, int K, int R, int S, i
 
 // The algorithm that will run this pass, or -1 when the forced one cannot.
 int choose_algo(int pass, const Problem& pr) {
-    const int forced = g_forced[pass].load(std::memory_order_relaxed);
+    const int forced = g_forced[pass];
     const bool dw_ok = miconv::depthwise_supports(pass, pr);
     const bool mfma_ok = miconv::mfma_supports(pass, pr);
     switch (forced) {
@@ -85,7 +89,7 @@ int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, 
     const int algo = choose_algo(pass, pr);
     if (algo < 0)
         return fail(MICONV_ERR_UNSUPPORTED, "forced algorithm %d cannot run this problem (pass %d)",
-                    g_forced[pass].load(), pass);
+                    g_forced[pass], pass);
     const size_t need = workspace_for(pass, algo, pr);
     if (need > 0) {
         if (!ws) return fail(MICONV_ERR_WORKSPACE, "workspace is NULL but %zu bytes are required", need);
@@ -145,10 +149,23 @@ size_t conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int R
     return workspace_for(pass, algo, pr);
 }
 
+const char* miconv_kernel_path(int pass, int N, int C, int H, int W, int K, int R, int S, int stride_h, int stride_w,
+                               int pad_h, int pad_w, int groups, int dtype) {
+    if (pass < 0 || pass > 2) return "none";
+    Problem pr;
+    if (make_problem(pr, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype) != MICONV_OK) return "none";
+    switch (choose_algo(pass, pr)) {
+        case MICONV_ALGO_DIRECT: return "direct";
+        case MICONV_ALGO_MFMA: return miconv::mfma_path_name(pass, pr);
+        case MICONV_ALGO_DEPTHWISE: return miconv::depthwise_path_name(pass, pr);
+        default: return "none";
+    }
+}
+
 int miconv_set_algo(int pass, int algo) {
     if (pass < 0 || pass > 2) return fail(MICONV_ERR_DTYPE, "unknown pass %d", pass);
     if (algo < MICONV_ALGO_AUTO || algo > MICONV_ALGO_DEPTHWISE) return fail(MICONV_ERR_DTYPE, "unknown algorithm %d", algo);
-    g_forced[pass].store(algo, std::memory_order_relaxed);
+    g_forced[pass] = algo;
     return MICONV_OK;
 }
 

@@ -22,6 +22,29 @@ __device__ __forceinline__ float bf16_to_float(uint16_t b) {
 __device__ __forceinline__ float load_elem(const float* p, size_t i) { return p[i]; }
 __device__ __forceinline__ float load_elem(const uint16_t* p, size_t i) { return bf16_to_float(p[i]); }
 
+// ---- device helpers shared by the kernel files ---------------------------------------------------
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef unsigned int v4u __attribute__((ext_vector_type(4)));
+typedef unsigned int v3u __attribute__((ext_vector_type(3)));
+typedef unsigned int v2u __attribute__((ext_vector_type(2)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+
+// Raw buffer loads: the hardware compares the byte offset with the descriptor's size and returns 0 at or
+// beyond it, so an element that must read as zero (outside the image or the tile, past the last channel,
+// an absent filter) is given the offset kOob and costs neither a branch nor a select on the result.
+// Every range a kernel describes this way is smaller than 2 GiB.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+constexpr unsigned kOob = 0x80000000u;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const float*) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0));
+}
+__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const uint16_t*) {
+    return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_raw_buffer_load_b16(r, byte_off, 0, 0)) << 16);
+}
+
 // ---- direct kernels (direct.hip): any valid problem -------------------------------------
 hipError_t direct_fwd(const Problem& pr, const void* x, const void* w, float* y, hipStream_t st);
 hipError_t direct_bwd_data(const Problem& pr, const void* dy, const void* w, float* dx, hipStream_t st);
@@ -34,6 +57,8 @@ hipError_t direct_bwd_weight(const Problem& pr, const void* x, const void* dy, f
 bool mfma_supports(int pass, const Problem& pr);
 size_t mfma_workspace_bytes(int pass, const Problem& pr);
 hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws, hipStream_t st);
+// The kernel family inside the MFMA paths that mfma_run would take ("none" if mfma_supports is false).
+const char* mfma_path_name(int pass, const Problem& pr);
 
 // Tiled forward / stride-1 backward-data kernels (mfma_tile.hip).
 bool tile_supports(int pass, const Problem& pr);
@@ -72,5 +97,6 @@ bool depthwise_supports(int pass, const Problem& pr);
 size_t depthwise_workspace_bytes(int pass, const Problem& pr);
 hipError_t depthwise_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws,
                          hipStream_t st);
+const char* depthwise_path_name(int pass, const Problem& pr);
 
 }  // namespace miconv

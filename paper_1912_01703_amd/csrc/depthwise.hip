@@ -26,21 +26,7 @@ namespace {
 
 constexpr int kThreads = 256;
 
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 constexpr int kStream = 2;   // cache policy "non-temporal": data that is read once (3 % on the backward-weight kernel)
-constexpr unsigned kOob = 0x80000000u;
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
-}
-__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const float*) {
-    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0));
-}
-__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const uint16_t*) {
-    return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_raw_buffer_load_b16(r, byte_off, 0, 0)) << 16);
-}
 __device__ __forceinline__ int fdiv(int e, float inv) { return (int)(((float)e + 0.5f) * inv); }
 
 struct DwArgs {
@@ -810,6 +796,9 @@ struct StripPlan {
 bool strip_plan(const Problem& pr, int oh, int ow, int pph, int ppw, int stride, int iplane, StripPlan& sp) {
     const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
     if ((size_t)pr.N * pr.C * pr.H * pr.W * esz >= lim || (size_t)pr.N * pr.K * pr.P * pr.Q * esz >= lim) return false;
+    // The strip kernels derive a plane's channel with a single-precision reciprocal, which is exact only for
+    // plane numbers well below 2^23.
+    if ((long long)pr.N * pr.C >= (1ll << 22)) return false;
     const int pps = pph * ppw;
     if (pr.dtype == 0 && ow < 8) return false;   // rows this short: the row kernels are a little faster (7x7: 18.4 -> 16.6 us)
     if (ow > 64 || pps > 1024) return false;
@@ -1257,41 +1246,82 @@ bool rows_wgrad_args(const Problem& pr, const void* x, const void* dy, DwRowWArg
     return true;
 }
 
+
+// Which kernel family serves a pass.  depthwise_supports, depthwise_workspace_bytes and depthwise_run all ask
+// these two functions, so a problem that is accepted always has a kernel to run on.
+enum class WPath { none, strip, rows, lds };
+enum class SPath { none, strip, lds, rows };
+
+WPath wgrad_path(const Problem& pr) {
+    DwStripWArgs b{};
+    if (strip_wgrad_args(pr, nullptr, nullptr, b)) return WPath::strip;
+    DwWArgs a{};
+    DwRowWArgs r{};
+    const bool lds = wgrad_args(pr, nullptr, nullptr, a), rows = rows_wgrad_args(pr, nullptr, nullptr, r);
+    // fp32: the row kernel (16-byte loads) beats the LDS kernel; bf16: the other way round
+    if (pr.dtype == 0) return rows ? WPath::rows : lds ? WPath::lds : WPath::none;
+    return lds ? WPath::lds : rows ? WPath::rows : WPath::none;
+}
+
+SPath stencil_path(int pass, const Problem& pr) {
+    int stride;
+    bool bwd2;
+    DwStripArgs sa{};
+    if (strip_stencil_args(pass, pr, nullptr, nullptr, nullptr, sa, stride)) return SPath::strip;
+    DwArgs a{};
+    DwRowArgs ra{};
+    const bool lds = stencil_args(pass, pr, nullptr, nullptr, nullptr, a, stride);
+    const bool rows = rows_args(pass, pr, nullptr, nullptr, nullptr, ra, stride, bwd2);
+    // bf16 planes that fit the LDS budget of a workgroup: the row kernel reads bf16 two bytes at a time
+    if (pr.dtype != 0 && lds) return SPath::lds;
+    // larger planes, and backward-data at stride 2: the row kernels
+    return rows ? SPath::rows : lds ? SPath::lds : SPath::none;
+}
+
 }  // namespace
 
 bool depthwise_supports(int pass, const Problem& pr) {
+    return pass == 2 ? wgrad_path(pr) != WPath::none : stencil_path(pass, pr) != SPath::none;
+}
+
+const char* depthwise_path_name(int pass, const Problem& pr) {
     if (pass == 2) {
-        DwWArgs a{};
-        DwStripWArgs b{};
-        DwRowWArgs r{};
-        return strip_wgrad_args(pr, nullptr, nullptr, b) || wgrad_args(pr, nullptr, nullptr, a) ||
-               rows_wgrad_args(pr, nullptr, nullptr, r);
+        switch (wgrad_path(pr)) {
+            case WPath::strip: return "depthwise/strip";
+            case WPath::rows: return "depthwise/rows";
+            case WPath::lds: return "depthwise/lds";
+            default: return "none";
+        }
     }
-    DwArgs a{};
-    int stride;
-    if (stencil_args(pass, pr, nullptr, nullptr, nullptr, a, stride)) return true;
-    DwRowArgs r{};
-    bool bwd2;
-    return rows_args(pass, pr, nullptr, nullptr, nullptr, r, stride, bwd2);
+    switch (stencil_path(pass, pr)) {
+        case SPath::strip: return "depthwise/strip";
+        case SPath::rows: return "depthwise/rows";
+        case SPath::lds: return "depthwise/lds";
+        default: return "none";
+    }
 }
 
 size_t depthwise_workspace_bytes(int pass, const Problem& pr) {
     if (pass != 2) return 0;
-    DwStripWArgs b{};
-    if (strip_wgrad_args(pr, nullptr, nullptr, b)) return b.wsplit > 1 ? (size_t)b.wsplit * pr.C * 9 * sizeof(float) : 0;
-    DwWArgs a{};
-    if (pr.dtype != 0 && wgrad_args(pr, nullptr, nullptr, a)) return a.nsplit > 1 ? (size_t)a.nsplit * pr.C * 9 * sizeof(float) : 0;
-    DwRowWArgs r{};
-    if (!rows_wgrad_args(pr, nullptr, nullptr, r)) return 0;
-    return r.nsplit > 1 ? (size_t)r.nsplit * pr.C * 9 * sizeof(float) : 0;
+    int nsplit = 1;
+    switch (wgrad_path(pr)) {
+        case WPath::strip: { DwStripWArgs b{}; strip_wgrad_args(pr, nullptr, nullptr, b); nsplit = b.wsplit; break; }
+        case WPath::lds: { DwWArgs a{}; wgrad_args(pr, nullptr, nullptr, a); nsplit = a.nsplit; break; }
+        case WPath::rows: { DwRowWArgs r{}; rows_wgrad_args(pr, nullptr, nullptr, r); nsplit = r.nsplit; break; }
+        default: return 0;
+    }
+    return nsplit > 1 ? (size_t)nsplit * pr.C * 9 * sizeof(float) : 0;
 }
 
 hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
                          hipStream_t st) {
     const int count = pr.C * 9;
     if (pass == 2) {
+        const WPath path = wgrad_path(pr);
+        if (path == WPath::none) return hipErrorNotSupported;
         DwStripWArgs b{};
-        if (strip_wgrad_args(pr, in0, in1, b)) {
+        if (path == WPath::strip) {
+            strip_wgrad_args(pr, in0, in1, b);
             b.out = static_cast<float*>(ws);
             int wsplit = 1;
             hipError_t e;
@@ -1302,9 +1332,9 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
             return hipGetLastError();
         }
         DwWArgs a{};
-        if (pr.dtype == 0 || !wgrad_args(pr, in0, in1, a)) {   // fp32: the row kernel (16-byte loads) also beats the LDS kernel
+        if (path == WPath::rows) {
             DwRowWArgs r{};
-            if (!rows_wgrad_args(pr, in0, in1, r)) return hipErrorNotSupported;
+            rows_wgrad_args(pr, in0, in1, r);
             r.out = r.nsplit > 1 ? static_cast<float*>(ws) : out;
             const unsigned grid = (unsigned)(pr.C * r.nsplit);
             if (pr.dtype == 0) {
@@ -1319,6 +1349,7 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
             dw_reduce_splits_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, r.nsplit, count);
             return hipGetLastError();
         }
+        wgrad_args(pr, in0, in1, a);
         a.out = a.nsplit > 1 ? static_cast<float*>(ws) : out;
         const int pps = a.PPH * a.PPW, yplane = pr.P * pr.Q;
         const int per_plane = pps + yplane > a.G4 * 9 ? pps + yplane : a.G4 * 9;
@@ -1336,21 +1367,23 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
         dw_reduce_splits_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, a.nsplit, count);
         return hipGetLastError();
     }
+    const SPath spath = stencil_path(pass, pr);
     DwStripArgs sa{};
     int stride;
-    if (strip_stencil_args(pass, pr, in0, in1, out, sa, stride)) {
+    if (spath == SPath::strip) {
+        strip_stencil_args(pass, pr, in0, in1, out, sa, stride);
         if (pr.dtype == 0) return stride == 1 ? launch_strip_stencil<float, 1>(sa, st) : launch_strip_stencil<float, 2>(sa, st);
         return stride == 1 ? launch_strip_stencil<uint16_t, 1>(sa, st) : launch_strip_stencil<uint16_t, 2>(sa, st);
     }
-    // bf16 planes that fit the LDS budget of a workgroup: the row kernel reads bf16 two bytes at a time
-    DwArgs a{};
-    if (pr.dtype != 0 && stencil_args(pass, pr, in0, in1, out, a, stride)) return launch_stencil<uint16_t>(a, stride, st);
-    // larger planes, and backward-data at stride 2: the row kernels
-    DwRowArgs ra{};
-    bool bwd2;
-    if (rows_args(pass, pr, in0, in1, out, ra, stride, bwd2))
+    if (spath == SPath::rows) {
+        DwRowArgs ra{};
+        bool bwd2;
+        rows_args(pass, pr, in0, in1, out, ra, stride, bwd2);
         return pr.dtype == 0 ? launch_rows<float>(ra, stride, bwd2, st) : launch_rows<uint16_t>(ra, stride, bwd2, st);
-    if (!stencil_args(pass, pr, in0, in1, out, a, stride)) return hipErrorNotSupported;
+    }
+    if (spath == SPath::none) return hipErrorNotSupported;
+    DwArgs a{};
+    stencil_args(pass, pr, in0, in1, out, a, stride);
     return pr.dtype == 0 ? launch_stencil<float>(a, stride, st) : launch_stencil<uint16_t>(a, stride, st);
 }
 

@@ -40,6 +40,16 @@ size_t mfma_workspace_bytes(int pass, const Problem& in) {
     return ws;
 }
 
+const char* mfma_path_name(int pass, const Problem& in) {
+    const Problem pr = canonical(in);
+    if (!mfma_supports(pass, in)) return "none";
+    if (smallc_supports(pass, pr)) return "mfma/smallc";
+    if (bf16_tile_supports(pass, pr)) return "mfma/bf16_tile";
+    if (pass == 2) return bf16_wgrad_supports(pr) ? "mfma/bf16_wgrad" : "mfma/wgrad";
+    if (pass == 0 || tile_supports(pass, pr)) return "mfma/tile";
+    return tile_merge2_supports(pr) ? "mfma/tile_merge2" : "mfma/tile_phase";
+}
+
 hipError_t mfma_run(int pass, const Problem& in, const void* a, const void* b, float* out, void* ws, hipStream_t st) {
     const Problem pr = canonical(in);
     if (smallc_supports(pass, pr)) return smallc_run(pass, pr, a, b, out, ws, st);

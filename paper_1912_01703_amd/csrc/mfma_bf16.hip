@@ -29,14 +29,6 @@
 namespace miconv {
 namespace {
 
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-constexpr unsigned kOob = 0x80000000u;  // tensors handled here are smaller than 2 GiB
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
-}
 
 // ---- pre-pass 1: [N][C][HW] -> [N][HW][C], 64 channels x 128 pixels per workgroup ----------
 // 64 channels are the 128 bytes of one cache line of the destination: a workgroup writes whole lines

@@ -34,14 +34,6 @@
 namespace miconv {
 namespace {
 
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-constexpr unsigned kOob = 0x80000000u;
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
-}
 
 // ---- pre-pass: [N][Ch][HW] -> [ceil(N/8)][Ch][HW][8] ------------------------------------------
 struct PackNArgs {
@@ -90,7 +82,6 @@ struct BwArgs {
     int kblocks, cblocks, nsplit, units;
 };
 
-typedef unsigned int v2u __attribute__((ext_vector_type(2)));
 
 constexpr int kSQ = 7, kSW = 4 * kSQ;                  // pixel groups and output columns per stage
 constexpr int kXW = 32;                                // x columns kept per row: image columns q0-2 .. q0+29

@@ -21,18 +21,6 @@
 namespace miconv {
 namespace {
 
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-constexpr unsigned kOob = 0x80000000u;
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
-}
-__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const float*) {
-    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0));
-}
-__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const uint16_t*) {
-    return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_raw_buffer_load_b16(r, byte_off, 0, 0)) << 16);
-}
 
 struct SmallArgs {
     const void* x;

@@ -35,7 +35,6 @@
 namespace miconv {
 namespace tile {
 
-typedef float v4f __attribute__((ext_vector_type(4)));
 
 struct TileArgs {
     const void* src;
@@ -59,23 +58,6 @@ struct TileArgs {
     int items;             // work item ids: units rounded up to a multiple of 8, times fblocks
     int fill2;             // phase mode, 1x1 filter at stride 2: the three pixels next to every written one get zeros
 };
-
-// Buffer loads: the hardware compares the byte offset with the descriptor's size and returns 0
-// beyond it, so an element that must read as zero (outside the image, past the last channel, an
-// absent filter) is given the offset kOob and costs neither a branch nor a select on the result.
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-typedef unsigned int v4u __attribute__((ext_vector_type(4)));
-typedef unsigned int v3u __attribute__((ext_vector_type(3)));
-constexpr unsigned kOob = 0x80000000u;  // tensors handled here are smaller than 2 GiB
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
-}
-__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const float*) {
-    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0));
-}
-__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const uint16_t*) {
-    return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_raw_buffer_load_b16(r, byte_off, 0, 0)) << 16);
-}
 
 // Smallest channel stride >= v such that kq consecutive channels span 16 banks (mod 32): the two
 // lane groups of a half-wave, which are kq channels apart, then read disjoint halves of the 32 LDS banks.

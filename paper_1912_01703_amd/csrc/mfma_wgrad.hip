@@ -25,8 +25,6 @@
 namespace miconv {
 namespace {
 
-typedef float v4f __attribute__((ext_vector_type(4)));
-typedef unsigned int v4u __attribute__((ext_vector_type(4)));
 
 struct WgradArgs {
     const void* x;
@@ -43,20 +41,6 @@ struct WgradArgs {
     int total_wgs;
     int xk, xc;            // blocks of one XCD form an xk x xc rectangle of the (k, c) block grid (0: linear runs)
 };
-
-// Buffer loads return 0 for a byte offset at or beyond the descriptor's size: elements that must
-// read as zero (outside the image or the tile, absent channels) are given the offset kOob.
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-constexpr unsigned kOob = 0x80000000u;  // one image's channels are far smaller than 2 GiB
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
-}
-__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const float*) {
-    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, byte_off, 0, 0));
-}
-__device__ __forceinline__ float buf_load(rsrc_t r, unsigned byte_off, const uint16_t*) {
-    return __uint_as_float(static_cast<unsigned>(__builtin_amdgcn_raw_buffer_load_b16(r, byte_off, 0, 0)) << 16);
-}
 
 constexpr int next_2_mod_4(int v) { return v + ((6 - v % 4) % 4); }   // smallest >= v that is 2 mod 4
 constexpr int next_odd(int v) { return v | 1; }
@@ -561,6 +545,10 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
     *err = hipSuccess;
     *ws_bytes = 0;
     if (pr.sh != pr.sw) return false;
+    // The kernel forms 32-bit byte offsets relative to the first image of a stage (at most four images) and
+    // uses offsets from 2^31 on as "reads zero": a stage's channels must stay below that.
+    const size_t esz = pr.dtype == 0 ? 4 : 2, lim = (size_t)1 << 31;
+    if (4 * (size_t)pr.C * pr.H * pr.W * esz >= lim || 4 * (size_t)pr.K * pr.P * pr.Q * esz >= lim) return false;
     if (pr.R == 3 && pr.S == 3 && pr.sh == 1 && pr.P <= 7 && pr.Q <= 7) {
         // planes of at most 7 x 7 pixels: stages of four images x 7 x 8 pixels (the eighth column lies outside the image)
         *err = launch_wgrad<T, 3, 3, 1, 7, 8, 1, 1, 1, 1, 8, 8, 4>(pr, x, dy, dw, ws, st, dry, ws_bytes);

@@ -110,3 +110,73 @@ def test_workspace_sizes_of_the_benchmark_layers(mc):
     assert 0 < got3 and got3 % (4 * 9 * l4a.K * l4a.C) == 0
     # 14x14 planes are not a multiple of 8 elements: bf16 inputs take the widening path, no layout copies
     assert mc.conv2d_workspace_bytes(0, *L["2a"].conv_args(), mc.BF16_F32ACC) == 0
+
+
+def test_kernel_path_of_the_benchmark_layers(mc):
+    """Host arithmetic only: which kernel family each benchmark layer is dispatched to."""
+    from paper_1912_01703_amd import workloads as wl
+    L = wl.LAYERS
+    path = lambda name, p, dt=mc.F32: mc.miconv_kernel_path(p, *L[name].conv_args(), dt)
+    for name in ("1", "2a", "2b", "4a", "4b", "5b"):
+        assert [path(name, p) for p in range(3)] == ["mfma/tile", "mfma/tile", "mfma/wgrad"], name
+    assert [path("2c", p) for p in range(3)] == ["mfma/tile", "mfma/tile_merge2", "mfma/wgrad"]
+    assert [path("3", p) for p in range(3)] == ["mfma/smallc"] * 3
+    assert [path("5a", p) for p in range(3)] == ["depthwise/strip"] * 3
+    for name in ("4a", "4b"):
+        assert [path(name, p, mc.BF16_F32ACC) for p in range(3)] == ["mfma/bf16_tile", "mfma/bf16_tile", "mfma/bf16_wgrad"]
+    assert mc.miconv_kernel_path(0, 1, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 3) == "none"      # invalid groups
+    assert mc.miconv_kernel_path(0, 1, 4, 9, 9, 4, 5, 4, 3, 2, 1, 1, 1) == "direct"    # no tuned kernel
+
+
+# Depthwise problems around the sizes at which individual kernel families bow out (tensors of 2 GiB and more,
+# millions of planes, planes too large for LDS): whatever the dispatcher accepts must have a kernel to run on.
+DW_LIMITS = [
+    # N     C    H    W  stride pad
+    (512, 512, 56, 56, 1, 1),       # 3.3 GB of fp32: beyond the 32-bit byte offsets of the strip and row kernels
+    (680, 512, 56, 56, 1, 1),       # just under 2^31 elements
+    (512, 512, 56, 56, 2, 1),
+    (40000, 128, 8, 8, 1, 1),       # 5.1 M planes: beyond the exact range of the strip kernels' channel decode
+    (65536, 96, 7, 7, 1, 1),
+    (2, 8, 300, 300, 1, 1),         # a plane larger than any LDS budget
+    (1, 16, 4000, 4000, 1, 1),
+    (3, 16, 2000, 3000, 2, 1),
+]
+
+
+@pytest.mark.parametrize("dtype", [0, 1])
+@pytest.mark.parametrize("row", DW_LIMITS, ids=["x".join(map(str, r)) for r in DW_LIMITS])
+def test_accepted_depthwise_problems_have_a_kernel(mc, row, dtype):
+    N, C, H, W, st, pd = row
+    args = (N, C, H, W, C, 3, 3, st, st, pd, pd, C)
+    for p in range(3):
+        auto = mc.miconv_kernel_path(p, *args, dtype)
+        assert auto != "none", (p, row)
+        assert mc.miconv_set_algo(p, mc.ALGO_DEPTHWISE) == mc.OK
+        try:
+            forced = mc.miconv_kernel_path(p, *args, dtype)
+        finally:
+            mc.miconv_set_algo(p, mc.ALGO_AUTO)
+        # AUTO picks the depthwise family exactly when the family says it can run the problem
+        assert (forced != "none") == auto.startswith("depthwise/"), (p, row, auto, forced)
+
+
+def test_backward_weight_declines_stages_beyond_32_bit_offsets(mc):
+    """N=2, C=512, 1024x1024 fp32: four images' channels exceed 2 GiB, so the matrix-core backward-weight
+    kernel (32-bit offsets within a stage) must not be chosen; the direct kernels take the problem."""
+    args = (2, 512, 1024, 1024, 1, 3, 3, 1, 1, 1, 1, 1)
+    assert mc.miconv_kernel_path(2, *args, mc.F32) == "direct"
+    assert mc.miconv_kernel_path(2, 2, 512, 64, 64, 64, 3, 3, 1, 1, 1, 1, 1, mc.F32) == "mfma/wgrad"
+
+
+def test_algorithm_override_is_per_thread(mc):
+    import threading
+    seen = {}
+    assert mc.miconv_set_algo(0, mc.ALGO_DIRECT) == mc.OK
+    try:
+        t = threading.Thread(target=lambda: seen.update(other=mc.miconv_kernel_path(0, *GOOD.values(), 0)))
+        t.start()
+        t.join()
+        seen["mine"] = mc.miconv_kernel_path(0, *GOOD.values(), 0)
+    finally:
+        mc.miconv_set_algo(0, mc.ALGO_AUTO)
+    assert seen == {"other": "mfma/tile", "mine": "direct"}
