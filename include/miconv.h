@@ -115,6 +115,30 @@ MICONV_API int conv2d_bwd_weight(const void *x, const void *dy, void *dw,
                       int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * conv2d_bwd_weight for callers that cannot allocate device memory (code under
+ * HIP graph capture, serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and the same result, bit for bit, as conv2d_bwd_weight, but the scratch memory (the
+ * partial sums of a split reduction) is a static device array inside the
+ * library instead of a caller workspace.  The call allocates and frees
+ * nothing.  Limits and rules:
+ *  - the array holds 32 MiB per GPU (kept by every GPU the library runs on until
+ *    the process ends); a problem whose conv2d_workspace_bytes(
+ *    MICONV_PASS_BWD_WEIGHT, ...) exceeds that returns MICONV_ERR_WORKSPACE and
+ *    launches nothing (all nine fp32 benchmark layers fit; bf16 layers that
+ *    need re-laid-out operand copies do not);
+ *  - all calls on one GPU share that GPU's array: calls that may overlap on one
+ *    GPU (different streams or host threads) race and must be serialised by the caller;
+ *  - the first call on each GPU looks up the array's device address
+ *    (hipGetSymbolAddress); make that call outside graph capture.
+ * Everything else (argument meaning, errors, stream behaviour) is as for
+ * conv2d_bwd_weight.
+ */
+MICONV_API int conv2d_bwd_weight_static_ws(const void *x, const void *dy, void *dw,
+                                int N, int C, int H, int W, int K, int R, int S,
+                                int stride_h, int stride_w, int pad_h, int pad_w, int groups,
+                                int dtype, void *hip_stream);
+
+/*
  * Bytes of workspace the given pass (a miconv_pass) needs for these arguments
  * under the current algorithm override.  Returns 0 for invalid arguments as
  * well; the compute call reports those.

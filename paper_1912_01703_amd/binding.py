@@ -36,6 +36,8 @@ for _name in ("conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight"):
     _fn = getattr(_lib, _name)
     _fn.restype = _i
     _fn.argtypes = [ctypes.c_void_p] * 3 + _dims + [_i, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.conv2d_bwd_weight_static_ws.restype = _i
+_lib.conv2d_bwd_weight_static_ws.argtypes = [ctypes.c_void_p] * 3 + _dims + [_i, ctypes.c_void_p]
 _lib.conv2d_workspace_bytes.restype = ctypes.c_size_t
 _lib.conv2d_workspace_bytes.argtypes = [_i] + _dims + [_i]
 _lib.miconv_kernel_path.restype = ctypes.c_char_p
@@ -96,6 +98,16 @@ def conv2d_bwd_weight(x, dy, dw, N, C, H, W, K, R, S, stride_h, stride_w, pad_h,
                       dtype=F32, workspace=None, stream=0, check=True):
     return _call(_lib.conv2d_bwd_weight, x, dy, dw, (N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups),
                  dtype, workspace, stream, check)
+
+
+def conv2d_bwd_weight_static_ws(x, dy, dw, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,
+                                dtype=F32, stream=0, check=True):
+    rc = _lib.conv2d_bwd_weight_static_ws(_ptr(x), _ptr(dy), _ptr(dw), N, C, H, W, K, R, S, stride_h, stride_w,
+                                          pad_h, pad_w, groups, int(dtype),
+                                          ctypes.c_void_p(int(stream)) if stream else None)
+    if check and rc != OK:
+        raise MiconvError(rc, last_error())
+    return rc
 
 
 def conv2d_workspace_bytes(pass_, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype=F32):

@@ -5,6 +5,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <mutex>
 
 #include "common.h"
 
@@ -24,6 +25,36 @@ int fail(int code, const char* fmt, ...) {
     return code;
 }
 
+// Scratch memory of conv2d_bwd_weight_static_ws: one array per GPU, held from the time the library's code is
+// loaded on that GPU until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the device address that call returns on the current device is what kernels are given.
+constexpr size_t kStaticWsBytes = size_t(32) << 20;
+__device__ __align__(256) unsigned char scratch[kStaticWsBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device (looked up once per device); nullptr with the error recorded.
+void* static_scratch() {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        fail(MICONV_ERR_LAUNCH, "hipGetDevice failed or device index %d is out of range: %s", dev, hipGetErrorString(e));
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) {
+            fail(MICONV_ERR_LAUNCH, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
 // Fills pr and returns MICONV_OK, or records why the arguments are invalid.
 int make_problem(Problem& pr, int N, int C, int H, int W, int K, int R, int S, int sh, int sw, int ph, int pw,
                  int groups, int dtype) {
@@ -38,9 +69,9 @@ int make_problem(Problem& pr, int N, int C, int H, int W, int K, int R, int S, i
     if (hp < 0 || wq < 0)
         return fail(MICONV_ERR_SHAPE, "filter %dx%d larger than padded input %dx%d (+2*%d,+2*%d)", R, S, H, W, ph, pw);
     const long long P = hp / sh + 1, Q = wq / sw + 1;
-    const long long lim = 1LL << 31;
+    constexpr long long lim = 1LL << 31;
     // products of four factors: each factor and the running product are clamped to 2^31, so nothing exceeds 2^62
-    const auto count = [lim](long long a, long long b, long long c, long long d) {
+    const auto count = [](long long a, long long b, long long c, long long d) {
         long long v = 1;
         for (long long f : {a, b, c, d}) v = v >= lim ? lim : v * (f >= lim ? lim : f);
         return v >= lim ? lim : v;
@@ -77,7 +108,8 @@ size_t workspace_for(int pass, int algo, const Problem& pr) {
 }
 
 int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, int W, int K, int R, int S, int sh,
-        int sw, int ph, int pw, int groups, int dtype, void* ws, size_t ws_bytes, void* stream) {
+        int sw, int ph, int pw, int groups, int dtype, void* ws, size_t ws_bytes, void* stream,
+        bool static_ws = false) {
     static const char* const in_names[3][2] = {{"x", "w"}, {"dy", "w"}, {"x", "dy"}};
     static const char* const out_names[3] = {"y", "dx", "dw"};
     Problem pr;
@@ -91,7 +123,13 @@ int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, 
         return fail(MICONV_ERR_UNSUPPORTED, "forced algorithm %d cannot run this problem (pass %d)",
                     g_forced[pass], pass);
     const size_t need = workspace_for(pass, algo, pr);
-    if (need > 0) {
+    if (static_ws) {
+        if (need > kStaticWsBytes)
+            return fail(MICONV_ERR_WORKSPACE, "this problem needs %zu bytes of scratch memory, the static array holds %zu: "
+                        "call conv2d_bwd_weight with a workspace instead", need, kStaticWsBytes);
+        ws = need > 0 ? static_scratch() : nullptr;
+        if (need > 0 && !ws) return MICONV_ERR_LAUNCH;
+    } else if (need > 0) {
         if (!ws) return fail(MICONV_ERR_WORKSPACE, "workspace is NULL but %zu bytes are required", need);
         if (ws_bytes < need) return fail(MICONV_ERR_WORKSPACE, "workspace has %zu bytes, %zu required", ws_bytes, need);
         if (reinterpret_cast<uintptr_t>(ws) % 256)
@@ -137,6 +175,13 @@ int conv2d_bwd_weight(const void* x, const void* dy, void* dw, int N, int C, int
                       size_t workspace_bytes, void* hip_stream) {
     return run(MICONV_PASS_BWD_WEIGHT, x, dy, dw, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,
                dtype, workspace, workspace_bytes, hip_stream);
+}
+
+int conv2d_bwd_weight_static_ws(const void* x, const void* dy, void* dw, int N, int C, int H, int W, int K, int R, int S,
+                                int stride_h, int stride_w, int pad_h, int pad_w, int groups, int dtype,
+                                void* hip_stream) {
+    return run(MICONV_PASS_BWD_WEIGHT, x, dy, dw, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,
+               dtype, nullptr, 0, hip_stream, true);
 }
 
 size_t conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int R, int S, int stride_h, int stride_w,
