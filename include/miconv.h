@@ -163,6 +163,20 @@ MICONV_API const char *miconv_kernel_path(int pass,
                                           int dtype);
 
 /*
+ * Measurement utility (used by the benchmark to state throughput against the
+ * clock the GPU really ran at; the paper's Section 6 reports measured
+ * throughput only).  Enqueues a one-wave kernel on hip_stream that runs for
+ * about duration_us microseconds (1 .. 1 000 000) without touching memory and
+ * then writes two uint64_t to `counts` (DEVICE pointer, 16 bytes, 8-byte
+ * aligned): counts[0] = shader-clock cycles that passed, counts[1] = ticks of
+ * the GPU's constant-rate counter that passed.  *wall_clock_khz (HOST pointer)
+ * receives that counter's rate, so the average shader clock over the interval
+ * is counts[0] / counts[1] * wall_clock_khz kHz.  Launch it on a stream other
+ * than the one the measured kernels run on.  Returns a miconv_status.
+ */
+MICONV_API int miconv_sample_shader_clock(void *counts, unsigned duration_us, int *wall_clock_khz, void *hip_stream);
+
+/*
  * Algorithm override for one pass (a miconv_algo), for the calling host thread
  * only (other threads keep their own setting; meant for tests and profiling).  With
  * MICONV_ALGO_AUTO (the default) every valid problem runs on some kernel.  A

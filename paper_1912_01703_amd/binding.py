@@ -42,6 +42,8 @@ _lib.conv2d_workspace_bytes.restype = ctypes.c_size_t
 _lib.conv2d_workspace_bytes.argtypes = [_i] + _dims + [_i]
 _lib.miconv_kernel_path.restype = ctypes.c_char_p
 _lib.miconv_kernel_path.argtypes = [_i] + _dims + [_i]
+_lib.miconv_sample_shader_clock.restype = _i
+_lib.miconv_sample_shader_clock.argtypes = [ctypes.c_void_p, ctypes.c_uint, ctypes.POINTER(_i), ctypes.c_void_p]
 _lib.miconv_set_algo.restype = _i
 _lib.miconv_set_algo.argtypes = [_i, _i]
 _lib.miconv_last_algo.restype = _i
@@ -118,6 +120,17 @@ def conv2d_workspace_bytes(pass_, N, C, H, W, K, R, S, stride_h, stride_w, pad_h
 def miconv_kernel_path(pass_, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype=F32) -> str:
     return _lib.miconv_kernel_path(int(pass_), N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,
                                    int(dtype)).decode()
+
+
+def miconv_sample_shader_clock(counts, duration_us, stream=0, check=True):
+    """Returns the constant-rate counter's frequency in kHz; `counts` (2 x int64 on the device) is filled by the
+    kernel once it has run."""
+    khz = _i(0)
+    rc = _lib.miconv_sample_shader_clock(_ptr(counts), int(duration_us), ctypes.byref(khz),
+                                         ctypes.c_void_p(int(stream)) if stream else None)
+    if check and rc != OK:
+        raise MiconvError(rc, "miconv_sample_shader_clock failed")
+    return int(khz.value)
 
 
 def miconv_set_algo(pass_, algo):

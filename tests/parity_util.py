@@ -156,29 +156,80 @@ def check_layer_full(layer, dtype="f32", passes=PASSES, algo=None, expect_algo=N
     return errs
 
 
-def check_layer_sampled(layer, dtype="f32", passes=PASSES, count=1 << 18, wcount=4096, algo=None,
-                        expect_algo=None):
-    """Parity on a seeded sample of outputs (layers too large for the full oracle)."""
+def structured_indices(layer, pass_name, count=1 << 18, tail_units=64, tail_channels=4):
+    """Flat output indices for a forward / backward-data check of a layer too large for the full oracle, placed
+    where a tiled, persistent, XCD-aware kernel would go wrong rather than uniformly.
+
+    The tuned kernels cut every (image, group) plane of the output into tiles of 12 x 16 pixels (planes at
+    least 96 rows high whose width is a multiple of 16) or 14 x 14 pixels otherwise, numbered row-major within
+    the plane, planes in image order: these are the "units".  The units are split into 8 equal contiguous
+    ranges (one per XCD, ceil(units / 8) each), and persistent workgroups walk the ids of a range in order, so
+    the last ids a workgroup walks are the last units of each range.  This function re-derives that map from
+    the description above (no kernel code is imported) and returns
+      (i)   every element of the first and of the last image (all channels, all tile seams and ragged tiles);
+      (ii)  for each of the 8 ranges: the first unit and the last unit as whole tiles over all channels, and the
+            last `tail_units` units as whole tiles over `tail_channels` channels (first, last, two seeded ones);
+      (iii) one whole plane in the middle of the batch (every seam row and column once more);
+      (iv)  wl.sample_indices' corners / edges / uniform random sample.
+    """
+    d0, d1, d2, d3 = out_shape(layer, pass_name)
+    th, tw = (12, 16) if (d3 % 16 == 0 and d2 >= 96) else (14, 14)
+    tiles_h, tiles_w = -(-d2 // th), -(-d3 // tw)
+    units = d0 * tiles_h * tiles_w            # groups == 1 for the layers this is used on
+    assert layer.groups == 1
+    per_xcd = -(-units // 8)
+    rng = np.random.Generator(np.random.PCG64(layer.seed + 11))
+    picks = []
+
+    def block(n, chans, r0, r1, c0, c1):
+        n = np.asarray(n).reshape(-1, 1, 1, 1)
+        ch = np.asarray(chans).reshape(1, -1, 1, 1)
+        rr = np.arange(r0, min(r1, d2)).reshape(1, 1, -1, 1)
+        cc = np.arange(c0, min(c1, d3)).reshape(1, 1, 1, -1)
+        picks.append((((n * d1 + ch) * d2 + rr) * d3 + cc).reshape(-1))
+
+    all_ch = np.arange(d1)
+    for n in sorted({0, d0 - 1}):
+        block(n, all_ch, 0, d2, 0, d3)                                    # (i)
+    few = np.unique(np.concatenate([[0, d1 - 1], rng.integers(0, d1, size=max(0, tail_channels - 2))]))
+    for x in range(8):                                                    # (ii)
+        lo, hi = x * per_xcd, min((x + 1) * per_xcd, units)
+        if lo >= hi:
+            continue
+        for u in range(max(lo, hi - tail_units), hi):
+            n, t = divmod(u, tiles_h * tiles_w)
+            ti, tj = divmod(t, tiles_w)
+            block(n, all_ch if u in (lo, hi - 1) else few, ti * th, (ti + 1) * th, tj * tw, (tj + 1) * tw)
+        n, t = divmod(lo, tiles_h * tiles_w)
+        ti, tj = divmod(t, tiles_w)
+        block(n, all_ch, ti * th, (ti + 1) * th, tj * tw, (tj + 1) * tw)
+    block(d0 // 2, [d1 // 2], 0, d2, 0, d3)                               # (iii)
+    picks.append(wl.sample_indices((d0, d1, d2, d3), count, seed=layer.seed + 7))   # (iv)
+    return np.unique(np.concatenate(picks))
+
+
+def check_layer_structured(layer, dtype="f32", expect_algo=None):
+    """Parity of a layer too large for the full oracle in forward and backward-data: outputs at the structured
+    places of structured_indices; backward-weight: every element of dw."""
+    import torch
     from paper_1912_01703_amd import binding as mc
     h = prepare(layer, dtype)
     gr = GpuRunner(layer, h, dtype)
     errs = {}
-    for p in passes:
-        pid = PASSES.index(p)
-        mc.miconv_set_algo(pid, algo if algo is not None else mc.ALGO_AUTO)
-        try:
-            print(f"[parity-sampled] layer={layer.name} dtype={dtype} pass={p} algo={algo}", flush=True)
-            out_t = gr.run(p)
-        finally:
-            mc.miconv_set_algo(pid, mc.ALGO_AUTO)
+    for p in PASSES:
+        print(f"[parity-structured] layer={layer.name} dtype={dtype} pass={p}", flush=True)
+        out_t = gr.run(p)
         if expect_algo is not None:
             assert gr.last_algo(p) == expect_algo, (p, gr.last_algo(p), expect_algo)
-        shape = out_shape(layer, p)
-        idx = wl.sample_indices(shape, wcount if p == "bwd_weight" else count, seed=layer.seed + 7)
         assert bool(self_finite(out_t)), f"{layer.name}/{p}: non-finite output"
-        import torch
-        sel = out_t.reshape(-1)[torch.from_numpy(idx).to(out_t.device)].cpu().numpy()
-        refv, den = oracle_at(layer, h, p, idx)
+        if p == "bwd_weight":
+            sel = out_t.cpu().numpy()
+            refv, den = oracle_full(layer, h, p)
+        else:
+            idx = structured_indices(layer, p)
+            sel = out_t.reshape(-1)[torch.from_numpy(idx).to(out_t.device)].cpu().numpy()
+            refv, den = oracle_at(layer, h, p, idx)
+            print(f"[parity-structured]   {idx.size} of {out_t.numel()} outputs", flush=True)
         err, ok = max_norm_err(sel, refv, den)
         assert ok, f"{layer.name}/{p}: non-zero where no tap reaches"
         assert err <= TOL[dtype], f"{layer.name}/{p}/{dtype}: normalised error {err:.3e} > {TOL[dtype]}"

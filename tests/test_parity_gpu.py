@@ -1,8 +1,10 @@
 """GPU parity: every pass through the C ABI against the CPU oracle.
 
-Full tensors for the layers the oracle finishes in seconds; a seeded sample of
-outputs (always including corners, edges and interior points) for the two
-VGG-sized layers.  Bounds and the error measure are in parity_util.
+Full tensors for the layers the oracle finishes in seconds.  The two VGG-sized
+layers are checked in full for backward-weight and, for forward and
+backward-data, on whole images, whole tiles at the structurally delicate places
+of the tuned kernels' work decomposition and a seeded random sample.  Bounds
+and the error measure are in parity_util.
 """
 import numpy as np
 import pytest
@@ -34,7 +36,8 @@ def odd_layer(row, seed_off=0):
 
 
 def test_tiny_config_auto():
-    errs = pu.check_layer_full(wl.LAYERS["1"])
+    from paper_1912_01703_amd import binding as mc
+    errs = pu.check_layer_full(wl.LAYERS["1"], expect_algo=mc.ALGO_MFMA)
     assert set(errs) == set(pu.PASSES)
 
 
@@ -252,15 +255,39 @@ def test_depthwise_shapes(row, dtype):
     pu.check_layer_full(L, dtype, algo=mc.ALGO_DEPTHWISE, expect_algo=mc.ALGO_DEPTHWISE)
 
 
+# the kernel family of each pass of each benchmark layer (fp32), as miconv_kernel_path names it
+FAMILY = {
+    "2a": ("mfma/tile", "mfma/tile", "mfma/wgrad"), "2b": ("mfma/tile", "mfma/tile", "mfma/wgrad"),
+    "2c": ("mfma/tile", "mfma/tile_merge2", "mfma/wgrad"), "3": ("mfma/smallc",) * 3,
+    "4a": ("mfma/tile", "mfma/tile", "mfma/wgrad"), "4b": ("mfma/tile", "mfma/tile", "mfma/wgrad"),
+    "5a": ("depthwise/strip",) * 3, "5b": ("mfma/tile", "mfma/tile", "mfma/wgrad"),
+}
+FAMILY_BF16 = {"4a": ("mfma/bf16_tile", "mfma/bf16_tile", "mfma/bf16_wgrad"),
+               "4b": ("mfma/bf16_tile", "mfma/bf16_tile", "mfma/bf16_wgrad")}
+
+
+def expected_dispatch(name, dtype="f32"):
+    """Asserts the tuned family every pass of the layer is dispatched to and returns the algorithm code."""
+    from paper_1912_01703_amd import binding as mc
+    fam = (FAMILY_BF16 if dtype == "bf16" else FAMILY)[name]
+    code = mc.BF16_F32ACC if dtype == "bf16" else mc.F32
+    got = tuple(mc.miconv_kernel_path(p, *wl.LAYERS[name].conv_args(), code) for p in range(3))
+    assert got == fam, (name, dtype, got)
+    return mc.ALGO_DEPTHWISE if fam[0].startswith("depthwise") else mc.ALGO_MFMA
+
+
 @pytest.mark.parametrize("name", ["2a", "2b", "2c", "3", "5a", "5b"])
 def test_full_size_layers_fp32(name):
-    pu.check_layer_full(wl.LAYERS[name])
+    pu.check_layer_full(wl.LAYERS[name], expect_algo=expected_dispatch(name))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("name", ["4a", "4b"])
-def test_vgg_layers_sampled(name, dtype):
-    pu.check_layer_sampled(wl.LAYERS[name], dtype)
+def test_vgg_layers_structured(name, dtype):
+    """The two VGG-sized layers: forward and backward-data on whole images, whole tiles at both ends of every
+    XCD's range of work, the tiles the persistent workgroups finish on, a mid-batch plane and a random sample;
+    backward-weight in full."""
+    pu.check_layer_structured(wl.LAYERS[name], dtype, expect_algo=expected_dispatch(name, dtype))
 
 
 def test_bwd_weight_is_bit_reproducible():
