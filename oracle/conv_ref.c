@@ -289,3 +289,50 @@ int conv2d_bwd_weight_ref_at(const void *x, const void *dy, const int64_t *idx, 
     }
     return 0;
 }
+
+/* ------------------------------------------------------- fused epilogues
+ * The paper's model code places a rectified linear unit directly behind its
+ * convolution layer (Section 4.1, the forward function of its first listing),
+ * and the layer it uses there carries a per-output-channel bias.  The two
+ * routines below are the convolution passes above with that neighbour folded
+ * in; each is the plain pass followed by the element-wise rule.
+ *
+ *   fwd_bias_relu   y[n,k,p,q]  = max(0, conv2d_fwd(x,w)[n,k,p,q] + bias[k])
+ *   bwd_data_relu   dx[n,c,h,w] = conv2d_bwd_data(dy,w)[n,c,h,w]  if act[n,c,h,w] > 0, else 0
+ *
+ * The second one is the vector-Jacobian product, with respect to z, of
+ * z -> conv2d_fwd(max(0,z), w) where act = max(0,z) is the activation the
+ * convolution was fed (derivative of max(0,.) taken as 0 at 0).
+ * bias is fp64 here; act has the element type `dtype` names and the shape of x.
+ */
+int conv2d_fwd_bias_relu_ref(const void *x, const void *w, const double *bias, double *y,
+                             int N, int C, int H, int W, int K, int R, int S,
+                             int stride_h, int stride_w, int pad_h, int pad_w,
+                             int groups, int dtype)
+{
+    const int rc = conv2d_fwd_ref(x, w, y, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype);
+    if (rc) return rc;
+    const int P = out_dim(H, pad_h, R, stride_h);
+    const int Q = out_dim(W, pad_w, S, stride_w);
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k)
+            for (int i = 0; i < P * Q; ++i) {
+                double *e = &y[((size_t)n * K + k) * P * Q + i];
+                const double v = *e + bias[k];
+                *e = v > 0.0 ? v : 0.0;
+            }
+    return 0;
+}
+
+int conv2d_bwd_data_relu_ref(const void *dy, const void *w, const void *act, double *dx,
+                             int N, int C, int H, int W, int K, int R, int S,
+                             int stride_h, int stride_w, int pad_h, int pad_w,
+                             int groups, int dtype)
+{
+    const int rc = conv2d_bwd_data_ref(dy, w, dx, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype);
+    if (rc) return rc;
+    const size_t count = (size_t)N * C * H * W;
+    for (size_t i = 0; i < count; ++i)
+        if (!(ld(act, i, dtype) > 0.0)) dx[i] = 0.0;
+    return 0;
+}
