@@ -64,6 +64,9 @@ def parse():
     ap.add_argument("--layer", default="2a")
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--epilogue", action="store_true",
+                    help="time the fused calls instead: conv2d_fwd_bias_relu and conv2d_bwd_data_relu_mask (mask = x); "
+                         "backward-weight is unchanged.  Not the headline configuration: no cpu baseline, no secondary")
     ap.add_argument("--no-secondary", action="store_true",
                     help="skip the depthwise layer's figures that the default run reports beside the headline layer")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MIB",
@@ -273,7 +276,7 @@ def make_sets(L, dtype, nsets, torch, np, wl, dev):
     return sets
 
 
-def measure_layer(L, dtype, steps, warmup, settle_ms, rotate, mc, wl, torch, np):
+def measure_layer(L, dtype, steps, warmup, settle_ms, rotate, mc, wl, torch, np, fused=False):
     """Times `steps` steps of layer L (wall clock between two synchronisations) and then, in a second region of
     the same launches, each pass's average launch duration with HIP events.  Returns a dict of figures."""
     code = mc.BF16_F32ACC if dtype == "bf16" else mc.F32
@@ -294,9 +297,14 @@ def measure_layer(L, dtype, steps, warmup, settle_ms, rotate, mc, wl, torch, np)
     ws_bytes = [mc.conv2d_workspace_bytes(p, *args, code) for p in range(3)]
     ws = torch.empty(max(ws_bytes + [256]), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
+    bias = torch.from_numpy(wl.make_epilogue_inputs(L)[0]).to(dev) if fused else None
 
     def run_pass(p, s):
-        if p == 0:
+        if p == 0 and fused:
+            mc.conv2d_fwd_bias_relu(s["x"], s["w"], bias, s["y"], *args, code, ws, stream)
+        elif p == 1 and fused:
+            mc.conv2d_bwd_data_relu_mask(s["dy"], s["w"], s["x"], s["dx"], *args, code, ws, stream)
+        elif p == 0:
             mc.conv2d_fwd(s["x"], s["w"], s["y"], *args, code, ws, stream)
         elif p == 1:
             mc.conv2d_bwd_data(s["dy"], s["w"], s["dx"], *args, code, ws, stream)
@@ -499,7 +507,7 @@ def main():
         sweep(mc, wl, torch)
         return
     L = wl.LAYERS[a.layer]
-    m = measure_layer(L, a.dtype, a.steps, a.warmup, a.settle_ms, a.rotate, mc, wl, torch, np)
+    m = measure_layer(L, a.dtype, a.steps, a.warmup, a.settle_ms, a.rotate, mc, wl, torch, np, fused=a.epilogue)
     tflops = 3.0 * L.flops / (m["ms_per_step"] * 1e-3) / 1e12
     out = {
         "metric": METRIC, "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -528,6 +536,11 @@ def main():
     else:
         out["measured_clock"] = None
         out["pct_of_measured_clock_peak"] = None
+    if a.epilogue:
+        out["config"]["epilogue"] = "fwd: bias + ReLU; bwd_data: ReLU mask (x); fused=%s" % [
+            mc.miconv_epilogue_is_fused(p, *L.conv_args(), mc.BF16_F32ACC if a.dtype == "bf16" else mc.F32) for p in (0, 1)]
+        print(json.dumps(out), flush=True)
+        return
     if a.layer == "2a" and a.dtype == "f32" and not a.no_secondary:
         out["secondary"] = secondary_depthwise(max(10, min(a.steps, 30)), a.warmup, a.settle_ms, mc, wl, torch, np)
     if not a.no_cpu_baseline:

@@ -115,6 +115,49 @@ MICONV_API int conv2d_bwd_weight(const void *x, const void *dy, void *dw,
                       int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * conv2d_fwd with the two operations the paper's model code puts around its
+ * convolution layer (Section 4.1, first listing: the layer's per-channel bias
+ * and the rectified linear unit applied to its output) folded into the
+ * write-out:
+ *   y[n,k,p,q] = max(0, conv2d_fwd(x, w)[n,k,p,q] + bias[k]).
+ * bias: DEVICE pointer to K floats (float for both dtypes), read only.
+ * Everything else as for conv2d_fwd.  Kernel families that have no epilogue
+ * of their own run one more element-wise pass over y; miconv_epilogue_is_fused
+ * tells which case applies.
+ */
+MICONV_API int conv2d_fwd_bias_relu(const void *x, const void *w, const float *bias, void *y,
+                         int N, int C, int H, int W, int K, int R, int S,
+                         int stride_h, int stride_w, int pad_h, int pad_w, int groups,
+                         int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * conv2d_bwd_data followed by the backward function (Section 4.2) of the
+ * rectified linear unit that produced the convolution's input (Section 4.1):
+ *   dx[n,c,h,w] = act[n,c,h,w] > 0 ? conv2d_bwd_data(dy, w)[n,c,h,w] : 0,
+ * i.e. the vector-Jacobian product of z -> conv2d_fwd(max(0, z), w) with
+ * respect to z, where act = max(0, z) is the tensor the forward pass was fed
+ * (the derivative of max(0, .) at 0 is taken as 0).
+ * act: DEVICE pointer, shaped like x ([N][C][H][W]) with the element type
+ * dtype names, read only; it may be the forward pass's x itself.
+ * Everything else as for conv2d_bwd_data.
+ */
+MICONV_API int conv2d_bwd_data_relu_mask(const void *dy, const void *w, const void *act, void *dx,
+                              int N, int C, int H, int W, int K, int R, int S,
+                              int stride_h, int stride_w, int pad_h, int pad_w, int groups,
+                              int dtype, void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Host-only query: 1 when the kernel that conv2d_fwd_bias_relu (pass
+ * MICONV_PASS_FWD) or conv2d_bwd_data_relu_mask (MICONV_PASS_BWD_DATA) runs
+ * for these arguments applies the epilogue in its own write-out (given
+ * 16-byte aligned tensors), 0 when a separate element-wise pass follows.
+ */
+MICONV_API int miconv_epilogue_is_fused(int pass,
+                             int N, int C, int H, int W, int K, int R, int S,
+                             int stride_h, int stride_w, int pad_h, int pad_w, int groups,
+                             int dtype);
+
+/*
  * conv2d_bwd_weight for callers that cannot allocate device memory (code under
  * HIP graph capture, serving loops, harnesses that forbid hipMalloc): the same
  * kernels and the same result, bit for bit, as conv2d_bwd_weight, but the scratch memory (the

@@ -36,6 +36,12 @@ for _name in ("conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight"):
     _fn = getattr(_lib, _name)
     _fn.restype = _i
     _fn.argtypes = [ctypes.c_void_p] * 3 + _dims + [_i, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+for _name in ("conv2d_fwd_bias_relu", "conv2d_bwd_data_relu_mask"):
+    _fn = getattr(_lib, _name)
+    _fn.restype = _i
+    _fn.argtypes = [ctypes.c_void_p] * 4 + _dims + [_i, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.miconv_epilogue_is_fused.restype = _i
+_lib.miconv_epilogue_is_fused.argtypes = [_i] + _dims + [_i]
 _lib.conv2d_bwd_weight_static_ws.restype = _i
 _lib.conv2d_bwd_weight_static_ws.argtypes = [ctypes.c_void_p] * 3 + _dims + [_i, ctypes.c_void_p]
 _lib.conv2d_workspace_bytes.restype = ctypes.c_size_t
@@ -100,6 +106,32 @@ def conv2d_bwd_weight(x, dy, dw, N, C, H, W, K, R, S, stride_h, stride_w, pad_h,
                       dtype=F32, workspace=None, stream=0, check=True):
     return _call(_lib.conv2d_bwd_weight, x, dy, dw, (N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups),
                  dtype, workspace, stream, check)
+
+
+def _call4(fn, a, b, c, out, dims, dtype, workspace, stream, check):
+    wptr, wbytes = _ws(workspace)
+    rc = fn(_ptr(a), _ptr(b), _ptr(c), _ptr(out), *[int(d) for d in dims], int(dtype), wptr, wbytes,
+            ctypes.c_void_p(int(stream)) if stream else None)
+    if check and rc != OK:
+        raise MiconvError(rc, last_error())
+    return rc
+
+
+def conv2d_fwd_bias_relu(x, w, bias, y, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,
+                         dtype=F32, workspace=None, stream=0, check=True):
+    return _call4(_lib.conv2d_fwd_bias_relu, x, w, bias, y,
+                  (N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups), dtype, workspace, stream, check)
+
+
+def conv2d_bwd_data_relu_mask(dy, w, act, dx, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,
+                              dtype=F32, workspace=None, stream=0, check=True):
+    return _call4(_lib.conv2d_bwd_data_relu_mask, dy, w, act, dx,
+                  (N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups), dtype, workspace, stream, check)
+
+
+def miconv_epilogue_is_fused(pass_, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype=F32) -> bool:
+    return bool(_lib.miconv_epilogue_is_fused(int(pass_), N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w,
+                                              groups, int(dtype)))
 
 
 def conv2d_bwd_weight_static_ws(x, dy, dw, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,

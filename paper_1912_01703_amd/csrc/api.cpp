@@ -109,7 +109,7 @@ size_t workspace_for(int pass, int algo, const Problem& pr) {
 
 int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, int W, int K, int R, int S, int sh,
         int sw, int ph, int pw, int groups, int dtype, void* ws, size_t ws_bytes, void* stream,
-        bool static_ws = false) {
+        bool static_ws = false, bool with_epilogue = false, const void* epilogue_arg = nullptr) {
     static const char* const in_names[3][2] = {{"x", "w"}, {"dy", "w"}, {"x", "dy"}};
     static const char* const out_names[3] = {"y", "dx", "dw"};
     Problem pr;
@@ -118,6 +118,11 @@ int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, 
     if (!a) return fail(MICONV_ERR_NULL, "%s is NULL", in_names[pass][0]);
     if (!b) return fail(MICONV_ERR_NULL, "%s is NULL", in_names[pass][1]);
     if (!out) return fail(MICONV_ERR_NULL, "%s is NULL", out_names[pass]);
+    if (with_epilogue) {
+        if (!epilogue_arg) return fail(MICONV_ERR_NULL, "%s is NULL", pass == MICONV_PASS_FWD ? "bias" : "act");
+        if (pass == MICONV_PASS_FWD) pr.bias = static_cast<const float*>(epilogue_arg);
+        else pr.relu_mask = epilogue_arg;
+    }
     const int algo = choose_algo(pass, pr);
     if (algo < 0)
         return fail(MICONV_ERR_UNSUPPORTED, "forced algorithm %d cannot run this problem (pass %d)",
@@ -137,16 +142,19 @@ int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, 
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
+    bool fused = false;
     float* o = static_cast<float*>(out);
     if (algo == MICONV_ALGO_DIRECT) {
         if (pass == MICONV_PASS_FWD) e = miconv::direct_fwd(pr, a, b, o, st);
         else if (pass == MICONV_PASS_BWD_DATA) e = miconv::direct_bwd_data(pr, a, b, o, st);
         else e = miconv::direct_bwd_weight(pr, a, b, o, st);
     } else if (algo == MICONV_ALGO_MFMA) {
-        e = miconv::mfma_run(pass, pr, a, b, o, ws, st);
+        e = miconv::mfma_run(pass, pr, a, b, o, ws, st, &fused);
     } else {
-        e = miconv::depthwise_run(pass, pr, a, b, o, ws, st);
+        e = miconv::depthwise_run(pass, pr, a, b, o, ws, st, &fused);
     }
+    // kernels without an epilogue of their own: one element-wise pass over the finished output
+    if (e == hipSuccess && with_epilogue && !fused) e = miconv::epilogue_run(pass, pr, o, st);
     if (e != hipSuccess) return fail(MICONV_ERR_LAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
     g_last_algo[pass] = algo;
     return MICONV_OK;
@@ -182,6 +190,32 @@ int conv2d_bwd_weight_static_ws(const void* x, const void* dy, void* dw, int N, 
                                 void* hip_stream) {
     return run(MICONV_PASS_BWD_WEIGHT, x, dy, dw, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,
                dtype, nullptr, 0, hip_stream, true);
+}
+
+int conv2d_fwd_bias_relu(const void* x, const void* w, const float* bias, void* y, int N, int C, int H, int W, int K, int R,
+                         int S, int stride_h, int stride_w, int pad_h, int pad_w, int groups, int dtype, void* workspace,
+                         size_t workspace_bytes, void* hip_stream) {
+    return run(MICONV_PASS_FWD, x, w, y, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype,
+               workspace, workspace_bytes, hip_stream, false, true, bias);
+}
+
+int conv2d_bwd_data_relu_mask(const void* dy, const void* w, const void* act, void* dx, int N, int C, int H, int W, int K,
+                              int R, int S, int stride_h, int stride_w, int pad_h, int pad_w, int groups, int dtype,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return run(MICONV_PASS_BWD_DATA, dy, w, dx, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype,
+               workspace, workspace_bytes, hip_stream, false, true, act);
+}
+
+int miconv_epilogue_is_fused(int pass, int N, int C, int H, int W, int K, int R, int S, int stride_h, int stride_w, int pad_h,
+                             int pad_w, int groups, int dtype) {
+    if (pass != MICONV_PASS_FWD && pass != MICONV_PASS_BWD_DATA) return 0;
+    Problem pr;
+    if (make_problem(pr, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype) != MICONV_OK) return 0;
+    switch (choose_algo(pass, pr)) {
+        case MICONV_ALGO_MFMA: return miconv::mfma_fuses_epilogue(pass, pr) ? 1 : 0;
+        case MICONV_ALGO_DEPTHWISE: return miconv::depthwise_fuses_epilogue(pass, pr) ? 1 : 0;
+        default: return 0;
+    }
 }
 
 size_t conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int R, int S, int stride_h, int stride_w,

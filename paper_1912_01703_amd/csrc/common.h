@@ -13,6 +13,10 @@ struct Problem {
     int sh, sw, ph, pw, groups;
     int P, Q, Cg, Kg;
     int dtype;  // 0 = fp32 inputs, 1 = bf16 inputs (fp32 accumulate and outputs)
+    // Fused epilogues (null: none).  Forward: y = max(0, y + bias[k]).  Backward-data: dx = relu_mask > 0 ? dx : 0,
+    // relu_mask shaped like x with the element type dtype names.
+    const float* bias = nullptr;
+    const void* relu_mask = nullptr;
 };
 
 // bf16 bit pattern -> float, exact.
@@ -56,7 +60,8 @@ hipError_t direct_bwd_weight(const Problem& pr, const void* x, const void* dy, f
 // of the pass in the order of the C ABI; out is y, dx or dw.
 bool mfma_supports(int pass, const Problem& pr);
 size_t mfma_workspace_bytes(int pass, const Problem& pr);
-hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws, hipStream_t st);
+hipError_t mfma_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws, hipStream_t st,
+                    bool* fused_epilogue);
 // The kernel family inside the MFMA paths that mfma_run would take ("none" if mfma_supports is false).
 const char* mfma_path_name(int pass, const Problem& pr);
 
@@ -92,11 +97,19 @@ hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* 
 bool wgrad_supports(const Problem& pr, size_t* ws_bytes);
 hipError_t wgrad_run(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st);
 
+// ---- epilogues (epilogue.hip) --------------------------------------------------------------
+// Whether the kernel a pass is dispatched to applies the problem's epilogue in its own write-out; if not, the
+// dispatcher runs epilogue_run over the finished output.
+bool mfma_fuses_epilogue(int pass, const Problem& pr);
+bool depthwise_fuses_epilogue(int pass, const Problem& pr);
+hipError_t epilogue_run(int pass, const Problem& pr, float* out, hipStream_t st);
+
 // ---- depthwise kernels (depthwise.hip): groups == C == K, no MFMA ------------------------
 bool depthwise_supports(int pass, const Problem& pr);
 size_t depthwise_workspace_bytes(int pass, const Problem& pr);
+// *fused_epilogue tells whether the launched kernel applied pr's epilogue itself.
 hipError_t depthwise_run(int pass, const Problem& pr, const void* a, const void* b, float* out, void* ws,
-                         hipStream_t st);
+                         hipStream_t st, bool* fused_epilogue);
 const char* depthwise_path_name(int pass, const Problem& pr);
 
 }  // namespace miconv

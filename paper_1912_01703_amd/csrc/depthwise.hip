@@ -270,6 +270,10 @@ struct DwStripArgs {
     float inv_ppw, inv_pps, inv_ow, inv_nseg, inv_c, inv_iplane, inv_iw;
     int flip, nbatches;
     unsigned src_bytes, w_bytes;
+    // fused epilogues of the 16-byte path (see EPI below)
+    const float* bias;   // [C]
+    const void* mask;    // float, shaped like dst
+    unsigned dst_bytes;
 };
 
 // NPIB: 64-lane passes over the batch's padded planes (NPIB*64 >= PB*PPH*PPW).  NPS: most compute passes.
@@ -280,8 +284,12 @@ struct DwStripArgs {
 // PPWC, OWC: padded-plane and output widths known at compile time (0: taken from the arguments), which
 // turns every LDS offset of the compute step into an immediate.  Such an instance also assumes that the
 // output height is a multiple of kSeg: every lane owns kSeg rows or none, and the per-row checks go.
-template <typename T, int ST, int NPIB, int NPS, bool WIDE, int PPWC = 0, int OWC = 0>
+// EPI (16-byte path only): 0 plain; 1 forward with bias and ReLU: the accumulator starts at the channel's bias (kept in
+// LDS behind the filter taps) and is clamped at zero; 2 backward-data with a ReLU mask: the mask values under a
+// batch's results are fetched together with the next batch and applied to the float4 on its way out.
+template <typename T, int ST, int NPIB, int NPS, bool WIDE, int PPWC = 0, int OWC = 0, int EPI = 0>
 __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs a) {
+    static_assert(EPI == 0 || (WIDE && sizeof(T) == 4), "fused epilogues exist on the 16-byte fp32 path");
     constexpr int NLV = 4;   // float4 passes over a batch's input / output (PB*plane/4 <= 256)
     extern __shared__ float lds[];
     constexpr unsigned ESZ = sizeof(T);
@@ -316,7 +324,7 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
         const bool ok = e < a.PB * PPS && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
         goff[i] = ok ? (unsigned)(pl * iplane + ih * a.IW + iw) * ESZ : kOob;
     }
-    int win[NPS], oo[NPS], rows[NPS], wof[NPS];
+    int win[NPS], oo[NPS], rows[NPS], wof[NPS], bof[NPS];
     {
         const int ul = fdiv(lane, a.inv_ow), q = lane - ul * ow;
 #pragma unroll
@@ -330,15 +338,18 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
             oo[ps] = pl * oplane + p0 * ow + q;
             rows[ps] = ok ? min(kSeg, a.OH - p0) : 0;
             wof[ps] = pl * 9;
+            bof[ps] = 9 * a.PB + pl;
         }
     }
 
     const rsrc_t srs = make_rsrc(a.src, a.src_bytes);
     const rsrc_t wrs = make_rsrc(a.w, a.w_bytes);
+    const rsrc_t mrs = make_rsrc(a.mask, EPI == 2 ? a.dst_bytes : 0u);
     const int nw = gridDim.x * (kThreads / 64);
     float v[WIDE ? 1 : NPIB];
     v4u v4[WIDE ? NLV : 1];
-    float wreg;
+    v4u m4[EPI == 2 ? NLV : 1], m4cur[EPI == 2 ? NLV : 1];
+    float wreg, breg = 0.f;
     // Planes past the end of the tensor lie beyond the descriptor: zeros.
     auto fetch = [&](int b) {
         const unsigned base = (unsigned)(b * a.PB * iplane) * ESZ;
@@ -354,6 +365,19 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
         const int plane = b * a.PB + pl;
         const int c = plane - fdiv(plane, a.inv_c) * a.C;
         wreg = buf_load(wrs, (pl < a.PB && plane < a.planes) ? (unsigned)(c * 9 + (a.flip ? 8 - t : t)) * ESZ : kOob, tnull);
+        if constexpr (EPI == 1) {   // lane l < PB fetches the bias of the batch's plane l
+            const int bplane = b * a.PB + lane;
+            const int bc = bplane - fdiv(bplane, a.inv_c) * a.C;
+            breg = (lane < a.PB && bplane < a.planes) ? a.bias[bc] : 0.f;
+        }
+        if constexpr (EPI == 2) {   // the mask under the batch's results, as the results will be stored
+            const unsigned mbase = (unsigned)(b * a.PB * oplane) * 4u;
+#pragma unroll
+            for (int i = 0; i < NLV; ++i) {
+                const int f = lane + 64 * i;
+                m4[i] = __builtin_amdgcn_raw_buffer_load_b128(mrs, 4 * f < a.PB * oplane ? mbase + (unsigned)f * 16u : kOob, 0, 0);
+            }
+        }
     };
     int b = blockIdx.x * (kThreads / 64) + wave;
     if (b < a.nbatches) fetch(b);   // the first batch is on its way while the rest of the plan is made
@@ -389,6 +413,13 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
                 if (lane + 64 * i < a.PB * PPS) my[lane + 64 * i] = v[i];
         }
         if (lane < 9 * a.PB) wl[lane] = wreg;
+        if constexpr (EPI == 1) {
+            if (lane < a.PB) wl[9 * a.PB + lane] = breg;
+        }
+        if constexpr (EPI == 2) {
+#pragma unroll
+            for (int i = 0; i < NLV; ++i) m4cur[i] = m4[i];
+        }
         if (b + nw < a.nbatches) fetch(b + nw);   // the next batch travels while this one is computed
         float* d = a.dst + (size_t)b * a.PB * oplane;
         const int live = min(a.PB, a.planes - b * a.PB) * oplane;   // outputs that exist in this batch
@@ -402,13 +433,15 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
             for (int r = 0; r < (kSeg - 1) * ST + 3; ++r)
 #pragma unroll
                 for (int s = 0; s < 3; ++s) xw[r][s] = xq[r * ppw + s];
+            const float bias0 = EPI == 1 ? wl[bof[ps]] : 0.f;
 #pragma unroll
             for (int i = 0; i < kSeg; ++i) {
-                float acc = 0.f;
+                float acc = bias0;
 #pragma unroll
                 for (int r = 0; r < 3; ++r)
 #pragma unroll
                     for (int s = 0; s < 3; ++s) acc = fmaf(xw[i * ST + r][s], wv[r * 3 + s], acc);
+                if constexpr (EPI == 1) acc = fmaxf(acc, 0.f);
                 const int o = oo[ps] + i * ow;
                 if constexpr (WIDE) {
                     if (WHOLE || i < rows[ps]) ol[o] = acc;
@@ -432,8 +465,14 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
                 const int f = lane + 64 * i;
                 // streamed past the caches: the results are not read again by this kernel, and a plain store
                 // costs a fifth more time (22.2 against 18.0 us on 14x14 planes, N*C = 65 536)
-                if (4 * f < live)
-                    __builtin_nontemporal_store(*reinterpret_cast<const v4f*>(ol + 4 * f), reinterpret_cast<v4f*>(d + 4 * f));
+                if (4 * f < live) {
+                    v4f r4 = *reinterpret_cast<const v4f*>(ol + 4 * f);
+                    if constexpr (EPI == 2) {
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) r4[k] = __uint_as_float(m4cur[i][k]) > 0.f ? r4[k] : 0.f;
+                    }
+                    __builtin_nontemporal_store(r4, reinterpret_cast<v4f*>(d + 4 * f));
+                }
             }
         }
     }
@@ -812,7 +851,7 @@ bool strip_plan(const Problem& pr, int oh, int ow, int pph, int ppw, int stride,
     sp.PB = pb;
     sp.passes = (pb * sp.NSEG + sp.UPP - 1) / sp.UPP;
     sp.w_off = (pb * pps + (kSeg * stride + 3) * ppw + 3) & ~3;
-    sp.o_off = (sp.w_off + 9 * pb + 3) & ~3;
+    sp.o_off = (sp.w_off + 10 * pb + 3) & ~3;   // nine taps and one bias per plane
     sp.lds_per_wave = ((sp.o_off + pb * oh * ow + 3) & ~3) + 4;   // the last word takes values that have no place
     return true;
 }
@@ -838,8 +877,9 @@ bool strip_stencil_args(int pass, const Problem& pr, const void* in0, const void
     return true;
 }
 
+// *fused is set when the launched instance applies the problem's epilogue (bias + ReLU or ReLU mask) itself.
 template <typename T, int ST>
-hipError_t launch_strip_stencil(const DwStripArgs& a, hipStream_t st) {
+hipError_t launch_strip_stencil(const DwStripArgs& a, hipStream_t st, bool* fused) {
     // Persistent waves: each keeps one batch in flight while it computes the previous one.
     // The grid is what is resident at once (256 CUs x the occupancy the register budget allows).
     const size_t smem = (size_t)4 * a.lds_per_wave * sizeof(float);
@@ -847,6 +887,7 @@ hipError_t launch_strip_stencil(const DwStripArgs& a, hipStream_t st) {
                       reinterpret_cast<uintptr_t>(a.src) % 16 == 0 && reinterpret_cast<uintptr_t>(a.dst) % 16 == 0;
     // Workgroups per CU: registers allow 4 for the 16-byte stride-1 kernel (3 otherwise), LDS 160 KB.
     int occ = wide && ST == 1 ? 4 : 3;
+    if (sizeof(T) == 4 && wide && a.mask) occ = ST == 1 ? 3 : 2;   // the mask instance holds a second set of float4 registers
     while (occ > 1 && occ * smem > 160 * 1024) --occ;
     const int resident = 256 * occ;
     // Every wave runs the same number of batches (a grid of `resident` would leave most waves idle in
@@ -854,7 +895,22 @@ hipError_t launch_strip_stencil(const DwStripArgs& a, hipStream_t st) {
     const int wg_batches = (a.nbatches + 3) / 4;
     const int rounds = (wg_batches + resident - 1) / resident;
     const int grid = (wg_batches + rounds - 1) / rounds;
-    if (wide && ST == 1 && a.PPW == 16 && a.OW == 14 && a.OH % kSeg == 0) dw_strip_stencil_kernel<T, 1, 16, 2, true, 16, 14><<<grid, kThreads, smem, st>>>(a);
+    const bool fixed = wide && ST == 1 && a.PPW == 16 && a.OW == 14 && a.OH % kSeg == 0;   // 14x14 planes, padding 1
+    if constexpr (sizeof(T) == 4) {
+        const bool mask_ok = a.mask && reinterpret_cast<uintptr_t>(a.mask) % 16 == 0;
+        if (wide && (a.bias || mask_ok)) {
+            *fused = true;
+            if (a.bias) {
+                if (fixed) dw_strip_stencil_kernel<T, 1, 16, 2, true, 16, 14, 1><<<grid, kThreads, smem, st>>>(a);
+                else dw_strip_stencil_kernel<T, ST, 16, 2, true, 0, 0, 1><<<grid, kThreads, smem, st>>>(a);
+            } else {
+                if (fixed) dw_strip_stencil_kernel<T, 1, 16, 2, true, 16, 14, 2><<<grid, kThreads, smem, st>>>(a);
+                else dw_strip_stencil_kernel<T, ST, 16, 2, true, 0, 0, 2><<<grid, kThreads, smem, st>>>(a);
+            }
+            return hipGetLastError();
+        }
+    }
+    if (fixed) dw_strip_stencil_kernel<T, 1, 16, 2, true, 16, 14><<<grid, kThreads, smem, st>>>(a);
     else if (wide) dw_strip_stencil_kernel<T, ST, 16, 2, true><<<grid, kThreads, smem, st>>>(a);
     else dw_strip_stencil_kernel<T, ST, 16, 2, false><<<grid, kThreads, smem, st>>>(a);
     return hipGetLastError();
@@ -1313,8 +1369,14 @@ size_t depthwise_workspace_bytes(int pass, const Problem& pr) {
     return nsplit > 1 ? (size_t)nsplit * pr.C * 9 * sizeof(float) : 0;
 }
 
+bool depthwise_fuses_epilogue(int pass, const Problem& pr) {
+    // (given 16-byte aligned tensors; depthwise_run reports what the launch really did)
+    return pass < 2 && pr.dtype == 0 && stencil_path(pass, pr) == SPath::strip && (pr.H * pr.W) % 4 == 0 && (pr.P * pr.Q) % 4 == 0;
+}
+
 hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
-                         hipStream_t st) {
+                         hipStream_t st, bool* fused) {
+    *fused = false;
     const int count = pr.C * 9;
     if (pass == 2) {
         const WPath path = wgrad_path(pr);
@@ -1372,8 +1434,11 @@ hipError_t depthwise_run(int pass, const Problem& pr, const void* in0, const voi
     int stride;
     if (spath == SPath::strip) {
         strip_stencil_args(pass, pr, in0, in1, out, sa, stride);
-        if (pr.dtype == 0) return stride == 1 ? launch_strip_stencil<float, 1>(sa, st) : launch_strip_stencil<float, 2>(sa, st);
-        return stride == 1 ? launch_strip_stencil<uint16_t, 1>(sa, st) : launch_strip_stencil<uint16_t, 2>(sa, st);
+        sa.bias = pass == 0 ? pr.bias : nullptr;
+        sa.mask = pass == 1 ? pr.relu_mask : nullptr;
+        sa.dst_bytes = (unsigned)((size_t)sa.planes * sa.OH * sa.OW * sizeof(float));
+        if (pr.dtype == 0) return stride == 1 ? launch_strip_stencil<float, 1>(sa, st, fused) : launch_strip_stencil<float, 2>(sa, st, fused);
+        return stride == 1 ? launch_strip_stencil<uint16_t, 1>(sa, st, fused) : launch_strip_stencil<uint16_t, 2>(sa, st, fused);
     }
     if (spath == SPath::rows) {
         DwRowArgs ra{};

@@ -1,5 +1,6 @@
 // Dispatcher of the MFMA paths: which kernel family serves which pass.
 #include "common.h"
+#include <cstring>
 namespace miconv {
 
 static bool is_depthwise(const Problem& pr) { return pr.groups == pr.C && pr.groups == pr.K && pr.groups > 1; }
@@ -50,8 +51,16 @@ const char* mfma_path_name(int pass, const Problem& in) {
     return tile_merge2_supports(pr) ? "mfma/tile_merge2" : "mfma/tile_phase";
 }
 
-hipError_t mfma_run(int pass, const Problem& in, const void* a, const void* b, float* out, void* ws, hipStream_t st) {
+// The kernels built on conv_tile_kernel apply bias + ReLU / the ReLU mask in their write-out.
+bool mfma_fuses_epilogue(int pass, const Problem& in) {
+    const char* path = mfma_path_name(pass, in);
+    return std::strncmp(path, "mfma/tile", 9) == 0;
+}
+
+hipError_t mfma_run(int pass, const Problem& in, const void* a, const void* b, float* out, void* ws, hipStream_t st,
+                    bool* fused_epilogue) {
     const Problem pr = canonical(in);
+    *fused_epilogue = mfma_fuses_epilogue(pass, in);
     if (smallc_supports(pass, pr)) return smallc_run(pass, pr, a, b, out, ws, st);
     if (bf16_tile_supports(pass, pr)) return bf16_tile_run(pass, pr, a, b, out, ws, st);
     if (pass == 2 && bf16_wgrad_supports(pr)) return bf16_wgrad_run(pr, a, b, out, ws, st);

@@ -106,6 +106,7 @@ bool make_args(int pass, const Problem& pr, const void* in0, const void* in1, fl
     if (pass == 0) {
         a = TileArgs{in0, in1, out, pr.N, pr.C, pr.H, pr.W, pr.K, pr.P, pr.Q, pr.Kg, pr.Cg, pr.groups,
                      pr.ph, pr.pw, 0, 0, 0, 0, wbytes};
+        a.bias = pr.bias;
         stride = pr.sh;
         return true;
     }
@@ -113,6 +114,7 @@ bool make_args(int pass, const Problem& pr, const void* in0, const void* in1, fl
         if (pr.sh != 1) return false;
         a = TileArgs{in0, in1, out, pr.N, pr.K, pr.P, pr.Q, pr.C, pr.H, pr.W, pr.Cg, pr.Kg, pr.groups,
                      pr.R - 1 - pr.ph, pr.S - 1 - pr.pw, 0, 0, 0, 0, wbytes};
+        a.mask = pr.relu_mask;
         stride = 1;
         return true;
     }

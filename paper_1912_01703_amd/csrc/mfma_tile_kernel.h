@@ -57,6 +57,9 @@ struct TileArgs {
     int tapoff[9];         // phase mode: offset of sub-filter tap t inside a (k, c) filter plane
     int items;             // work item ids: units rounded up to a multiple of 8, times fblocks
     int fill2;             // phase mode, 1x1 filter at stride 2: the three pixels next to every written one get zeros
+    // Fused epilogues of the write-out (both null: plain convolution).
+    const float* bias;     // [Cdst]: dst = max(0, dst + bias[channel])
+    const void* mask;      // shaped and typed like the destination's counterpart among the inputs: dst = mask > 0 ? dst : 0
 };
 
 // Smallest channel stride >= v such that kq consecutive channels span 16 banks (mod 32): the two
@@ -392,19 +395,60 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         const int fq = it.fblk * (16 * WF) + wf * 16 + 4 * kk;
         const int dplane = PHASE || MERGE2 ? a.DH * a.DW : a.OH * a.OW;
         float* dst = a.dst + (size_t)(it.n * a.Cdst + it.g * a.Fg) * dplane;
-#pragma unroll
-        for (int i = 0; i < NBW; ++i) {
+        // Where accumulator set q of pixel block i goes: destination pixel index inside a plane, or -1 for none.
+        // MERGE2: set (a, b) holds destination pixel (2*oh + 1 - a, 2*ow + 1 - b).
+        auto pixel = [&](int i, int q, int& oh, int& ow) __attribute__((always_inline)) -> int {
             const int j = 16 * (wp + WP * i) + li;
             const int th = j / TW, tw = j - th * TW;
-            const int oh = it.oh0 + th, ow = it.ow0 + tw;
-            if (!it.ok || j >= NPX || oh >= a.OH || ow >= a.OW) continue;
+            oh = it.oh0 + th; ow = it.ow0 + tw;
+            if (!it.ok || j >= NPX || oh >= a.OH || ow >= a.OW) return -1;
+            const int dh = 2 * oh + 1 - q / 2, dw = 2 * ow + 1 - q % 2;
+            if (MERGE2 && (dh >= a.DH || dw >= a.DW)) return -1;
+            return MERGE2 ? dh * a.DW + dw : (PHASE ? (oh * a.o_sh + a.o_oh) * a.DW + ow * a.o_sw + a.o_ow : oh * a.OW + ow);
+        };
+        // Epilogues (wave-uniform branches on kernel arguments).  Bias + ReLU: the bias of the lane's four filters.
+        if (a.bias) {
+            float bv[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int v = 0; v < 4; ++v)
+                if (it.ok && fq + v < a.Fg) bv[v] = a.bias[it.g * a.Fg + fq + v];
+#pragma unroll
+            for (int q = 0; q < NSET; ++q)
+#pragma unroll
+                for (int i = 0; i < NBW; ++i)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[q][i][v] = fmaxf(acc[q][i][v] + bv[v], 0.f);
+        }
+        // ReLU mask: the mask element under every result is requested first (buffer loads without branches, an
+        // out-of-range offset where there is no result), so that the item waits for memory once, not per element.
+        if (a.mask) {
+            const rsrc_t mrs = make_rsrc(static_cast<const T*>(a.mask) + (size_t)(it.n * a.Cdst + it.g * a.Fg) * dplane,
+                                         it.ok ? (unsigned)((size_t)a.Fg * dplane * sizeof(T)) : 0u);
+            float mv[NSET][NBW][4];
+#pragma unroll
+            for (int q = 0; q < NSET; ++q)
+#pragma unroll
+                for (int i = 0; i < NBW; ++i) {
+                    int oh, ow;
+                    const int pix = pixel(i, q, oh, ow);
+#pragma unroll
+                    for (int v = 0; v < 4; ++v)
+                        mv[q][i][v] = buf_load(mrs, pix >= 0 && fq + v < a.Fg ? (unsigned)((fq + v) * dplane + pix) * (unsigned)sizeof(T) : kOob, tnull);
+                }
+#pragma unroll
+            for (int q = 0; q < NSET; ++q)
+#pragma unroll
+                for (int i = 0; i < NBW; ++i)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) acc[q][i][v] = mv[q][i][v] > 0.f ? acc[q][i][v] : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
 #pragma unroll
             for (int q = 0; q < NSET; ++q) {
-                // MERGE2: set (a, b) holds destination pixel (2*oh + 1 - a, 2*ow + 1 - b)
-                const int dh = 2 * oh + 1 - q / 2, dw = 2 * ow + 1 - q % 2;
-                if (MERGE2 && (dh >= a.DH || dw >= a.DW)) continue;
-                const int pix = MERGE2 ? dh * a.DW + dw
-                                       : (PHASE ? (oh * a.o_sh + a.o_oh) * a.DW + ow * a.o_sw + a.o_ow : oh * a.OW + ow);
+                int oh, ow;
+                const int pix = pixel(i, q, oh, ow);
+                if (pix < 0) continue;
                 if (PHASE && a.fill2) {
                     // pix = (2 oh, 2 ow): the 2 x 2 block it heads belongs to this lane alone (no tap reaches the other three)
                     const bool right = 2 * ow + 1 < a.DW, below = 2 * oh + 1 < a.DH;

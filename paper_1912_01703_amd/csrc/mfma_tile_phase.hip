@@ -118,6 +118,7 @@ hipError_t tile_merge2_run(const Problem& pr, const void* dy, const void* w, flo
     t.wgt_bytes = (unsigned)((size_t)pr.K * pr.Cg * pr.R * pr.S * esz);
     t.DH = pr.H; t.DW = pr.W;
     t.w_rs = 9;
+    t.mask = pr.relu_mask;
     if (t.Fg <= 16) return pr.dtype == 0 ? launch_merge2<float, 1, 4>(t, st) : launch_merge2<uint16_t, 1, 4>(t, st);
     return pr.dtype == 0 ? launch_merge2<float, 2, 4>(t, st) : launch_merge2<uint16_t, 2, 4>(t, st);
 }
@@ -169,6 +170,7 @@ hipError_t tile_phase_run(const Problem& pr, const void* dy, const void* w, floa
             t.o_oh = pr.sh * ph.i0 + a - pr.ph; t.o_ow = pr.sw * pw.i0 + b - pr.pw;
             t.DH = pr.H; t.DW = pr.W;
             t.w_rs = pr.R * pr.S;
+            t.mask = pr.relu_mask;
             t.fill2 = fill2 ? (pr.W % 2 == 0 && reinterpret_cast<uintptr_t>(dx) % 8 == 0 ? 2 : 1) : 0;
             for (int jr = 0; jr < ph.J; ++jr)
                 for (int js = 0; js < pw.J; ++js)

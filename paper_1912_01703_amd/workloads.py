@@ -113,6 +113,16 @@ def make_inputs(layer: Layer):
     return x, w, dy
 
 
+def make_epilogue_inputs(layer: Layer):
+    """Inputs of the fused epilogues, drawn from PCG64(layer.seed + 1000): bias ~ N(0,1) per output channel
+    (float32) and act = max(0, z), z ~ N(0,1), shaped like x: the output of a rectified linear unit, about half of it
+    exactly zero."""
+    rng = np.random.Generator(np.random.PCG64(layer.seed + 1000))
+    bias = rng.standard_normal(size=(layer.K,), dtype=np.float32)
+    act = np.maximum(rng.standard_normal(size=layer.x_shape, dtype=np.float32), np.float32(0.0))
+    return bias, act
+
+
 def to_bf16_bits(a: np.ndarray) -> np.ndarray:
     """Round float32 to bfloat16 (nearest, ties to even); returns uint16 bit patterns.
     NaN inputs are not expected in the synthetic data and are not special-cased."""

@@ -17,12 +17,16 @@ hipError_t direct_bwd_data(const Problem&, const void*, const void*, float*, hip
 hipError_t direct_bwd_weight(const Problem&, const void*, const void*, float*, hipStream_t) { ++g_launches; return hipSuccess; }
 bool mfma_supports(int, const Problem& pr) { return pr.R == 3 && pr.groups == 1; }
 size_t mfma_workspace_bytes(int pass, const Problem& pr) { return pass == 2 ? (size_t)pr.K * pr.Cg * pr.R * pr.S * 8 : 0; }
-hipError_t mfma_run(int, const Problem&, const void*, const void*, float*, void*, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t mfma_run(int, const Problem&, const void*, const void*, float*, void*, hipStream_t, bool* fused) { ++g_launches; *fused = false; return hipSuccess; }
 const char* mfma_path_name(int, const Problem&) { return "mfma/stub"; }
 bool depthwise_supports(int, const Problem& pr) { return pr.groups == pr.C && pr.groups == pr.K && pr.groups > 1; }
 size_t depthwise_workspace_bytes(int, const Problem&) { return 0; }
-hipError_t depthwise_run(int, const Problem&, const void*, const void*, float*, void*, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t depthwise_run(int, const Problem&, const void*, const void*, float*, void*, hipStream_t, bool* fused) { ++g_launches; *fused = true; return hipSuccess; }
 const char* depthwise_path_name(int, const Problem&) { return "depthwise/stub"; }
+static int g_epilogues = 0;
+bool mfma_fuses_epilogue(int, const Problem&) { return false; }
+bool depthwise_fuses_epilogue(int, const Problem&) { return true; }
+hipError_t epilogue_run(int, const Problem&, float*, hipStream_t) { ++g_epilogues; return hipSuccess; }
 }  // namespace miconv
 
 typedef int (*pass_fn)(const void*, const void*, void*, int, int, int, int, int, int, int, int, int, int, int, int, int, void*,

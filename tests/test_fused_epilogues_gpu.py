@@ -1,0 +1,122 @@
+"""GPU parity of the fused epilogues against the CPU oracle, through the C ABI.
+
+conv2d_fwd_bias_relu:       y  = max(0, conv(x, w) + bias[k])
+conv2d_bwd_data_relu_mask:  dx = act > 0 ? bwd_data(dy, w) : 0
+
+Error measure: |gpu - ref| / D per element, with D = sum |x||w| + |bias[k]| for the forward call (max(0, .) is
+1-Lipschitz, so the bound of the plain pass carries through the kink) and D = sum |dy||w| for the backward call;
+bounds 1e-5 (fp32 inputs) and 1e-2 (bf16 inputs).  Where D is zero, and wherever act is not positive, the GPU value
+must be exactly zero.
+"""
+import numpy as np
+import pytest
+
+from oracle import convref as ref
+from paper_1912_01703_amd import workloads as wl
+
+import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+
+
+def run_fused(L, dtype, which, algo=None):
+    """Runs one fused call on the GPU and the oracle on the same inputs; returns (gpu, ref, D, act or None)."""
+    import torch
+    from paper_1912_01703_amd import binding as mc
+    h = pu.prepare(L, dtype)
+    bias, act = wl.make_epilogue_inputs(L)
+    code = mc.BF16_F32ACC if dtype == "bf16" else mc.F32
+    st, pd, g = L.strides, L.pads, L.groups
+    dev = "cuda:0"
+    up = lambda a: torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).to(dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    pid = 0 if which == "fwd" else 1
+    need = mc.conv2d_workspace_bytes(pid, *L.conv_args(), code)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    mc.miconv_set_algo(pid, algo if algo is not None else mc.ALGO_AUTO)
+    print(f"[fused] layer={L.name} dtype={dtype} call={which} algo={algo}", flush=True)
+    try:
+        if which == "fwd":
+            out = torch.full(L.y_shape, float("nan"), device=dev)
+            mc.conv2d_fwd_bias_relu(up(h["x"]), up(h["w"]), up(bias), out, *L.conv_args(), code, ws, stream)
+            want = ref.conv2d_fwd_bias_relu(h["xo"], h["wo"], bias, st, pd, g)
+            den = ref.conv2d_fwd(pu._abs(h["xo"]), pu._abs(h["wo"]), st, pd, g) + np.abs(bias.astype(np.float64))[None, :, None, None]
+            mask = None
+        else:
+            a_in = wl.to_bf16_bits(act) if dtype == "bf16" else act
+            out = torch.full(L.x_shape, float("nan"), device=dev)
+            mc.conv2d_bwd_data_relu_mask(up(h["dy"]), up(h["w"]), up(a_in), out, *L.conv_args(), code, ws, stream)
+            want = ref.conv2d_bwd_data_relu(h["dyo"], h["wo"], a_in, st, pd, g)
+            den = ref.conv2d_bwd_data(pu._abs(h["dyo"]), pu._abs(h["wo"]), L.x_shape, st, pd, g)
+            mask = (wl.bf16_bits_to_f32(a_in) if dtype == "bf16" else a_in) > 0
+        torch.cuda.synchronize()
+    finally:
+        mc.miconv_set_algo(pid, mc.ALGO_AUTO)
+    return out.cpu().numpy(), want, den, mask
+
+
+def check(L, dtype, which, algo=None):
+    got, want, den, mask = run_fused(L, dtype, which, algo)
+    err, ok = pu.max_norm_err(got, want, den)
+    assert ok, f"{L.name}/{which}: non-finite output or non-zero where nothing reaches"
+    assert err <= pu.TOL[dtype], f"{L.name}/{which}/{dtype}: normalised error {err:.3e}"
+    if mask is not None:
+        assert np.all(got[~mask] == 0.0), f"{L.name}: values where act is not positive"
+        assert np.count_nonzero(got[mask]) > 0
+    else:
+        assert np.all(got >= 0.0) and 0.05 < np.mean(got == 0.0) < 0.95     # the clamp is really active
+
+
+@pytest.mark.parametrize("which", ["fwd", "bwd_data"])
+@pytest.mark.parametrize("name", ["1", "2a", "2b", "2c", "3", "5a", "5b"])
+def test_fused_epilogues_on_benchmark_layers_fp32(name, which):
+    from paper_1912_01703_amd import binding as mc
+    L = wl.LAYERS[name]
+    if name in ("2a", "2b", "2c", "5a", "5b"):      # these run the epilogue inside the convolution kernel's write-out
+        assert mc.miconv_epilogue_is_fused(0 if which == "fwd" else 1, *L.conv_args(), mc.F32)
+    check(L, "f32", which)
+
+
+SHAPES = [
+    # name       N   C   H   W   K  R  S  stride  pad  groups
+    ("e3x3b", 3, 16, 17, 19, 40, 3, 3, 1, 1, 1),       # ragged tiles, K not a multiple of 16: partial bias quads
+    ("e3x3g", 2, 64, 14, 14, 96, 3, 3, 1, 1, 2),       # groups: bias and mask offsets per group
+    ("e1x1d", 2, 72, 20, 28, 40, 1, 1, 1, 0, 1),       # 1x1 on row bands
+    ("e1x1i", 1, 24, 14, 112, 40, 1, 1, 1, 0, 1),      # plane presented with another shape
+    ("e3x3p", 5, 16, 210, 210, 24, 3, 3, 1, 1, 1),     # persistent workgroups: an epilogue per work item
+    ("e3x3s2d", 2, 24, 57, 60, 40, 3, 3, 2, 1, 1),     # merged-phase backward-data
+    ("e5x5s2", 2, 16, 20, 20, 16, 5, 5, 2, 2, 1),      # one launch per phase
+    ("e1x1s2", 3, 40, 28, 28, 72, 1, 1, 2, 0, 1),      # 1x1 stride 2: zeros next to every written pixel
+    ("e3x3z", 5, 40, 7, 7, 72, 3, 3, 1, 1, 1),         # 7x7 tiles
+    ("eodd4", 2, 3, 13, 9, 5, 4, 3, (3, 2), (1, 0), 1),  # direct kernels: separate epilogue pass
+    ("eodd1", 1, 4, 9, 8, 6, 3, 2, (2, 1), (0, 1), 2),
+    ("edw14", 3, 40, 14, 14, 40, 3, 3, 1, 1, 40),      # depthwise 14x14: fused instance with compile-time widths
+    ("edw28s2", 2, 24, 28, 28, 24, 3, 3, 2, 1, 24),    # depthwise stride 2
+    ("edw9x13", 5, 33, 9, 13, 33, 3, 3, 1, 0, 33),     # planes not a multiple of four: separate pass
+    ("edw16", 4, 8, 16, 20, 8, 3, 3, 1, 1, 8),         # generic 16-byte instance
+    ("edw112", 1, 3, 112, 112, 3, 3, 3, 1, 1, 3),      # row kernels: separate pass
+]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("which", ["fwd", "bwd_data"])
+@pytest.mark.parametrize("row", SHAPES, ids=[r[0] for r in SHAPES])
+def test_fused_epilogues_shapes(row, which, dtype):
+    name, N, C, H, W, K, R, S, st, pd, g = row
+    L = wl.custom_layer(name, N, C, H, W, K, R, S, st, pd, g, seed=8000 + SHAPES.index(row))
+    check(L, dtype, which)
+
+
+def test_fused_epilogue_on_the_bf16_matrix_core_path():
+    L = wl.custom_layer("eb3x3e", 1, 160, 28, 28, 128, 3, 3, 1, 1, 1, seed=8100)
+    for which in ("fwd", "bwd_data"):
+        check(L, "bf16", which)
+
+
+def test_fused_calls_reject_a_missing_epilogue_operand():
+    import torch
+    from paper_1912_01703_amd import binding as mc
+    t = torch.zeros(4096, device="cuda:0")
+    args = (1, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1)
+    assert mc.conv2d_fwd_bias_relu(t, t, None, t, *args, check=False) == mc.ERR_NULL and "bias" in mc.last_error()
+    assert mc.conv2d_bwd_data_relu_mask(t, t, None, t, *args, check=False) == mc.ERR_NULL and "act" in mc.last_error()
