@@ -435,6 +435,44 @@ def secondary_depthwise(steps, warmup, settle_ms, mc, wl, torch, np):
     return out
 
 
+def batchnorm_figures(mc, wl, torch, np, reps=20):
+    """batchnorm2d_fwd / batchnorm2d_bwd on the two benchmark shapes, cold (buffer sets rotated so that more than
+    the 256 MB Infinity Cache passes between two uses of a buffer), against the HBM peak.  Algorithmic bytes:
+    forward x once + y once (8 B per element), backward x, dy once + dx once (12 B per element)."""
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {"bound": "hbm", "peak": PEAK_HBM_GBS, "unit": "GB/s", "shapes": {}}
+    for idx, (name, N, C, H, W) in enumerate(wl.BN_SHAPES):
+        elems = N * C * H * W
+        nsets = max(4, int(600e6 // (elems * 12)) + 2)
+        x, dy, gamma, beta = wl.make_bn_inputs(N, C, H, W, 512 + idx)
+        sets = [dict(x=torch.from_numpy(x).to(dev), dy=torch.from_numpy(dy).to(dev),
+                     y=torch.empty((N, C, H, W), device=dev), dx=torch.empty((N, C, H, W), device=dev)) for _ in range(nsets)]
+        g, b = torch.from_numpy(gamma).to(dev), torch.from_numpy(beta).to(dev)
+        mean, inv_std, dg, db = (torch.empty(C, device=dev) for _ in range(4))
+        ws = torch.empty(max(256, max(mc.batchnorm2d_workspace_bytes(p, N, C, H, W) for p in (0, 1))), dtype=torch.uint8, device=dev)
+        fwd = lambda s: mc.batchnorm2d_fwd(s["x"], g, b, s["y"], mean, inv_std, N, C, H, W, 1e-5, mc.F32, ws, stream)
+        bwd = lambda s: mc.batchnorm2d_bwd(s["x"], s["dy"], g, mean, inv_std, s["dx"], dg, db, N, C, H, W, mc.F32, ws, stream)
+        row = {"N": N, "C": C, "H": H, "W": W, "buffer_sets_rotated": nsets}
+        for pname, call, bpe in (("fwd", fwd, 8), ("bwd", bwd, 12)):
+            for j in range(nsets):
+                call(sets[j])
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for j in range(reps):
+                call(sets[j % nsets])
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / reps
+            gbs = elems * bpe / (us * 1e-6) / 1e9
+            row[pname] = {"us": us, "algorithmic_bytes_per_launch": elems * bpe, "gbs": gbs, "frac": gbs / PEAK_HBM_GBS}
+        out["shapes"][name] = row
+        del sets
+        torch.cuda.empty_cache()
+    return out
+
+
 def sweep(mc, wl, torch):
     """Times every pass of wl.MORE_SHAPES (fp32, seeded inputs of the workloads module, back-to-back launches between
     two events)."""
@@ -543,6 +581,7 @@ def main():
         return
     if a.layer == "2a" and a.dtype == "f32" and not a.no_secondary:
         out["secondary"] = secondary_depthwise(max(10, min(a.steps, 30)), a.warmup, a.settle_ms, mc, wl, torch, np)
+        out["batchnorm"] = batchnorm_figures(mc, wl, torch, np)
     if not a.no_cpu_baseline:
         def gpu_results():
             s = make_sets(L, a.dtype, 1, torch, np, wl, "cuda:0")[0]

@@ -158,6 +158,48 @@ MICONV_API int miconv_epilogue_is_fused(int pass,
                              int dtype);
 
 /*
+ * Batch normalisation of an NCHW tensor in training mode: the other operator
+ * the paper names next to convolution in its ResNet-50 execution trace
+ * (Section 6.1, Figure 1).  With M = N*H*W and sums over n, h, w of channel c:
+ *   save_mean[c]    = sum x / M
+ *   save_inv_std[c] = 1 / sqrt(sum (x - save_mean[c])^2 / M + eps)     (biased variance)
+ *   y[n,c,h,w]      = gamma[c] * (x[n,c,h,w] - save_mean[c]) * save_inv_std[c] + beta[c]
+ * x, y: DEVICE pointers to [N][C][H][W] floats; gamma, beta, save_mean,
+ * save_inv_std: DEVICE pointers to C floats.  eps >= 0.  dtype must be
+ * MICONV_F32.  workspace: at least batchnorm2d_workspace_bytes(0, ...) bytes,
+ * 256-byte aligned (0 when a channel fits the registers of one workgroup:
+ * N*H*W <= 32768 with 16-byte aligned tensors and H*W a multiple of 4).
+ * Ownership, stream behaviour and error codes as for the convolution calls;
+ * running statistics are not kept.  Results do not depend on launch timing.
+ */
+MICONV_API int batchnorm2d_fwd(const void *x, const float *gamma, const float *beta, void *y,
+                    float *save_mean, float *save_inv_std,
+                    int N, int C, int H, int W, float eps, int dtype,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * Backward function of batchnorm2d_fwd in the sense of the paper's Section
+ * 4.2: the vector-Jacobian product with respect to x, gamma and beta, given the
+ * statistics batchnorm2d_fwd saved:
+ *   dbeta[c]  = sum dy
+ *   dgamma[c] = sum dy * xhat,        xhat = (x - save_mean[c]) * save_inv_std[c]
+ *   dx        = gamma[c] * save_inv_std[c] * (dy - dbeta[c]/M - xhat * dgamma[c]/M)
+ * x, dy, dx: [N][C][H][W] floats; gamma, save_mean, save_inv_std, dgamma,
+ * dbeta: C floats; all DEVICE pointers.  workspace: at least
+ * batchnorm2d_workspace_bytes(1, ...) bytes.
+ */
+MICONV_API int batchnorm2d_bwd(const void *x, const void *dy, const float *gamma,
+                    const float *save_mean, const float *save_inv_std,
+                    void *dx, float *dgamma, float *dbeta,
+                    int N, int C, int H, int W, int dtype,
+                    void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of workspace that batchnorm2d_fwd (pass 0) or batchnorm2d_bwd (pass 1) may need at most for these arguments
+ * (tensors that are 16-byte aligned need less, and none at all when a channel fits one workgroup); 0 for invalid
+ * arguments as well. */
+MICONV_API size_t batchnorm2d_workspace_bytes(int pass, int N, int C, int H, int W, int dtype);
+
+/*
  * conv2d_bwd_weight for callers that cannot allocate device memory (code under
  * HIP graph capture, serving loops, harnesses that forbid hipMalloc): the same
  * kernels and the same result, bit for bit, as conv2d_bwd_weight, but the scratch memory (the

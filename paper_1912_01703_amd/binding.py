@@ -42,6 +42,13 @@ for _name in ("conv2d_fwd_bias_relu", "conv2d_bwd_data_relu_mask"):
     _fn.argtypes = [ctypes.c_void_p] * 4 + _dims + [_i, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
 _lib.miconv_epilogue_is_fused.restype = _i
 _lib.miconv_epilogue_is_fused.argtypes = [_i] + _dims + [_i]
+_f = ctypes.c_float
+_lib.batchnorm2d_fwd.restype = _i
+_lib.batchnorm2d_fwd.argtypes = [ctypes.c_void_p] * 6 + [_i, _i, _i, _i, _f, _i, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.batchnorm2d_bwd.restype = _i
+_lib.batchnorm2d_bwd.argtypes = [ctypes.c_void_p] * 8 + [_i, _i, _i, _i, _i, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p]
+_lib.batchnorm2d_workspace_bytes.restype = ctypes.c_size_t
+_lib.batchnorm2d_workspace_bytes.argtypes = [_i] * 6
 _lib.conv2d_bwd_weight_static_ws.restype = _i
 _lib.conv2d_bwd_weight_static_ws.argtypes = [ctypes.c_void_p] * 3 + _dims + [_i, ctypes.c_void_p]
 _lib.conv2d_workspace_bytes.restype = ctypes.c_size_t
@@ -132,6 +139,32 @@ def conv2d_bwd_data_relu_mask(dy, w, act, dx, N, C, H, W, K, R, S, stride_h, str
 def miconv_epilogue_is_fused(pass_, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype=F32) -> bool:
     return bool(_lib.miconv_epilogue_is_fused(int(pass_), N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w,
                                               groups, int(dtype)))
+
+
+def batchnorm2d_fwd(x, gamma, beta, y, save_mean, save_inv_std, N, C, H, W, eps, dtype=F32, workspace=None, stream=0,
+                    check=True):
+    wptr, wbytes = _ws(workspace)
+    rc = _lib.batchnorm2d_fwd(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(save_mean), _ptr(save_inv_std),
+                              N, C, H, W, float(eps), int(dtype), wptr, wbytes,
+                              ctypes.c_void_p(int(stream)) if stream else None)
+    if check and rc != OK:
+        raise MiconvError(rc, last_error())
+    return rc
+
+
+def batchnorm2d_bwd(x, dy, gamma, save_mean, save_inv_std, dx, dgamma, dbeta, N, C, H, W, dtype=F32, workspace=None,
+                    stream=0, check=True):
+    wptr, wbytes = _ws(workspace)
+    rc = _lib.batchnorm2d_bwd(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(save_mean), _ptr(save_inv_std), _ptr(dx),
+                              _ptr(dgamma), _ptr(dbeta), N, C, H, W, int(dtype), wptr, wbytes,
+                              ctypes.c_void_p(int(stream)) if stream else None)
+    if check and rc != OK:
+        raise MiconvError(rc, last_error())
+    return rc
+
+
+def batchnorm2d_workspace_bytes(pass_, N, C, H, W, dtype=F32):
+    return int(_lib.batchnorm2d_workspace_bytes(int(pass_), N, C, H, W, int(dtype)))
 
 
 def conv2d_bwd_weight_static_ws(x, dy, dw, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups,

@@ -17,13 +17,20 @@ thread_local char g_err[256] = "";
 thread_local int g_last_algo[3] = {MICONV_ALGO_AUTO, MICONV_ALGO_AUTO, MICONV_ALGO_AUTO};
 thread_local int g_forced[3] = {MICONV_ALGO_AUTO, MICONV_ALGO_AUTO, MICONV_ALGO_AUTO};
 
-int fail(int code, const char* fmt, ...) {
+}  // namespace
+
+namespace miconv {
+int record_error(int code, const char* fmt, ...) {
     va_list ap;
     va_start(ap, fmt);
     vsnprintf(g_err, sizeof g_err, fmt, ap);
     va_end(ap);
     return code;
 }
+}  // namespace miconv
+
+namespace {
+using miconv::record_error;
 
 // Scratch memory of conv2d_bwd_weight_static_ws: one array per GPU, held from the time the library's code is
 // loaded on that GPU until the process ends.  In host code the array's name is only a handle for
@@ -39,7 +46,7 @@ void* static_scratch() {
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) {
-        fail(MICONV_ERR_LAUNCH, "hipGetDevice failed or device index %d is out of range: %s", dev, hipGetErrorString(e));
+        record_error(MICONV_ERR_LAUNCH, "hipGetDevice failed or device index %d is out of range: %s", dev, hipGetErrorString(e));
         return nullptr;
     }
     std::lock_guard<std::mutex> lock(g_scratch_mutex);
@@ -47,7 +54,7 @@ void* static_scratch() {
         void* ptr = nullptr;
         e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
         if (e != hipSuccess || !ptr) {
-            fail(MICONV_ERR_LAUNCH, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+            record_error(MICONV_ERR_LAUNCH, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
             return nullptr;
         }
         g_scratch_ptr[dev] = ptr;
@@ -59,15 +66,15 @@ void* static_scratch() {
 int make_problem(Problem& pr, int N, int C, int H, int W, int K, int R, int S, int sh, int sw, int ph, int pw,
                  int groups, int dtype) {
     if (N < 1 || C < 1 || H < 1 || W < 1 || K < 1 || R < 1 || S < 1)
-        return fail(MICONV_ERR_SHAPE, "N,C,H,W,K,R,S must all be >= 1 (got %d,%d,%d,%d,%d,%d,%d)", N, C, H, W, K, R, S);
-    if (sh < 1 || sw < 1) return fail(MICONV_ERR_SHAPE, "strides must be >= 1 (got %d,%d)", sh, sw);
-    if (ph < 0 || pw < 0) return fail(MICONV_ERR_SHAPE, "padding must be >= 0 (got %d,%d)", ph, pw);
+        return record_error(MICONV_ERR_SHAPE, "N,C,H,W,K,R,S must all be >= 1 (got %d,%d,%d,%d,%d,%d,%d)", N, C, H, W, K, R, S);
+    if (sh < 1 || sw < 1) return record_error(MICONV_ERR_SHAPE, "strides must be >= 1 (got %d,%d)", sh, sw);
+    if (ph < 0 || pw < 0) return record_error(MICONV_ERR_SHAPE, "padding must be >= 0 (got %d,%d)", ph, pw);
     if (groups < 1 || C % groups || K % groups)
-        return fail(MICONV_ERR_GROUPS, "groups=%d must be >= 1 and divide C=%d and K=%d", groups, C, K);
-    if (dtype != MICONV_F32 && dtype != MICONV_BF16_F32ACC) return fail(MICONV_ERR_DTYPE, "unknown dtype %d", dtype);
+        return record_error(MICONV_ERR_GROUPS, "groups=%d must be >= 1 and divide C=%d and K=%d", groups, C, K);
+    if (dtype != MICONV_F32 && dtype != MICONV_BF16_F32ACC) return record_error(MICONV_ERR_DTYPE, "unknown dtype %d", dtype);
     const long long hp = (long long)H + 2LL * ph - R, wq = (long long)W + 2LL * pw - S;
     if (hp < 0 || wq < 0)
-        return fail(MICONV_ERR_SHAPE, "filter %dx%d larger than padded input %dx%d (+2*%d,+2*%d)", R, S, H, W, ph, pw);
+        return record_error(MICONV_ERR_SHAPE, "filter %dx%d larger than padded input %dx%d (+2*%d,+2*%d)", R, S, H, W, ph, pw);
     const long long P = hp / sh + 1, Q = wq / sw + 1;
     constexpr long long lim = 1LL << 31;
     // products of four factors: each factor and the running product are clamped to 2^31, so nothing exceeds 2^62
@@ -78,7 +85,7 @@ int make_problem(Problem& pr, int N, int C, int H, int W, int K, int R, int S, i
     };
     const long long nx = count(N, C, H, W), ny = count(N, K, P, Q), nw = count(K, C / groups, R, S);
     if (nx >= lim || ny >= lim || nw >= lim)
-        return fail(MICONV_ERR_SHAPE, "tensor too large: x=%lld y=%lld w=%lld elements (counts are capped at the limit, 2^31)", nx, ny, nw);
+        return record_error(MICONV_ERR_SHAPE, "tensor too large: x=%lld y=%lld w=%lld elements (counts are capped at the limit, 2^31)", nx, ny, nw);
     pr.N = N; pr.C = C; pr.H = H; pr.W = W; pr.K = K; pr.R = R; pr.S = S;
     pr.sh = sh; pr.sw = sw; pr.ph = ph; pr.pw = pw; pr.groups = groups;
     pr.P = (int)P; pr.Q = (int)Q; pr.Cg = C / groups; pr.Kg = K / groups; pr.dtype = dtype;
@@ -115,30 +122,30 @@ int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, 
     Problem pr;
     const int rc = make_problem(pr, N, C, H, W, K, R, S, sh, sw, ph, pw, groups, dtype);
     if (rc != MICONV_OK) return rc;
-    if (!a) return fail(MICONV_ERR_NULL, "%s is NULL", in_names[pass][0]);
-    if (!b) return fail(MICONV_ERR_NULL, "%s is NULL", in_names[pass][1]);
-    if (!out) return fail(MICONV_ERR_NULL, "%s is NULL", out_names[pass]);
+    if (!a) return record_error(MICONV_ERR_NULL, "%s is NULL", in_names[pass][0]);
+    if (!b) return record_error(MICONV_ERR_NULL, "%s is NULL", in_names[pass][1]);
+    if (!out) return record_error(MICONV_ERR_NULL, "%s is NULL", out_names[pass]);
     if (with_epilogue) {
-        if (!epilogue_arg) return fail(MICONV_ERR_NULL, "%s is NULL", pass == MICONV_PASS_FWD ? "bias" : "act");
+        if (!epilogue_arg) return record_error(MICONV_ERR_NULL, "%s is NULL", pass == MICONV_PASS_FWD ? "bias" : "act");
         if (pass == MICONV_PASS_FWD) pr.bias = static_cast<const float*>(epilogue_arg);
         else pr.relu_mask = epilogue_arg;
     }
     const int algo = choose_algo(pass, pr);
     if (algo < 0)
-        return fail(MICONV_ERR_UNSUPPORTED, "forced algorithm %d cannot run this problem (pass %d)",
+        return record_error(MICONV_ERR_UNSUPPORTED, "forced algorithm %d cannot run this problem (pass %d)",
                     g_forced[pass], pass);
     const size_t need = workspace_for(pass, algo, pr);
     if (static_ws) {
         if (need > kStaticWsBytes)
-            return fail(MICONV_ERR_WORKSPACE, "this problem needs %zu bytes of scratch memory, the static array holds %zu: "
+            return record_error(MICONV_ERR_WORKSPACE, "this problem needs %zu bytes of scratch memory, the static array holds %zu: "
                         "call conv2d_bwd_weight with a workspace instead", need, kStaticWsBytes);
         ws = need > 0 ? static_scratch() : nullptr;
         if (need > 0 && !ws) return MICONV_ERR_LAUNCH;
     } else if (need > 0) {
-        if (!ws) return fail(MICONV_ERR_WORKSPACE, "workspace is NULL but %zu bytes are required", need);
-        if (ws_bytes < need) return fail(MICONV_ERR_WORKSPACE, "workspace has %zu bytes, %zu required", ws_bytes, need);
+        if (!ws) return record_error(MICONV_ERR_WORKSPACE, "workspace is NULL but %zu bytes are required", need);
+        if (ws_bytes < need) return record_error(MICONV_ERR_WORKSPACE, "workspace has %zu bytes, %zu required", ws_bytes, need);
         if (reinterpret_cast<uintptr_t>(ws) % 256)
-            return fail(MICONV_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+            return record_error(MICONV_ERR_WORKSPACE, "workspace must be 256-byte aligned");
     }
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
@@ -155,7 +162,7 @@ int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, 
     }
     // kernels without an epilogue of their own: one element-wise pass over the finished output
     if (e == hipSuccess && with_epilogue && !fused) e = miconv::epilogue_run(pass, pr, o, st);
-    if (e != hipSuccess) return fail(MICONV_ERR_LAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
+    if (e != hipSuccess) return record_error(MICONV_ERR_LAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
     g_last_algo[pass] = algo;
     return MICONV_OK;
 }
@@ -242,8 +249,8 @@ const char* miconv_kernel_path(int pass, int N, int C, int H, int W, int K, int 
 }
 
 int miconv_set_algo(int pass, int algo) {
-    if (pass < 0 || pass > 2) return fail(MICONV_ERR_DTYPE, "unknown pass %d", pass);
-    if (algo < MICONV_ALGO_AUTO || algo > MICONV_ALGO_DEPTHWISE) return fail(MICONV_ERR_DTYPE, "unknown algorithm %d", algo);
+    if (pass < 0 || pass > 2) return record_error(MICONV_ERR_DTYPE, "unknown pass %d", pass);
+    if (algo < MICONV_ALGO_AUTO || algo > MICONV_ALGO_DEPTHWISE) return record_error(MICONV_ERR_DTYPE, "unknown algorithm %d", algo);
     g_forced[pass] = algo;
     return MICONV_OK;
 }

@@ -26,6 +26,9 @@ __device__ __forceinline__ float bf16_to_float(uint16_t b) {
 __device__ __forceinline__ float load_elem(const float* p, size_t i) { return p[i]; }
 __device__ __forceinline__ float load_elem(const uint16_t* p, size_t i) { return bf16_to_float(p[i]); }
 
+// Records the text miconv_last_error() returns on this host thread and hands `code` back (api.cpp).
+int record_error(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+
 // ---- device helpers shared by the kernel files ---------------------------------------------------
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef unsigned int v4u __attribute__((ext_vector_type(4)));

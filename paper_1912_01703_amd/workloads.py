@@ -123,6 +123,26 @@ def make_epilogue_inputs(layer: Layer):
     return bias, act
 
 
+def make_bn_inputs(N, C, H, W, seed):
+    """Inputs of the batch-normalisation passes, float32, drawn from PCG64(seed) in the order x, dy, gamma, beta.
+    x is shaped like the output of a convolution layer in training: per channel a mean offset m_c ~ N(0, 1) and a
+    scale s_c ~ U[0.5, 2], x = m_c + s_c * N(0, 1); dy ~ N(0, 1); gamma ~ N(1, 0.25); beta ~ N(0, 1)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    x = rng.standard_normal(size=(N, C, H, W), dtype=np.float32)
+    m = rng.standard_normal(size=(1, C, 1, 1), dtype=np.float32)
+    s = rng.uniform(0.5, 2.0, size=(1, C, 1, 1)).astype(np.float32)
+    x = (m + s * x).astype(np.float32)
+    dy = rng.standard_normal(size=(N, C, H, W), dtype=np.float32)
+    gamma = (1.0 + 0.5 * rng.standard_normal(size=(C,), dtype=np.float32)).astype(np.float32)
+    beta = rng.standard_normal(size=(C,), dtype=np.float32)
+    return x, dy, gamma, beta
+
+
+# Batch-normalisation shapes of the benchmark: the tensor behind the ResNet-50 3x3 bottleneck layer and the one
+# behind its first (7x7 stride-2) layer.  (name, N, C, H, W)
+BN_SHAPES = [("bn14", 64, 256, 14, 14), ("bn112", 64, 64, 112, 112)]
+
+
 def to_bf16_bits(a: np.ndarray) -> np.ndarray:
     """Round float32 to bfloat16 (nearest, ties to even); returns uint16 bit patterns.
     NaN inputs are not expected in the synthetic data and are not special-cased."""
