@@ -478,6 +478,24 @@ __global__ __launch_bounds__(kThreads) void dw_strip_stencil_kernel(DwStripArgs 
     }
 }
 
+// Sum of v over the 64 lanes of a wave, returned to every lane, by data-parallel-primitive moves (no LDS traffic):
+// four shifts inside each row of 16 lanes leave the row's total in its last lane, two broadcasts of a row's last
+// lane into the following rows carry the totals to lane 63.  Lanes whose source lies outside the row (or whose row
+// is masked off) receive 0.  The order of the additions is fixed.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+    return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ float wave_total(float v) {
+    v = dpp_add<0x111, 0xF>(v);   // row_shr:1
+    v = dpp_add<0x112, 0xF>(v);   // row_shr:2
+    v = dpp_add<0x114, 0xF>(v);   // row_shr:4
+    v = dpp_add<0x118, 0xF>(v);   // row_shr:8
+    v = dpp_add<0x142, 0xA>(v);   // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xC>(v);   // row_bcast:31 into rows 2 and 3
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63));
+}
+
 struct DwStripWArgs {
     const void* x;
     const void* dy;
@@ -500,7 +518,7 @@ struct DwStripWArgs {
 // channel stay in the lanes' registers over the whole range, the next batch is fetched while the
 // current one is multiplied, and at the end lanes, then the waves of the workgroup (the image
 // ranges), are added in a fixed order: bit-reproducible, no atomics.
-// Most waves per workgroup (two per SIMD: the kernels use up to 209 registers).
+// Most waves per workgroup (two per SIMD).
 constexpr int kStripWgradWaves = 8;
 
 template <typename T, int ST, int NPIB, int NPS, bool WIDE, int PPWC = 0, int QC = 0>
@@ -568,7 +586,7 @@ __global__ __launch_bounds__(64 * kStripWgradWaves) void dw_strip_wgrad_kernel(D
         const bool ok = e < a.PB * PPS && c0 + ch < a.C && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W;
         goff[i] = ok ? (unsigned)(po * xplane + ih * a.W + iw) * ESZ : kOob;
     }
-    int win[NPS], rows[NPS], yli[NPS];
+    int win[NPS], rows[NPS], yli[NPS], chn[NPS];   // chn: channel (within the group) the lane works for in a pass, -1: none
     unsigned yo[NPS];
     {
         const int ul = fdiv(lane, a.inv_q), q = lane - ul * qw;
@@ -585,6 +603,7 @@ __global__ __launch_bounds__(64 * kStripWgradWaves) void dw_strip_wgrad_kernel(D
             yo[ps] = c0 + ch < a.C ? (unsigned)(po * yplane + p0 * qw + q) * ESZ : kOob;
             yli[ps] = pl * yplane + p0 * qw + q;
             rows[ps] = ok ? min(kSeg, a.P - p0) : 0;
+            chn[ps] = ok ? ch : -1;
         }
     }
 
@@ -597,9 +616,11 @@ __global__ __launch_bounds__(64 * kStripWgradWaves) void dw_strip_wgrad_kernel(D
 #pragma unroll
         for (int t = 0; t < 9; ++t) acc[ps][t] = 0.f;
 
-    // The 16-byte path keeps two batches in flight per wave (two register sets): with one, a wave's
-    // range is a chain of as many memory round trips as it has batches.
-    constexpr int DEPTH = WIDE ? 2 : 1;
+    // One batch in flight per wave.  With two or three register sets per wave the kernel was slower (14x14 planes,
+    // N*C = 65 536: 20.3 us with one set, 21.5 with two, 24.5 with three): sixteen waves per CU with one batch each
+    // already queue more requests than the memory system serves at its best rate, and the smaller register
+    // footprint lets four waves share a SIMD.
+    constexpr int DEPTH = 1;
     float xv[WIDE ? 1 : NPIB], yv[WIDE ? 1 : NPS][kSeg];
     v4u x4[DEPTH][WIDE ? NLV : 1], y4[DEPTH][WIDE ? NLV : 1];
     // Batches past the range lie beyond the descriptors: zeros, no traffic.
@@ -679,7 +700,6 @@ __global__ __launch_bounds__(64 * kStripWgradWaves) void dw_strip_wgrad_kernel(D
         }
     };
     fetch(n0, std::integral_constant<int, 0>{});   // on their way while the rest of the plan is made
-    if constexpr (DEPTH == 2) fetch(n0 + a.IB, std::integral_constant<int, 1>{});
 
     // wide path: where the four values of float4 f of the x planes land in LDS
     if constexpr (WIDE) {
@@ -700,40 +720,25 @@ __global__ __launch_bounds__(64 * kStripWgradWaves) void dw_strip_wgrad_kernel(D
     }
     for (int n = n0; n < n1; n += DEPTH * a.IB) {
         step(n, std::integral_constant<int, 0>{});
-        if constexpr (DEPTH == 2) {
-            if (n + a.IB < n1) step(n + a.IB, std::integral_constant<int, 1>{});
-        }
     }
 
-    // Lanes -> channels.  Every lane leaves its sums in the wave's own LDS region (operations of one wave
-    // on LDS run in program order).  The lanes that worked for plane pl in pass ps are those of the
-    // units [pl*NSEG, (pl+1)*NSEG) - ps*UPP, a contiguous run; lane 9*ch + t adds, in plane and lane order,
-    // the planes ch, ch + CPB, ... of its channel.
-#pragma unroll
-    for (int ps = 0; ps < NPS; ++ps)
-#pragma unroll
-        for (int t = 0; t < 9; ++t) my[(ps * 64 + lane) * 9 + t] = acc[ps][t];
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // Lanes -> channels, without a trip through LDS: for every channel of the group, the sums of the lanes (and
+    // passes) that worked for it are added over the wave in registers, in a fixed order.  (Through LDS, with the
+    // 9 * CPB receiving lanes walking their share one read after the other, this took 2 us of 23 on 14x14 planes.)
     const int opl = lane / 9, ot = lane - opl * 9;
     float sum = 0.f;
-    if (opl < a.CPB) {
-        for (int pl = opl; pl < a.PB; pl += a.CPB) {
+    for (int ch = 0; ch < a.CPB; ++ch) {
+        float v[9];
 #pragma unroll
-            for (int ps = 0; ps < NPS; ++ps) {
-                if (ps >= a.passes) break;
-                const int ulo = min(max(pl * a.NSEG - ps * a.UPP, 0), a.UPP), uhi = min(max((pl + 1) * a.NSEG - ps * a.UPP, 0), a.UPP);
-                const float* src = my + ps * 64 * 9 + ot;
-                const int hi = uhi * qw;
-                for (int j = ulo * qw; j < hi; j += 4) {   // four independent reads per round
-                    const float v0 = src[j * 9];
-                    const float v1 = j + 1 < hi ? src[(j + 1) * 9] : 0.f;
-                    const float v2 = j + 2 < hi ? src[(j + 2) * 9] : 0.f;
-                    const float v3 = j + 3 < hi ? src[(j + 3) * 9] : 0.f;
-                    sum = (((sum + v0) + v1) + v2) + v3;
-                }
-            }
+        for (int t = 0; t < 9; ++t) {
+            v[t] = 0.f;
+#pragma unroll
+            for (int ps = 0; ps < NPS; ++ps) v[t] += chn[ps] == ch ? acc[ps][t] : 0.f;
+        }
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const float tot = wave_total(v[t]);
+            sum = (opl == ch && ot == t) ? tot : sum;
         }
     }
     wres[wave * 64 + lane] = sum;
@@ -948,11 +953,12 @@ bool strip_wgrad_args(const Problem& pr, const void* x, const void* dy, DwStripW
     a.inv_ppw = 1.0f / a.PPW; a.inv_pps = 1.0f / (a.PPH * a.PPW); a.inv_q = 1.0f / pr.Q; a.inv_nseg = 1.0f / sp.NSEG;
     a.inv_xplane = 1.0f / (pr.H * pr.W); a.inv_w = 1.0f / pr.W; a.inv_yplane = 1.0f / (pr.P * pr.Q);
     if (a.lds_per_wave < 2 * 64 * 9) a.lds_per_wave = 2 * 64 * 9;   // the lane sums of both passes
-    // As many consecutive channels per wave as still leave a workgroup for every CU; the rest of the batch
-    // are further images of the same channels.
+    // As many consecutive channels per wave as still leave two workgroups for every CU (they run at different
+    // points of their image ranges, so one's start-up and final reduction overlap the other's loads: 20.3 -> 19.9 us
+    // on 14x14 planes, N*C = 65 536); the rest of the batch are further images of the same channels.
     a.CPB = 1;
     for (int d = 2; d <= sp.PB; ++d)
-        if (sp.PB % d == 0 && (pr.C + d - 1) / d >= 256) a.CPB = d;
+        if (sp.PB % d == 0 && (pr.C + d - 1) / d >= 512) a.CPB = d;
     a.IB = sp.PB / a.CPB;
     a.cgroups = (pr.C + a.CPB - 1) / a.CPB;
     split_images(a, kStripWgradWaves);
