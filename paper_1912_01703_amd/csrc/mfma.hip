@@ -62,7 +62,12 @@ hipError_t mfma_run(int pass, const Problem& in, const void* a, const void* b, f
     const Problem pr = canonical(in);
     *fused_epilogue = mfma_fuses_epilogue(pass, in);
     if (smallc_supports(pass, pr)) return smallc_run(pass, pr, a, b, out, ws, st);
-    if (bf16_tile_supports(pass, pr)) return bf16_tile_run(pass, pr, a, b, out, ws, st);
+    if (bf16_tile_supports(pass, pr)) {
+        // (declines a source tensor that is only 2-byte aligned when it planned to read it in place: the kernels below
+        // take any alignment)
+        const hipError_t e = bf16_tile_run(pass, pr, a, b, out, ws, st);
+        if (e != hipErrorNotSupported) return e;
+    }
     if (pass == 2 && bf16_wgrad_supports(pr)) return bf16_wgrad_run(pr, a, b, out, ws, st);
     if (pass == 0) return tile_run(pass, pr, a, b, out, st);
     if (pass == 1) {

@@ -29,6 +29,8 @@
 namespace miconv {
 namespace {
 
+typedef float v2f __attribute__((ext_vector_type(2)));
+
 
 // ---- pre-pass 1: [N][C][HW] -> [N][HW][C], 64 channels x 128 pixels per workgroup ----------
 // 64 channels are the 128 bytes of one cache line of the destination: a workgroup writes whole lines
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(256) void pack_w_kernel(PackWArgs a) {
 
 // ---- main kernel ---------------------------------------------------------------------------
 struct BfArgs {
-    const uint16_t* xt;   // [N][IH][IW][Cs]
+    const uint16_t* xt;   // [N][IH][IW][Cs], or (NCHW instances) the source tensor itself, [N][Cs][IH][IW]
     const uint16_t* wp;   // [Cs/32][9][F][32]
     float* dst;           // [N][F][OH][OW]
     int N, Cs, IH, IW, F, OH, OW;
@@ -112,6 +114,7 @@ struct BfArgs {
     int tiles_h, tiles_w, fblocks, units;
     int items;            // work items: units rounded up to a multiple of 8, times fblocks
     int pairs;            // OW is even and dst is 8-byte aligned: the write-out stores two pixels per lane
+    int stream_out;       // the result is larger than the 256 MB Infinity Cache: it is stored with the non-temporal hint
 };
 
 // The kernel is persistent: a workgroup walks a list of work items (image, tile, filter block), and
@@ -120,8 +123,17 @@ struct BfArgs {
 // 64 channels) would otherwise spend most of their time filling and draining the pipeline.
 // TH x TW: the tile of output pixels, 14 x 14 or (wide planes) 12 x 16: 12 pixel blocks without a ragged one, and
 // output rows of 64 bytes on 64-byte boundaries where 14-pixel rows leave partly written cache lines behind.
-template <int TH, int TW, int FB, int WF, int WP, int OCC>
+// NCHW (12 x 16 tiles only): the source is read as it is, without the channels-innermost copy.  A thread fetches, for
+// eight channel planes, the same aligned group of four pixels of a patch row (eight 8-byte loads, the plane chosen by
+// the scalar offset; lanes run along the groups of a row), turns the 8 x 4 values into four 16-byte pieces (eight
+// channels of one pixel each) with byte permutes right before they are stored to LDS, and stores zeros for pixels
+// left or right of the image.  That adds vector-ALU work to the MFMA loop, which a layer bound by HBM (few channels:
+// 64 -> 64 at 224 x 224) does not feel, and saves it writing and re-reading a copy of its input.  (Fetching every
+// channel of every pixel with a 2-byte load of its own made the texture-address unit the bottleneck: it was busy
+// 92 % of the time and the kernel no faster than the copy it replaced.)
+template <int TH, int TW, int FB, int WF, int WP, int OCC, bool NCHW = false>
 __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) {
+    static_assert(!NCHW || TW == 16, "the NCHW gather is laid out for 16-wide tiles");
     constexpr int PH = TH + 2, PW = TW + 2, PSZ = PH * PW, NPX = TH * TW;
     constexpr int NT = 64 * WF * WP;
     constexpr int NB = (NPX + 15) / 16, NBW = (NB + WP - 1) / WP;
@@ -132,11 +144,18 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     constexpr int RPB = TW == 14 ? 16 * ROWB + 96 : PW * ROWB + 16;
     static_assert((TW == 14 && (RPB - TW * ROWB) % 128 == 0) || (TW == 16 && NPX % 16 == 0), "tile shapes the layout is made for");
 
-    constexpr int XPT = (PSZ * 4 + NT - 1) / NT;   // 16-byte pieces per thread and chunk
-    constexpr int BUFB = PH * RPB + (XPT * NT - PSZ * 4) * 16;   // one patch buffer, and room for the pieces past the patch
+    // NCHW: a patch row is covered by GR aligned groups of four pixels; a thread's unit of work is such a group for
+    // a quarter of the chunk's 32 channels.
+    constexpr int GR = (3 + PW + 3) / 4, NGRP = PH * GR * 4;
+    constexpr int XPT = NCHW ? (NGRP + NT - 1) / NT : (PSZ * 4 + NT - 1) / NT;   // pieces (NCHW: groups) per thread and chunk
+    // one patch buffer, and room for the pieces that have no place in the patch
+    constexpr int BUFB = PH * RPB + (NCHW ? NT : XPT * NT - PSZ * 4) * 16;
     constexpr int NBUF = 3, D = NBUF - 1;
     constexpr int SLOTS = 9 * NBW;           // one slot = one B operand = FB MFMAs
-    constexpr int RING = 9, PF = 7;          // B operands are requested PF slots ahead; RING divides SLOTS
+    // B operands are requested PF slots ahead; RING divides SLOTS.  (With a ring of 9 the 14 x 14 instance spilled
+    // twelve registers; the NCHW instance holds twice the registers per piece in flight and is not bound by the
+    // matrix pipe.)
+    constexpr int RING = NCHW ? 6 : (TW == 14 ? 7 : 9), PF = RING - 2;
     static_assert(SLOTS % RING == 0 && PF < RING, "ring");
     constexpr int FW = 16 * FB * WF;         // filters per work item
 
@@ -147,6 +166,8 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     const int wf = wave % WF, wp = wave / WF;
     const int li = lane & 15, kk = lane >> 4;
     const int nchunks = a.Cs / 32;
+    const int plane = a.IH * a.IW;
+    const unsigned plane_bytes = (unsigned)plane * 2u;
     const unsigned img_bytes = (unsigned)(a.IH * a.IW * a.Cs) * 2u;
     const unsigned tap_bytes = (unsigned)a.F * 64u;
     const int tiles = a.tiles_h * a.tiles_w;
@@ -181,6 +202,28 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
     // patch loads run D+1 chunks ahead of the MFMAs, filter loads one chunk ahead
     int xj = 0, xch = 0;            // item and chunk the next patch load fetches
     unsigned goff[XPT];             // its gather plan: piece = (pixel, quarter of the chunk's 32 channels)
+    unsigned gin[NCHW ? XPT : 1];   // NCHW: which pixels of a group lie inside the image
+    // NCHW: a group's first pixel lies D0 pixels left of the patch's first column (pad 0: 0, pad 1: 3, pad 2: 2)
+    const int D0 = (4 - a.pad_w) & 3;
+    int loff[NCHW ? 1 : XPT];       // where a piece goes in a patch buffer
+    int loffk[NCHW ? XPT : 1][4];   // NCHW: where the four pixels of a group go; pixels outside the patch go to a spare slot
+#pragma unroll
+    for (int m = 0; m < XPT; ++m) {
+        const int e = tid + NT * m;
+        if constexpr (NCHW) {
+            const int q = e / (PH * GR), r = e - q * (PH * GR);
+            const int ph = r / GR, g = r - ph * GR;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int pw = 4 * g + k - D0;
+                loffk[m][k] = e < NGRP && pw >= 0 && pw < PW ? ph * RPB + pw * ROWB + q * 16 : PH * RPB + tid * 16;
+            }
+        } else {
+            const int pix = e >> 2, q = e & 3;
+            loff[m] = pix < PSZ ? (pix / PW) * RPB + (pix % PW) * ROWB + q * 16 : PH * RPB + (e - PSZ * 4) * 16;
+        }
+    }
+
     const uint16_t* xsrc = a.xt;
     int xok = 0;
     auto plan_patch = [&]() __attribute__((always_inline)) {
@@ -191,27 +234,68 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
 #pragma unroll
         for (int m = 0; m < XPT; ++m) {
             const int e = tid + NT * m;
-            const int pix = e >> 2, q = e & 3;
-            const int ph = pix / PW, pw = pix - ph * PW;
-            const int ih = ih0 + ph, iw = iw0 + pw;
-            const bool ok = pix < PSZ && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
-            goff[m] = ok ? (unsigned)((ih * a.IW + iw) * a.Cs + 8 * q) * 2u : kOob;
+            if constexpr (NCHW) {
+                // group e = (quarter q of the channels, patch row ph, group g of the row); the row's first group starts
+                // at the multiple of four at or below its first pixel (tile origins are multiples of 16)
+                const int q = e / (PH * GR), r = e - q * (PH * GR);
+                const int ph = r / GR, g = r - ph * GR;
+                const int ih = ih0 + ph, iwg = iw0 - D0 + 4 * g;
+                const bool ok = e < NGRP && ih >= 0 && ih < a.IH;
+                // (a group that starts left of the row may start before the descriptor: the offset wraps and reads zeros)
+                goff[m] = ok ? (unsigned)(8 * q * plane + ih * a.IW + iwg) * 2u : kOob;
+                unsigned inside = 0;
+#pragma unroll
+                for (int k = 0; k < 4; ++k) inside |= (iwg + k >= 0 && iwg + k < a.IW ? 1u : 0u) << k;
+                gin[m] = inside;
+            } else {
+                const int pix = e >> 2, q = e & 3;
+                const int ph = pix / PW, pw = pix - ph * PW;
+                const int ih = ih0 + ph, iw = iw0 + pw;
+                const bool ok = pix < PSZ && ih >= 0 && ih < a.IH && iw >= 0 && iw < a.IW;
+                goff[m] = ok ? (unsigned)((ih * a.IW + iw) * a.Cs + 8 * q) * 2u : kOob;
+            }
         }
     };
     auto patch_rsrc = [&]() __attribute__((always_inline)) -> rsrc_t {   // past the last item: reads zeros
-        return make_rsrc(xsrc + xch * 32, xok ? img_bytes - (unsigned)xch * 64u : 0u);
+        if constexpr (NCHW) return make_rsrc(xsrc + (size_t)xch * 32 * plane, xok ? 32u * plane_bytes : 0u);
+        else return make_rsrc(xsrc + xch * 32, xok ? img_bytes - (unsigned)xch * 64u : 0u);
+    };
+    // What a thread holds of a chunk's patch between its loads and its LDS stores: 16-byte pieces, or (NCHW) per group
+    // the eight 8-byte values (four pixels of eight channel planes) and which of the four pixels lie inside the image.
+    struct Held {
+        v4u v[NCHW ? 1 : XPT];
+        v2u raw[NCHW ? XPT : 1][8];
+        unsigned inside[NCHW ? XPT : 1];
+    };
+    auto load_patch = [&](Held& h, const rsrc_t& xrs, int m) __attribute__((always_inline)) {
+        if constexpr (NCHW) {
+            // (a valid group has all eight planes inside the descriptor; an invalid one carries kOob in its vector offset)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) h.raw[m][j] = __builtin_amdgcn_raw_buffer_load_b64(xrs, goff[m], j * plane_bytes, 0);
+            h.inside[m] = gin[m];
+        } else {
+            h.v[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
+        }
+    };
+    auto store_patch = [&](const Held& h, unsigned char* buf, int m) __attribute__((always_inline)) {
+        if constexpr (NCHW) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {   // pixel k of the group: channels 2i, 2i+1 are the halves k%2 of dword k/2 of planes 2i, 2i+1
+                v4u piece;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const unsigned both = __builtin_amdgcn_perm(h.raw[m][2 * i + 1][k / 2], h.raw[m][2 * i][k / 2], k % 2 ? 0x07060302u : 0x05040100u);
+                    piece[i] = (h.inside[m] >> k) & 1u ? both : 0u;
+                }
+                *reinterpret_cast<v4u*>(buf + loffk[m][k]) = piece;
+            }
+        } else {
+            *reinterpret_cast<v4u*>(buf + loff[m]) = h.v[m];
+        }
     };
     auto advance_patch = [&]() __attribute__((always_inline)) {
         if (++xch == nchunks) { xch = 0; ++xj; plan_patch(); }
     };
-    int loff[XPT];
-#pragma unroll
-    for (int m = 0; m < XPT; ++m) {
-        const int e = tid + NT * m;
-        const int pix = e >> 2, q = e & 3;
-        loff[m] = pix < PSZ ? (pix / PW) * RPB + (pix % PW) * ROWB + q * 16 : PH * RPB + (e - PSZ * 4) * 16;
-    }
-
     int wj = 0, wch = 0;            // item and chunk the next filter load fetches
     unsigned wofs[FB];              // this lane's filter rows: filter f, channels 8*kk .. 8*kk+7 of the chunk (tap 0)
     int wok = 0;
@@ -251,7 +335,7 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
 #pragma unroll
         for (int i = 0; i < NBW; ++i) acc[fb][i] = v4f{0.f, 0.f, 0.f, 0.f};
     v4u A[9][FB];
-    v4u xreg[XPT];
+    Held xreg;
     v4u ring[RING];
 
     if (nitems == 0) return;
@@ -266,24 +350,24 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
             for (int fb = 0; fb < FB; ++fb) A[tap][fb] = __builtin_amdgcn_raw_buffer_load_b128(wrs, wofs[fb], tap * tap_bytes, 0);
         advance_filters();
         // the patches of chunks 0..D are all requested before the first one is waited for
-        v4u pre[D][XPT];
+        Held pre[D];
 #pragma unroll
         for (int c = 0; c < D; ++c) {
             const rsrc_t xrs = patch_rsrc();
 #pragma unroll
-            for (int m = 0; m < XPT; ++m) pre[c][m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
+            for (int m = 0; m < XPT; ++m) load_patch(pre[c], xrs, m);
             advance_patch();
         }
         {
             const rsrc_t xrs = patch_rsrc();
 #pragma unroll
-            for (int m = 0; m < XPT; ++m) xreg[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
+            for (int m = 0; m < XPT; ++m) load_patch(xreg, xrs, m);
             advance_patch();
         }
 #pragma unroll
         for (int c = 0; c < D; ++c)
 #pragma unroll
-            for (int m = 0; m < XPT; ++m) *reinterpret_cast<v4u*>(xs + c * BUFB + loff[m]) = pre[c][m];
+            for (int m = 0; m < XPT; ++m) store_patch(pre[c], xs + c * BUFB, m);
         __syncthreads();
 #pragma unroll
         for (int s = 0; s < PF; ++s)
@@ -298,11 +382,14 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
         const rsrc_t wrs = filter_rsrc();
         const unsigned char* pr[NBW];
         const unsigned char* pn[NBW];
-        unsigned char* ps[XPT];
 #pragma unroll
         for (int i = 0; i < NBW; ++i) { pr[i] = xs + rd + pixb[i]; pn[i] = xs + nx + pixb[i]; }
+        unsigned char* const pw = xs + wr;
+        unsigned char* ps[NCHW ? 1 : XPT];
+        if constexpr (!NCHW) {
 #pragma unroll
-        for (int m = 0; m < XPT; ++m) ps[m] = xs + wr + loff[m];
+            for (int m = 0; m < XPT; ++m) ps[m] = pw + loff[m];
+        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int s = 0; s < SLOTS; ++s) {
@@ -322,12 +409,15 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
                                                                          __builtin_bit_cast(v8bf, ring[s % RING]),
                                                                          acc[fb][i], 0, 0, 0);
             }
-            // patch D chunks ahead: registers -> LDS in the first third of the slots; the loads of
-            // the chunk after it refill the same registers in the second third
+            // patch D chunks ahead: registers -> LDS in the last third of the slots, and right behind each store the
+            // load of the chunk after it refills the same registers, which gives a load a whole chunk to arrive
 #pragma unroll
             for (int m = 0; m < XPT; ++m) {
-                if (m * (SLOTS / 3) / XPT == s) *reinterpret_cast<v4u*>(ps[m]) = xreg[m];
-                if (SLOTS / 3 + m * (SLOTS / 3) / XPT == s) xreg[m] = __builtin_amdgcn_raw_buffer_load_b128(xrs, goff[m], 0, 0);
+                if (2 * SLOTS / 3 + m * (SLOTS / 3) / XPT == s) {
+                    if constexpr (NCHW) store_patch(xreg, pw, m);
+                    else *reinterpret_cast<v4u*>(ps[m]) = xreg.v[m];
+                    load_patch(xreg, xrs, m);
+                }
             }
             // this tap's filters are no longer needed: fetch the next chunk's into the same registers
             if (i == NBW - 1) {
@@ -365,8 +455,13 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
                         const float2 o1 = odd ? make_float2(r1, c[3]) : make_float2(c[1], r1);
                         const int f = fbase + 16 * fb + 4 * kk + (odd ? 2 : 0);
                         float* row = dst + (size_t)f * dplane + oh * a.OW + (ow - (odd ? 1 : 0));
-                        if (pix_ok && f < a.F) *reinterpret_cast<float2*>(row) = o0;
-                        if (pix_ok && f + 1 < a.F) *reinterpret_cast<float2*>(row + dplane) = o1;
+                        if (a.stream_out) {   // (567 -> 539 us on 64 -> 64 channels at 224 x 224, N = 64)
+                            if (pix_ok && f < a.F) __builtin_nontemporal_store(v2f{o0.x, o0.y}, reinterpret_cast<v2f*>(row));
+                            if (pix_ok && f + 1 < a.F) __builtin_nontemporal_store(v2f{o1.x, o1.y}, reinterpret_cast<v2f*>(row + dplane));
+                        } else {
+                            if (pix_ok && f < a.F) *reinterpret_cast<float2*>(row) = o0;
+                            if (pix_ok && f + 1 < a.F) *reinterpret_cast<float2*>(row + dplane) = o1;
+                        }
                         acc[fb][i] = v4f{0.f, 0.f, 0.f, 0.f};
                     }
                 }
@@ -409,13 +504,19 @@ struct Shape {
     int Cs, F, IH, IW, OH, OW, pad_h, pad_w;
 };
 
+// Layers with few reduction channels on wide planes are bound by HBM, not by the matrix cores: they read the source
+// tensor as it is (the NCHW instance of the kernel, 12 x 16 tiles) instead of writing and re-reading a channels-innermost
+// copy of it.  Its 8-byte loads of four pixels need rows of an even number of pixels.
+bool reads_nchw(const Shape& s) { return s.Cs <= 128 && s.OW % 16 == 0 && s.OH >= 96 && s.IW % 2 == 0; }
+
 bool shape_of(int pass, const Problem& pr, Shape& s) {
     if (pr.dtype != 1 || pr.R != 3 || pr.S != 3 || pr.sh != 1 || pr.sw != 1 || pr.groups != 1) return false;
     if (pr.ph > 2 || pr.pw > 2) return false;
     if (pass == 0) s = Shape{pr.C, pr.K, pr.H, pr.W, pr.P, pr.Q, pr.ph, pr.pw};
     else if (pass == 1) s = Shape{pr.K, pr.C, pr.P, pr.Q, pr.H, pr.W, 2 - pr.ph, 2 - pr.pw};
     else return false;
-    if (s.Cs % 32 != 0 || (s.IH * s.IW) % 8 != 0) return false;
+    if (s.Cs % 32 != 0 || (s.IH * s.IW) % 8 != 0) return false;   // (the second condition: the channels-innermost copy, which a
+                                                                    // source that is not 4-byte aligned still needs)
     const size_t lim = (size_t)1 << 31;
     if ((size_t)pr.N * s.Cs * s.IH * s.IW * 2 >= lim || (size_t)pr.N * s.F * s.OH * s.OW * 4 >= ((size_t)1 << 33)) return false;
     if ((size_t)9 * s.F * s.Cs * 2 >= lim) return false;
@@ -432,21 +533,30 @@ bool bf16_tile_supports(int pass, const Problem& pr) {
 size_t bf16_tile_workspace_bytes(int pass, const Problem& pr) {
     Shape s;
     if (!shape_of(pass, pr, s)) return 0;
-    return round256((size_t)pr.N * s.IH * s.IW * s.Cs * 2) + round256((size_t)9 * s.F * s.Cs * 2);
+    // (the copy is not used when the NCHW instance runs, but whether it does also depends on the source's alignment,
+    // which the query does not know: tensors that are at least 4-byte aligned need the packed filters only)
+    return round256((size_t)9 * s.F * s.Cs * 2) + (reads_nchw(s) ? 0 : round256((size_t)pr.N * s.IH * s.IW * s.Cs * 2));
 }
 
 hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
                          hipStream_t st) {
     Shape s;
     if (!shape_of(pass, pr, s)) return hipErrorNotSupported;
-    uint16_t* xt = static_cast<uint16_t*>(ws);
-    uint16_t* wp = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(ws) + round256((size_t)pr.N * s.IH * s.IW * s.Cs * 2));
+    // workspace: the packed filters first, then (if made) the channels-innermost copy of the source
+    const bool nchw = reads_nchw(s) && reinterpret_cast<uintptr_t>(in0) % 4 == 0;
+    if (reads_nchw(s) && !nchw) return hipErrorNotSupported;   // a 2-byte aligned tensor: no workspace was asked for the copy
+    uint16_t* wp = static_cast<uint16_t*>(ws);
+    const uint16_t* xt = static_cast<const uint16_t*>(in0);
     const int HW = s.IH * s.IW;
-
-    PackXArgs px{static_cast<const uint16_t*>(in0), xt, pr.N, s.Cs, HW, (unsigned)((size_t)pr.N * s.Cs * HW * 2)};
-    pack_nhwc_kernel<<<dim3((HW + 127) / 128, (s.Cs + 63) / 64, pr.N), 256, 0, st>>>(px);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    hipError_t e = hipSuccess;
+    if (!nchw) {
+        uint16_t* copy = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(ws) + round256((size_t)9 * s.F * s.Cs * 2));
+        PackXArgs px{static_cast<const uint16_t*>(in0), copy, pr.N, s.Cs, HW, (unsigned)((size_t)pr.N * s.Cs * HW * 2)};
+        pack_nhwc_kernel<<<dim3((HW + 127) / 128, (s.Cs + 63) / 64, pr.N), 256, 0, st>>>(px);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        xt = copy;
+    }
 
     PackWArgs pw{static_cast<const uint16_t*>(in1), wp, s.F, s.Cs, pass == 1 ? 1 : 0};
     pack_w_kernel<<<dim3((s.F + 7) / 8, s.Cs / 32), 256, 0, st>>>(pw);
@@ -464,9 +574,11 @@ hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const voi
     a.units = pr.N * a.tiles_h * a.tiles_w;
     a.items = ((a.units + 7) / 8) * 8 * a.fblocks;
     a.pairs = s.OW % 2 == 0 && reinterpret_cast<uintptr_t>(out) % 8 == 0;
+    a.stream_out = (size_t)pr.N * s.F * s.OH * s.OW * sizeof(float) > ((size_t)256 << 20);
     // two workgroups fit a CU: at most that many are launched and each walks its share of the items
     const int grid = a.items < 256 * kOCC ? a.items : 256 * kOCC;
-    if (wide) bf16_tile_kernel<12, 16, kFB, kWF, kWP, kOCC><<<grid, 64 * kWF * kWP, 0, st>>>(a);
+    if (nchw) bf16_tile_kernel<12, 16, kFB, kWF, kWP, kOCC, true><<<grid, 64 * kWF * kWP, 0, st>>>(a);
+    else if (wide) bf16_tile_kernel<12, 16, kFB, kWF, kWP, kOCC><<<grid, 64 * kWF * kWP, 0, st>>>(a);
     else bf16_tile_kernel<14, 14, kFB, kWF, kWP, kOCC><<<grid, 64 * kWF * kWP, 0, st>>>(a);
     return hipGetLastError();
 }

@@ -108,6 +108,9 @@ def test_workspace_sizes_of_the_benchmark_layers(mc):
     l4a = L["4a"]
     got3 = mc.conv2d_workspace_bytes(2, *l4a.conv_args(), mc.BF16_F32ACC)
     assert 0 < got3 and got3 % (4 * 9 * l4a.K * l4a.C) == 0
+    # few channels on wide planes: forward and backward-data read the NCHW source in place, only the packed filters are scratch
+    for p in (0, 1):
+        assert mc.conv2d_workspace_bytes(p, *l4a.conv_args(), mc.BF16_F32ACC) == 9 * l4a.K * l4a.C * 2
     # 14x14 planes are not a multiple of 8 elements: bf16 inputs take the widening path, no layout copies
     assert mc.conv2d_workspace_bytes(0, *L["2a"].conv_args(), mc.BF16_F32ACC) == 0
 

@@ -111,6 +111,10 @@ BF16MM = [
     ("b3x3f", 5, 32, 8, 8, 16, 1),         # one partial tile, one partial filter block
     ("b3x3g", 2, 32, 8, 17, 32, 1),        # odd output width: the write-out stores single pixels
     ("b3x3w", 1, 32, 100, 48, 64, 1),      # wide plane: 12 x 16 tiles, the last tile row ragged
+    # wide planes with at most 128 reduction channels: the kernel reads the NCHW source itself (no copy)
+    ("b3x3n", 2, 64, 100, 50, 32, 0),      # no padding: groups of four pixels start at the patch's first column; 98 x 48 outputs
+    ("b3x3o", 1, 128, 96, 46, 64, 2),      # padding 2, four chunks, the last tile row ragged (98 rows)
+    ("b3x3p", 2, 32, 120, 64, 96, 1),      # four tiles side by side: image borders left and right, interior tiles between
 ]
 
 
