@@ -21,6 +21,14 @@
  *  dtype      MICONV_F32: x, w, dy are float.  MICONV_BF16_F32ACC: x, w, dy are
  *             bfloat16 bit patterns (uint16_t); products are accumulated in
  *             fp32.  Outputs (y, dx, dw) are float in both cases.
+ *             MICONV_BF16_BF16OUT: as MICONV_BF16_F32ACC with y and dx stored
+ *             as bfloat16 (dw remains float).  The 3x3 stride-1 kernels on the
+ *             bf16 matrix cores write bfloat16 themselves; every other kernel
+ *             writes float into the workspace (conv2d_workspace_bytes accounts
+ *             for it) and a conversion pass follows.  Where a fused epilogue
+ *             is applied by a separate pass to a result that is already
+ *             bfloat16, the bias is added to the rounded value and the sum is
+ *             rounded again.
  *  Pointers   x, w, dy, y, dx, dw and workspace are DEVICE pointers on the
  *             current HIP device.  The caller owns all of them; the library
  *             never allocates, frees or keeps them.  Inputs are read only.
@@ -69,7 +77,12 @@ typedef enum {
     MICONV_ERR_UNSUPPORTED = 7 /* a forced algorithm cannot run this problem */
 } miconv_status;
 
-typedef enum { MICONV_F32 = 0, MICONV_BF16_F32ACC = 1 } miconv_dtype;
+typedef enum {
+    MICONV_F32 = 0,          /* x, w, dy float; y, dx, dw float */
+    MICONV_BF16_F32ACC = 1,  /* x, w, dy bfloat16, fp32 accumulation; y, dx, dw float */
+    MICONV_BF16_BF16OUT = 2  /* as 1, but y and dx are written as bfloat16 (the fp32 sum rounded to nearest even);
+                              * dw stays float.  act of conv2d_bwd_data_relu_mask is bfloat16 as for 1. */
+} miconv_dtype;
 
 typedef enum { MICONV_PASS_FWD = 0, MICONV_PASS_BWD_DATA = 1, MICONV_PASS_BWD_WEIGHT = 2 } miconv_pass;
 

@@ -19,7 +19,7 @@ import torch  # noqa: F401
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmiconv.so")
 
 OK, ERR_NULL, ERR_SHAPE, ERR_GROUPS, ERR_DTYPE, ERR_WORKSPACE, ERR_LAUNCH, ERR_UNSUPPORTED = range(8)
-F32, BF16_F32ACC = 0, 1
+F32, BF16_F32ACC, BF16_BF16OUT = 0, 1, 2
 PASS_FWD, PASS_BWD_DATA, PASS_BWD_WEIGHT = 0, 1, 2
 ALGO_AUTO, ALGO_DIRECT, ALGO_MFMA, ALGO_DEPTHWISE = 0, 1, 2, 3
 

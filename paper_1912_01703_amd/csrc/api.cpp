@@ -71,7 +71,8 @@ int make_problem(Problem& pr, int N, int C, int H, int W, int K, int R, int S, i
     if (ph < 0 || pw < 0) return record_error(MICONV_ERR_SHAPE, "padding must be >= 0 (got %d,%d)", ph, pw);
     if (groups < 1 || C % groups || K % groups)
         return record_error(MICONV_ERR_GROUPS, "groups=%d must be >= 1 and divide C=%d and K=%d", groups, C, K);
-    if (dtype != MICONV_F32 && dtype != MICONV_BF16_F32ACC) return record_error(MICONV_ERR_DTYPE, "unknown dtype %d", dtype);
+    if (dtype != MICONV_F32 && dtype != MICONV_BF16_F32ACC && dtype != MICONV_BF16_BF16OUT)
+        return record_error(MICONV_ERR_DTYPE, "unknown dtype %d", dtype);
     const long long hp = (long long)H + 2LL * ph - R, wq = (long long)W + 2LL * pw - S;
     if (hp < 0 || wq < 0)
         return record_error(MICONV_ERR_SHAPE, "filter %dx%d larger than padded input %dx%d (+2*%d,+2*%d)", R, S, H, W, ph, pw);
@@ -88,7 +89,8 @@ int make_problem(Problem& pr, int N, int C, int H, int W, int K, int R, int S, i
         return record_error(MICONV_ERR_SHAPE, "tensor too large: x=%lld y=%lld w=%lld elements (counts are capped at the limit, 2^31)", nx, ny, nw);
     pr.N = N; pr.C = C; pr.H = H; pr.W = W; pr.K = K; pr.R = R; pr.S = S;
     pr.sh = sh; pr.sw = sw; pr.ph = ph; pr.pw = pw; pr.groups = groups;
-    pr.P = (int)P; pr.Q = (int)Q; pr.Cg = C / groups; pr.Kg = K / groups; pr.dtype = dtype;
+    pr.P = (int)P; pr.Q = (int)Q; pr.Cg = C / groups; pr.Kg = K / groups;
+    pr.dtype = dtype == MICONV_F32 ? 0 : 1;   // element type of the inputs; the bf16-output variant is the caller's business
     return MICONV_OK;
 }
 
@@ -114,6 +116,23 @@ size_t workspace_for(int pass, int algo, const Problem& pr) {
     return 0;
 }
 
+size_t round256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// bf16 results (y, dx) from a kernel that only writes float: the float result goes to scratch memory behind the kernel's
+// own and is converted from there.
+bool wants_bf16_out(int pass, int dtype) { return dtype == MICONV_BF16_BF16OUT && pass != MICONV_PASS_BWD_WEIGHT; }
+size_t out_elems(int pass, const Problem& pr) {
+    return pass == MICONV_PASS_FWD ? (size_t)pr.N * pr.K * pr.P * pr.Q : (size_t)pr.N * pr.C * pr.H * pr.W;
+}
+// in0 == nullptr: the query, which assumes a first input tensor that is at least 4-byte aligned
+size_t total_workspace(int pass, int algo, const Problem& pr, int dtype, const void* in0, bool* native_bf16) {
+    const size_t own = workspace_for(pass, algo, pr);
+    *native_bf16 = false;
+    if (!wants_bf16_out(pass, dtype)) return own;
+    *native_bf16 = algo == MICONV_ALGO_MFMA && miconv::mfma_writes_bf16(pass, pr, in0);
+    return *native_bf16 ? own : round256(own) + out_elems(pass, pr) * sizeof(float);
+}
+
 int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, int W, int K, int R, int S, int sh,
         int sw, int ph, int pw, int groups, int dtype, void* ws, size_t ws_bytes, void* stream,
         bool static_ws = false, bool with_epilogue = false, const void* epilogue_arg = nullptr) {
@@ -134,7 +153,9 @@ int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, 
     if (algo < 0)
         return record_error(MICONV_ERR_UNSUPPORTED, "forced algorithm %d cannot run this problem (pass %d)",
                     g_forced[pass], pass);
-    const size_t need = workspace_for(pass, algo, pr);
+    bool native_bf16 = false;
+    const bool bf16_out = wants_bf16_out(pass, dtype);
+    const size_t need = total_workspace(pass, algo, pr, dtype, a, &native_bf16);
     if (static_ws) {
         if (need > kStaticWsBytes)
             return record_error(MICONV_ERR_WORKSPACE, "this problem needs %zu bytes of scratch memory, the static array holds %zu: "
@@ -150,7 +171,11 @@ int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, 
     hipStream_t st = static_cast<hipStream_t>(stream);
     hipError_t e = hipSuccess;
     bool fused = false;
-    float* o = static_cast<float*>(out);
+    // where the kernel writes: the caller's tensor, or (bf16 results from a float-only kernel) the staging area
+    const bool staged = bf16_out && !native_bf16;
+    float* o = staged ? reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + round256(workspace_for(pass, algo, pr)))
+                      : static_cast<float*>(out);
+    pr.out_bf16 = native_bf16;
     if (algo == MICONV_ALGO_DIRECT) {
         if (pass == MICONV_PASS_FWD) e = miconv::direct_fwd(pr, a, b, o, st);
         else if (pass == MICONV_PASS_BWD_DATA) e = miconv::direct_bwd_data(pr, a, b, o, st);
@@ -161,7 +186,8 @@ int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, 
         e = miconv::depthwise_run(pass, pr, a, b, o, ws, st, &fused);
     }
     // kernels without an epilogue of their own: one element-wise pass over the finished output
-    if (e == hipSuccess && with_epilogue && !fused) e = miconv::epilogue_run(pass, pr, o, st);
+    if (e == hipSuccess && with_epilogue && !fused) e = miconv::epilogue_run(pass, pr, o, native_bf16, st);
+    if (e == hipSuccess && staged) e = miconv::convert_to_bf16(o, out, out_elems(pass, pr), st);
     if (e != hipSuccess) return record_error(MICONV_ERR_LAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
     g_last_algo[pass] = algo;
     return MICONV_OK;
@@ -232,7 +258,8 @@ size_t conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int R
     if (make_problem(pr, N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w, groups, dtype) != MICONV_OK) return 0;
     const int algo = choose_algo(pass, pr);
     if (algo < 0) return 0;
-    return workspace_for(pass, algo, pr);
+    bool native;
+    return total_workspace(pass, algo, pr, dtype, nullptr, &native);
 }
 
 const char* miconv_kernel_path(int pass, int N, int C, int H, int W, int K, int R, int S, int stride_h, int stride_w,

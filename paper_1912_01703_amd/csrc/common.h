@@ -17,6 +17,9 @@ struct Problem {
     // relu_mask shaped like x with the element type dtype names.
     const float* bias = nullptr;
     const void* relu_mask = nullptr;
+    // The kernel is to write y / dx as bf16 (round to nearest even) instead of float: set only for kernel families
+    // that say they can (mfma_writes_bf16); everything else writes float into scratch memory and is converted.
+    bool out_bf16 = false;
 };
 
 // bf16 bit pattern -> float, exact.
@@ -74,6 +77,7 @@ hipError_t tile_run(int pass, const Problem& pr, const void* in0, const void* in
 
 // bf16 matrix-core forward / stride-1 backward-data for 3x3 filters (mfma_bf16.hip); needs workspace.
 bool bf16_tile_supports(int pass, const Problem& pr);
+bool bf16_tile_accepts(int pass, const Problem& pr, const void* in0);   // ... and will not decline this source tensor
 size_t bf16_tile_workspace_bytes(int pass, const Problem& pr);
 hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
                          hipStream_t st);
@@ -105,7 +109,11 @@ hipError_t wgrad_run(const Problem& pr, const void* x, const void* dy, float* dw
 // dispatcher runs epilogue_run over the finished output.
 bool mfma_fuses_epilogue(int pass, const Problem& pr);
 bool depthwise_fuses_epilogue(int pass, const Problem& pr);
-hipError_t epilogue_run(int pass, const Problem& pr, float* out, hipStream_t st);
+hipError_t epilogue_run(int pass, const Problem& pr, void* out, bool out_is_bf16, hipStream_t st);
+// float -> bf16 (round to nearest even), count elements.
+hipError_t convert_to_bf16(const float* src, void* dst, size_t count, hipStream_t st);
+// Whether the MFMA kernel this pass is dispatched to can write bf16 results itself, given the first input tensor.
+bool mfma_writes_bf16(int pass, const Problem& pr, const void* in0);
 
 // ---- depthwise kernels (depthwise.hip): groups == C == K, no MFMA ------------------------
 bool depthwise_supports(int pass, const Problem& pr);

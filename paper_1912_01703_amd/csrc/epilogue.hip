@@ -56,9 +56,65 @@ __global__ __launch_bounds__(256) void relu_mask_kernel(float* __restrict__ dx, 
     }
 }
 
+// The same on results that are already bf16 (the bias is then added to the rounded value and the sum rounded again).
+__device__ __forceinline__ uint16_t to_bf16(float f) {
+    const unsigned u = __float_as_uint(f);
+    return static_cast<uint16_t>((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);   // nearest, ties to even (finite values)
+}
+
+__global__ __launch_bounds__(256) void bias_relu_bf16_kernel(uint16_t* __restrict__ y, const float* __restrict__ bias, int K, int plane,
+                                                             size_t count) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    y[i] = to_bf16(fmaxf(bf16_to_float(y[i]) + bias[(i / (size_t)plane) % (size_t)K], 0.f));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void relu_mask_bf16_kernel(uint16_t* __restrict__ dx, const T* __restrict__ act, size_t count) {
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= count) return;
+    if (!(load_elem(act, i) > 0.f)) dx[i] = 0;
+}
+
+__global__ __launch_bounds__(256) void to_bf16_kernel(const float* __restrict__ src, uint16_t* __restrict__ dst, size_t count) {
+    const size_t i0 = ((size_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i0 >= count) return;
+    if (i0 + 4 <= count && reinterpret_cast<uintptr_t>(src) % 16 == 0 && reinterpret_cast<uintptr_t>(dst) % 8 == 0) {
+        const float4 v = *reinterpret_cast<const float4*>(src + i0);
+        uint2 o;
+        o.x = (unsigned)to_bf16(v.x) | ((unsigned)to_bf16(v.y) << 16);
+        o.y = (unsigned)to_bf16(v.z) | ((unsigned)to_bf16(v.w) << 16);
+        *reinterpret_cast<uint2*>(dst + i0) = o;
+    } else {
+        for (size_t i = i0; i < count && i < i0 + 4; ++i) dst[i] = to_bf16(src[i]);
+    }
+}
+
 }  // namespace
 
-hipError_t epilogue_run(int pass, const Problem& pr, float* out, hipStream_t st) {
+hipError_t convert_to_bf16(const float* src, void* dst, size_t count, hipStream_t st) {
+    to_bf16_kernel<<<(unsigned)((count + 1023) / 1024), 256, 0, st>>>(src, static_cast<uint16_t*>(dst), count);
+    return hipGetLastError();
+}
+
+hipError_t epilogue_run(int pass, const Problem& pr, void* outv, bool out_is_bf16, hipStream_t st) {
+    if (out_is_bf16) {
+        uint16_t* o16 = static_cast<uint16_t*>(outv);
+        if (pass == 0 && pr.bias) {
+            const size_t count = (size_t)pr.N * pr.K * pr.P * pr.Q;
+            bias_relu_bf16_kernel<<<(unsigned)((count + 255) / 256), 256, 0, st>>>(o16, pr.bias, pr.K, pr.P * pr.Q, count);
+            return hipGetLastError();
+        }
+        if (pass == 1 && pr.relu_mask) {
+            const size_t count = (size_t)pr.N * pr.C * pr.H * pr.W;
+            const unsigned grid = (unsigned)((count + 255) / 256);
+            if (pr.dtype == 0) relu_mask_bf16_kernel<float><<<grid, 256, 0, st>>>(o16, static_cast<const float*>(pr.relu_mask), count);
+            else relu_mask_bf16_kernel<uint16_t><<<grid, 256, 0, st>>>(o16, static_cast<const uint16_t*>(pr.relu_mask), count);
+            return hipGetLastError();
+        }
+        return hipSuccess;
+    }
+    float* out = static_cast<float*>(outv);
     if (pass == 0 && pr.bias) {
         const size_t count = (size_t)pr.N * pr.K * pr.P * pr.Q;
         bias_relu_kernel<<<(unsigned)((count + 1023) / 1024), 256, 0, st>>>(out, pr.bias, pr.K, pr.P * pr.Q, count);

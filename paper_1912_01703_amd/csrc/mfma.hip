@@ -51,6 +51,11 @@ const char* mfma_path_name(int pass, const Problem& in) {
     return tile_merge2_supports(pr) ? "mfma/tile_merge2" : "mfma/tile_phase";
 }
 
+bool mfma_writes_bf16(int pass, const Problem& in, const void* in0) {
+    const Problem pr = canonical(in);
+    return pass < 2 && !smallc_supports(pass, pr) && bf16_tile_supports(pass, pr) && bf16_tile_accepts(pass, pr, in0);
+}
+
 // The kernels built on conv_tile_kernel apply bias + ReLU / the ReLU mask in their write-out.
 bool mfma_fuses_epilogue(int pass, const Problem& in) {
     const char* path = mfma_path_name(pass, in);

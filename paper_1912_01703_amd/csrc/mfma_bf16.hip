@@ -31,6 +31,13 @@ namespace {
 
 typedef float v2f __attribute__((ext_vector_type(2)));
 
+// Two floats rounded to bf16 (nearest, ties to even; finite values), lo in the low half.
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
+    const unsigned a = __float_as_uint(lo), b = __float_as_uint(hi);
+    const unsigned ra = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16, rb = (b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u;
+    return ra | rb;
+}
+
 
 // ---- pre-pass 1: [N][C][HW] -> [N][HW][C], 64 channels x 128 pixels per workgroup ----------
 // 64 channels are the 128 bytes of one cache line of the destination: a workgroup writes whole lines
@@ -115,6 +122,7 @@ struct BfArgs {
     int items;            // work items: units rounded up to a multiple of 8, times fblocks
     int pairs;            // OW is even and dst is 8-byte aligned: the write-out stores two pixels per lane
     int stream_out;       // the result is larger than the 256 MB Infinity Cache: it is stored with the non-temporal hint
+    int out_bf16;         // dst holds bf16 (uint16_t) elements: results are rounded to nearest even
 };
 
 // The kernel is persistent: a workgroup walks a list of work items (image, tile, filter block), and
@@ -434,7 +442,41 @@ __global__ __launch_bounds__(64 * WF * WP, OCC) void bf16_tile_kernel(BfArgs a) 
             const int dplane = a.OH * a.OW;
             float* dst = a.dst + (size_t)it.n * a.F * dplane;
             const int fbase = it.fblk * FW + wf * (16 * FB);
-            if (a.pairs) {
+            if (a.out_bf16) {
+                // bf16 results: after the same trade between neighbouring lanes a lane packs its two pixels of a filter
+                // into one 4-byte store (rows of an even number of pixels), else every value is a 2-byte store
+                uint16_t* dst16 = reinterpret_cast<uint16_t*>(a.dst) + (size_t)it.n * a.F * dplane;
+                const bool odd = li & 1;
+#pragma unroll
+                for (int i = 0; i < NBW; ++i) {
+                    const int j = 16 * (wp + WP * i) + li;
+                    const int th = j / TW, tw = j - th * TW;
+                    const int oh = it.oh0 + th, ow = it.ow0 + tw;
+                    const bool pix_ok = it.ok && j < NPX && oh < a.OH && ow < a.OW;
+#pragma unroll
+                    for (int fb = 0; fb < FB; ++fb) {
+                        const v4f c = acc[fb][i];
+                        if (a.pairs) {
+                            const float s0 = odd ? c[0] : c[2], s1 = odd ? c[1] : c[3];
+                            const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s0), 0xB1, 0xF, 0xF, true));
+                            const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, s1), 0xB1, 0xF, 0xF, true));
+                            const unsigned o0 = odd ? pack_bf16(r0, c[2]) : pack_bf16(c[0], r0);
+                            const unsigned o1 = odd ? pack_bf16(r1, c[3]) : pack_bf16(c[1], r1);
+                            const int f = fbase + 16 * fb + 4 * kk + (odd ? 2 : 0);
+                            uint16_t* row = dst16 + (size_t)f * dplane + oh * a.OW + (ow - (odd ? 1 : 0));
+                            if (pix_ok && f < a.F) *reinterpret_cast<unsigned*>(row) = o0;
+                            if (pix_ok && f + 1 < a.F) *reinterpret_cast<unsigned*>(row + dplane) = o1;
+                        } else {
+#pragma unroll
+                            for (int v = 0; v < 4; ++v) {
+                                const int f = fbase + 16 * fb + 4 * kk + v;
+                                if (pix_ok && f < a.F) dst16[(size_t)f * dplane + oh * a.OW + ow] = static_cast<uint16_t>(pack_bf16(c[v], 0.f));
+                            }
+                        }
+                        acc[fb][i] = v4f{0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+            } else if (a.pairs) {
                 // Neighbouring lanes hold neighbouring pixels of one row (tile width, block size and tile origin
                 // are even).  They trade two of their four filters, after which the even lane owns filters
                 // 4kk, 4kk+1 and the odd lane 4kk+2, 4kk+3 of both pixels: 8-byte stores, half as many.
@@ -530,6 +572,11 @@ bool bf16_tile_supports(int pass, const Problem& pr) {
     return shape_of(pass, pr, s);
 }
 
+bool bf16_tile_accepts(int pass, const Problem& pr, const void* in0) {
+    Shape s;
+    return shape_of(pass, pr, s) && (!reads_nchw(s) || reinterpret_cast<uintptr_t>(in0) % 4 == 0);
+}
+
 size_t bf16_tile_workspace_bytes(int pass, const Problem& pr) {
     Shape s;
     if (!shape_of(pass, pr, s)) return 0;
@@ -573,8 +620,10 @@ hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const voi
     a.fblocks = (s.F + 16 * kFB * kWF - 1) / (16 * kFB * kWF);
     a.units = pr.N * a.tiles_h * a.tiles_w;
     a.items = ((a.units + 7) / 8) * 8 * a.fblocks;
-    a.pairs = s.OW % 2 == 0 && reinterpret_cast<uintptr_t>(out) % 8 == 0;
-    a.stream_out = (size_t)pr.N * s.F * s.OH * s.OW * sizeof(float) > ((size_t)256 << 20);
+    a.out_bf16 = pr.out_bf16 ? 1 : 0;
+    // two pixels per store: rows of an even number of pixels, and a result aligned to one such store
+    a.pairs = s.OW % 2 == 0 && reinterpret_cast<uintptr_t>(out) % (pr.out_bf16 ? 4 : 8) == 0;
+    a.stream_out = !pr.out_bf16 && (size_t)pr.N * s.F * s.OH * s.OW * sizeof(float) > ((size_t)256 << 20);
     // two workgroups fit a CU: at most that many are launched and each walks its share of the items
     const int grid = a.items < 256 * kOCC ? a.items : 256 * kOCC;
     if (nchw) bf16_tile_kernel<12, 16, kFB, kWF, kWP, kOCC, true><<<grid, 64 * kWF * kWP, 0, st>>>(a);

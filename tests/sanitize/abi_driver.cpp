@@ -26,7 +26,10 @@ const char* depthwise_path_name(int, const Problem&) { return "depthwise/stub"; 
 static int g_epilogues = 0;
 bool mfma_fuses_epilogue(int, const Problem&) { return false; }
 bool depthwise_fuses_epilogue(int, const Problem&) { return true; }
-hipError_t epilogue_run(int, const Problem&, float*, hipStream_t) { ++g_epilogues; return hipSuccess; }
+hipError_t epilogue_run(int, const Problem&, void*, bool, hipStream_t) { ++g_epilogues; return hipSuccess; }
+static int g_conversions = 0;
+hipError_t convert_to_bf16(const float*, void*, size_t, hipStream_t) { ++g_conversions; return hipSuccess; }
+bool mfma_writes_bf16(int, const Problem& pr, const void*) { return pr.C == 8; }
 }  // namespace miconv
 
 typedef int (*pass_fn)(const void*, const void*, void*, int, int, int, int, int, int, int, int, int, int, int, int, int, void*,
@@ -72,6 +75,16 @@ int main() {
     EXPECT(miconv::g_launches == 0);
     EXPECT(conv2d_bwd_weight(p, p, p, 1, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 0, p, need, nullptr) == MICONV_OK);
     EXPECT(miconv::g_launches == 1 && miconv_last_algo(2) == MICONV_ALGO_MFMA);
+    miconv::g_launches = 0;
+    // bf16 results: a kernel that writes float needs room for its float result behind its own scratch memory
+    EXPECT(conv2d_workspace_bytes(0, 1, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, MICONV_BF16_BF16OUT) == 1 * 4 * 8 * 8 * 4);
+    EXPECT(conv2d_workspace_bytes(0, 1, 8, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, MICONV_BF16_BF16OUT) == 0);    // (the stub writes bf16 itself)
+    EXPECT(conv2d_workspace_bytes(2, 1, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, MICONV_BF16_BF16OUT) == need);  // dw stays float
+    EXPECT(conv2d_fwd(p, p, p, 1, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, MICONV_BF16_BF16OUT, nullptr, 0, nullptr) == MICONV_ERR_WORKSPACE);
+    EXPECT(conv2d_fwd(p, p, p, 1, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, MICONV_BF16_BF16OUT, p, 1024, nullptr) == MICONV_OK);
+    EXPECT(miconv::g_conversions == 1);
+    EXPECT(conv2d_fwd(p, p, p, 1, 8, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, MICONV_BF16_BF16OUT, nullptr, 0, nullptr) == MICONV_OK);
+    EXPECT(miconv::g_conversions == 1);
     // dispatch and overrides
     EXPECT(std::strcmp(miconv_kernel_path(0, 1, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1, 0), "mfma/stub") == 0);
     EXPECT(std::strcmp(miconv_kernel_path(0, 1, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 4, 0), "depthwise/stub") == 0);
