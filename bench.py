@@ -162,7 +162,7 @@ def traffic_lines(directory):
         per_pass = {p: 0.0 for p in PASSES}
         code = mc.BF16_F32ACC if dtype == "bf16" else mc.F32
         for k in sorted(fetch):
-            if "miconv" not in k:
+            if "miconv" not in k or "clock_sampler" in k:
                 continue
             rd, wr = fetch[k] * scale["FETCH_SIZE"] * 1024, write.get(k, 0.0) * scale["WRITE_SIZE"] * 1024
             short = re.sub(r"\(anonymous namespace\)::|void |miconv::", "", k)
