@@ -16,6 +16,10 @@ int conv2d_bwd_weight_ref(const void *, const void *, double *, int, int, int, i
 int conv2d_fwd_ref_at(const void *, const void *, const int64_t *, int64_t, double *, int, int, int, int, int, int, int, int, int, int, int, int, int);
 int conv2d_bwd_data_ref_at(const void *, const void *, const int64_t *, int64_t, double *, int, int, int, int, int, int, int, int, int, int, int, int, int);
 int conv2d_bwd_weight_ref_at(const void *, const void *, const int64_t *, int64_t, double *, int, int, int, int, int, int, int, int, int, int, int, int, int);
+int conv2d_fwd_bias_relu_ref(const void *, const void *, const double *, double *, int, int, int, int, int, int, int, int, int, int, int, int, int);
+int conv2d_bwd_data_relu_ref(const void *, const void *, const void *, double *, int, int, int, int, int, int, int, int, int, int, int, int, int);
+int batchnorm2d_fwd_ref(const void *, const double *, const double *, double *, double *, double *, int, int, int, int, double, int);
+int batchnorm2d_bwd_ref(const void *, const void *, const double *, double *, double *, double *, int, int, int, int, double, int);
 
 /* N C H W K R S sh sw ph pw groups */
 static const int CASES[][12] = {
@@ -95,6 +99,35 @@ int main(void)
             for (size_t i = 0; i < nw; ++i) bad |= at[i] != dw[i];
             if (rc || bad) { fprintf(stderr, "single-element variants disagree on case %d\n", ci); return 3; }
             printf("%d %d %.17g %.17g %.17g\n", ci, dtype, checksum(y, ny), checksum(dx, nx), checksum(dw, nw));
+            /* the fused epilogues and batch normalisation on the same tensors: consistency with the plain passes, and
+             * the sanitizers watching every access */
+            double *bias = malloc((size_t)K * sizeof *bias), *y2 = malloc(ny * sizeof *y2), *dx2 = malloc(nx * sizeof *dx2);
+            for (int k = 0; k < K; ++k) bias[k] = (double)(k % 5) - 2.0;
+            rc = conv2d_fwd_bias_relu_ref(x, w, bias, y2, N, C, H, W, K, R, S, sh, sw, ph, pw, g, dtype);
+            for (size_t i = 0; i < ny; ++i) {
+                const double v = y[i] + bias[(i / ((size_t)P * Q)) % K];
+                bad |= y2[i] != (v > 0.0 ? v : 0.0);
+            }
+            rc |= conv2d_bwd_data_relu_ref(dy, w, x, dx2, N, C, H, W, K, R, S, sh, sw, ph, pw, g, dtype);   /* x as the activation */
+            for (size_t i = 0; i < nx; ++i) bad |= dx2[i] != 0.0 && dx2[i] != dx[i];
+            if (rc || bad) { fprintf(stderr, "fused epilogues disagree with the plain passes on case %d\n", ci); return 6; }
+            double *gam = malloc((size_t)C * sizeof *gam), *bet = malloc((size_t)C * sizeof *bet), *mean = malloc((size_t)C * sizeof *mean),
+                   *istd = malloc((size_t)C * sizeof *istd), *dgam = malloc((size_t)C * sizeof *dgam), *dbet = malloc((size_t)C * sizeof *dbet);
+            for (int c = 0; c < C; ++c) { gam[c] = 1.0 + 0.25 * c; bet[c] = 0.5 - c; }
+            void *gx = make(nx, dtype, 53u + ci);   /* an upstream gradient shaped like x */
+            rc = batchnorm2d_fwd_ref(x, gam, bet, dx2, mean, istd, N, C, H, W, 1e-3, dtype);
+            double worst = 0.0;
+            for (int c = 0; c < C; ++c) {   /* with gamma = 1 + c/4, beta = 1/2 - c the channel mean of y is beta */
+                double m = 0.0;
+                for (int n = 0; n < N; ++n)
+                    for (int i = 0; i < H * W; ++i) m += dx2[((size_t)n * C + c) * H * W + i];
+                m = m / ((double)N * H * W) - bet[c];
+                if (m < 0) m = -m;
+                if (m > worst) worst = m;
+            }
+            rc |= batchnorm2d_bwd_ref(x, gx, gam, dx2, dgam, dbet, N, C, H, W, 1e-3, dtype);
+            if (rc || worst > 1e-12) { fprintf(stderr, "batch normalisation failed on case %d (%g)\n", ci, worst); return 7; }
+            free(bias); free(y2); free(dx2); free(gam); free(bet); free(mean); free(istd); free(dgam); free(dbet); free(gx);
             free(x); free(w); free(dy); free(y); free(dx); free(dw); free(idx); free(at);
         }
     /* rejected problems must be refused before any access */

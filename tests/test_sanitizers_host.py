@@ -2,7 +2,7 @@
 
 Two small programs are compiled here and run once each:
 
-* the CPU oracle (``oracle/conv_ref.c``) over odd shapes in all three input
+* the CPU oracle (``oracle/conv_ref.c``, ``oracle/bn_ref.c``) over odd shapes in all three input
   types, with buffers exactly as large as the tensors; its checksums must equal
   those of the ordinary (unsanitized) oracle library;
 * the C ABI's host side (``csrc/api.cpp``: validation, dispatch, workspace
@@ -35,7 +35,8 @@ def test_oracle_under_address_and_undefined_sanitizers(tmp_path):
     exe = str(tmp_path / "oracle_san")
     run(["gcc", "-std=c11", "-O1", "-g", "-fopenmp", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
          "-fno-omit-frame-pointer", "-Wall", "-Wextra", "-o", exe,
-         os.path.join(SAN, "oracle_driver.c"), os.path.join(ROOT, "oracle", "conv_ref.c")])
+         os.path.join(SAN, "oracle_driver.c"), os.path.join(ROOT, "oracle", "conv_ref.c"),
+         os.path.join(ROOT, "oracle", "bn_ref.c"), "-lm"])
     lines = run([exe], env=ENV).split("\n")
     assert lines[-2] == "ok"
     got = {(int(a), int(b)): (float(c), float(d), float(e)) for a, b, c, d, e in (l.split() for l in lines[:-2])}
