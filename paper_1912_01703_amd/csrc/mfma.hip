@@ -36,7 +36,12 @@ size_t mfma_workspace_bytes(int pass, const Problem& in) {
     if (is_depthwise(pr)) return 0;
     if (smallc_supports(pass, pr)) return smallc_workspace_bytes(pass, pr);
     if (bf16_tile_supports(pass, pr)) return bf16_tile_workspace_bytes(pass, pr);
-    if (pass == 2 && bf16_wgrad_supports(pr)) return bf16_wgrad_workspace_bytes(pr);
+    if (pass == 2 && bf16_wgrad_supports(pr)) {
+        // (room for the fp32-matrix-core kernel as well: it takes over when a tensor is only 2-byte aligned)
+        wgrad_supports(pr, &ws);
+        const size_t own = bf16_wgrad_workspace_bytes(pr);
+        return own > ws ? own : ws;
+    }
     if (pass == 2) wgrad_supports(pr, &ws);
     return ws;
 }
@@ -73,7 +78,10 @@ hipError_t mfma_run(int pass, const Problem& in, const void* a, const void* b, f
         const hipError_t e = bf16_tile_run(pass, pr, a, b, out, ws, st);
         if (e != hipErrorNotSupported) return e;
     }
-    if (pass == 2 && bf16_wgrad_supports(pr)) return bf16_wgrad_run(pr, a, b, out, ws, st);
+    if (pass == 2 && bf16_wgrad_supports(pr)) {
+        const hipError_t e = bf16_wgrad_run(pr, a, b, out, ws, st);
+        if (e != hipErrorNotSupported) return e;
+    }
     if (pass == 0) return tile_run(pass, pr, a, b, out, st);
     if (pass == 1) {
         if (tile_supports(pass, pr)) return tile_run(pass, pr, a, b, out, st);

@@ -45,7 +45,7 @@ __device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {
 struct PackXArgs {
     const uint16_t* src;
     uint16_t* dst;
-    int N, C, HW;          // C % 32 == 0, HW % 8 == 0
+    int N, C, HW;          // C % 32 == 0, HW % 2 == 0 (a plane then starts on a 4-byte boundary)
     unsigned src_bytes;
 };
 
@@ -59,7 +59,9 @@ __global__ __launch_bounds__(256) void pack_nhwc_kernel(PackXArgs a) {
     for (int i = 0; i < 4; ++i) {
         const int q = t + 256 * i;
         const int c = q >> 4, pc = q & 15;
-        const int p = p0 + 8 * pc;   // 8 consecutive pixels of one channel; all inside the plane or none
+        // 8 consecutive pixels of one channel (16-byte loads need only 4-byte alignment); the last group of a plane may
+        // run into the next plane: those values land in tile columns that no thread reads
+        const int p = p0 + 8 * pc;
         const unsigned off = p < a.HW && c0 + c < a.C ? (unsigned)((n * a.C + c0 + c) * a.HW + p) * 2u : kOob;
         const v4u v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 0);
         *reinterpret_cast<v4u*>(&tile[c * LS + 8 * pc]) = v;
@@ -557,8 +559,7 @@ bool shape_of(int pass, const Problem& pr, Shape& s) {
     if (pass == 0) s = Shape{pr.C, pr.K, pr.H, pr.W, pr.P, pr.Q, pr.ph, pr.pw};
     else if (pass == 1) s = Shape{pr.K, pr.C, pr.P, pr.Q, pr.H, pr.W, 2 - pr.ph, 2 - pr.pw};
     else return false;
-    if (s.Cs % 32 != 0 || (s.IH * s.IW) % 8 != 0) return false;   // (the second condition: the channels-innermost copy, which a
-                                                                    // source that is not 4-byte aligned still needs)
+    if (s.Cs % 32 != 0 || (s.IH * s.IW) % 2 != 0) return false;   // (planes of an even number of pixels start 4-byte aligned)
     const size_t lim = (size_t)1 << 31;
     if ((size_t)pr.N * s.Cs * s.IH * s.IW * 2 >= lim || (size_t)pr.N * s.F * s.OH * s.OW * 4 >= ((size_t)1 << 33)) return false;
     if ((size_t)9 * s.F * s.Cs * 2 >= lim) return false;
@@ -574,7 +575,7 @@ bool bf16_tile_supports(int pass, const Problem& pr) {
 
 bool bf16_tile_accepts(int pass, const Problem& pr, const void* in0) {
     Shape s;
-    return shape_of(pass, pr, s) && (!reads_nchw(s) || reinterpret_cast<uintptr_t>(in0) % 4 == 0);
+    return shape_of(pass, pr, s) && reinterpret_cast<uintptr_t>(in0) % 4 == 0;
 }
 
 size_t bf16_tile_workspace_bytes(int pass, const Problem& pr) {
@@ -590,8 +591,8 @@ hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const voi
     Shape s;
     if (!shape_of(pass, pr, s)) return hipErrorNotSupported;
     // workspace: the packed filters first, then (if made) the channels-innermost copy of the source
-    const bool nchw = reads_nchw(s) && reinterpret_cast<uintptr_t>(in0) % 4 == 0;
-    if (reads_nchw(s) && !nchw) return hipErrorNotSupported;   // a 2-byte aligned tensor: no workspace was asked for the copy
+    if (reinterpret_cast<uintptr_t>(in0) % 4 != 0) return hipErrorNotSupported;   // every path here loads 4 bytes and more at a time
+    const bool nchw = reads_nchw(s);
     uint16_t* wp = static_cast<uint16_t*>(ws);
     const uint16_t* xt = static_cast<const uint16_t*>(in0);
     const int HW = s.IH * s.IW;

@@ -39,15 +39,15 @@ namespace {
 struct PackNArgs {
     const uint16_t* src;
     uint16_t* dst;
-    int N, Ch, HW;   // HW % 8 == 0
+    int N, Ch, HW;   // HW % 2 == 0 (planes start on 4-byte boundaries)
     unsigned src_bytes;
-    int total;       // ceil(N/8) * Ch * HW / 8 threads
+    int total;       // ceil(N/8) * Ch * ceil(HW / 8) threads
 };
 
 __global__ __launch_bounds__(256) void pack_n8_kernel(PackNArgs a) {
     const int t = blockIdx.x * 256 + threadIdx.x;
     if (t >= a.total) return;
-    const int per = a.HW / 8;
+    const int per = (a.HW + 7) / 8;   // the last group of a plane may run into the next plane: those pixels are not stored
     const int pc = t % per, rest = t / per;
     const int ch = rest % a.Ch, nb = rest / a.Ch;
     const rsrc_t rs = make_rsrc(a.src, a.src_bytes);
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void pack_n8_kernel(PackNArgs a) {
             const unsigned lo = r[2 * m][j / 2], hi = r[2 * m + 1][j / 2];
             v[m] = (j & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
         }
-        o[j] = v;
+        if (8 * pc + j < a.HW) o[j] = v;
     }
 }
 
@@ -403,7 +403,7 @@ bool make_plan(const Problem& pr, Plan& pl) {
     // near K C / (K + C) = 60.
     pl.x_bytes = (size_t)pl.NB * pr.C * pr.H * pr.W * 16;
     pl.y_bytes = (size_t)pl.NB * pr.K * pr.P * pr.Q * 16;
-    pl.packed = (size_t)pr.K * pr.C >= (size_t)60 * (pr.K + pr.C) && (pr.H * pr.W) % 8 == 0 && (pr.P * pr.Q) % 8 == 0 &&
+    pl.packed = (size_t)pr.K * pr.C >= (size_t)60 * (pr.K + pr.C) && (pr.H * pr.W) % 2 == 0 && (pr.P * pr.Q) % 2 == 0 &&
                 pl.x_bytes < lim && pl.y_bytes < lim;
     if (!pl.packed) {
         pl.x_bytes = pl.y_bytes = 0;
@@ -442,6 +442,8 @@ size_t bf16_wgrad_workspace_bytes(const Problem& pr) {
 hipError_t bf16_wgrad_run(const Problem& pr, const void* x, const void* dy, float* dw, void* ws, hipStream_t st) {
     Plan pl;
     if (!make_plan(pr, pl)) return hipErrorNotSupported;
+    // every load here is 4 bytes or wider: tensors that start on an odd element go to the kernels that take any alignment
+    if (reinterpret_cast<uintptr_t>(x) % 4 != 0 || reinterpret_cast<uintptr_t>(dy) % 4 != 0) return hipErrorNotSupported;
     unsigned char* base = static_cast<unsigned char*>(ws);
     uint16_t* xP = reinterpret_cast<uint16_t*>(base);
     uint16_t* yP = reinterpret_cast<uint16_t*>(base + round256(pl.x_bytes));
@@ -451,10 +453,10 @@ hipError_t bf16_wgrad_run(const Problem& pr, const void* x, const void* dy, floa
     a.x = static_cast<const uint16_t*>(x); a.dy = static_cast<const uint16_t*>(dy);
     if (pl.packed) {
         PackNArgs px{a.x, xP, pr.N, pr.C, pr.H * pr.W, (unsigned)((size_t)pr.N * pr.C * pr.H * pr.W * 2),
-                     pl.NB * pr.C * (pr.H * pr.W / 8)};
+                     pl.NB * pr.C * ((pr.H * pr.W + 7) / 8)};
         pack_n8_kernel<<<(px.total + 255) / 256, 256, 0, st>>>(px);
         PackNArgs py{a.dy, yP, pr.N, pr.K, pr.P * pr.Q, (unsigned)((size_t)pr.N * pr.K * pr.P * pr.Q * 2),
-                     pl.NB * pr.K * (pr.P * pr.Q / 8)};
+                     pl.NB * pr.K * ((pr.P * pr.Q + 7) / 8)};
         pack_n8_kernel<<<(py.total + 255) / 256, 256, 0, st>>>(py);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

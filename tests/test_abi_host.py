@@ -111,8 +111,14 @@ def test_workspace_sizes_of_the_benchmark_layers(mc):
     # few channels on wide planes: forward and backward-data read the NCHW source in place, only the packed filters are scratch
     for p in (0, 1):
         assert mc.conv2d_workspace_bytes(p, *l4a.conv_args(), mc.BF16_F32ACC) == 9 * l4a.K * l4a.C * 2
-    # 14x14 planes are not a multiple of 8 elements: bf16 inputs take the widening path, no layout copies
-    assert mc.conv2d_workspace_bytes(0, *L["2a"].conv_args(), mc.BF16_F32ACC) == 0
+    # 14x14 planes with bf16 inputs: the bf16 matrix cores too (a channels-innermost copy of x and the packed filters)
+    l2a = L["2a"]
+    assert mc.miconv_kernel_path(0, *l2a.conv_args(), mc.BF16_F32ACC) == "mfma/bf16_tile"
+    got4 = mc.conv2d_workspace_bytes(0, *l2a.conv_args(), mc.BF16_F32ACC)
+    need4 = l2a.N * l2a.H * l2a.W * l2a.C * 2 + 9 * l2a.K * l2a.C * 2
+    assert need4 <= got4 <= need4 + 512
+    # planes of an odd number of pixels: bf16 inputs take the fp32 matrix cores on widened values, no layout copies
+    assert mc.conv2d_workspace_bytes(0, 4, 64, 7, 7, 64, 3, 3, 1, 1, 1, 1, 1, mc.BF16_F32ACC) == 0
 
 
 def test_kernel_path_of_the_benchmark_layers(mc):

@@ -22,7 +22,7 @@ SHAPES = [
     ("o3x3e", 1, 160, 28, 28, 128, 3, 3, 1, 1, 1),     # ... several chunks and filter blocks
     ("o1x1a", 2, 48, 14, 14, 80, 1, 1, 1, 0, 1),       # fp32 matrix cores on widened inputs: float result staged, then converted
     ("o3x3s2", 2, 32, 28, 28, 32, 3, 3, 2, 1, 1),      # strided: merged-phase backward-data
-    ("o14", 2, 64, 14, 14, 64, 3, 3, 1, 1, 1),         # 14x14 planes: not on the bf16 cores
+    ("o7", 2, 64, 7, 7, 64, 3, 3, 1, 1, 1),            # 7x7 planes (an odd number of pixels): not on the bf16 cores
     ("oodd4", 2, 3, 13, 9, 5, 4, 3, (3, 2), (1, 0), 1),   # direct kernels
     ("odw14", 3, 40, 14, 14, 40, 3, 3, 1, 1, 40),      # depthwise
     ("oa11", 2, 3, 63, 63, 64, 11, 11, 4, 2, 1),       # three-channel first layer
@@ -96,7 +96,7 @@ def test_bf16_output_needs_no_staging_on_the_bf16_matrix_cores():
         L = wl.LAYERS[name]
         for p in (0, 1):
             assert mc.conv2d_workspace_bytes(p, *L.conv_args(), mc.BF16_BF16OUT) == mc.conv2d_workspace_bytes(p, *L.conv_args(), mc.BF16_F32ACC)
-    L = wl.LAYERS["2a"]      # 14x14 planes: fp32 matrix cores, the float result is staged
+    L = wl.LAYERS["2b"]      # 1x1: fp32 matrix cores on widened inputs, the float result is staged
     assert mc.conv2d_workspace_bytes(0, *L.conv_args(), mc.BF16_BF16OUT) == 4 * L.N * L.K * L.P * L.Q
 
 
