@@ -49,6 +49,7 @@ FAMILY_SOURCES = {
     "mfma/smallc": ("common.h", "mfma_smallc.hip"),
     "mfma/bf16_tile": ("common.h", "mfma_bf16.hip"),
     "mfma/bf16_wgrad": ("common.h", "mfma_bf16_wgrad.hip"),
+    "mfma/bf16_gemm": ("common.h", "mfma_bf16_gemm.hip"),
     "depthwise/strip": ("common.h", "depthwise.hip"),
     "depthwise/rows": ("common.h", "depthwise.hip"),
     "depthwise/lds": ("common.h", "depthwise.hip"),

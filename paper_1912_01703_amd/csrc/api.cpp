@@ -125,11 +125,11 @@ size_t out_elems(int pass, const Problem& pr) {
     return pass == MICONV_PASS_FWD ? (size_t)pr.N * pr.K * pr.P * pr.Q : (size_t)pr.N * pr.C * pr.H * pr.W;
 }
 // in0 == nullptr: the query, which assumes a first input tensor that is at least 4-byte aligned
-size_t total_workspace(int pass, int algo, const Problem& pr, int dtype, const void* in0, bool* native_bf16) {
+size_t total_workspace(int pass, int algo, const Problem& pr, int dtype, const void* in0, const void* in1, bool* native_bf16) {
     const size_t own = workspace_for(pass, algo, pr);
     *native_bf16 = false;
     if (!wants_bf16_out(pass, dtype)) return own;
-    *native_bf16 = algo == MICONV_ALGO_MFMA && miconv::mfma_writes_bf16(pass, pr, in0);
+    *native_bf16 = algo == MICONV_ALGO_MFMA && miconv::mfma_writes_bf16(pass, pr, in0, in1);
     return *native_bf16 ? own : round256(own) + out_elems(pass, pr) * sizeof(float);
 }
 
@@ -155,7 +155,7 @@ int run(int pass, const void* a, const void* b, void* out, int N, int C, int H, 
                     g_forced[pass], pass);
     bool native_bf16 = false;
     const bool bf16_out = wants_bf16_out(pass, dtype);
-    const size_t need = total_workspace(pass, algo, pr, dtype, a, &native_bf16);
+    const size_t need = total_workspace(pass, algo, pr, dtype, a, b, &native_bf16);
     if (static_ws) {
         if (need > kStaticWsBytes)
             return record_error(MICONV_ERR_WORKSPACE, "this problem needs %zu bytes of scratch memory, the static array holds %zu: "
@@ -259,7 +259,7 @@ size_t conv2d_workspace_bytes(int pass, int N, int C, int H, int W, int K, int R
     const int algo = choose_algo(pass, pr);
     if (algo < 0) return 0;
     bool native;
-    return total_workspace(pass, algo, pr, dtype, nullptr, &native);
+    return total_workspace(pass, algo, pr, dtype, nullptr, nullptr, &native);
 }
 
 const char* miconv_kernel_path(int pass, int N, int C, int H, int W, int K, int R, int S, int stride_h, int stride_w,

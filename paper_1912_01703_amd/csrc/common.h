@@ -82,6 +82,12 @@ size_t bf16_tile_workspace_bytes(int pass, const Problem& pr);
 hipError_t bf16_tile_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws,
                          hipStream_t st);
 
+// bf16 matrix-core 1x1 layers, all three passes (mfma_bf16_gemm.hip); needs workspace.
+bool bf16_gemm_supports(int pass, const Problem& pr);
+bool bf16_gemm_accepts(int pass, const Problem& pr, const void* in0, const void* in1);   // ... and will not decline these tensors
+size_t bf16_gemm_workspace_bytes(int pass, const Problem& pr);
+hipError_t bf16_gemm_run(int pass, const Problem& pr, const void* in0, const void* in1, float* out, void* ws, hipStream_t st);
+
 // bf16 matrix-core backward-weight for 3x3 stride-1 filters (mfma_bf16_wgrad.hip); needs workspace.
 bool bf16_wgrad_supports(const Problem& pr);
 size_t bf16_wgrad_workspace_bytes(const Problem& pr);
@@ -113,7 +119,7 @@ hipError_t epilogue_run(int pass, const Problem& pr, void* out, bool out_is_bf16
 // float -> bf16 (round to nearest even), count elements.
 hipError_t convert_to_bf16(const float* src, void* dst, size_t count, hipStream_t st);
 // Whether the MFMA kernel this pass is dispatched to can write bf16 results itself, given the first input tensor.
-bool mfma_writes_bf16(int pass, const Problem& pr, const void* in0);
+bool mfma_writes_bf16(int pass, const Problem& pr, const void* in0, const void* in1);
 
 // ---- depthwise kernels (depthwise.hip): groups == C == K, no MFMA ------------------------
 bool depthwise_supports(int pass, const Problem& pr);

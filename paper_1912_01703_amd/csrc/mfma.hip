@@ -21,6 +21,7 @@ static Problem canonical(const Problem& in) {
 bool mfma_supports(int pass, const Problem& in) {
     const Problem pr = canonical(in);
     if (is_depthwise(pr)) return false;  // one input channel per filter: nothing to contract
+    if (bf16_gemm_supports(pass, in)) return true;
     if (smallc_supports(pass, pr)) return true;
     if (bf16_tile_supports(pass, pr)) return true;
     if (pass == 2 && bf16_wgrad_supports(pr)) return true;
@@ -34,6 +35,12 @@ size_t mfma_workspace_bytes(int pass, const Problem& in) {
     const Problem pr = canonical(in);
     size_t ws = 0;
     if (is_depthwise(pr)) return 0;
+    if (bf16_gemm_supports(pass, in)) {
+        // (room for the fp32-matrix-core backward-weight kernel as well: it takes over when a tensor is only 2-byte aligned)
+        if (pass == 2) wgrad_supports(pr, &ws);
+        const size_t own = bf16_gemm_workspace_bytes(pass, in);
+        return own > ws ? own : ws;
+    }
     if (smallc_supports(pass, pr)) return smallc_workspace_bytes(pass, pr);
     if (bf16_tile_supports(pass, pr)) return bf16_tile_workspace_bytes(pass, pr);
     if (pass == 2 && bf16_wgrad_supports(pr)) {
@@ -49,6 +56,7 @@ size_t mfma_workspace_bytes(int pass, const Problem& in) {
 const char* mfma_path_name(int pass, const Problem& in) {
     const Problem pr = canonical(in);
     if (!mfma_supports(pass, in)) return "none";
+    if (bf16_gemm_supports(pass, in)) return "mfma/bf16_gemm";
     if (smallc_supports(pass, pr)) return "mfma/smallc";
     if (bf16_tile_supports(pass, pr)) return "mfma/bf16_tile";
     if (pass == 2) return bf16_wgrad_supports(pr) ? "mfma/bf16_wgrad" : "mfma/wgrad";
@@ -56,7 +64,8 @@ const char* mfma_path_name(int pass, const Problem& in) {
     return tile_merge2_supports(pr) ? "mfma/tile_merge2" : "mfma/tile_phase";
 }
 
-bool mfma_writes_bf16(int pass, const Problem& in, const void* in0) {
+bool mfma_writes_bf16(int pass, const Problem& in, const void* in0, const void* in1) {
+    if (pass < 2 && bf16_gemm_supports(pass, in)) return bf16_gemm_accepts(pass, in, in0, in1);
     const Problem pr = canonical(in);
     return pass < 2 && !smallc_supports(pass, pr) && bf16_tile_supports(pass, pr) && bf16_tile_accepts(pass, pr, in0);
 }
@@ -71,12 +80,19 @@ hipError_t mfma_run(int pass, const Problem& in, const void* a, const void* b, f
                     bool* fused_epilogue) {
     const Problem pr = canonical(in);
     *fused_epilogue = mfma_fuses_epilogue(pass, in);
+    if (bf16_gemm_supports(pass, in)) {
+        // (declines tensors that are only 2-byte aligned: the kernels below take any alignment)
+        const hipError_t e = bf16_gemm_run(pass, in, a, b, out, ws, st);
+        if (e != hipErrorNotSupported) return e;
+        *fused_epilogue = pass < 2;   // the fp32 tile kernels that take over apply the epilogue in their write-out
+    }
     if (smallc_supports(pass, pr)) return smallc_run(pass, pr, a, b, out, ws, st);
     if (bf16_tile_supports(pass, pr)) {
         // (declines a source tensor that is only 2-byte aligned when it planned to read it in place: the kernels below
         // take any alignment)
         const hipError_t e = bf16_tile_run(pass, pr, a, b, out, ws, st);
         if (e != hipErrorNotSupported) return e;
+        *fused_epilogue = true;   // the fp32 tile kernel that takes over applies the epilogue in its write-out
     }
     if (pass == 2 && bf16_wgrad_supports(pr)) {
         const hipError_t e = bf16_wgrad_run(pr, a, b, out, ws, st);

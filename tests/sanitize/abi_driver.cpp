@@ -29,7 +29,7 @@ bool depthwise_fuses_epilogue(int, const Problem&) { return true; }
 hipError_t epilogue_run(int, const Problem&, void*, bool, hipStream_t) { ++g_epilogues; return hipSuccess; }
 static int g_conversions = 0;
 hipError_t convert_to_bf16(const float*, void*, size_t, hipStream_t) { ++g_conversions; return hipSuccess; }
-bool mfma_writes_bf16(int, const Problem& pr, const void*) { return pr.C == 8; }
+bool mfma_writes_bf16(int, const Problem& pr, const void*, const void*) { return pr.C == 8; }
 }  // namespace miconv
 
 typedef int (*pass_fn)(const void*, const void*, void*, int, int, int, int, int, int, int, int, int, int, int, int, int, void*,

@@ -21,6 +21,7 @@ SHAPES = [
     ("o3x3w", 1, 32, 100, 48, 64, 3, 3, 1, 1, 1),      # ... the instance that reads NCHW in place
     ("o3x3e", 1, 160, 28, 28, 128, 3, 3, 1, 1, 1),     # ... several chunks and filter blocks
     ("o1x1a", 2, 48, 14, 14, 80, 1, 1, 1, 0, 1),       # fp32 matrix cores on widened inputs: float result staged, then converted
+    ("o1x1g", 16, 64, 14, 14, 128, 1, 1, 1, 0, 1),     # 1x1 as a matrix product on the bf16 cores: bf16 stored by the kernel
     ("o3x3s2", 2, 32, 28, 28, 32, 3, 3, 2, 1, 1),      # strided: merged-phase backward-data
     ("o7", 2, 64, 7, 7, 64, 3, 3, 1, 1, 1),            # 7x7 planes (an odd number of pixels): not on the bf16 cores
     ("oodd4", 2, 3, 13, 9, 5, 4, 3, (3, 2), (1, 0), 1),   # direct kernels
@@ -83,7 +84,8 @@ def test_bf16_output_shapes(row, which):
 
 
 @pytest.mark.parametrize("which", ["fwd", "bwd_data"])
-@pytest.mark.parametrize("row", [SHAPES[0], SHAPES[2], SHAPES[4], SHAPES[8]], ids=["native", "native-nchw", "staged-mfma", "staged-dw"])
+@pytest.mark.parametrize("row", [SHAPES[0], SHAPES[2], SHAPES[4], SHAPES[5], SHAPES[9]],
+                         ids=["native", "native-nchw", "staged-mfma", "native-1x1", "staged-dw"])
 def test_bf16_output_with_fused_epilogues(row, which):
     name, N, C, H, W, K, R, S, st, pd, g = row
     L = wl.custom_layer(name + "e", N, C, H, W, K, R, S, st, pd, g, seed=8600 + SHAPES.index(row))
@@ -96,8 +98,10 @@ def test_bf16_output_needs_no_staging_on_the_bf16_matrix_cores():
         L = wl.LAYERS[name]
         for p in (0, 1):
             assert mc.conv2d_workspace_bytes(p, *L.conv_args(), mc.BF16_BF16OUT) == mc.conv2d_workspace_bytes(p, *L.conv_args(), mc.BF16_F32ACC)
-    L = wl.LAYERS["2b"]      # 1x1: fp32 matrix cores on widened inputs, the float result is staged
+    L = wl.LAYERS["3"]       # the three-channel first layer: fp32 matrix cores on widened inputs, the float result is staged
     assert mc.conv2d_workspace_bytes(0, *L.conv_args(), mc.BF16_BF16OUT) == 4 * L.N * L.K * L.P * L.Q
+    L = wl.LAYERS["2b"]      # 1x1 on the bf16 matrix cores: bf16 written by the kernel, scratch for the channels-innermost copy only
+    assert mc.conv2d_workspace_bytes(0, *L.conv_args(), mc.BF16_BF16OUT) == mc.conv2d_workspace_bytes(0, *L.conv_args(), mc.BF16_F32ACC)
 
 
 def test_bf16_output_backward_weight_is_the_float_result():

@@ -182,6 +182,46 @@ def test_bf16_tensors_that_start_on_an_odd_element(shape):
         assert ok and err <= pu.TOL["bf16"], (p, err)
 
 
+BF16GEMM = [
+    # name      N    C    H   W    K      1x1, stride 1, bf16: all three passes as matrix products on the bf16 matrix cores
+    ("g1x1a", 16, 64, 14, 14, 128),      # one 128 x 128 tile column, 25 pixel tiles, two chunks
+    ("g1x1b", 6, 200, 14, 14, 136),      # partial tiles in every dimension, a partial last chunk (200 = 3 * 64 + 8)
+    ("g1x1c", 16, 72, 20, 28, 40),       # fewer filters than a tile
+    ("g1x1d", 4, 256, 9, 6, 520),        # planes of 54 pixels: backward-weight rows end inside a 16-byte piece
+    ("g1x1e", 160, 32, 7, 8, 64),        # half a chunk of channels; backward-weight: 56-pixel rows, 160 images over the splits
+    ("g1x1f", 2, 1024, 14, 14, 256),     # sixteen chunks
+]
+
+
+@pytest.mark.parametrize("row", BF16GEMM, ids=[r[0] for r in BF16GEMM])
+def test_bf16_matrix_core_1x1(row):
+    from paper_1912_01703_amd import binding as mc
+    name, N, C, H, W, K = row
+    L = wl.custom_layer(name, N, C, H, W, K, 1, 1, 1, 0, 1, seed=6300 + BF16GEMM.index(row))
+    for p in range(3):
+        assert mc.miconv_kernel_path(p, *L.conv_args(), mc.BF16_F32ACC) == "mfma/bf16_gemm", (name, p)
+    pu.check_layer_full(L, "bf16", algo=mc.ALGO_MFMA, expect_algo=mc.ALGO_MFMA)
+
+
+def test_bf16_1x1_tensors_that_start_on_an_odd_element():
+    import torch
+    L = wl.custom_layer("g-odd-start", 16, 64, 14, 14, 128, 1, 1, 1, 0, 1, seed=6310)
+    h = pu.prepare(L, "bf16")
+    gr = pu.GpuRunner(L, h, "bf16")
+
+    def shifted(t):
+        flat = torch.empty(t.numel() + 1, dtype=t.dtype, device=t.device)
+        flat[1:].copy_(t.reshape(-1))
+        return flat[1:].view(t.shape)
+
+    gr.x, gr.w, gr.dy = shifted(gr.x), shifted(gr.w), shifted(gr.dy)
+    for p in pu.PASSES:
+        out = gr.run(p).cpu().numpy()
+        refv, den = pu.oracle_full(L, h, p)
+        err, ok = pu.max_norm_err(out, refv, den)
+        assert ok and err <= pu.TOL["bf16"], (p, err)
+
+
 PHASED = [
     # name      N   C   H   W   K   R   S  stride pad groups      backward-data only (per-phase MFMA launches)
     ("p5x5s2", 2, 16, 20, 20, 16, 5, 5, 2, 2, 1),
