@@ -120,3 +120,37 @@ def test_fused_calls_reject_a_missing_epilogue_operand():
     args = (1, 4, 8, 8, 4, 3, 3, 1, 1, 1, 1, 1)
     assert mc.conv2d_fwd_bias_relu(t, t, None, t, *args, check=False) == mc.ERR_NULL and "bias" in mc.last_error()
     assert mc.conv2d_bwd_data_relu_mask(t, t, None, t, *args, check=False) == mc.ERR_NULL and "act" in mc.last_error()
+
+
+@pytest.mark.parametrize("shape", [(2, 64, 14, 14, 64, 3), (16, 64, 14, 14, 128, 1)], ids=["3x3", "1x1"])
+def test_fused_epilogue_is_applied_once_when_a_bf16_kernel_declines_the_tensors(shape):
+    """bf16 tensors that start on an odd element are declined by the bf16 matrix-core kernels at run time; the fp32 tile
+    kernels that take over apply the epilogue in their write-out, and no second pass may follow."""
+    import torch
+    from paper_1912_01703_amd import binding as mc
+    N, C, H, W, K, R = shape
+    L = wl.custom_layer("decline", N, C, H, W, K, R, R, 1, R // 2, 1, seed=8200)
+    h = pu.prepare(L, "bf16")
+    bias, _ = wl.make_epilogue_inputs(L)
+    bias = np.abs(bias) + 1.0          # a bias added twice would show in every element
+    dev = "cuda:0"
+
+    def shifted(a):
+        t = torch.from_numpy(a.view(np.int16))
+        flat = torch.empty(t.numel() + 1, dtype=t.dtype, device=dev)
+        flat[1:].copy_(t.reshape(-1))
+        return flat[1:].view(t.shape)
+
+    x, w = shifted(h["x"]), shifted(h["w"])
+    assert x.data_ptr() % 4 == 2
+    need = mc.conv2d_workspace_bytes(0, *L.conv_args(), mc.BF16_F32ACC)
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+    out = torch.full(L.y_shape, float("nan"), device=dev)
+    mc.conv2d_fwd_bias_relu(x, w, torch.from_numpy(bias).to(dev), out, *L.conv_args(), mc.BF16_F32ACC, ws,
+                            torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    st, pd, g = L.strides, L.pads, L.groups
+    want = ref.conv2d_fwd_bias_relu(h["xo"], h["wo"], bias, st, pd, g)
+    den = ref.conv2d_fwd(pu._abs(h["xo"]), pu._abs(h["wo"]), st, pd, g) + np.abs(bias.astype(np.float64))[None, :, None, None]
+    err, ok = pu.max_norm_err(out.cpu().numpy(), want, den)
+    assert ok and err <= pu.TOL["bf16"], err
