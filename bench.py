@@ -83,6 +83,11 @@ def parse():
     ap.add_argument("--rotate", type=int, default=0,
                     help="number of distinct buffer sets cycled between steps (0: auto; "
                          "bandwidth-bound layers use enough to exceed the 256 MB Infinity Cache)")
+    ap.add_argument("--all-layers", action="store_true",
+                    help="instead of the benchmark, time every benchmark layer (fp32; the two VGG layers also with bf16 "
+                         "inputs) and print one JSON line per layer and dtype: per pass time, TFLOP/s, GB/s, fraction of the "
+                         "roof that bounds it, kernel family and (layers the oracle finishes in seconds) the largest "
+                         "normalised error against the oracle")
     ap.add_argument("--traffic-lines", metavar="DIR",
                     help="instead of the benchmark, read the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE csv files under DIR "
                          "(sub-folders copy_<COUNTER>, l<layer>[bf16]_<COUNTER>) and print the per-kernel table and the "
@@ -483,6 +488,41 @@ def batchnorm_figures(mc, wl, torch, np, reps=20):
     return out
 
 
+def all_layers(a, mc, wl, torch, np):
+    """One JSON line per (layer, dtype) of the benchmark configurations."""
+    from oracle import convref as ref
+    runs = [(n, "f32") for n in wl.LAYERS] + [("4a", "bf16"), ("4b", "bf16")]
+    for name, dtype in runs:
+        L = wl.LAYERS[name]
+        steps = max(5, min(a.steps, int(400.0 / max(1e-3, 3 * L.flops / 100e12 * 1e3))))   # about 0.4 s of timed work per region
+        m = measure_layer(L, dtype, steps, min(a.warmup, steps), a.settle_ms, a.rotate, mc, wl, torch, np)
+        peak = PEAK_HBM_GBS if m["hbm_bound"] else PEAK_TFLOPS[dtype]
+        line = {"layer": name, "note": L.note, "dtype": dtype, "seed": L.seed, "bound": "hbm" if m["hbm_bound"] else "mfma",
+                "peak": peak, "unit": "GB/s" if m["hbm_bound"] else "TFLOP/s", "steps": steps,
+                "step_tflops": 3.0 * L.flops / (m["ms_per_step"] * 1e-3) / 1e12, "passes": {}}
+        errs = None
+        if 3.0 * L.flops <= 60e9:      # the oracle finishes the layer (and its absolute-value twin) in seconds
+            def gpu_results(L=L, dtype=dtype):
+                s = make_sets(L, dtype, 1, torch, np, wl, "cuda:0")[0]
+                code = mc.BF16_F32ACC if dtype == "bf16" else mc.F32
+                args = L.conv_args()
+                ws = torch.empty(max([256] + [mc.conv2d_workspace_bytes(p, *args, code) for p in range(3)]), dtype=torch.uint8, device="cuda:0")
+                st = torch.cuda.current_stream().cuda_stream
+                mc.conv2d_fwd(s["x"], s["w"], s["y"], *args, code, ws, st)
+                mc.conv2d_bwd_data(s["dy"], s["w"], s["dx"], *args, code, ws, st)
+                mc.conv2d_bwd_weight(s["x"], s["dy"], s["dw"], *args, code, ws, st)
+                torch.cuda.synchronize()
+                return s["y"].cpu().numpy(), s["dx"].cpu().numpy(), s["dw"].cpu().numpy()
+            errs = cpu_baseline(L, dtype, gpu_results)["max_norm_err_vs_gpu"]
+        for pname in PASSES:
+            p = m["passes"][pname]
+            ach = p["gbs"] if m["hbm_bound"] else p["tflops"]
+            line["passes"][pname] = {"us_avg": p["ms_avg"] * 1e3, "us_median": p["ms_median"] * 1e3, "us_min": p["ms_min"] * 1e3,
+                                     "tflops": p["tflops"], "gbs": p["gbs"], "frac_of_roof": ach / peak,
+                                     "kernel_path": p["kernel_path"], "max_norm_err": errs[pname] if errs else None}
+        print(json.dumps(line), flush=True)
+
+
 def sweep(mc, wl, torch):
     """Times every pass of wl.MORE_SHAPES (fp32, seeded inputs of the workloads module, back-to-back launches between
     two events)."""
@@ -553,6 +593,9 @@ def main():
         return
     if a.sweep:
         sweep(mc, wl, torch)
+        return
+    if a.all_layers:
+        all_layers(a, mc, wl, torch, np)
         return
     L = wl.LAYERS[a.layer]
     m = measure_layer(L, a.dtype, a.steps, a.warmup, a.settle_ms, a.rotate, mc, wl, torch, np, fused=a.epilogue)
