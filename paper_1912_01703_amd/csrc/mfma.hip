@@ -70,10 +70,10 @@ bool mfma_writes_bf16(int pass, const Problem& in, const void* in0, const void* 
     return pass < 2 && !smallc_supports(pass, pr) && bf16_tile_supports(pass, pr) && bf16_tile_accepts(pass, pr, in0);
 }
 
-// The kernels built on conv_tile_kernel apply bias + ReLU / the ReLU mask in their write-out.
+// The kernels built on conv_tile_kernel and the bf16 1x1 product kernel apply bias + ReLU / the ReLU mask in their write-out.
 bool mfma_fuses_epilogue(int pass, const Problem& in) {
     const char* path = mfma_path_name(pass, in);
-    return std::strncmp(path, "mfma/tile", 9) == 0;
+    return std::strncmp(path, "mfma/tile", 9) == 0 || (pass < 2 && std::strcmp(path, "mfma/bf16_gemm") == 0);
 }
 
 hipError_t mfma_run(int pass, const Problem& in, const void* a, const void* b, float* out, void* ws, hipStream_t st,

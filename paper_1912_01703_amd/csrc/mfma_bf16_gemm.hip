@@ -35,6 +35,9 @@ struct GemmArgs {
     int batches, splits;       // reduction batches, and how many workgroups share a tile's batches
     int tiles_m, tiles_n;
     int mode, HW, out_bf16;
+    // fused epilogues of mode 0 (both null: none): y = max(0, y + bias[m]); dx = mask > 0 ? dx : 0 (mask: bf16, shaped like out)
+    const float* bias;
+    const uint16_t* mask;
 };
 
 __device__ __forceinline__ unsigned pack_bf16_pair(float lo, float hi) {
@@ -192,6 +195,29 @@ __global__ __launch_bounds__(NTHREADS, OCC) void bf16_gemm_kernel(GemmArgs a) {
             nbase = (size_t)sp * a.M * a.N + n;
             mstride = (size_t)a.N;
         }
+        if (a.bias) {   // (wave-uniform branches on kernel arguments)
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = m0 + wm * (BM / 2) + i * 16 + 4 * kk + v;
+                    acc[i][j][v] = fmaxf(acc[i][j][v] + (m < a.M ? a.bias[m] : 0.f), 0.f);
+                }
+        }
+        if (a.mask) {   // the mask elements under this column's results are requested together, then applied
+            float mv[MB][4];
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int m = m0 + wm * (BM / 2) + i * 16 + 4 * kk + v;
+                    mv[i][v] = m < a.M ? bf16_to_float(a.mask[nbase + (size_t)m * mstride]) : 0.f;
+                }
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[i][j][v] = mv[i][v] > 0.f ? acc[i][j][v] : 0.f;
+        }
 #pragma unroll
         for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -334,6 +360,8 @@ hipError_t bf16_gemm_run(int pass, const Problem& pr, const void* in0, const voi
         a.batches = 1; a.splits = 1;
         a.mode = 0;
         a.out_bf16 = pr.out_bf16 ? 1 : 0;
+        a.bias = pass == 0 ? pr.bias : nullptr;
+        a.mask = pass == 1 ? static_cast<const uint16_t*>(pr.relu_mask) : nullptr;
     } else {
         a.A = static_cast<const uint16_t*>(in1);   // dy [N][K][HW]
         a.B = static_cast<const uint16_t*>(in0);   // x  [N][C][HW]

@@ -83,6 +83,7 @@ SHAPES = [
     ("e3x3g", 2, 64, 14, 14, 96, 3, 3, 1, 1, 2),       # groups: bias and mask offsets per group
     ("e1x1d", 2, 72, 20, 28, 40, 1, 1, 1, 0, 1),       # 1x1 on row bands
     ("e1x1i", 1, 24, 14, 112, 40, 1, 1, 1, 0, 1),      # plane presented with another shape
+    ("e1x1g", 16, 72, 14, 14, 136, 1, 1, 1, 0, 1),     # bf16: the matrix-product kernel applies the epilogue in its write-out
     ("e3x3p", 5, 16, 210, 210, 24, 3, 3, 1, 1, 1),     # persistent workgroups: an epilogue per work item
     ("e3x3s2d", 2, 24, 57, 60, 40, 3, 3, 2, 1, 1),     # merged-phase backward-data
     ("e5x5s2", 2, 16, 20, 20, 16, 5, 5, 2, 2, 1),      # one launch per phase
