@@ -50,8 +50,15 @@ __device__ __forceinline__ unsigned pack_bf16_pair(float lo, float hi) {
 // cover the time a chunk's loads take to arrive (a chunk is multiplied in a few hundred cycles, a load takes thousands).
 // DEPTH: chunks kept in flight in registers (1 or 2).  With two register sets a chunk's loads are issued two chunks
 // of MFMAs before they are needed instead of one.
-template <int BM, int BN, int OCC, int DEPTH>
+// BT: B is not given with k innermost but as an NCHW tensor [img][k][HW] whose rows n = img * HW + hw are its pixels
+// (forward: x, backward-data: dy), and is transposed on the way into LDS: half of the threads each fetch, for eight
+// channel planes, the same aligned group of four pixels (eight 8-byte loads, the plane picked by the scalar offset;
+// lanes run along the pixels), and byte permutes turn the 8 x 4 values into the four 16-byte pieces "eight channels of
+// one pixel".  Planes are multiples of four pixels, so a group never straddles two images.  This saves writing and
+// re-reading a channels-innermost copy of the tensor (17 of 54 us on 512 -> 512 channels at 14 x 14, N = 128).
+template <int BM, int BN, int OCC, int DEPTH, bool BT>
 __global__ __launch_bounds__(NTHREADS, OCC) void bf16_gemm_kernel(GemmArgs a) {
+    static_assert(!BT || (BN == 64 && BK == 64), "the in-flight transposition is laid out for 64 pixels x 64 channels");
     constexpr int MB = BM / 32, NB = BN / 32;                  // 16 x 16 blocks per wave along m and n
     constexpr int PA = BM * (BK / 8) / NTHREADS, PB = BN * (BK / 8) / NTHREADS;   // 16-byte pieces per thread
     constexpr int A_BYTES = BM * PITCH, BUF_BYTES = (BM + BN) * PITCH;
@@ -86,7 +93,8 @@ __global__ __launch_bounds__(NTHREADS, OCC) void bf16_gemm_kernel(GemmArgs a) {
     }
     const bool ktail = (a.Kd & 7) != 0;
 
-    v4u ra[DEPTH][PA], rb[DEPTH][PB];
+    v4u ra[DEPTH][PA], rb[DEPTH][BT ? 1 : PB];
+    v2u rt[DEPTH][BT ? 8 : 1];   // BT: four pixels of eight channel planes
     int nva[DEPTH];   // elements of this thread's pieces inside their rows (for the piece that straddles a row's end)
     // Row offsets are fixed for the whole kernel (rows past the tile's operand: the out-of-range marker, which stays
     // out of range when a chunk's offset, below 2^31, is added); the chunk walk keeps its batch and k position in counters, so a
@@ -96,7 +104,21 @@ __global__ __launch_bounds__(NTHREADS, OCC) void bf16_gemm_kernel(GemmArgs a) {
     for (int i = 0; i < PA; ++i) aoff[i] = m0 + prow[i] < a.M ? (unsigned)((m0 + prow[i]) * a.lda + pcol) * 2u : kOob;
 #pragma unroll
     for (int i = 0; i < PB; ++i) boff[i] = n0 + prow[i] < a.N ? (unsigned)((n0 + prow[i]) * a.ldb + pcol) * 2u : kOob;
-    const unsigned a_bytes = (unsigned)((size_t)a.M * a.lda * 2), b_bytes = (unsigned)((size_t)a.N * a.ldb * 2);
+    const unsigned a_bytes = (unsigned)((size_t)a.M * a.lda * 2);
+    const unsigned b_bytes = BT ? (unsigned)((size_t)a.N * a.Kd * 2) : (unsigned)((size_t)a.N * a.ldb * 2);
+    // BT: thread u < 128 owns pixel group u % 16 (pixels n0 + 4 * (u % 16) ..) and channel group u / 16 of a chunk
+    const int tpg = tid & 15, tcg = tid >> 4;
+    unsigned toff = kOob;                 // byte offset of (image, channel 8 * tcg, pixel) or the out-of-range marker
+    int tlds = 0;
+    if constexpr (BT) {
+        const int n = n0 + 4 * tpg;
+        if (tid < 128 && n < a.N) {
+            const int img = n / a.HW, hw = n - img * a.HW;
+            toff = (unsigned)((img * a.Kd + 8 * tcg) * a.HW + hw) * 2u;
+        }
+        tlds = 4 * tpg * PITCH + tcg * 16;
+    }
+    const unsigned plane_bytes = (unsigned)a.HW * 2u;
     int fb = b_begin, fk = 0;   // batch and first k of the next chunk to fetch
     auto fetch = [&](auto setc) __attribute__((always_inline)) {
         constexpr int SET = decltype(setc)::value;
@@ -106,8 +128,15 @@ __global__ __launch_bounds__(NTHREADS, OCC) void bf16_gemm_kernel(GemmArgs a) {
         const unsigned kb = (unsigned)fk * 2u;
 #pragma unroll
         for (int i = 0; i < PA; ++i) ra[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(ars, kin ? aoff[i] + kb : kOob, 0, 0);
+        if constexpr (BT) {
+            // (a valid group has its eight planes inside the tensor; channels past the last chunk's end: out of range)
+            const unsigned off = fk + 8 * tcg < a.Kd ? toff + (unsigned)fk * plane_bytes : kOob;
 #pragma unroll
-        for (int i = 0; i < PB; ++i) rb[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(brs, kin ? boff[i] + kb : kOob, 0, 0);
+            for (int j = 0; j < 8; ++j) rt[SET][j] = __builtin_amdgcn_raw_buffer_load_b64(brs, off, j * plane_bytes, 0);
+        } else {
+#pragma unroll
+            for (int i = 0; i < PB; ++i) rb[SET][i] = __builtin_amdgcn_raw_buffer_load_b128(brs, kin ? boff[i] + kb : kOob, 0, 0);
+        }
         nva[SET] = a.Kd - (fk + pcol);
         fk += BK;
         if (fk >= a.Kd) { fk = 0; ++fb; }
@@ -125,8 +154,21 @@ __global__ __launch_bounds__(NTHREADS, OCC) void bf16_gemm_kernel(GemmArgs a) {
         };
 #pragma unroll
         for (int i = 0; i < PA; ++i) put(la + plds[i], ra[SET][i]);
+        if constexpr (BT) {
+            if (tid < 128) {
 #pragma unroll
-        for (int i = 0; i < PB; ++i) put(lb + plds[i], rb[SET][i]);
+                for (int k = 0; k < 4; ++k) {   // pixel k of the group: channels 2i, 2i+1 are the halves k % 2 of dword k / 2 of planes 2i, 2i+1
+                    v4u piece;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        piece[i] = __builtin_amdgcn_perm(rt[SET][2 * i + 1][k / 2], rt[SET][2 * i][k / 2], k % 2 ? 0x07060302u : 0x05040100u);
+                    *reinterpret_cast<v4u*>(lb + tlds + k * PITCH) = piece;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < PB; ++i) put(lb + plds[i], rb[SET][i]);
+        }
     };
 
     v4f acc[MB][NB];
@@ -325,11 +367,20 @@ bool bf16_gemm_accepts(int pass, const Problem& pr, const void* in0, const void*
     return bf16_gemm_supports(pass, pr) && reinterpret_cast<uintptr_t>(in0) % 4 == 0 && reinterpret_cast<uintptr_t>(in1) % 4 == 0;
 }
 
+// Planes of a multiple of four pixels can be transposed inside the product kernel instead of getting a channels-
+// innermost copy.  Every m tile of a pixel tile then transposes the same B data again (with 8-byte loads on half of the
+// threads), so this pays only with few destination channels: 1024 -> 256 channels forward 40 -> 33 us (4 m tiles), but
+// 512 -> 512 54 -> 56 us (8) and 256 -> 1024 backward-data 36 -> 41 us (16).
+bool transposes_in_flight(int pass, const Problem& pr) {
+    return ((long long)pr.H * pr.W) % 4 == 0 && (pass == 0 ? pr.K : pr.C) <= 4 * kEdge;
+}
+
 size_t bf16_gemm_workspace_bytes(int pass, const Problem& pr) {
     if (!bf16_gemm_supports(pass, pr)) return 0;
     const size_t HW = (size_t)pr.H * pr.W;
-    if (pass == 0) return round256((size_t)pr.N * HW * pr.C * 2);
-    if (pass == 1) return round256((size_t)pr.N * HW * pr.K * 2) + round256((size_t)pr.K * pr.C * 2);
+    const bool bt = transposes_in_flight(pass, pr);
+    if (pass == 0) return bt ? 0 : round256((size_t)pr.N * HW * pr.C * 2);
+    if (pass == 1) return (bt ? 0 : round256((size_t)pr.N * HW * pr.K * 2)) + round256((size_t)pr.K * pr.C * 2);
     const int s = wgrad_splits(pr);
     return s > 1 ? (size_t)s * pr.K * pr.C * sizeof(float) : 0;
 }
@@ -338,23 +389,31 @@ hipError_t bf16_gemm_run(int pass, const Problem& pr, const void* in0, const voi
     if (!bf16_gemm_accepts(pass, pr, in0, in1)) return hipErrorNotSupported;
     const int HW = pr.H * pr.W;
     GemmArgs a{};
+    bool bt = false;
     a.HW = HW;
     a.out = out;
     hipError_t e = hipSuccess;
     if (pass < 2) {
         const int Cs = pass == 0 ? pr.C : pr.K, F = pass == 0 ? pr.K : pr.C;   // reduction / destination channels
-        uint16_t* srcT = static_cast<uint16_t*>(ws);
-        PackArgs pa{static_cast<const uint16_t*>(in0), srcT, pr.N, Cs, HW, (unsigned)((size_t)pr.N * Cs * HW * 2)};
-        gemm_pack_nhwc_kernel<<<dim3((HW + 127) / 128, (Cs + 63) / 64, pr.N), 256, 0, st>>>(pa);
-        if ((e = hipGetLastError()) != hipSuccess) return e;
+        bt = transposes_in_flight(pass, pr);
+        const uint16_t* bmat = static_cast<const uint16_t*>(in0);   // transposed in flight: the NCHW tensor itself
+        size_t used = 0;
+        if (!bt) {
+            uint16_t* srcT = static_cast<uint16_t*>(ws);
+            PackArgs pa{static_cast<const uint16_t*>(in0), srcT, pr.N, Cs, HW, (unsigned)((size_t)pr.N * Cs * HW * 2)};
+            gemm_pack_nhwc_kernel<<<dim3((HW + 127) / 128, (Cs + 63) / 64, pr.N), 256, 0, st>>>(pa);
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            bmat = srcT;
+            used = round256((size_t)pr.N * HW * Cs * 2);
+        }
         const uint16_t* wmat = static_cast<const uint16_t*>(in1);   // forward: w[K][C] as it is
         if (pass == 1) {
-            uint16_t* wt = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(ws) + round256((size_t)pr.N * HW * Cs * 2));
+            uint16_t* wt = reinterpret_cast<uint16_t*>(static_cast<unsigned char*>(ws) + used);
             gemm_transpose_kernel<<<dim3((pr.C + 31) / 32, (pr.K + 31) / 32), 256, 0, st>>>(wmat, wt, pr.K, pr.C);
             if ((e = hipGetLastError()) != hipSuccess) return e;
             wmat = wt;
         }
-        a.A = wmat; a.B = srcT;
+        a.A = wmat; a.B = bmat;
         a.M = F; a.N = pr.N * HW; a.Kd = Cs;
         a.lda = Cs; a.ldb = Cs;
         a.batches = 1; a.splits = 1;
@@ -376,7 +435,8 @@ hipError_t bf16_gemm_run(int pass, const Problem& pr, const void* in0, const voi
     a.tiles_n = (a.N + kEdge - 1) / kEdge;
     const long long grid = (((long long)a.tiles_m * a.tiles_n * a.splits + 7) / 8) * 8;
     if (grid >= (1ll << 31)) return hipErrorNotSupported;
-    bf16_gemm_kernel<kEdge, kEdge, 4, 2><<<(unsigned)grid, NTHREADS, 0, st>>>(a);
+    if (bt) bf16_gemm_kernel<kEdge, kEdge, 4, 2, true><<<(unsigned)grid, NTHREADS, 0, st>>>(a);
+    else bf16_gemm_kernel<kEdge, kEdge, 4, 2, false><<<(unsigned)grid, NTHREADS, 0, st>>>(a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if (pass == 2 && a.splits > 1) {
         const size_t count = (size_t)pr.K * pr.C;
