@@ -25,7 +25,11 @@
  *             as bfloat16 (dw remains float).  The 3x3 stride-1 kernels on the
  *             bf16 matrix cores write bfloat16 themselves; every other kernel
  *             writes float into the workspace (conv2d_workspace_bytes accounts
- *             for it) and a conversion pass follows.  Where a fused epilogue
+ *             for it, assuming x / dy and w start on 4-byte boundaries; a
+ *             tensor that starts on an odd element makes those kernels step
+ *             aside, and the call then needs room for a float result as
+ *             well or returns MICONV_ERR_WORKSPACE) and a conversion pass
+ *             follows.  Where a fused epilogue
  *             is applied by a separate pass to a result that is already
  *             bfloat16, the bias is added to the rounded value and the sum is
  *             rounded again.
