@@ -60,12 +60,14 @@ def worst(got, want, den):
     return float(np.max(np.abs(got[live] - want[live]) / den[live])) if live.any() else 0.0
 
 
-def run_case(name, N, C, H, W, seed, offset=0):
+def run_case(name, N, C, H, W, seed, offset=0, shift=0.0, eps=EPS):
     import torch
     from paper_1912_01703_amd import binding as mc
     x, dy, gamma, beta = wl.make_bn_inputs(N, C, H, W, seed)
-    y_ref, mean_ref, inv_ref = ref.batchnorm2d_fwd(x, gamma, beta, EPS)
-    dx_ref, dg_ref, db_ref = ref.batchnorm2d_bwd(x, dy, gamma, EPS)
+    if shift:
+        x = (x + np.float32(shift)).astype(np.float32)
+    y_ref, mean_ref, inv_ref = ref.batchnorm2d_fwd(x, gamma, beta, eps)
+    dx_ref, dg_ref, db_ref = ref.batchnorm2d_bwd(x, dy, gamma, eps)
     den = bounds(x, dy, gamma, beta, mean_ref, inv_ref)
     dev = "cuda:0"
 
@@ -82,7 +84,7 @@ def run_case(name, N, C, H, W, seed, offset=0):
     ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream().cuda_stream
     print(f"[batchnorm] case={name} N={N} C={C} H={H} W={W} offset={offset} workspace={need}", flush=True)
-    mc.batchnorm2d_fwd(xd, gd, bd, y, mean, inv_std, N, C, H, W, EPS, mc.F32, ws, stream)
+    mc.batchnorm2d_fwd(xd, gd, bd, y, mean, inv_std, N, C, H, W, eps, mc.F32, ws, stream)
     stats = (up(mean_ref.astype(np.float32)), up(inv_ref.astype(np.float32)))
     mc.batchnorm2d_bwd(xd, dyd, gd, stats[0], stats[1], dx, dgamma, dbeta, N, C, H, W, mc.F32, ws, stream)
     torch.cuda.synchronize()
@@ -106,6 +108,18 @@ def test_batchnorm_shapes(row):
 def test_batchnorm_unaligned_tensors_take_the_four_byte_path(row):
     name, N, C, H, W = row
     run_case(name, N, C, H, W, seed=9100, offset=1)
+
+
+@pytest.mark.parametrize("row", [("bn14m", 64, 32, 14, 14), ("bn56m", 16, 4, 56, 56)], ids=["resident", "split"])
+def test_batchnorm_with_a_mean_far_from_zero(row):
+    """Channels whose mean is a thousand standard deviations away from zero: the variance must come from the centred
+    values (a sum of squares minus the squared mean would lose all its digits in fp32)."""
+    name, N, C, H, W = row
+    run_case(name, N, C, H, W, seed=9400, shift=1000.0)
+
+
+def test_batchnorm_without_eps():
+    run_case("bn0", 8, 16, 14, 14, seed=9410, eps=0.0)
 
 
 def test_batchnorm_forward_statistics_feed_the_backward_call():

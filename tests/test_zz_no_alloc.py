@@ -54,3 +54,23 @@ def test_static_workspace_rejects_what_does_not_fit():
     assert rc == mc.ERR_WORKSPACE and "static array" in mc.last_error()
     torch.cuda.synchronize()
     assert float(dummy.abs().sum()) == 0.0               # nothing was launched
+
+
+def test_static_workspace_with_bf16_inputs():
+    """bf16 tensors, 1x1 layer: the matrix-product kernel's partial sums (a few MB) live in the static array too."""
+    import torch
+    from paper_1912_01703_amd import binding as mc
+    L = wl.custom_layer("nabf", 16, 64, 14, 14, 128, 1, 1, 1, 0, 1, seed=7100)
+    args = L.conv_args()
+    need = mc.conv2d_workspace_bytes(2, *args, mc.BF16_F32ACC)
+    assert 0 < need <= 32 << 20 and mc.miconv_kernel_path(2, *args, mc.BF16_F32ACC) == "mfma/bf16_gemm"
+    h = pu.prepare(L, "bf16")
+    gr = pu.GpuRunner(L, h, "bf16")
+    want = gr.run("bwd_weight").clone()
+    got = torch.full(L.w_shape, float("nan"), device="cuda:0")
+    mc.conv2d_bwd_weight_static_ws(gr.x, gr.dy, got, *args, mc.BF16_F32ACC, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(got, want)
+    refv, den = pu.oracle_full(L, h, "bwd_weight")
+    err, ok = pu.max_norm_err(got.cpu().numpy(), refv, den)
+    assert ok and err <= pu.TOL["bf16"], err
