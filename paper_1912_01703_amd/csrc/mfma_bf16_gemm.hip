@@ -120,10 +120,11 @@ __global__ __launch_bounds__(NTHREADS, OCC) void bf16_gemm_kernel(GemmArgs a) {
     }
     const unsigned plane_bytes = (unsigned)a.HW * 2u;
     int fb = b_begin, fk = 0;   // batch and first k of the next chunk to fetch
+    // the descriptors change with the batch only (once per image in backward-weight, never otherwise)
+    rsrc_t ars = make_rsrc(a.A + (size_t)fb * a.a_batch, a_bytes);
+    rsrc_t brs = make_rsrc(a.B + (size_t)fb * a.b_batch, b_bytes);
     auto fetch = [&](auto setc) __attribute__((always_inline)) {
         constexpr int SET = decltype(setc)::value;
-        const rsrc_t ars = make_rsrc(a.A + (size_t)fb * a.a_batch, a_bytes);
-        const rsrc_t brs = make_rsrc(a.B + (size_t)fb * a.b_batch, b_bytes);
         const bool kin = fk + pcol < a.Kd;   // else this thread's pieces lie beyond their rows: zeros
         const unsigned kb = (unsigned)fk * 2u;
 #pragma unroll
@@ -139,7 +140,12 @@ __global__ __launch_bounds__(NTHREADS, OCC) void bf16_gemm_kernel(GemmArgs a) {
         }
         nva[SET] = a.Kd - (fk + pcol);
         fk += BK;
-        if (fk >= a.Kd) { fk = 0; ++fb; }
+        if (fk >= a.Kd) {
+            fk = 0;
+            ++fb;
+            ars = make_rsrc(a.A + (size_t)fb * a.a_batch, a_bytes);
+            brs = make_rsrc(a.B + (size_t)fb * a.b_batch, b_bytes);
+        }
     };
     auto stash = [&](int buf, auto setc) __attribute__((always_inline)) {
         constexpr int SET = decltype(setc)::value;
