@@ -375,6 +375,21 @@ def test_bwd_weight_is_bit_reproducible():
     assert torch.equal(a, b)
 
 
+@pytest.mark.parametrize("name,dtype", [("2b", "f32"), ("2c", "f32"), ("5a", "f32"), ("3", "f32"), ("2b", "bf16"), ("2a", "bf16")],
+                         ids=["split-1x1", "split-3x3s2", "depthwise", "three-channel", "bf16-product", "bf16-3x3"])
+def test_bwd_weight_is_bit_reproducible_on_the_split_paths(name, dtype):
+    """Paths that sum partial results (workspace partials, wave shares, register reductions) do so in a fixed order:
+    two runs give the same bits."""
+    import torch
+    L = wl.LAYERS[name]
+    h = pu.prepare(L, dtype)
+    gr = pu.GpuRunner(L, h, dtype)
+    a = gr.run("bwd_weight").clone()
+    b = gr.run("bwd_weight")
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+
+
 def test_inputs_are_not_modified():
     import torch
     L = odd_layer(ODD[6])
