@@ -108,6 +108,15 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int NPX = TH * TW;
     constexpr int NB = (NPX + 15) / 16;      // 16-pixel blocks in the tile
     constexpr int NBW = (NB + WP - 1) / WP;  // blocks per wave
+    // A last block of at most four pixels (196 = 12 * 16 + 4) is not run as a 16 x 16 x 4 MFMA with twelve idle
+    // columns: v_mfma_f32_4x4x1_16B_f32 (sixteen independent 4 x 4 x 1 products, a quarter of the time) takes it,
+    // block b = 4 * kq + fg of the instruction being filters 4 * fg .. + 3 times the four pixels for the reduction
+    // channel of lane group kq.  Lane l = 4 * b + i is row i of block b for A and column i for B, which is the layout
+    // the filter registers already have (filter l % 16, lane group l / 16); the B operand is the pixel l % 4.  The
+    // four partial sums per (filter, pixel) are added and moved to the 16 x 16 layout once, before the write-out.
+    constexpr int RAG = NPX % 16;
+    constexpr bool QUAD = RAG >= 1 && RAG <= 4;
+    constexpr int QWP = (NB - 1) % WP;        // the wave (along pixels) whose last slot is that block
 
     static_assert(NBUF == 2 || NBUF == 3, "two or three patch buffers");
     // Each buffer is followed by 64 words that lanes without an element store to (no branch around a
@@ -220,9 +229,10 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 
     // ---- per-lane pixel offsets into the LDS patch -----------------------------------------
     int pixoff[NBW];
+    const bool quad_here = QUAD && wp == QWP;   // wave-uniform
 #pragma unroll
     for (int i = 0; i < NBW; ++i) {
-        int j = 16 * (wp + WP * i) + li;
+        int j = 16 * (wp + WP * i) + (quad_here && i == NBW - 1 ? li & 3 : li);
         if (j >= NPX) j = 0;  // padding lanes read a valid address; their results are never stored
         const int th = j / TW, tw = j - th * TW;
         pixoff[i] = kk * KQ * CS + th * PST * PW + tw * PST;
@@ -375,7 +385,10 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
                 if (mine) {
                     if (g + 1 < G) bq[(PAR + g + 1) & 1][i] = pr[i][off];
                     else if (NBUF == 3) bq[(PAR + g + 1) & 1][i] = pn[i][tap_off(0)];      // group 0 of the next chunk
-                    acc[tap_set(g / KQ)][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[(PAR + g) & 1][i], acc[tap_set(g / KQ)][i], 0, 0, 0);
+                    if (QUAD && i == NBW - 1 && (QWP == 0 || quad_here))   // (QWP == 0: only wave 0 owns this slot)
+                        acc[tap_set(g / KQ)][i] = __builtin_amdgcn_mfma_f32_4x4x1f32(av, bq[(PAR + g) & 1][i], acc[tap_set(g / KQ)][i], 0, 0, 0);
+                    else
+                        acc[tap_set(g / KQ)][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[(PAR + g) & 1][i], acc[tap_set(g / KQ)][i], 0, 0, 0);
                 }
                 {   // patch stores m with floor(m * SG*NBW / XPT) == this slot
                     constexpr int SACT = SG * NBW;
@@ -392,6 +405,21 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 
     // ---- write-out of an item: D[f = 4*kk+v][pixel = li] ---------------------------------------
     auto write_out = [&](const Item& it) __attribute__((always_inline)) {
+        if (QUAD && quad_here) {
+            // 4 x 4 x 1 blocks: lane 4 * (4 * kq + fg) + p holds in register v the partial sum over lane group kq's
+            // channels for (filter 4 * fg + v, pixel p).  The 16 x 16 layout wants (filter 4 * kk + v, pixel li) in
+            // lane 16 * kk + li: it adds the four partial sums of lanes p + 4 * kk + 16 * kq, kq in order.
+#pragma unroll
+            for (int q = 0; q < NSET; ++q)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const float part = acc[q][NBW - 1][v];
+                    float s = __shfl(part, (li & 3) + 4 * kk, 64);
+#pragma unroll
+                    for (int kq = 1; kq < 4; ++kq) s += __shfl(part, (li & 3) + 4 * kk + 16 * kq, 64);
+                    acc[q][NBW - 1][v] = s;
+                }
+        }
         const int fq = it.fblk * (16 * WF) + wf * 16 + 4 * kk;
         const int dplane = PHASE || MERGE2 ? a.DH * a.DW : a.OH * a.OW;
         float* dst = a.dst + (size_t)(it.n * a.Cdst + it.g * a.Fg) * dplane;
