@@ -107,16 +107,22 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int XPT = XW ? (XE / 4 + NT - 1) / NT : (XE + NT - 1) / NT;   // load pieces per thread
     constexpr int NPX = TH * TW;
     constexpr int NB = (NPX + 15) / 16;      // 16-pixel blocks in the tile
-    constexpr int NBW = (NB + WP - 1) / WP;  // blocks per wave
     // A last block of at most four pixels (196 = 12 * 16 + 4) is not run as a 16 x 16 x 4 MFMA with twelve idle
     // columns: v_mfma_f32_4x4x1_16B_f32 (sixteen independent 4 x 4 x 1 products, a quarter of the time) takes it,
     // block b = 4 * kq + fg of the instruction being filters 4 * fg .. + 3 times the four pixels for the reduction
     // channel of lane group kq.  Lane l = 4 * b + i is row i of block b for A and column i for B, which is the layout
     // the filter registers already have (filter l % 16, lane group l / 16); the B operand is the pixel l % 4.  The
     // four partial sums per (filter, pixel) are added and moved to the 16 x 16 layout once, before the write-out.
+    // Only where every wave keeps at least two full blocks: on 7 x 7 tiles (three full blocks for two waves) the wave
+    // left with one MFMA per group no longer covers its LDS reads (3x3, 512 channels: forward 173 -> 201 us).
     constexpr int RAG = NPX % 16;
-    constexpr bool QUAD = RAG >= 1 && RAG <= 4;
-    constexpr int QWP = (NB - 1) % WP;        // the wave (along pixels) whose last slot is that block
+    constexpr bool QUAD = RAG >= 1 && RAG <= 4 && (NB - 1) >= 2 * WP;
+    // Block slots of a wave: the full blocks are dealt out to the WP waves in turn (wave wp, slot i: block wp + WP * i),
+    // and the small last block has a slot of its own behind them, which belongs to wave 0.  So a slot is of one kind
+    // for every wave, and what differs between waves is only whether they own it (a wave-uniform skip).
+    constexpr int NBF = QUAD ? NB - 1 : NB;                  // blocks run as 16 x 16 x 4
+    constexpr int NBWF = (NBF + WP - 1) / WP;                // their slots
+    constexpr int NBW = NBWF + (QUAD ? 1 : 0);               // slots per wave
 
     static_assert(NBUF == 2 || NBUF == 3, "two or three patch buffers");
     // Each buffer is followed by 64 words that lanes without an element store to (no branch around a
@@ -229,16 +235,21 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
 
     // ---- per-lane pixel offsets into the LDS patch -----------------------------------------
     int pixoff[NBW];
-    const bool quad_here = QUAD && wp == QWP;   // wave-uniform
+    const bool quad_here = QUAD && wp == 0;                       // wave-uniform
+    const bool last_ok = wp + WP * (NBWF - 1) < NBF;              // does this wave own a block in the last full slot?
+    // block of slot i, and whether this wave owns it
+    auto block_of = [&](int i) __attribute__((always_inline)) { return QUAD && i == NBW - 1 ? NB - 1 : wp + WP * i; };
+    auto owns = [&](int i) __attribute__((always_inline)) {
+        return QUAD && i == NBW - 1 ? (WP == 1 || quad_here) : !(NBF % WP != 0 && i == NBWF - 1 && !last_ok);
+    };
 #pragma unroll
     for (int i = 0; i < NBW; ++i) {
-        int j = 16 * (wp + WP * i) + (quad_here && i == NBW - 1 ? li & 3 : li);
+        int j = 16 * block_of(i) + (QUAD && i == NBW - 1 ? li & 3 : li);
         if (j >= NPX) j = 0;  // padding lanes read a valid address; their results are never stored
         const int th = j / TW, tw = j - th * TW;
         pixoff[i] = kk * KQ * CS + th * PST * PW + tw * PST;
     }
 
-    const bool last_ok = wp + WP * (NBW - 1) < NB;   // does this wave own a block in its last slot?
     // Per-tap LDS offset and accumulator set.  Plain correlation: tap (r, s) reads patch row r, column s.
     // MERGE2: tap index r reads patch row roff(r) = (r == 0) and belongs to row phase a = r % 2.
     constexpr auto tap_off = [](int t) {
@@ -381,11 +392,11 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
             const float av = ac[(g % KQ) * RS + g / KQ];
 #pragma unroll
             for (int i = 0; i < NBW; ++i) {
-                const bool mine = !(NB % WP != 0 && i == NBW - 1 && !last_ok);   // wave-uniform: this wave may have one block fewer
+                const bool mine = owns(i);   // wave-uniform: this wave may have one block fewer
                 if (mine) {
                     if (g + 1 < G) bq[(PAR + g + 1) & 1][i] = pr[i][off];
                     else if (NBUF == 3) bq[(PAR + g + 1) & 1][i] = pn[i][tap_off(0)];      // group 0 of the next chunk
-                    if (QUAD && i == NBW - 1 && (QWP == 0 || quad_here))   // (QWP == 0: only wave 0 owns this slot)
+                    if (QUAD && i == NBW - 1)
                         acc[tap_set(g / KQ)][i] = __builtin_amdgcn_mfma_f32_4x4x1f32(av, bq[(PAR + g) & 1][i], acc[tap_set(g / KQ)][i], 0, 0, 0);
                     else
                         acc[tap_set(g / KQ)][i] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bq[(PAR + g) & 1][i], acc[tap_set(g / KQ)][i], 0, 0, 0);
@@ -426,10 +437,10 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
         // Where accumulator set q of pixel block i goes: destination pixel index inside a plane, or -1 for none.
         // MERGE2: set (a, b) holds destination pixel (2*oh + 1 - a, 2*ow + 1 - b).
         auto pixel = [&](int i, int q, int& oh, int& ow) __attribute__((always_inline)) -> int {
-            const int j = 16 * (wp + WP * i) + li;
+            const int j = 16 * block_of(i) + li;
             const int th = j / TW, tw = j - th * TW;
             oh = it.oh0 + th; ow = it.ow0 + tw;
-            if (!it.ok || j >= NPX || oh >= a.OH || ow >= a.OW) return -1;
+            if (!it.ok || !owns(i) || j >= NPX || oh >= a.OH || ow >= a.OW) return -1;
             const int dh = 2 * oh + 1 - q / 2, dw = 2 * ow + 1 - q % 2;
             if (MERGE2 && (dh >= a.DH || dw >= a.DW)) return -1;
             return MERGE2 ? dh * a.DW + dw : (PHASE ? (oh * a.o_sh + a.o_oh) * a.DW + ow * a.o_sw + a.o_ow : oh * a.OW + ow);
