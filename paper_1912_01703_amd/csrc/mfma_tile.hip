@@ -6,7 +6,10 @@ namespace miconv {
 namespace {
 using namespace tile;
 
-template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, int NBUF = 3, bool PERSIST = false>
+// Two patch buffers everywhere: a third one lets the first LDS operands of the next chunk be requested before the
+// barrier, but the shorter start-up and the smaller LDS footprint of two were worth more on every layer measured
+// (1-4 %; 1x1 at stride 2 and on 7 x 7 planes 5-7 %).
+template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, int NBUF = 2, bool PERSIST = false>
 hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
     TileArgs a = base;
     a.tiles_h = (a.OH + TH - 1) / TH;
@@ -49,9 +52,9 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
         const long long ids = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
         // Wide planes take 12 x 16 tiles: 12 pixel blocks without a ragged one (14 x 14 = 12.25 blocks run as 13), and
         // output rows of 64 bytes that start on 64-byte boundaries
-        if (a.Rg <= 128 && ids >= 1024 && a.OW % 16 == 0 && a.OH >= 96) *err = launch_tile<T, 3, 3, 1, 12, 16, 16, 4, 2, BWD, 3, true>(a, st);
-        else if (a.Rg <= 128 && ids >= 1024) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD, 3, true>(a, st);
-        else *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD>(a, st);
+        if (a.Rg <= 128 && ids >= 1024 && a.OW % 16 == 0 && a.OH >= 96) *err = launch_tile<T, 3, 3, 1, 12, 16, 16, 4, 2, BWD, 2, true>(a, st);
+        else if (a.Rg <= 128 && ids >= 1024) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD, 2, true>(a, st);
+        else *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD, 2>(a, st);
         return true;
     }
     if (R == 1 && S == 1 && stride == 1) {
@@ -74,8 +77,8 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
             }
         }
         const long long ids = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
-        if (a.Rg <= 256 && ids >= 1024) *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD, 3, true>(a, st);
-        else *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD>(a, st);
+        if (a.Rg <= 256 && ids >= 1024) *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD, 2, true>(a, st);
+        else *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD, 2>(a, st);
         return true;
     }
     if (!BWD && R == 1 && S == 1 && stride == 2) {
@@ -86,10 +89,15 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
     }
     if (!BWD && R == 3 && S == 3 && stride == 2) {
         if (dry) return true;
-        // 64 filters per workgroup unless that leaves CUs without one; then 32 filters on twice the workgroups
+        // 64 filters x 14 x 14 pixels per workgroup unless that leaves CUs without one; then half tiles (7 x 14) on twice
+        // the workgroups, eight waves and two patch buffers (128 -> 128 channels, 28 -> 14, N=64: 40.2 -> 37.2 us; with
+        // 32 filters x 14 x 14 pixels every workgroup fetched the whole patch for half of the MFMAs), and only when
+        // that is still too few, 32 filters per workgroup
         const long long wgs64 = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
+        const long long wgs64h = (long long)a.N * a.groups * ((a.OH + 6) / 7) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
         if (wgs64 >= 200) *err = launch_tile<T, 3, 3, 2, 14, 14, 8, 4, 1, false>(a, st);
-        else *err = launch_tile<T, 3, 3, 2, 14, 14, 8, 2, 4, false>(a, st);
+        else if (wgs64h >= 200) *err = launch_tile<T, 3, 3, 2, 7, 14, 8, 4, 2, false, 2>(a, st);
+        else *err = launch_tile<T, 3, 3, 2, 14, 14, 8, 2, 4, false, 2>(a, st);
         return true;
     }
     return false;

@@ -25,7 +25,8 @@
 //     are stored to its buffer, then refilled with the loads of chunk i+NBUF; the filters of chunk
 //     i+1 are loaded into the second register set.  One barrier per chunk and no separate copy phase.
 //     With three buffers the next chunk's patch was complete a barrier earlier, so the first LDS
-//     operands of chunk i+1 are requested before the barrier and the MFMA stream runs through it.
+//     operands of chunk i+1 are requested before the barrier and the MFMA stream runs through it;
+//     the launchers nevertheless use two (shorter start-up, less LDS), which measured faster.
 //   * An ordinary vector instruction does not overlap with a running MFMA of its own SIMD, so the
 //     loop holds only MFMAs, LDS accesses, loads and waits: every address is a register prepared
 //     outside the loop plus an immediate.
@@ -86,7 +87,7 @@ constexpr int lds_channel_stride(int v, int kq) {
 //     h = 2*i + 1 - a for grid row i, tap r reads dy row i + (r == 0), see roff() below.
 // XW: the patch is TH full rows of the source plane (1x1 filter, no padding, tile as wide as the plane) and planes are
 //     multiples of 16 bytes: a chunk's patch is then one contiguous run of CK planes, read 16 bytes per lane.
-template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, bool WV, bool PHASE, int NBUF = 3,
+template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, bool WV, bool PHASE, int NBUF = 2,
           bool XW = false, bool PERSIST = false, bool MERGE2 = false>
 __global__ __launch_bounds__(64 * WF * WP) void conv_tile_kernel(TileArgs a) {
     constexpr int NT = 64 * WF * WP;

@@ -86,6 +86,8 @@ SHAPES = [
     ("e1x1g", 16, 72, 14, 14, 136, 1, 1, 1, 0, 1),     # bf16: the matrix-product kernel applies the epilogue in its write-out
     ("e3x3p", 5, 16, 210, 210, 24, 3, 3, 1, 1, 1),     # persistent workgroups: an epilogue per work item
     ("e3x3s2d", 2, 24, 57, 60, 40, 3, 3, 2, 1, 1),     # merged-phase backward-data
+    ("e3x3s2i", 1, 128, 27, 31, 8, 3, 3, 2, 1, 1),     # ... 64 destination channels per workgroup on 7 x 14 grid tiles
+    ("e3x3s2e", 50, 8, 28, 28, 128, 3, 3, 2, 1, 1),    # forward on 7 x 14 half tiles
     ("e5x5s2", 2, 16, 20, 20, 16, 5, 5, 2, 2, 1),      # one launch per phase
     ("e1x1s2", 3, 40, 28, 28, 72, 1, 1, 2, 0, 1),      # 1x1 stride 2: zeros next to every written pixel
     ("e3x3z", 5, 40, 7, 7, 72, 3, 3, 1, 1, 1),         # 7x7 tiles

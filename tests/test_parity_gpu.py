@@ -83,6 +83,10 @@ MFMA = [
     ("m3x3s2c", 2, 16, 16, 16, 24, 3, 3, 2, 0, 1),    # no padding: the last input row/column feeds nothing
     ("m3x3s2g", 1, 32, 14, 14, 32, 3, 3, 2, 1, 2),
     ("m3x3s2d", 2, 24, 57, 60, 40, 3, 3, 2, 1, 1),    # merged-phase backward-data over several ragged tiles
+    ("m3x3s2e", 50, 16, 28, 28, 128, 3, 3, 2, 1, 1),  # forward on 7 x 14 half tiles (14 x 14 tiles would leave CUs idle)
+    ("m3x3s2f", 56, 8, 26, 25, 72, 3, 3, 2, 1, 1),    # ... ragged: 13 x 13 outputs, a partial second filter block
+    ("m3x3s2h", 2, 64, 28, 28, 16, 3, 3, 2, 1, 1),    # backward-data: 64 destination channels on 7 x 14 grid tiles
+    ("m3x3s2i", 1, 128, 27, 31, 8, 3, 3, 2, 1, 1),    # ... odd plane, two channel blocks, three ragged grid tiles
     ("m3x3z", 5, 40, 7, 7, 72, 3, 3, 1, 1, 1),        # 7 x 7 planes: tiles of 7 x 7 pixels
     ("m1x1z", 6, 72, 7, 7, 136, 1, 1, 1, 0, 1),
     ("m3x3y", 3, 24, 6, 5, 24, 3, 3, 1, 1, 1),        # ... smaller than the tile
