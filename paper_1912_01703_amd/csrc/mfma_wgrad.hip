@@ -563,11 +563,15 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 2) {
-        *err = launch_wgrad<T, 1, 1, 2, 2, 14, 4, 4, 2, 2, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        // 128 x 128 channel blocks where both channel counts fill them (256 -> 512 channels, 56 -> 28, N=64: 233 -> 164 us)
+        if (pr.Kg > 64 && pr.Cg > 64) *err = launch_wgrad<T, 1, 1, 2, 2, 14, 8, 8, 2, 2, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        else *err = launch_wgrad<T, 1, 1, 2, 2, 14, 4, 4, 2, 2, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && pr.P <= 7 && pr.Q <= 7) {
-        *err = launch_wgrad<T, 1, 1, 1, 7, 8, 4, 4, 2, 2, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        // 128 output x 64 input channels per workgroup (512 <-> 2048 channels, N=64: 111 -> 91 us; 128 x 128 blocks: 146 us)
+        if (pr.Kg > 64) *err = launch_wgrad<T, 1, 1, 1, 7, 8, 8, 4, 2, 2, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        else *err = launch_wgrad<T, 1, 1, 1, 7, 8, 4, 4, 2, 2, 2, 2, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && (pr.Cg <= 64 || pr.Kg <= 64) && pr.ph == 0 && pr.pw == 0 &&
@@ -579,8 +583,8 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && pr.ph == 0 && pr.pw == 0 && (pr.Q == 28 || pr.Q == 56) && pr.Cg > 64 && pr.Kg > 64) {
         // many channels on wide planes: stages of 56 pixels in full rows
-        if (pr.Q == 28) *err = launch_wgrad<T, 1, 1, 1, 2, 28, 8, 8, 2, 2, 2, 1, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
-        else *err = launch_wgrad<T, 1, 1, 1, 1, 56, 8, 8, 2, 2, 2, 1, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        if (pr.Q == 28) *err = launch_wgrad<T, 1, 1, 1, 2, 28, 8, 4, 2, 2, 2, 1, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        else *err = launch_wgrad<T, 1, 1, 1, 1, 56, 8, 4, 2, 2, 2, 1, 1, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1 && (pr.Cg <= 64 || pr.Kg <= 64)) {
@@ -589,7 +593,9 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
         return true;
     }
     if (pr.R == 1 && pr.S == 1 && pr.sh == 1) {
-        *err = launch_wgrad<T, 1, 1, 1, 2, 14, 8, 8, 2, 2, 2, 1, 2, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+        // 128 output x 64 input channels per workgroup: twice the workgroups of 128 x 128 blocks, so half the partial
+        // results to add afterwards (1024 -> 256 channels, 14 x 14, N=64: 67.5 -> 62.5 us; 512 -> 512, N=128: 114 -> 112 us)
+        *err = launch_wgrad<T, 1, 1, 1, 2, 14, 8, 4, 2, 2, 2, 1, 2, 1, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }
     return false;

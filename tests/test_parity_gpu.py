@@ -92,6 +92,7 @@ MFMA = [
     ("m3x3y", 3, 24, 6, 5, 24, 3, 3, 1, 1, 1),        # ... smaller than the tile
     ("m1x1s2", 3, 40, 28, 28, 72, 1, 1, 2, 0, 1),     # 1x1 stride 2: three of four dx phases receive nothing
     ("m1x1s2b", 2, 136, 15, 19, 24, 1, 1, 2, 0, 1),   # ... odd sizes, more than one 128-channel block
+    ("m1x1s2c", 2, 136, 15, 19, 72, 1, 1, 2, 0, 1),   # ... more than 64 channels on both sides: 128 x 128 blocks in backward-weight
 ]
 
 
