@@ -9,7 +9,9 @@ using namespace tile;
 // Two patch buffers everywhere: a third one lets the first LDS operands of the next chunk be requested before the
 // barrier, but the shorter start-up and the smaller LDS footprint of two were worth more on every layer measured
 // (1-4 %; 1x1 at stride 2 and on 7 x 7 planes 5-7 %).
-template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, int NBUF = 2, bool PERSIST = false>
+// XWONLY: the caller has checked that the patch is a run of full rows of an aligned plane, so only that instance is built.
+template <typename T, int R, int S, int ST, int TH, int TW, int CK, int WF, int WP, bool BWD, int NBUF = 2, bool PERSIST = false,
+          bool XWONLY = false>
 hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
     TileArgs a = base;
     a.tiles_h = (a.OH + TH - 1) / TH;
@@ -31,7 +33,8 @@ hipError_t launch_tile(const TileArgs& base, hipStream_t st) {
             return hipGetLastError();
         }
     }
-    if (wv) conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true, false, NBUF, false, PERSIST><<<grid, 64 * WF * WP, 0, st>>>(a);
+    if constexpr (XWONLY) return hipErrorNotSupported;
+    else if (wv) conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, true, false, NBUF, false, PERSIST><<<grid, 64 * WF * WP, 0, st>>>(a);
     else conv_tile_kernel<T, R, S, ST, TH, TW, CK, WF, WP, BWD, false, false, NBUF, false, PERSIST><<<grid, 64 * WF * WP, 0, st>>>(a);
     return hipGetLastError();
 }
@@ -45,15 +48,23 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
         if (dry) return true;
         // planes of at most 7 x 7 pixels: a 7 x 7 tile is 4 pixel blocks (a 14 x 14 tile would run 13 for 3.06)
         if (a.OH <= 7 && a.OW <= 7) {
-            *err = launch_tile<T, 3, 3, 1, 7, 7, 16, 4, 2, BWD>(a, st);
+            // (128 filters per workgroup where the layer has them: 512 channels, N=64: 174 / 134 -> 137 / 113 us)
+            if (a.Fg >= 128) *err = launch_tile<T, 3, 3, 1, 7, 7, 16, 8, 1, BWD>(a, st);
+            else *err = launch_tile<T, 3, 3, 1, 7, 7, 16, 4, 2, BWD>(a, st);
             return true;
         }
         // Few chunks per item and many items: persistent workgroups hide each item's start-up and write-out
         const long long ids = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
         // Wide planes take 12 x 16 tiles: 12 pixel blocks without a ragged one (14 x 14 = 12.25 blocks run as 13), and
         // output rows of 64 bytes that start on 64-byte boundaries
-        if (a.Rg <= 128 && ids >= 1024 && a.OW % 16 == 0 && a.OH >= 96) *err = launch_tile<T, 3, 3, 1, 12, 16, 16, 4, 2, BWD, 2, true>(a, st);
+        // (with 128 filters per workgroup where the layer has them: 64 -> 128 channels at 112 x 112, N=32: 500 -> 476 us)
+        if (a.Fg >= 128 && a.Rg <= 128 && ids >= 1024 && a.OW % 16 == 0 && a.OH >= 96) *err = launch_tile<T, 3, 3, 1, 12, 16, 16, 8, 1, BWD, 2, true>(a, st);
+        else if (a.Rg <= 128 && ids >= 1024 && a.OW % 16 == 0 && a.OH >= 96) *err = launch_tile<T, 3, 3, 1, 12, 16, 16, 4, 2, BWD, 2, true>(a, st);
         else if (a.Rg <= 128 && ids >= 1024) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD, 2, true>(a, st);
+        // 128 filters per workgroup (eight waves x 16 filters x all 13 pixel blocks) where that leaves a workgroup for
+        // every CU: the patch is fetched and stored to LDS once per 128 filters and a wave's filter values are used 12.25
+        // times (512 channels at 28 x 28, N=64: 1679 / 1657 -> 1606 / 1596 us; 256 channels at 56 x 56, N=32: 871 -> 823 us)
+        else if (a.Fg >= 128 && ids >= 512) *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 8, 1, BWD, 2>(a, st);
         else *err = launch_tile<T, 3, 3, 1, 14, 14, 16, 4, 2, BWD, 2>(a, st);
         return true;
     }
@@ -62,7 +73,10 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
         // 32-channel chunks on eight waves (64-channel chunks leave one workgroup per CU: 80 instead of 68 us on
         // the 1024 -> 256 channel layer); persistent workgroups when there are many short items
         if (a.OH <= 7 && a.OW <= 7) {
-            *err = launch_tile<T, 1, 1, 1, 7, 7, 32, 4, 2, BWD>(a, st);
+            // 128 filters per workgroup where the layer has them: each of the eight waves then runs the plane's three full
+            // pixel blocks and the one-pixel block (512 <-> 2048 channels, N=64: 72-79 -> 62-64 us)
+            if (a.Fg >= 128) *err = launch_tile<T, 1, 1, 1, 7, 7, 32, 8, 1, BWD>(a, st);
+            else *err = launch_tile<T, 1, 1, 1, 7, 7, 32, 4, 2, BWD>(a, st);
             return true;
         }
         // planes 28, 56 or 112 pixels wide: bands of full rows, 224 pixels = 14 blocks, fetched 16 bytes per lane; two
@@ -70,13 +84,29 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
         if constexpr (sizeof(T) == 4) {
             if (a.pad_h == 0 && a.pad_w == 0 && a.IH == a.OH && a.IW == a.OW && (a.OW == 28 || a.OW == 56 || a.OW == 112) &&
                 reinterpret_cast<uintptr_t>(a.src) % 16 == 0) {
-                if (a.OW == 28) *err = launch_tile<T, 1, 1, 1, 8, 28, 32, 4, 2, BWD, 2, true>(a, st);
-                else if (a.OW == 56) *err = launch_tile<T, 1, 1, 1, 4, 56, 32, 4, 2, BWD, 2, true>(a, st);
-                else *err = launch_tile<T, 1, 1, 1, 2, 112, 32, 4, 2, BWD, 2, true>(a, st);
+                // 128 filters per workgroup where the layer has them (3-7 %)
+                if (a.Fg >= 128) {
+                    if (a.OW == 28) *err = launch_tile<T, 1, 1, 1, 8, 28, 32, 8, 1, BWD, 2, true, true>(a, st);
+                    else if (a.OW == 56) *err = launch_tile<T, 1, 1, 1, 4, 56, 32, 8, 1, BWD, 2, true, true>(a, st);
+                    else *err = launch_tile<T, 1, 1, 1, 2, 112, 32, 8, 1, BWD, 2, true, true>(a, st);
+                    return true;
+                }
+                if (a.OW == 28) *err = launch_tile<T, 1, 1, 1, 8, 28, 32, 4, 2, BWD, 2, true, true>(a, st);
+                else if (a.OW == 56) *err = launch_tile<T, 1, 1, 1, 4, 56, 32, 4, 2, BWD, 2, true, true>(a, st);
+                else *err = launch_tile<T, 1, 1, 1, 2, 112, 32, 4, 2, BWD, 2, true, true>(a, st);
                 return true;
             }
         }
         const long long ids = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
+        // 128 filters per workgroup (eight waves x 16 filters x all 13 pixel blocks) where that still leaves two
+        // workgroups per CU: a chunk then lasts twice as long against the same patch traffic, and a wave's filter values are
+        // used 12.25 times instead of 6 (512 -> 512 channels, N=128: forward 117 -> 106 us, backward-data 119 -> 107 us;
+        // 256 -> 1024 channels backward-data, N=64: 68 -> 62 us)
+        const long long ids128 = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 127) / 128);
+        if (ids128 >= 512 && (a.Fg % 128 == 0 || a.Fg >= 512)) {
+            *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 8, 1, BWD, 2>(a, st);
+            return true;
+        }
         if (a.Rg <= 256 && ids >= 1024) *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD, 2, true>(a, st);
         else *err = launch_tile<T, 1, 1, 1, 14, 14, 32, 4, 2, BWD, 2>(a, st);
         return true;
@@ -84,7 +114,9 @@ bool dispatch_tile(int R, int S, int stride, const TileArgs& a, hipStream_t st, 
     if (!BWD && R == 1 && S == 1 && stride == 2) {
         // the 1x1 stride-2 shortcut of a residual network: every other pixel of every other row
         if (dry) return true;
-        *err = launch_tile<T, 1, 1, 2, 14, 14, 32, 4, 2, false>(a, st);
+        // (128 filters per workgroup: 256 -> 512 channels, 56 -> 28, N=64: 182 -> 145 us)
+        if (a.Fg >= 128) *err = launch_tile<T, 1, 1, 2, 14, 14, 32, 8, 1, false>(a, st);
+        else *err = launch_tile<T, 1, 1, 2, 14, 14, 32, 4, 2, false>(a, st);
         return true;
     }
     if (!BWD && R == 3 && S == 3 && stride == 2) {

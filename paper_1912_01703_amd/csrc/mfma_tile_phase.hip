@@ -55,6 +55,8 @@ hipError_t launch_phase(const TileArgs& a, hipStream_t st) {
     if (a.Fg <= 16) return launch_phase_waves<T, JH, JW, 1, 4>(a, st);
     // 64 destination channels per workgroup unless that leaves CUs without one; then 32 on twice the workgroups
     const long long wgs64 = (long long)a.N * a.groups * ((a.OH + 13) / 14) * ((a.OW + 13) / 14) * ((a.Fg + 63) / 64);
+    // 128 destination channels on eight waves where that leaves two workgroups per CU (1x1, 512 -> 256 channels, 28 -> 56, N=64: 163 -> 145 us)
+    if (a.Fg >= 128 && wgs64 >= 1024) return launch_phase_waves<T, JH, JW, 8, 1>(a, st);
     return wgs64 >= 200 ? launch_phase_waves<T, JH, JW, 4, 1>(a, st) : launch_phase_waves<T, JH, JW, 2, 4>(a, st);
 }
 

@@ -92,7 +92,18 @@ MFMA = [
     ("m3x3y", 3, 24, 6, 5, 24, 3, 3, 1, 1, 1),        # ... smaller than the tile
     ("m1x1s2", 3, 40, 28, 28, 72, 1, 1, 2, 0, 1),     # 1x1 stride 2: three of four dx phases receive nothing
     ("m1x1s2b", 2, 136, 15, 19, 24, 1, 1, 2, 0, 1),   # ... odd sizes, more than one 128-channel block
-    ("m1x1s2c", 2, 136, 15, 19, 72, 1, 1, 2, 0, 1),   # ... more than 64 channels on both sides: 128 x 128 blocks in backward-weight
+    ("m1x1s2c", 2, 136, 15, 19, 136, 1, 1, 2, 0, 1),  # ... more than 128 channels on both sides: 128 x 128 blocks in backward-weight,
+                                                      # 128 filters per workgroup forward
+    ("m1x1s2d", 128, 512, 28, 28, 8, 1, 1, 2, 0, 1),  # ... backward-data with 1024 work items: 128 destination channels per workgroup
+    # 128 filters (destination channels) per workgroup where the layer has them and the grid stays large enough
+    ("m1x1w", 128, 16, 14, 14, 512, 1, 1, 1, 0, 1),   # 1x1 on 14 x 14 planes, forward
+    ("m1x1v", 103, 640, 14, 14, 8, 1, 1, 1, 0, 1),    # ... backward-data, five blocks of 128 channels
+    ("m1x1y", 3, 136, 7, 7, 40, 1, 1, 1, 0, 1),       # 7 x 7 planes, backward-data, partial second block
+    ("m1x1k", 1, 16, 4, 112, 136, 1, 1, 1, 0, 1),     # row bands of a 112-wide plane
+    ("m3x3x", 3, 136, 7, 7, 136, 3, 3, 1, 1, 1),      # 3x3 on 7 x 7 planes, both directions
+    ("m3x3v", 64, 8, 14, 14, 512, 3, 3, 1, 1, 1),     # 3x3 on 14 x 14 tiles, forward
+    ("m3x3v2", 64, 512, 14, 14, 8, 3, 3, 1, 1, 1),    # ... backward-data
+    ("m3x3v3", 7, 8, 96, 112, 136, 3, 3, 1, 1, 1),    # ... persistent workgroups on 12 x 16 tiles
 ]
 
 
