@@ -555,6 +555,17 @@ bool dispatch_wgrad(const Problem& pr, const void* x, const void* dy, float* dw,
         return true;
     }
     if (pr.R == 3 && pr.S == 3 && pr.sh == 1) {
+        // Blocks of 32 x 32 channels (four waves own a 16 x 16 block each, two shares of the pixel steps, one image per
+        // stage) where the work is enough for 32 stages per workgroup: every dy and x value is then fetched and stored
+        // to LDS for twice the MFMAs (512 channels at 28 x 28, N=64: 1792 -> 1604 us; 64 channels at 224 x 224: 2060 ->
+        // 1884 us).  Smaller layers keep 16 x 16 blocks: on 256 channels at 14 x 14, N=64, both run 115 us, and only the
+        // larger blocks need a split reduction there.
+        const long long stages = (long long)pr.N * ((pr.P + 13) / 14) * ((pr.Q + 13) / 14);
+        const long long blocks32 = (long long)(pr.Kg / 32) * (pr.Cg / 32) * pr.groups;
+        if (pr.Kg % 32 == 0 && pr.Cg % 32 == 0 && stages * blocks32 >= 8192) {
+            *err = launch_wgrad<T, 3, 3, 1, 14, 14, 2, 2, 2, 2, 2, 2, 1>(pr, x, dy, dw, ws, st, dry, ws_bytes);
+            return true;
+        }
         *err = launch_wgrad<T, 3, 3, 1, 14, 14, 1, 1, 1, 1, 8, 8, 2>(pr, x, dy, dw, ws, st, dry, ws_bytes);
         return true;
     }

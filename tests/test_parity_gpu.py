@@ -104,6 +104,9 @@ MFMA = [
     ("m3x3v", 64, 8, 14, 14, 512, 3, 3, 1, 1, 1),     # 3x3 on 14 x 14 tiles, forward
     ("m3x3v2", 64, 512, 14, 14, 8, 3, 3, 1, 1, 1),    # ... backward-data
     ("m3x3v3", 7, 8, 96, 112, 136, 3, 3, 1, 1, 1),    # ... persistent workgroups on 12 x 16 tiles
+    # backward-weight with 32 x 32 channel blocks (enough stages per workgroup)
+    ("m3x3wg", 128, 256, 14, 14, 256, 3, 3, 1, 1, 1), # 64 blocks, split four ways
+    ("m3x3wh", 228, 64, 30, 30, 64, 3, 3, 1, 1, 1),   # four blocks, nine tiles per image, the outer ones ragged
 ]
 
 
