@@ -374,19 +374,27 @@ __global__ __launch_bounds__(512) void smallc_wgrad_kernel(SmallArgs a) {
     }
 }
 
+// Sum of the partial results in a fixed order: a workgroup of four waves owns 64 elements, wave w adds its quarter of
+// the splits in split order (eight loads in flight at a time), and the four sums are added in wave order through LDS.
 __global__ __launch_bounds__(256) void smallc_reduce_kernel(const float* __restrict__ part, float* __restrict__ dw,
                                                             int nsplit, int count) {
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i >= count) return;
+    __shared__ float sh[4][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int i = blockIdx.x * 64 + lane;
+    const int s_begin = nsplit * w / 4, s_end = nsplit * (w + 1) / 4;
     float sum = 0.f;
-    for (int s0 = 0; s0 < nsplit; s0 += 8) {
-        float v[8];
+    if (i < count) {
+        for (int s0 = s_begin; s0 < s_end; s0 += 8) {
+            float v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = s0 + k < nsplit ? part[(size_t)(s0 + k) * count + i] : 0.f;
+            for (int k = 0; k < 8; ++k) v[k] = s0 + k < s_end ? part[(size_t)(s0 + k) * count + i] : 0.f;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) sum += v[k];
+            for (int k = 0; k < 8; ++k) sum += v[k];
+        }
     }
-    dw[i] = sum;
+    sh[w][lane] = sum;
+    __syncthreads();
+    if (w == 0 && i < count) dw[i] = ((sh[0][lane] + sh[1][lane]) + sh[2][lane]) + sh[3][lane];
 }
 
 
@@ -785,7 +793,7 @@ hipError_t smallc_run(int pass, const Problem& pr, const void* in0, const void* 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.nsplit == 1) return e;
     const int count = pr.K * pr.C * pr.R * pr.S;
-    smallc_reduce_kernel<<<(count + 255) / 256, 256, 0, st>>>(static_cast<const float*>(ws), out, a.nsplit, count);
+    smallc_reduce_kernel<<<(count + 63) / 64, 256, 0, st>>>(static_cast<const float*>(ws), out, a.nsplit, count);
     return hipGetLastError();
 }
 

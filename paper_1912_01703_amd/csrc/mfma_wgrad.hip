@@ -459,8 +459,21 @@ __global__ __launch_bounds__(256) void reduce_splits_kernel(const float* __restr
                                                             int nsplit, size_t count) {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= count) return;
+    // in split order, eight loads in flight at a time
     float sum = part[i];
-    for (int s = 1; s < nsplit; ++s) sum += part[(size_t)s * count + i];
+    int s = 1;
+    for (; s + 8 <= nsplit; s += 8) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = part[(size_t)(s + k) * count + i];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sum += v[k];
+    }
+    float v[7];
+#pragma unroll
+    for (int k = 0; k < 7; ++k) v[k] = s + k < nsplit ? part[(size_t)(s + k) * count + i] : 0.f;
+#pragma unroll
+    for (int k = 0; k < 7; ++k) sum += v[k];
     dw[i] = sum;
 }
 
